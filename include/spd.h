@@ -1,0 +1,152 @@
+/*
+ * spd - all-pairs distances between the rows of two CSR matrices on one MI355X (gfx950),
+ * computed as a sparse semiring product, with an optional fused brute-force k-NN.
+ *
+ * The operation is the one stated in Section 2 of "GPU Semiring Primitives for Sparse
+ * Neighborhood Methods": A is m x k, B is n x k, both in CSR with ascending columns
+ * inside each row, and the result is the dense m x n matrix C with C[i][j] = d(A_i, B_j),
+ * produced without transposing or copying the inputs in full.  Each distance of Table 1
+ * is a product()/sum() pair; the distances of the dot-product family are finished by
+ * an expansion function over row norms (Section 3.4), the others apply their product over
+ * the union of the non-zero columns of the two rows (Section 2.2, Eq. 2).  k-NN follows
+ * the benchmark protocol of Section 4.2: distances of every query row to every index row,
+ * then the k nearest.
+ *
+ * Conventions
+ *  - Every pointer inside spd_csr and every `out*` pointer is a DEVICE pointer owned by
+ *    the caller.  Inputs are read only.  Outputs need no initialisation and are fully
+ *    overwritten.  A and B may be the same matrix.
+ *  - All functions return a status; nothing is thrown across the boundary.
+ *    spd_last_error() gives a text for the last failure on the handle.
+ *  - spd_pairwise / spd_knn first read the two row-pointer arrays back to the host
+ *    (one stream synchronisation) to bin rows by degree, then enqueue all kernels on the
+ *    handle's stream and return without waiting for them.
+ *  - Scratch memory comes from the handle's own grow-only allocation, or from the caller
+ *    through spd_set_workspace().
+ *  - Stored zeros are legal and count as absent.  Values must be finite; Hellinger, KL and
+ *    Jensen-Shannon expect non-negative values (anything else is undefined, and reported by
+ *    spd_csr_validate()).
+ */
+#ifndef SPD_H
+#define SPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spd_handle spd_handle;
+
+typedef struct {
+    int64_t n_rows, n_cols, nnz;
+    const int64_t *indptr;  /* device, n_rows+1, indptr[0]==0, non-decreasing, last==nnz */
+    const int32_t *indices; /* device, nnz, strictly ascending inside a row, 0<=c<n_cols  */
+    const float *values;    /* device, nnz, finite                                        */
+} spd_csr;
+
+/* Table 1 of the paper.  The comment gives the value returned for rows x, y of length k. */
+typedef enum {
+    SPD_INNER_PRODUCT = 0,  /* sum x y (a similarity; spd_knn returns the LARGEST values)   */
+    SPD_COSINE,             /* 1 - <x,y>/(|x|_2 |y|_2); 1 if one row is zero, 0 if both are */
+    SPD_L2_EXPANDED,        /* sqrt(max(0, |x|^2 - 2<x,y> + |y|^2))                         */
+    SPD_CORRELATION,        /* 1 - Pearson correlation, means over all k; 1 if no variance  */
+    SPD_JACCARD,            /* 1 - |sx & sy|/|sx | sy| on the supports; 0 if both empty     */
+    SPD_DICE,               /* 1 - 2|sx & sy|/(|sx|+|sy|) on the supports; 0 if both empty  */
+    SPD_HELLINGER,          /* sqrt(sum (sqrt x - sqrt y)^2)/sqrt 2, x,y >= 0               */
+    SPD_L1,                 /* sum |x-y|                                                     */
+    SPD_CHEBYSHEV,          /* max |x-y|                                                     */
+    SPD_MINKOWSKI,          /* (sum |x-y|^p)^(1/p), p > 0                                    */
+    SPD_CANBERRA,           /* sum |x-y|/(|x|+|y|), 0/0 = 0                                  */
+    SPD_HAMMING,            /* #{x != y} / k                                                 */
+    SPD_KL_DIVERGENCE,      /* sum over columns present in both rows of x log(x/y)           */
+    SPD_JENSEN_SHANNON,     /* sqrt(sum(x log(x/mu) + y log(y/mu))/2), mu=(x+y)/2           */
+    SPD_RUSSELL_RAO,        /* (k - |sx & sy|)/k                                             */
+    SPD_METRIC_COUNT
+} spd_metric;
+
+typedef enum {
+    SPD_OK = 0,
+    SPD_ERR_NULL,          /* a required pointer is NULL                                   */
+    SPD_ERR_DIM_MISMATCH,  /* A.n_cols != B.n_cols, or negative / inconsistent sizes       */
+    SPD_ERR_BAD_CSR,       /* row pointers or (spd_csr_validate only) contents are invalid */
+    SPD_ERR_BAD_METRIC,
+    SPD_ERR_BAD_P,         /* Minkowski needs a finite p > 0                               */
+    SPD_ERR_BAD_K,         /* k < 1, k > index rows, or k > SPD_KNN_MAX_K                  */
+    SPD_ERR_WORKSPACE,     /* caller workspace too small, or allocation failed             */
+    SPD_ERR_HIP,           /* a HIP runtime call failed (no device, launch failure, ...)   */
+    SPD_ERR_UNSUPPORTED    /* sizes beyond what the kernels index (see spd_last_error)     */
+} spd_status;
+
+/* Largest k the fused selection keeps per query (one list entry per lane of a wavefront). */
+#define SPD_KNN_MAX_K 64
+
+/* Creates a handle bound to a HIP stream (`hip_stream` is a hipStream_t, NULL = the null
+ * stream) on the current device.  The handle owns pinned staging memory and, unless
+ * spd_set_workspace() is used, its device scratch.  Destroy it with spd_destroy(). */
+spd_status spd_create(spd_handle **handle, void *hip_stream);
+spd_status spd_destroy(spd_handle *handle);
+
+/* Upper bound, from the shapes alone, of the device scratch one spd_pairwise /
+ * spd_knn call with these operands needs (`k_neighbors` = 0 for spd_pairwise). */
+spd_status spd_workspace_bytes(const spd_handle *handle, const spd_csr *A, const spd_csr *B,
+                               spd_metric metric, int k_neighbors, size_t *bytes);
+
+/* Makes the handle use caller memory (device, 256-byte aligned) as scratch instead of its
+ * own allocation; (NULL, 0) returns to the internal one.  The memory must stay valid until
+ * the work enqueued by later calls has finished. */
+spd_status spd_set_workspace(spd_handle *handle, void *device_ptr, size_t bytes);
+
+/* out[i * B.n_rows + j] = d(A_i, B_j), fp32, row-major, m x n (Section 2; Table 1).
+ * `p` is read for SPD_MINKOWSKI only. */
+spd_status spd_pairwise(spd_handle *handle, const spd_csr *A, const spd_csr *B, spd_metric metric,
+                        float p, float *out);
+
+/* For each query row the k index rows at the smallest distance (largest value for
+ * SPD_INNER_PRODUCT), selected inside the distance kernels without materialising the
+ * m x n matrix (Section 4.2).  out_idx[i*k + t] (int64) and out_dist[i*k + t] (fp32) are
+ * ordered by (distance, index) ascending: equal distances go to the lower index. */
+spd_status spd_knn(spd_handle *handle, const spd_csr *Q, const spd_csr *Index, spd_metric metric,
+                   float p, int k, int64_t *out_idx, float *out_dist);
+
+/* Device pass over a matrix that checks what the other calls assume: row pointers start
+ * at 0, never decrease and end at nnz; columns ascend strictly inside a row and lie in
+ * [0, n_cols); values are finite (and, if `require_nonnegative`, not negative).
+ * Synchronises the stream.  Returns SPD_ERR_BAD_CSR if a check fails. */
+spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_nonnegative);
+
+/* Planner knobs, mainly for tests that need to reach a particular staging path:
+ *   "lds_budget"  bytes of LDS a workgroup may use (default: the device limit)
+ *   "force_kind"  0 auto, 1 dense strip, 2 column-slot strip, 3 hash
+ *   "max_rows"    largest number of A rows staged together (1, 2, 4, 8 or 16)
+ *   "split_len"   B rows at least this long are split over several lanes
+ *   "window"      B rows per degree-sorting window
+ *   "chunks"      number of B chunks (0 = automatic)
+ *   "profile"     1: bracket every kernel launch with HIP events (see spd_profile_read)
+ * Unknown names or values out of range return SPD_ERR_UNSUPPORTED. */
+spd_status spd_set_option(spd_handle *handle, const char *name, int64_t value);
+
+/* Kernel timings of the last spd_pairwise / spd_knn call made with option "profile" = 1.
+ * One record per launch, in launch order.  Waits for the call's kernels to finish. */
+typedef struct {
+    char name[24];        /* "pack_b", "scan", "finalize", "knn_merge"                   */
+    int32_t rows_per_group; /* scan: R, the rows of A staged together; else 0            */
+    int32_t staging_kind; /* scan: 1 dense strip, 2 column-slot strip, 3 hash; else 0    */
+    int32_t block;        /* scan: threads per workgroup; else 0                          */
+    int32_t lds_bytes;    /* scan: dynamic LDS per workgroup; else 0                      */
+    int64_t a_rows;       /* scan: rows (or slices of rows) of A the launch covers        */
+    int64_t workgroups;
+    double ms;            /* HIP-event time of the launch on the handle's stream          */
+} spd_kernel_time;
+/* Writes at most `cap` records to `out`, returns how many the call produced (<0: error). */
+int spd_profile_read(spd_handle *handle, spd_kernel_time *out, int cap);
+
+const char *spd_last_error(const spd_handle *handle);
+const char *spd_metric_name(spd_metric metric);
+const char *spd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPD_H */

@@ -1,0 +1,227 @@
+"""Thin ctypes binding of libspd.so: argument marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels; PyTorch is used for
+device memory and streams.  The names mirror include/spd.h.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libspd.so")
+
+METRICS = (
+    "inner_product", "cosine", "l2_expanded", "correlation", "jaccard", "dice", "hellinger", "l1",
+    "chebyshev", "minkowski", "canberra", "hamming", "kl_divergence", "jensen_shannon", "russell_rao",
+)
+METRIC_ID = {name: i for i, name in enumerate(METRICS)}
+STATUS = ("SPD_OK", "SPD_ERR_NULL", "SPD_ERR_DIM_MISMATCH", "SPD_ERR_BAD_CSR", "SPD_ERR_BAD_METRIC",
+          "SPD_ERR_BAD_P", "SPD_ERR_BAD_K", "SPD_ERR_WORKSPACE", "SPD_ERR_HIP", "SPD_ERR_UNSUPPORTED")
+KNN_MAX_K = 64
+
+
+class SpdError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        self.status = status
+        self.status_name = STATUS[status] if 0 <= status < len(STATUS) else str(status)
+        super().__init__("%s: %s" % (self.status_name, message))
+
+
+class CsrStruct(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int64), ("n_cols", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("values", ctypes.c_void_p)]
+
+
+class KernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 24), ("rows_per_group", ctypes.c_int32), ("staging_kind", ctypes.c_int32),
+                ("block", ctypes.c_int32), ("lds_bytes", ctypes.c_int32), ("a_rows", ctypes.c_int64),
+                ("workgroups", ctypes.c_int64), ("ms", ctypes.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libspd.so; there is no fallback when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_2104_06357_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+        csr_p = ctypes.POINTER(CsrStruct)
+        L.spd_create.argtypes = [ctypes.POINTER(vp), vp]
+        L.spd_destroy.argtypes = [vp]
+        L.spd_workspace_bytes.argtypes = [vp, csr_p, csr_p, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+        L.spd_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+        L.spd_pairwise.argtypes = [vp, csr_p, csr_p, i32, f32, vp]
+        L.spd_knn.argtypes = [vp, csr_p, csr_p, i32, f32, i32, vp, vp]
+        L.spd_csr_validate.argtypes = [vp, csr_p, i32]
+        L.spd_set_option.argtypes = [vp, ctypes.c_char_p, i64]
+        L.spd_last_error.argtypes = [vp]
+        L.spd_last_error.restype = ctypes.c_char_p
+        L.spd_metric_name.argtypes = [i32]
+        L.spd_metric_name.restype = ctypes.c_char_p
+        L.spd_version.restype = ctypes.c_char_p
+        L.spd_profile_read.argtypes = [vp, ctypes.POINTER(KernelTime), i32]
+        L.spd_profile_read.restype = ctypes.c_int
+        L.spd_host_pair_value.argtypes = [i32, f32, i64, vp, vp, i64, vp, vp, i64, ctypes.POINTER(f32)]
+        L.spd_host_plan_summary.argtypes = [vp, i64, vp, i64, i64, i32, i32, ctypes.POINTER(ctypes.c_char_p),
+                                            ctypes.POINTER(i64), i32, ctypes.c_char_p, ctypes.c_size_t]
+        for fn in ("spd_create", "spd_destroy", "spd_workspace_bytes", "spd_set_workspace", "spd_pairwise",
+                   "spd_knn", "spd_csr_validate", "spd_set_option", "spd_host_pair_value",
+                   "spd_host_plan_summary"):
+            getattr(L, fn).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def metric_id(metric) -> int:
+    if isinstance(metric, str):
+        if metric not in METRIC_ID:
+            raise ValueError("unknown metric %r" % metric)
+        return METRIC_ID[metric]
+    return int(metric)
+
+
+class DeviceCsr:
+    """A CSR matrix whose three arrays are torch tensors on the GPU."""
+
+    def __init__(self, n_rows, n_cols, indptr, indices, values):
+        import torch
+        assert indptr.dtype == torch.int64 and indices.dtype == torch.int32 and values.dtype == torch.float32
+        assert indptr.is_cuda and indices.is_cuda and values.is_cuda
+        self.n_rows, self.n_cols = int(n_rows), int(n_cols)
+        self.indptr, self.indices, self.values = indptr.contiguous(), indices.contiguous(), values.contiguous()
+        self.nnz = int(self.indices.numel())
+
+    @classmethod
+    def from_host(cls, csr: dict, device="cuda:0"):
+        import torch
+        return cls(csr["n_rows"], csr["n_cols"],
+                   torch.from_numpy(csr["indptr"]).to(device),
+                   torch.from_numpy(csr["indices"]).to(device),
+                   torch.from_numpy(csr["values"]).to(device))
+
+    def struct(self) -> CsrStruct:
+        return CsrStruct(self.n_rows, self.n_cols, self.nnz, self.indptr.data_ptr(),
+                         self.indices.data_ptr() if self.nnz else None,
+                         self.values.data_ptr() if self.nnz else None)
+
+
+class Handle:
+    """spd_handle bound to torch's current stream at creation (or to `stream`)."""
+
+    def __init__(self, stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("spd needs a GPU: torch.cuda.is_available() is False")
+        self._lib = lib()
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self._h = ctypes.c_void_p()
+        st = self._lib.spd_create(ctypes.byref(self._h), ctypes.c_void_p(self.stream.cuda_stream))
+        if st != 0:
+            raise SpdError(st, "spd_create failed")
+
+    def close(self):
+        if self._h:
+            self._lib.spd_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != 0:
+            raise SpdError(st, (self._lib.spd_last_error(self._h) or b"").decode())
+
+    def set_option(self, name: str, value: int):
+        self._check(self._lib.spd_set_option(self._h, name.encode(), int(value)))
+
+    def profile_read(self):
+        """Kernel timings of the last call (option "profile" = 1): a list of dicts."""
+        buf = (KernelTime * 64)()
+        n = self._lib.spd_profile_read(self._h, buf, 64)
+        if n < 0:
+            raise SpdError(8, "spd_profile_read failed (%d)" % n)
+        return [{f[0]: (getattr(buf[i], f[0]).decode() if f[0] == "name" else getattr(buf[i], f[0]))
+                 for f in KernelTime._fields_} for i in range(min(n, 64))]
+
+    def workspace_bytes(self, A: DeviceCsr, B: DeviceCsr, metric, k_neighbors: int = 0) -> int:
+        out = ctypes.c_size_t()
+        sa, sb = A.struct(), B.struct()
+        self._check(self._lib.spd_workspace_bytes(self._h, ctypes.byref(sa), ctypes.byref(sb), metric_id(metric),
+                                                  int(k_neighbors), ctypes.byref(out)))
+        return int(out.value)
+
+    def set_workspace(self, tensor):
+        if tensor is None:
+            self._check(self._lib.spd_set_workspace(self._h, None, 0))
+        else:
+            self._ws_keepalive = tensor
+            self._check(self._lib.spd_set_workspace(self._h, tensor.data_ptr(), tensor.numel() * tensor.element_size()))
+
+    def csr_validate(self, M: DeviceCsr, require_nonnegative: bool = False):
+        s = M.struct()
+        self._check(self._lib.spd_csr_validate(self._h, ctypes.byref(s), int(require_nonnegative)))
+
+    def pairwise(self, A: DeviceCsr, B: DeviceCsr, metric, p: float = 2.0, out=None):
+        """out[i, j] = d(A_i, B_j) as an fp32 torch tensor (m, n) on the GPU."""
+        import torch
+        if out is None:
+            out = torch.empty((A.n_rows, B.n_rows), dtype=torch.float32, device=A.indptr.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        assert tuple(out.shape) == (A.n_rows, B.n_rows)
+        sa, sb = A.struct(), B.struct()
+        self._check(self._lib.spd_pairwise(self._h, ctypes.byref(sa), ctypes.byref(sb), metric_id(metric),
+                                           float(p), out.data_ptr() if out.numel() else None))
+        return out
+
+    def knn(self, Q: DeviceCsr, Index: DeviceCsr, metric, k: int, p: float = 2.0, out_idx=None, out_dist=None):
+        """(idx int64 [m, k], dist fp32 [m, k]) of the k nearest index rows per query row."""
+        import torch
+        if out_idx is None:
+            out_idx = torch.empty((Q.n_rows, k), dtype=torch.int64, device=Q.indptr.device)
+        if out_dist is None:
+            out_dist = torch.empty((Q.n_rows, k), dtype=torch.float32, device=Q.indptr.device)
+        sa, sb = Q.struct(), Index.struct()
+        self._check(self._lib.spd_knn(self._h, ctypes.byref(sa), ctypes.byref(sb), metric_id(metric), float(p), int(k),
+                                      out_idx.data_ptr() if out_idx.numel() else None,
+                                      out_dist.data_ptr() if out_dist.numel() else None))
+        return out_idx, out_dist
+
+
+# ---- host-only test hooks (include/spd_testing.h) -------------------------------------------
+def host_pair_value(metric, p, n_cols, a_cols, a_vals, b_cols, b_vals) -> float:
+    import numpy as np
+    a_cols = np.ascontiguousarray(a_cols, dtype=np.int32); a_vals = np.ascontiguousarray(a_vals, dtype=np.float32)
+    b_cols = np.ascontiguousarray(b_cols, dtype=np.int32); b_vals = np.ascontiguousarray(b_vals, dtype=np.float32)
+    out = ctypes.c_float()
+    st = lib().spd_host_pair_value(metric_id(metric), float(p), int(n_cols), a_cols.ctypes.data, a_vals.ctypes.data,
+                                   a_cols.size, b_cols.ctypes.data, b_vals.ctypes.data, b_cols.size, ctypes.byref(out))
+    if st != 0:
+        raise SpdError(st, "spd_host_pair_value")
+    return float(out.value)
+
+
+def host_plan_summary(a_indptr, b_indptr, n_cols, metric, k_neighbors=0, **options) -> dict:
+    import json
+
+    import numpy as np
+    a_indptr = np.ascontiguousarray(a_indptr, dtype=np.int64)
+    b_indptr = np.ascontiguousarray(b_indptr, dtype=np.int64)
+    names = (ctypes.c_char_p * max(1, len(options)))(*[k.encode() for k in options])
+    vals = (ctypes.c_int64 * max(1, len(options)))(*[int(v) for v in options.values()])
+    buf = ctypes.create_string_buffer(1 << 16)
+    st = lib().spd_host_plan_summary(a_indptr.ctypes.data, a_indptr.size - 1, b_indptr.ctypes.data, b_indptr.size - 1,
+                                     int(n_cols), metric_id(metric), int(k_neighbors), names, vals, len(options),
+                                     buf, len(buf))
+    text = buf.value.decode()
+    if st != 0:
+        raise SpdError(st, text)
+    return json.loads(text)

@@ -1,0 +1,546 @@
+// C-ABI of the library (include/spd.h): argument checks, planning on the host, scratch
+// layout, and the sequence of launches of one spd_pairwise / spd_knn call.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/spd.h"
+#include "spd_kernels.h"
+#include "spd_plan.h"
+
+using namespace spd;
+
+struct spd_handle {
+    hipStream_t stream = nullptr;
+    int device = 0;
+    PlanOptions opt;
+    std::string err;
+    void *pinned = nullptr;
+    size_t pinned_bytes = 0;
+    void *ws = nullptr;          // device scratch in use
+    size_t ws_bytes = 0;
+    bool ws_external = false;
+    void *own_ws = nullptr;      // the handle's own allocation
+    size_t own_ws_bytes = 0;
+    int32_t *flag = nullptr;     // device word for spd_csr_validate
+    bool profile = false;
+    struct Timed { spd_kernel_time rec; hipEvent_t start, stop; };
+    std::vector<Timed> timed;    // launches of the last call (profile mode)
+    std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+const char *const kMetricNames[SPD_METRIC_COUNT] = {
+    "inner_product", "cosine", "l2_expanded", "correlation", "jaccard", "dice", "hellinger", "l1",
+    "chebyshev", "minkowski", "canberra", "hamming", "kl_divergence", "jensen_shannon", "russell_rao"};
+
+spd_status fail(spd_handle *h, spd_status st, const std::string &msg) {
+    if (h) h->err = msg;
+    return st;
+}
+
+spd_status hip_fail(spd_handle *h, hipError_t e, const char *where) {
+    return fail(h, SPD_ERR_HIP, std::string(where) + ": " + hipGetErrorString(e));
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Sequential carving of the scratch buffer.
+struct Carver {
+    size_t off = 0;
+    size_t take(size_t bytes) { size_t at = off; off = align256(off + bytes); return at; }
+};
+
+spd_status check_csr_args(spd_handle *h, const spd_csr *M, const char *name) {
+    if (!M) return fail(h, SPD_ERR_NULL, std::string(name) + " is NULL");
+    if (M->n_rows < 0 || M->n_cols < 0 || M->nnz < 0)
+        return fail(h, SPD_ERR_DIM_MISMATCH, std::string(name) + " has a negative size");
+    if (!M->indptr) return fail(h, SPD_ERR_NULL, std::string(name) + ".indptr is NULL");
+    if (M->nnz > 0 && (!M->indices || !M->values))
+        return fail(h, SPD_ERR_NULL, std::string(name) + ".indices / .values is NULL");
+    if (M->n_rows >= ((int64_t)1 << 31) - 1 || M->n_cols >= ((int64_t)1 << 31) - 1)
+        return fail(h, SPD_ERR_UNSUPPORTED, std::string(name) + ": more than 2^31-2 rows or columns");
+    if (M->nnz >= ((int64_t)1 << 40))
+        return fail(h, SPD_ERR_UNSUPPORTED, std::string(name) + ": more than 2^40 stored entries");
+    return SPD_OK;
+}
+
+spd_status check_call_args(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, int knn_k,
+                           bool is_knn, const void *o1, const void *o2) {
+    if (!h) return SPD_ERR_NULL;
+    h->err.clear();
+    spd_status st = check_csr_args(h, A, is_knn ? "Q" : "A");
+    if (st != SPD_OK) return st;
+    st = check_csr_args(h, B, is_knn ? "Index" : "B");
+    if (st != SPD_OK) return st;
+    if (A->n_cols != B->n_cols) return fail(h, SPD_ERR_DIM_MISMATCH, "the two matrices differ in n_cols");
+    if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return fail(h, SPD_ERR_BAD_METRIC, "unknown metric");
+    if (metric == SPD_MINKOWSKI && !(p > 0.0f && std::isfinite(p)))
+        return fail(h, SPD_ERR_BAD_P, "Minkowski needs a finite p > 0");
+    if (is_knn) {
+        if (knn_k < 1 || (int64_t)knn_k > B->n_rows || knn_k > SPD_KNN_MAX_K)
+            return fail(h, SPD_ERR_BAD_K, "k must lie in [1, min(Index.n_rows, SPD_KNN_MAX_K)]");
+        if (A->n_rows > 0 && (!o1 || !o2)) return fail(h, SPD_ERR_NULL, "out_idx / out_dist is NULL");
+    } else {
+        if (A->n_rows > 0 && B->n_rows > 0 && !o1) return fail(h, SPD_ERR_NULL, "out is NULL");
+    }
+    return SPD_OK;
+}
+
+spd_status ensure_pinned(spd_handle *h, size_t bytes) {
+    if (bytes <= h->pinned_bytes) return SPD_OK;
+    if (h->pinned) { hipError_t e = hipStreamSynchronize(h->stream); (void)e; (void)hipHostFree(h->pinned); h->pinned = nullptr; h->pinned_bytes = 0; }
+    size_t want = align256(bytes + bytes / 4);
+    hipError_t e = hipHostMalloc(&h->pinned, want, hipHostMallocDefault);
+    if (e != hipSuccess) return hip_fail(h, e, "hipHostMalloc");
+    h->pinned_bytes = want;
+    return SPD_OK;
+}
+
+spd_status ensure_workspace(spd_handle *h, size_t bytes) {
+    if (h->ws_external) {
+        if (bytes > h->ws_bytes)
+            return fail(h, SPD_ERR_WORKSPACE, "caller workspace too small: need " + std::to_string(bytes) + " bytes");
+        return SPD_OK;
+    }
+    if (bytes > h->own_ws_bytes) {
+        if (h->own_ws) {
+            hipError_t e = hipStreamSynchronize(h->stream);
+            if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+            (void)hipFree(h->own_ws);
+            h->own_ws = nullptr; h->own_ws_bytes = 0;
+        }
+        size_t want = align256(bytes + bytes / 8);
+        hipError_t e = hipMalloc(&h->own_ws, want);
+        if (e != hipSuccess) return fail(h, SPD_ERR_WORKSPACE, std::string("hipMalloc of scratch failed: ") + hipGetErrorString(e));
+        h->own_ws_bytes = want;
+    }
+    h->ws = h->own_ws;
+    h->ws_bytes = h->own_ws_bytes;
+    return SPD_OK;
+}
+
+// Profile mode: events around one launch.
+struct LaunchTimer {
+    spd_handle *h;
+    bool on;
+    spd_handle::Timed t;
+    LaunchTimer(spd_handle *hh, const char *name, int R, int kind, int block, uint32_t lds, int64_t a_rows, int64_t wgs)
+        : h(hh), on(hh->profile) {
+        if (!on) return;
+        std::memset(&t.rec, 0, sizeof t.rec);
+        std::snprintf(t.rec.name, sizeof t.rec.name, "%s", name);
+        t.rec.rows_per_group = R; t.rec.staging_kind = kind; t.rec.block = block; t.rec.lds_bytes = (int32_t)lds;
+        t.rec.a_rows = a_rows; t.rec.workgroups = wgs; t.rec.ms = -1.0;
+        auto get = [&](hipEvent_t &e) {
+            if (!h->event_pool.empty()) { e = h->event_pool.back(); h->event_pool.pop_back(); return true; }
+            return hipEventCreate(&e) == hipSuccess;
+        };
+        if (!get(t.start) || !get(t.stop)) { on = false; return; }
+        (void)hipEventRecord(t.start, h->stream);
+    }
+    void done() {
+        if (!on) return;
+        (void)hipEventRecord(t.stop, h->stream);
+        h->timed.push_back(t);
+    }
+};
+
+// Everything one call uploads, laid out in one pinned blob mirrored 1:1 in the scratch.
+struct Upload {
+    std::vector<std::pair<size_t, std::pair<const void *, size_t>>> parts;   // scratch offset, (src, bytes)
+    void add(size_t off, const void *src, size_t bytes) { if (bytes) parts.push_back({off, {src, bytes}}); }
+};
+
+spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, int knn_k,
+               float *out, int64_t *out_idx, float *out_dist) {
+    const int64_t m = A->n_rows, n = B->n_rows;
+    for (auto &t : h->timed) { h->event_pool.push_back(t.start); h->event_pool.push_back(t.stop); }
+    h->timed.clear();
+    if (m == 0 || n == 0) return SPD_OK;
+    hipError_t e = hipSetDevice(h->device);
+    if (e != hipSuccess) return hip_fail(h, e, "hipSetDevice");
+
+    // ---- row pointers to the host ---------------------------------------------------
+    const bool same = A->indptr == B->indptr && m == n;
+    size_t ip_bytes = (size_t)(m + 1) * 8 + (same ? 0 : (size_t)(n + 1) * 8);
+    spd_status st = ensure_pinned(h, ip_bytes);
+    if (st != SPD_OK) return st;
+    int64_t *a_ip = reinterpret_cast<int64_t *>(h->pinned);
+    int64_t *b_ip = same ? a_ip : a_ip + (m + 1);
+    e = hipMemcpyAsync(a_ip, A->indptr, (size_t)(m + 1) * 8, hipMemcpyDeviceToHost, h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "copy of A.indptr");
+    if (!same) {
+        e = hipMemcpyAsync(b_ip, B->indptr, (size_t)(n + 1) * 8, hipMemcpyDeviceToHost, h->stream);
+        if (e != hipSuccess) return hip_fail(h, e, "copy of B.indptr");
+    }
+    e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+    if (a_ip[m] != A->nnz || b_ip[n] != B->nnz) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
+
+    // ---- plan -------------------------------------------------------------------------
+    const MetricInfo mi = metric_info((int)metric);
+    APlan ap;
+    BPlan bp;
+    std::string why = plan_a(a_ip, m, A->n_cols, (int)metric, knn_k, h->opt, ap);
+    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
+    why = plan_b(b_ip, n, h->opt, bp);
+    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
+    int groups_total = 0;
+    for (const AClass &c : ap.classes) groups_total += c.n_groups;
+    plan_chunks(bp, groups_total, h->opt);
+    why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, knn_k, h->opt);
+    if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
+    for (const AClass &c : ap.classes)
+        if ((int64_t)c.n_groups * bp.n_chunks >= ((int64_t)1 << 31))
+            return fail(h, SPD_ERR_UNSUPPORTED, "launch grid beyond 2^31 workgroups");
+
+    // ---- scratch layout ---------------------------------------------------------------
+    const int planes = metric_planes((int)metric);
+    const size_t lanes = (size_t)bp.n_slabs * kWave;
+    Carver cv;
+    Upload up;
+    const size_t o_packed = cv.take((size_t)bp.nnz * 8);
+    const size_t o_norms = cv.take((size_t)n * 16);
+    const size_t o_slab_base = cv.take(bp.slab_base.size() * 8);
+    const size_t o_slab_steps = cv.take(bp.slab_steps.size() * 4);
+    const size_t o_slab_split = cv.take(bp.slab_split.size());
+    const size_t o_seg_start = cv.take(lanes * 8);
+    const size_t o_seg_len = cv.take(lanes * 4);
+    const size_t o_seg_row = cv.take(lanes * 4);
+    const size_t o_seg_glog = cv.take(lanes);
+    const size_t o_chunks = cv.take(bp.chunk_begin.size() * 4);
+    up.add(o_slab_base, bp.slab_base.data(), bp.slab_base.size() * 8);
+    up.add(o_slab_steps, bp.slab_steps.data(), bp.slab_steps.size() * 4);
+    up.add(o_slab_split, bp.slab_split.data(), bp.slab_split.size());
+    up.add(o_seg_start, bp.seg_start.data(), lanes * 8);
+    up.add(o_seg_len, bp.seg_len.data(), lanes * 4);
+    up.add(o_seg_row, bp.seg_row.data(), lanes * 4);
+    up.add(o_seg_glog, bp.seg_glog.data(), lanes);
+    up.add(o_chunks, bp.chunk_begin.data(), bp.chunk_begin.size() * 4);
+    std::vector<size_t> o_rows(ap.classes.size()), o_sumlen(ap.classes.size());
+    for (size_t ci = 0; ci < ap.classes.size(); ++ci) {
+        const AClass &c = ap.classes[ci];
+        o_rows[ci] = cv.take(c.rows.size() * sizeof(ARow));
+        o_sumlen[ci] = cv.take(c.sumlen.size() * 4);
+        up.add(o_rows[ci], c.rows.data(), c.rows.size() * sizeof(ARow));
+        up.add(o_sumlen[ci], c.sumlen.data(), c.sumlen.size() * 4);
+    }
+    const size_t o_spilled = cv.take(ap.spilled.size() * sizeof(SpilledRow));
+    up.add(o_spilled, ap.spilled.data(), ap.spilled.size() * sizeof(SpilledRow));
+    const size_t o_partial = cv.take((size_t)ap.n_partial_slots * planes * (size_t)n * 8);
+    const size_t o_partial_norms = cv.take((size_t)ap.n_partial_slots * 16);
+    std::vector<uint8_t> is_spilled;
+    size_t o_knn_part = 0, o_is_spilled = 0;
+    if (knn_k > 0) {
+        o_knn_part = cv.take((size_t)m * bp.n_chunks * knn_k * sizeof(KnnEntry));
+        if (!ap.spilled.empty()) {
+            is_spilled.assign((size_t)m, 0);
+            for (const SpilledRow &s : ap.spilled) is_spilled[(size_t)s.row] = 1;
+            o_is_spilled = cv.take((size_t)m);
+            up.add(o_is_spilled, is_spilled.data(), (size_t)m);
+        }
+    }
+    st = ensure_workspace(h, cv.off);
+    if (st != SPD_OK) return st;
+    unsigned char *ws = reinterpret_cast<unsigned char *>(h->ws);
+
+    // ---- upload the plan (through pinned memory, so the copies are asynchronous) --------
+    size_t blob = 0;
+    for (auto &pt : up.parts) blob += align256(pt.second.second);
+    st = ensure_pinned(h, blob);
+    if (st != SPD_OK) return st;
+    {
+        unsigned char *pin = reinterpret_cast<unsigned char *>(h->pinned);
+        size_t at = 0;
+        for (auto &pt : up.parts) {
+            std::memcpy(pin + at, pt.second.first, pt.second.second);
+            e = hipMemcpyAsync(ws + pt.first, pin + at, pt.second.second, hipMemcpyHostToDevice, h->stream);
+            if (e != hipSuccess) return hip_fail(h, e, "upload of the plan");
+            at += align256(pt.second.second);
+        }
+    }
+
+    // ---- launches ---------------------------------------------------------------------
+    BDevice bd;
+    bd.packed = reinterpret_cast<const uint2 *>(ws + o_packed);
+    bd.slab_base = reinterpret_cast<const int64_t *>(ws + o_slab_base);
+    bd.slab_steps = reinterpret_cast<const int32_t *>(ws + o_slab_steps);
+    bd.slab_split = ws + o_slab_split;
+    bd.seg_start = reinterpret_cast<const int64_t *>(ws + o_seg_start);
+    bd.seg_len = reinterpret_cast<const int32_t *>(ws + o_seg_len);
+    bd.seg_row = reinterpret_cast<const int32_t *>(ws + o_seg_row);
+    bd.seg_glog = ws + o_seg_glog;
+    bd.norms = reinterpret_cast<const double *>(ws + o_norms);
+    bd.chunk_begin = reinterpret_cast<const int32_t *>(ws + o_chunks);
+    bd.n_slabs = bp.n_slabs;
+    bd.n_chunks = bp.n_chunks;
+    bd.n_rows = n;
+
+    OpParams q;
+    q.p = p;
+    q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : 1.0f;
+    q.k = (double)A->n_cols;
+    q.metric = (int)metric;
+    if (metric != SPD_MINKOWSKI) q.p = 1.0f;
+
+    {
+        LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, (bp.n_slabs + 3) / 4);
+        e = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd, reinterpret_cast<uint2 *>(ws + o_packed),
+                          reinterpret_cast<double *>(ws + o_norms), (int)metric, mi.transform, mi.norm, q.p, q.k);
+        if (e != hipSuccess) return hip_fail(h, e, "pack kernel");
+        lt.done();
+    }
+
+    for (size_t ci = 0; ci < ap.classes.size(); ++ci) {
+        const AClass &c = ap.classes[ci];
+        ScanArgs sa;
+        sa.a_indices = A->indices;
+        sa.a_values = A->values;
+        sa.arows = reinterpret_cast<const ARow *>(ws + o_rows[ci]);
+        sa.sumlen = reinterpret_cast<const int32_t *>(ws + o_sumlen[ci]);
+        sa.n_groups = c.n_groups;
+        sa.b_indptr = B->indptr;
+        sa.b_indices = B->indices;
+        sa.b = bd;
+        sa.q = q;
+        sa.kind = c.kind;
+        sa.transform = mi.transform;
+        sa.norm = mi.norm;
+        sa.k = (uint32_t)A->n_cols;
+        sa.padcol = (c.kind == KIND_HASH) ? kEmptyKey : (uint32_t)A->n_cols;
+        sa.out = out;
+        sa.partial = reinterpret_cast<double *>(ws + o_partial);
+        sa.partial_norms = reinterpret_cast<double *>(ws + o_partial_norms);
+        sa.planes = planes;
+        sa.knn_k = knn_k;
+        sa.knn_part = reinterpret_cast<KnnEntry *>(ws + o_knn_part);
+        int64_t live_rows = 0;
+        for (const ARow &r : c.rows) live_rows += (r.out != -1);
+        LaunchTimer lt(h, "scan", c.R, c.kind, c.block, c.lds_bytes, live_rows, (int64_t)c.n_groups * bp.n_chunks);
+        e = launch_scan(h->stream, mi.op, c.R, c.block, c.lds_bytes, sa);
+        if (e != hipSuccess) return hip_fail(h, e, "scan kernel");
+        lt.done();
+    }
+
+    if (!ap.spilled.empty()) {
+        FinalizeArgs fa;
+        fa.spilled = reinterpret_cast<const SpilledRow *>(ws + o_spilled);
+        fa.n_spilled = (int32_t)ap.spilled.size();
+        fa.partial = reinterpret_cast<const double *>(ws + o_partial);
+        fa.partial_norms = reinterpret_cast<const double *>(ws + o_partial_norms);
+        fa.norms_b = bd.norms;
+        fa.planes = planes;
+        fa.n_b = n;
+        fa.q = q;
+        fa.out = out;
+        fa.knn_k = knn_k;
+        fa.out_idx = out_idx;
+        fa.out_dist = out_dist;
+        LaunchTimer lt(h, "finalize", 0, 0, 0, 0, (int64_t)ap.spilled.size(), 0);
+        e = launch_finalize(h->stream, fa);
+        if (e != hipSuccess) return hip_fail(h, e, "finalize kernel");
+        lt.done();
+    }
+    if (knn_k > 0) {
+        LaunchTimer lt(h, "knn_merge", 0, 0, 0, 0, m, (m + 3) / 4);
+        e = launch_knn_merge(h->stream, reinterpret_cast<const KnnEntry *>(ws + o_knn_part), m, bp.n_chunks, knn_k,
+                             ap.spilled.empty() ? nullptr : ws + o_is_spilled, metric == SPD_INNER_PRODUCT ? 1 : 0,
+                             out_idx, out_dist);
+        if (e != hipSuccess) return hip_fail(h, e, "k-NN merge kernel");
+        lt.done();
+    }
+    return SPD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+spd_status spd_create(spd_handle **handle, void *hip_stream) {
+    if (!handle) return SPD_ERR_NULL;
+    *handle = nullptr;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return SPD_ERR_HIP;
+    spd_handle *h = new (std::nothrow) spd_handle();
+    if (!h) return SPD_ERR_WORKSPACE;
+    h->device = dev;
+    h->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    int lds = 0, cus = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && lds > 0)
+        h->opt.lds_budget = std::min<int64_t>(lds, 160 * 1024);
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        h->opt.n_cus = cus;
+    e = hipMalloc(reinterpret_cast<void **>(&h->flag), 256);
+    if (e != hipSuccess) { delete h; return SPD_ERR_HIP; }
+    *handle = h;
+    return SPD_OK;
+}
+
+spd_status spd_destroy(spd_handle *h) {
+    if (!h) return SPD_ERR_NULL;
+    hipError_t e = hipStreamSynchronize(h->stream);
+    (void)e;
+    if (h->pinned) (void)hipHostFree(h->pinned);
+    if (h->own_ws) (void)hipFree(h->own_ws);
+    if (h->flag) (void)hipFree(h->flag);
+    for (auto &t : h->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+    for (hipEvent_t ev : h->event_pool) (void)hipEventDestroy(ev);
+    delete h;
+    return SPD_OK;
+}
+
+spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric,
+                               int k_neighbors, size_t *bytes) {
+    if (!h || !A || !B || !bytes) return SPD_ERR_NULL;
+    if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return SPD_ERR_BAD_METRIC;
+    if (A->n_rows < 0 || B->n_rows < 0 || A->nnz < 0 || B->nnz < 0 || A->n_cols != B->n_cols) return SPD_ERR_DIM_MISMATCH;
+    const PlanOptions &o = h->opt;
+    const size_t m = (size_t)A->n_rows, n = (size_t)B->n_rows;
+    const size_t seg_target = (size_t)std::max(1, std::max(2, o.split_len) / 2);
+    const size_t window = (size_t)std::max(64, o.window);
+    size_t slabs = n / 64 + n / window + (n + 4 * (size_t)B->nnz / seg_target) / 64 + 4;
+    size_t lanes = slabs * 64;
+    size_t chunks = 4096;
+    {
+        size_t groups_min = std::max<size_t>(1, (m + 15) / 16);
+        size_t want = ((size_t)6 * (size_t)o.n_cus + groups_min - 1) / groups_min;
+        chunks = o.chunks > 0 ? (size_t)o.chunks : std::min<size_t>(4096, (std::max<size_t>(want, 8) + 7) / 8 * 8);
+    }
+    // rows of A that do not fit alone are cut into slices of at least 1/2 of the largest
+    // slice the budget admits; 512 entries is a floor for any budget the planner accepts
+    size_t slices = 2 * (size_t)A->nnz / 512 + 2;
+    slices = std::min(slices, (size_t)A->nnz / 64 + 2);
+    size_t planes = (size_t)metric_planes((int)metric);
+    size_t total = 0;
+    auto add = [&](size_t b) { total += align256(b); };
+    add((size_t)B->nnz * 8); add(n * 16); add((slabs + 1) * 8); add(slabs * 4); add(slabs);
+    add(lanes * 8); add(lanes * 4); add(lanes * 4); add(lanes); add((chunks + 1) * 4);
+    add((m + slices + 16 * 6) * sizeof(ARow)); add((m + slices + 6) * 4); total += 12 * 256;
+    add(slices * sizeof(SpilledRow));
+    // partial results exist only for sliced rows; a row needs slicing only above ~9,000 entries
+    size_t sliced_rows_max = (size_t)A->nnz / 4096 + 1;
+    size_t partial_slots = std::min(slices, 2 * sliced_rows_max + (size_t)A->nnz / 4096);
+    add(partial_slots * planes * n * 8); add(partial_slots * 16);
+    if (k_neighbors > 0) { add(m * chunks * (size_t)k_neighbors * sizeof(KnnEntry)); add(m); }
+    *bytes = total;
+    return SPD_OK;
+}
+
+spd_status spd_set_workspace(spd_handle *h, void *device_ptr, size_t bytes) {
+    if (!h) return SPD_ERR_NULL;
+    h->err.clear();
+    if (!device_ptr || bytes == 0) {
+        h->ws_external = false;
+        h->ws = h->own_ws;
+        h->ws_bytes = h->own_ws_bytes;
+        return SPD_OK;
+    }
+    if ((reinterpret_cast<uintptr_t>(device_ptr) & 255u) != 0) return fail(h, SPD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    h->ws_external = true;
+    h->ws = device_ptr;
+    h->ws_bytes = bytes;
+    return SPD_OK;
+}
+
+spd_status spd_pairwise(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, float *out) {
+    spd_status st = check_call_args(h, A, B, metric, p, 0, false, out, nullptr);
+    if (st != SPD_OK) return st;
+    return run(h, A, B, metric, p, 0, out, nullptr, nullptr);
+}
+
+spd_status spd_knn(spd_handle *h, const spd_csr *Q, const spd_csr *Index, spd_metric metric, float p, int k,
+                   int64_t *out_idx, float *out_dist) {
+    spd_status st = check_call_args(h, Q, Index, metric, p, k, true, out_idx, out_dist);
+    if (st != SPD_OK) return st;
+    return run(h, Q, Index, metric, p, k, nullptr, out_idx, out_dist);
+}
+
+spd_status spd_csr_validate(spd_handle *h, const spd_csr *M, int require_nonnegative) {
+    if (!h) return SPD_ERR_NULL;
+    h->err.clear();
+    spd_status st = check_csr_args(h, M, "M");
+    if (st != SPD_OK) return st;
+    if (M->n_rows == 0) return M->nnz == 0 ? SPD_OK : fail(h, SPD_ERR_BAD_CSR, "no rows but nnz > 0");
+    hipError_t e = hipMemsetAsync(h->flag, 0, 4, h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "hipMemsetAsync");
+    e = launch_validate(h->stream, M->indptr, M->indices, M->values, M->n_rows, M->n_cols, M->nnz,
+                        require_nonnegative, h->flag);
+    if (e != hipSuccess) return hip_fail(h, e, "validate kernel");
+    int32_t flag = 0;
+    e = hipMemcpyAsync(&flag, h->flag, 4, hipMemcpyDeviceToHost, h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "hipMemcpyAsync");
+    e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+    if (flag) {
+        std::string what;
+        if (flag & 1) what += " row pointers;";
+        if (flag & 2) what += " column order or range;";
+        if (flag & 4) what += " values;";
+        return fail(h, SPD_ERR_BAD_CSR, "invalid CSR:" + what);
+    }
+    return SPD_OK;
+}
+
+spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
+    if (!h || !name) return SPD_ERR_NULL;
+    h->err.clear();
+    std::string s(name);
+    PlanOptions &o = h->opt;
+    if (s == "lds_budget") {
+        if (value < 8192 || value > 160 * 1024) return fail(h, SPD_ERR_UNSUPPORTED, "lds_budget must lie in [8192, 163840]");
+        o.lds_budget = value;
+    } else if (s == "force_kind") {
+        if (value < 0 || value > 3) return fail(h, SPD_ERR_UNSUPPORTED, "force_kind must be 0..3");
+        o.force_kind = (int)value;
+    } else if (s == "max_rows") {
+        if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
+            return fail(h, SPD_ERR_UNSUPPORTED, "max_rows must be 1, 2, 4, 8 or 16");
+        o.max_rows = (int)value;
+    } else if (s == "split_len") {
+        if (value < 2 || value > (1 << 20)) return fail(h, SPD_ERR_UNSUPPORTED, "split_len must lie in [2, 2^20]");
+        o.split_len = (int)value;
+    } else if (s == "window") {
+        if (value < 64 || value > (1 << 24)) return fail(h, SPD_ERR_UNSUPPORTED, "window must lie in [64, 2^24]");
+        o.window = (int)value;
+    } else if (s == "chunks") {
+        if (value < 0 || value > 4096) return fail(h, SPD_ERR_UNSUPPORTED, "chunks must lie in [0, 4096]");
+        o.chunks = (int)value;
+    } else if (s == "profile") {
+        if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "profile must be 0 or 1");
+        h->profile = value != 0;
+    } else {
+        return fail(h, SPD_ERR_UNSUPPORTED, "unknown option " + s);
+    }
+    return SPD_OK;
+}
+
+int spd_profile_read(spd_handle *h, spd_kernel_time *out, int cap) {
+    if (!h || (cap > 0 && !out)) return -1;
+    if (h->timed.empty()) return 0;
+    if (hipEventSynchronize(h->timed.back().stop) != hipSuccess) return -2;
+    int n = 0;
+    for (auto &t : h->timed) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.start, t.stop) == hipSuccess) t.rec.ms = (double)ms;
+        if (n < cap) out[n] = t.rec;
+        ++n;
+    }
+    return n;
+}
+
+const char *spd_last_error(const spd_handle *h) { return h ? h->err.c_str() : "null handle"; }
+
+const char *spd_metric_name(spd_metric metric) {
+    return ((int)metric >= 0 && (int)metric < SPD_METRIC_COUNT) ? kMetricNames[(int)metric] : "unknown";
+}
+
+const char *spd_version(void) { return "spd 0.1 (gfx950)"; }
+
+}  // extern "C"

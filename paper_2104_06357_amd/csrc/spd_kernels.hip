@@ -1,0 +1,227 @@
+// Kernels around the staged scan: repacking of B into 64-lane slabs with its row norms
+// (Section 3.4: norms by a row-wise reduction), summation of the slices of spilled rows
+// (Section 3.3.3), merging of k-NN candidate lists, and CSR validation.
+#include <hip/hip_runtime.h>
+
+#include "spd_kernels.h"
+#include "spd_scan_impl.h"
+
+namespace spd {
+
+// ------------------------------------------------------------------------------------
+// B: CSR -> slabs.  One wavefront per slab, one segment per lane; the t-th entries of
+// the lanes that still have one are written side by side, so the scan reads them back
+// with one coalesced load per step.  The lane also sums its part of the row norm.
+// ------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restrict__ b_indptr,
+                                                         const int32_t *__restrict__ b_indices,
+                                                         const float *__restrict__ b_values, BDevice b,
+                                                         uint2 *__restrict__ packed, double *__restrict__ norms,
+                                                         int metric, int transform, int norm, float p, double k) {
+    const int lane = (int)threadIdx.x & 63;
+    const int s = (int)blockIdx.x * 4 + ((int)threadIdx.x >> 6);
+    if (s >= b.n_slabs) return;
+    const size_t at = (size_t)s * kWave + lane;
+    const int64_t start = b.seg_start[at];
+    const int len = b.seg_len[at];
+    const int row = b.seg_row[at];
+    const int glog = b.seg_glog[at];
+    const int steps = b.slab_steps[s];
+    int64_t off = b.slab_base[s];
+    double s0 = 0.0, s1 = 0.0;
+    for (int t = 0; t < steps; ++t) {
+        const bool active = t < len;
+        const uint64_t m = __ballot(active);
+        if (active) {
+            float v = transform_value(transform, b_values[start + t]);
+            norm_accumulate(norm, v, p, s0, s1);
+            packed[off + lane_rank_in(m)] = make_uint2((uint32_t)b_indices[start + t], __float_as_uint(v));
+        }
+        off += __popcll(m);
+    }
+    if (b.slab_split[s]) {
+#pragma unroll
+        for (int step = 0; step < 6; ++step) {
+            double o0 = __shfl_xor(s0, 1 << step), o1 = __shfl_xor(s1, 1 << step);
+            if (step < glog) { s0 += o0; s1 += o1; }
+        }
+    }
+    if (row >= 0 && (lane & ((1 << glog) - 1)) == 0) {
+        double d0, d1;
+        norm_derive(metric, k, s0, s1, d0, d1);
+        norms[(size_t)row * 2] = d0;
+        norms[(size_t)row * 2 + 1] = d1;
+    }
+}
+
+hipError_t launch_pack_b(hipStream_t st, const int64_t *b_indptr, const int32_t *b_indices, const float *b_values,
+                         const BDevice &b, uint2 *packed_out, double *norms_out, int metric, int transform,
+                         int norm, float p, double k) {
+    if (b.n_slabs <= 0) return hipSuccess;
+    dim3 grid((unsigned)((b.n_slabs + 3) / 4));
+    hipLaunchKernelGGL(spd_pack_b_kernel, grid, dim3(256), 0, st, b_indptr, b_indices, b_values, b, packed_out,
+                       norms_out, metric, transform, norm, p, k);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// Spilled rows of A: add up the partial results of their slices, then finish.
+// Pairwise: grid (column tiles, spilled rows).  k-NN: one workgroup per spilled row keeps
+// the k best while it walks the row.
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ float finalize_one(const FinalizeArgs &a, const SpilledRow &sr, int64_t j,
+                                              double na0, double na1) {
+    double v0 = 0.0, v1 = 0.0, v2 = 0.0;
+    for (int q = 0; q < sr.n_slots; ++q) {
+        size_t slot = (size_t)(sr.first_slot + q);
+        double t = a.partial[(slot * a.planes) * (size_t)a.n_b + (size_t)j];
+        if (a.q.metric == MT_CHEBYSHEV) v0 = fmax(v0, t); else v0 += t;
+        if (a.planes >= 2) v1 += a.partial[(slot * a.planes + 1) * (size_t)a.n_b + (size_t)j];
+        if (a.planes == 3) v2 += a.partial[(slot * 3 + 2) * (size_t)a.n_b + (size_t)j];
+    }
+    return finish(a.q, v0, v1, v2, na0, na1, a.norms_b[(size_t)j * 2], a.norms_b[(size_t)j * 2 + 1]);
+}
+
+__device__ __forceinline__ void spilled_row_norms(const FinalizeArgs &a, const SpilledRow &sr, double &na0,
+                                                  double &na1) {
+    double r0 = 0.0, r1 = 0.0;
+    for (int q = 0; q < sr.n_slots; ++q) {
+        r0 += a.partial_norms[(size_t)(sr.first_slot + q) * 2];
+        r1 += a.partial_norms[(size_t)(sr.first_slot + q) * 2 + 1];
+    }
+    norm_derive(a.q.metric, a.q.k, r0, r1, na0, na1);
+}
+
+__global__ void __launch_bounds__(256) spd_finalize_pairwise_kernel(const FinalizeArgs a) {
+    const SpilledRow sr = a.spilled[blockIdx.y];
+    double na0, na1;
+    spilled_row_norms(a, sr, na0, na1);
+    int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j < a.n_b) a.out[(size_t)sr.row * (size_t)a.n_b + (size_t)j] = finalize_one(a, sr, j, na0, na1);
+}
+
+__global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArgs a) {
+    __shared__ KnnEntry s_area[4 * kKnnMaxK];
+    const SpilledRow sr = a.spilled[blockIdx.x];
+    const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
+    const int kk = a.knn_k;
+    double na0, na1;
+    spilled_row_norms(a, sr, na0, na1);
+    KnnList list;
+    list.reset();
+    for (int64_t j0 = 0; j0 < a.n_b; j0 += 256) {
+        int64_t j = j0 + threadIdx.x;
+        bool valid = j < a.n_b;
+        float d = 0.f;
+        if (valid) {
+            d = finalize_one(a, sr, j, na0, na1);
+            if (a.q.metric == MT_INNER) d = -d;
+        }
+        list.offer(d, (int)j, valid, kk);
+    }
+    if (lane < kk) s_area[wave * kk + lane] = KnnEntry{list.d, list.j};
+    __syncthreads();
+    if (wave == 0) {
+        KnnList merged;
+        merged.reset();
+        const int total = 4 * kk;
+        for (int e0 = 0; e0 < total; e0 += 64) {
+            int e = e0 + lane;
+            bool valid = e < total;
+            KnnEntry c = KnnEntry{0.f, 0};
+            if (valid) c = s_area[e];
+            valid = valid && c.j != 0x7fffffff;
+            merged.offer(c.d, c.j, valid, kk);
+        }
+        if (lane < kk) {
+            a.out_idx[(size_t)sr.row * kk + lane] = (int64_t)merged.j;
+            a.out_dist[(size_t)sr.row * kk + lane] = a.q.metric == MT_INNER ? -merged.d : merged.d;
+        }
+    }
+}
+
+hipError_t launch_finalize(hipStream_t st, const FinalizeArgs &args) {
+    if (args.n_spilled <= 0) return hipSuccess;
+    if (args.knn_k > 0) {
+        hipLaunchKernelGGL(spd_finalize_knn_kernel, dim3((unsigned)args.n_spilled), dim3(256), 0, st, args);
+    } else {
+        dim3 grid((unsigned)((args.n_b + 255) / 256), (unsigned)args.n_spilled);
+        hipLaunchKernelGGL(spd_finalize_pairwise_kernel, grid, dim3(256), 0, st, args);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// k-NN: one wavefront per query row merges the lists its chunks produced.
+// ------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) spd_knn_merge_kernel(const KnnEntry *__restrict__ part, int64_t n_rows,
+                                                            int n_chunks, int k,
+                                                            const uint8_t *__restrict__ row_is_spilled, int negate,
+                                                            int64_t *__restrict__ out_idx,
+                                                            float *__restrict__ out_dist) {
+    const int lane = (int)threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + ((int)threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    if (row_is_spilled && row_is_spilled[row]) return;     // written by the finalize kernel
+    KnnList merged;
+    merged.reset();
+    const int total = n_chunks * k;
+    const KnnEntry *src = part + (size_t)row * (size_t)total;
+    for (int e0 = 0; e0 < total; e0 += 64) {
+        int e = e0 + lane;
+        bool valid = e < total;
+        KnnEntry c = KnnEntry{0.f, 0};
+        if (valid) c = src[e];
+        valid = valid && c.j != 0x7fffffff;
+        merged.offer(c.d, c.j, valid, k);
+    }
+    if (lane < k) {
+        out_idx[(size_t)row * k + lane] = (int64_t)merged.j;
+        out_dist[(size_t)row * k + lane] = negate ? -merged.d : merged.d;
+    }
+}
+
+hipError_t launch_knn_merge(hipStream_t st, const KnnEntry *part, int64_t n_rows, int n_chunks, int k,
+                            const uint8_t *row_is_spilled, int negate, int64_t *out_idx, float *out_dist) {
+    if (n_rows <= 0) return hipSuccess;
+    dim3 grid((unsigned)((n_rows + 3) / 4));
+    hipLaunchKernelGGL(spd_knn_merge_kernel, grid, dim3(256), 0, st, part, n_rows, n_chunks, k, row_is_spilled,
+                       negate, out_idx, out_dist);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// CSR validation: bit 0 row pointers, bit 1 column order / range, bit 2 values.
+// ------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) spd_validate_kernel(const int64_t *__restrict__ indptr,
+                                                           const int32_t *__restrict__ indices,
+                                                           const float *__restrict__ values, int64_t n_rows,
+                                                           int64_t n_cols, int64_t nnz, int require_nonnegative,
+                                                           int32_t *flag) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_rows) return;
+    int bad = 0;
+    const int64_t a = indptr[i], b = indptr[i + 1];
+    if ((i == 0 && a != 0) || (i == n_rows - 1 && b != nnz) || a > b || a < 0 || b > nnz) {
+        bad |= 1;
+    } else {
+        for (int64_t q = a; q < b; ++q) {
+            int32_t c = indices[q];
+            if (c < 0 || c >= n_cols || (q > a && indices[q - 1] >= c)) bad |= 2;
+            float v = values[q];
+            if (!(v - v == 0.0f) || (require_nonnegative && v < 0.0f)) bad |= 4;
+        }
+    }
+    if (bad) atomicOr(flag, bad);
+}
+
+hipError_t launch_validate(hipStream_t st, const int64_t *indptr, const int32_t *indices, const float *values,
+                           int64_t n_rows, int64_t n_cols, int64_t nnz, int require_nonnegative, int32_t *flag) {
+    if (n_rows <= 0) return hipSuccess;
+    dim3 grid((unsigned)((n_rows + 255) / 256));
+    hipLaunchKernelGGL(spd_validate_kernel, grid, dim3(256), 0, st, indptr, indices, values, n_rows, n_cols, nnz,
+                       require_nonnegative, flag);
+    return hipGetLastError();
+}
+
+}  // namespace spd

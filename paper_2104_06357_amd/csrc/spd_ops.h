@@ -1,0 +1,280 @@
+// Per-visit products, row norms and expansion functions of the distances of Table 1,
+// in the single-pass form the kernels use.
+//
+// Every distance is evaluated as
+//     d(x, y) = finish( sum over the stored entries b_c of y of  g(x_c, b_c),  N(x), N(y) )
+// where x_c is 0 when column c is not stored in x, and g(0, b) = 0 for every product, so
+// that only columns present in both rows contribute:
+//   * dot-product family (Section 3.4): g = x*y on transformed values, N = row norms,
+//     finish = the expansion function.
+//   * union family (Section 2.2, Eq. 2): with f the non-annihilating product,
+//     sum over the union of f = F(x) + F(y) + sum over the intersection of
+//     [ f(x_c,y_c) - f(x_c,0) - f(0,y_c) ], F(x) = sum_c f(x_c, 0).  This covers the three
+//     parts of Eq. 2 in one sweep over y instead of the two passes of Section 3.3.
+//   * Chebyshev (sum() = max) keeps max |x_c - y_c| over the entries of y; the part of x
+//     that y does not store is completed by the kernel from x's largest entries.
+// Sums are carried in fp64 so the cancellations of the expanded forms (Section 2.1) stay
+// far below the fp32 result's resolution.
+#pragma once
+#include <math.h>
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define SPD_HD __host__ __device__ __forceinline__
+#else
+#define SPD_HD inline
+#endif
+
+namespace spd {
+
+enum OpId { OP_DOT = 0, OP_L1, OP_MINK, OP_CANB, OP_HAMM, OP_KL, OP_JS, OP_CHEB, OP_COUNT };
+enum Transform { TR_ID = 0, TR_SQRT, TR_NONZERO };
+enum NormKind { NORM_NONE = 0, NORM_SUMSQ, NORM_SUM_SUMSQ, NORM_SUM, NORM_SUM_ABS, NORM_SUM_POW, NORM_NNZ };
+
+// metric ids follow spd_metric in include/spd.h
+enum MetricId {
+    MT_INNER = 0, MT_COSINE, MT_L2, MT_CORRELATION, MT_JACCARD, MT_DICE, MT_HELLINGER, MT_L1,
+    MT_CHEBYSHEV, MT_MINKOWSKI, MT_CANBERRA, MT_HAMMING, MT_KL, MT_JS, MT_RUSSELL_RAO, MT_COUNT
+};
+
+struct MetricInfo { int op, transform, norm; };
+
+SPD_HD MetricInfo metric_info(int metric) {
+    switch (metric) {
+    case MT_INNER:       return {OP_DOT, TR_ID, NORM_NONE};
+    case MT_COSINE:      return {OP_DOT, TR_ID, NORM_SUMSQ};
+    case MT_L2:          return {OP_DOT, TR_ID, NORM_SUMSQ};
+    case MT_CORRELATION: return {OP_DOT, TR_ID, NORM_SUM_SUMSQ};
+    case MT_JACCARD:     return {OP_DOT, TR_NONZERO, NORM_SUM};
+    case MT_DICE:        return {OP_DOT, TR_NONZERO, NORM_SUM};
+    case MT_HELLINGER:   return {OP_DOT, TR_SQRT, NORM_SUMSQ};
+    case MT_L1:          return {OP_L1, TR_ID, NORM_SUM_ABS};
+    case MT_CHEBYSHEV:   return {OP_CHEB, TR_ID, NORM_NONE};
+    case MT_MINKOWSKI:   return {OP_MINK, TR_ID, NORM_SUM_POW};
+    case MT_CANBERRA:    return {OP_CANB, TR_ID, NORM_NNZ};
+    case MT_HAMMING:     return {OP_HAMM, TR_ID, NORM_NNZ};
+    case MT_KL:          return {OP_KL, TR_ID, NORM_NONE};
+    case MT_JS:          return {OP_JS, TR_ID, NORM_SUM};
+    case MT_RUSSELL_RAO: return {OP_DOT, TR_NONZERO, NORM_NONE};
+    default:             return {-1, 0, 0};
+    }
+}
+
+struct OpParams {
+    float p;        // Minkowski degree
+    float inv_p;
+    double k;       // number of columns
+    int metric;
+};
+
+// |v|^p in fp32.  The same function feeds the row norm F and the per-visit product, so
+// the terms that have to cancel are bit-identical (pow_abs(0) == 0).
+SPD_HD float pow_abs(float v, float p) {
+    float a = fabsf(v);
+    return a == 0.0f ? 0.0f : exp2f(p * log2f(a));
+}
+
+SPD_HD float transform_value(int tr, float v) {
+    if (tr == TR_SQRT) return sqrtf(v);
+    if (tr == TR_NONZERO) return v != 0.0f ? 1.0f : 0.0f;
+    return v;
+}
+
+// Contribution of one (transformed) stored value to the two raw row sums.
+SPD_HD void norm_accumulate(int norm, float t, float p, double &s0, double &s1) {
+    double d = (double)t;
+    switch (norm) {
+    case NORM_SUMSQ:     s0 += d * d; break;
+    case NORM_SUM_SUMSQ: s0 += d; s1 += d * d; break;
+    case NORM_SUM:       s0 += d; break;
+    case NORM_SUM_ABS:   s0 += fabs(d); break;
+    case NORM_SUM_POW:   s0 += (double)pow_abs(t, p); s1 += (t != 0.0f) ? 1.0 : 0.0; break;
+    case NORM_NNZ:       s0 += (t != 0.0f) ? 1.0 : 0.0; break;
+    default: break;
+    }
+}
+
+// Raw row sums -> the two numbers the expansion function reads.
+SPD_HD void norm_derive(int metric, double k, double s0, double s1, double &d0, double &d1) {
+    d0 = s0; d1 = s1;
+    if (metric == MT_COSINE) {
+        d1 = s0 > 0.0 ? 1.0 / sqrt(s0) : 0.0;
+    } else if (metric == MT_CORRELATION) {
+        double var = k * s1 - s0 * s0;                 // k^2 times the variance
+        d1 = var > 0.0 ? 1.0 / sqrt(var) : 0.0;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// per-visit products.  Acc is what one (A row, B row) pair accumulates; Bv what is
+// derived once from a stored value of B and reused for every staged A row.
+// v0/v1/v2 expose the sums as doubles (for the slices of spilled rows and for finish()).
+// ------------------------------------------------------------------------------------
+template <int OP> struct Op;
+
+template <> struct Op<OP_DOT> {
+    struct Acc { double v; };
+    struct Bv { double db; };
+    SPD_HD static void init(Acc &x) { x.v = 0.0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {(double)b}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) { x.v = fma((double)a, b.db, x.v); }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
+    SPD_HD static double v0(const Acc &x) { return x.v; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+template <> struct Op<OP_L1> {
+    struct Acc { double v; };
+    struct Bv { double db, adb; };
+    SPD_HD static void init(Acc &x) { x.v = 0.0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {(double)b, fabs((double)b)}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
+        double da = (double)a;
+        x.v += (fabs(da - b.db) - fabs(da)) - b.adb;   // 0 when a == 0
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
+    SPD_HD static double v0(const Acc &x) { return x.v; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+// Minkowski keeps the differences on shared columns (d) apart from what they replace in the
+// two row norms (s), and counts the shared columns: the p-th root would otherwise blow the
+// rounding residue of F(x) + F(y) - s up when the two rows have the same support.
+template <> struct Op<OP_MINK> {
+    struct Acc { double d, s; int hits; };
+    struct Bv { float b; double pwb; };
+    SPD_HD static void init(Acc &x) { x.d = 0.0; x.s = 0.0; x.hits = 0; }
+    SPD_HD static Bv prep(float b, const OpParams &q) { return {b, (double)pow_abs(b, q.p)}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
+        bool hit = (a != 0.0f) && (b.b != 0.0f);
+        x.d += hit ? (double)pow_abs(a - b.b, q.p) : 0.0;
+        x.s += hit ? (double)pow_abs(a, q.p) + b.pwb : 0.0;
+        x.hits += hit ? 1 : 0;
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.d += y.d; x.s += y.s; x.hits += y.hits; }
+    SPD_HD static double v0(const Acc &x) { return x.d; }
+    SPD_HD static double v1(const Acc &x) { return x.s; }
+    SPD_HD static double v2(const Acc &x) { return (double)x.hits; }
+};
+
+template <> struct Op<OP_CANB> {
+    struct Acc { double v; };
+    struct Bv { float b; };
+    SPD_HD static void init(Acc &x) { x.v = 0.0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
+        bool hit = (a != 0.0f) && (b.b != 0.0f);
+        float ratio = fabsf(a - b.b) / (fabsf(a) + fabsf(b.b));   // NaN only when !hit
+        x.v += hit ? (double)ratio - 2.0 : 0.0;                   // each one-sided column counts 1
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
+    SPD_HD static double v0(const Acc &x) { return x.v; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+template <> struct Op<OP_HAMM> {
+    struct Acc { int c; };
+    struct Bv { float b; };
+    SPD_HD static void init(Acc &x) { x.c = 0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
+        bool hit = (a != 0.0f) && (b.b != 0.0f);
+        x.c += hit ? ((a != b.b) ? -1 : -2) : 0;
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.c += y.c; }
+    SPD_HD static double v0(const Acc &x) { return (double)x.c; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+template <> struct Op<OP_KL> {
+    struct Acc { double v; };
+    struct Bv { float b; };
+    SPD_HD static void init(Acc &x) { x.v = 0.0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
+        bool hit = (a > 0.0f) && (b.b > 0.0f);
+        float t = a * logf(hit ? a / b.b : 1.0f);
+        x.v += hit ? (double)t : 0.0;
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
+    SPD_HD static double v0(const Acc &x) { return x.v; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+// Jensen-Shannon: f(a,b) = a log(2a/(a+b)) + b log(2b/(a+b)) on shared columns (exactly 0
+// for a == b); a one-sided column adds its value times log 2, which the finish step takes
+// from the row sums minus `s`, the sum of the values seen on shared columns.
+template <> struct Op<OP_JS> {
+    struct Acc { double f, s; };
+    struct Bv { float b; double db; };
+    SPD_HD static void init(Acc &x) { x.f = 0.0; x.s = 0.0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b, (double)b}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
+        bool hit = (a > 0.0f) && (b.b > 0.0f);
+        float r = hit ? 2.0f / (a + b.b) : 1.0f;
+        float aa = hit ? a : 0.5f, bb = hit ? b.b : 0.5f;
+        float t = aa * logf(aa * r) + bb * logf(bb * r);
+        x.f += hit ? (double)t : 0.0;
+        x.s += hit ? (double)a + b.db : 0.0;
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.f += y.f; x.s += y.s; }
+    SPD_HD static double v0(const Acc &x) { return x.f; }
+    SPD_HD static double v1(const Acc &x) { return x.s; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+template <> struct Op<OP_CHEB> {
+    struct Acc { float m; };
+    struct Bv { float b; };
+    SPD_HD static void init(Acc &x) { x.m = 0.0f; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) { x.m = fmaxf(x.m, fabsf(a - b.b)); }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.m = fmaxf(x.m, y.m); }
+    SPD_HD static double v0(const Acc &x) { return (double)x.m; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+// Expansion function (Table 1, "Expansion" column, and the closing steps of the union
+// family).  v, s, w: the accumulated sums; a0,a1 / b0,b1: derived norms of the two rows.
+SPD_HD float finish(const OpParams &q, double v, double s, double w, double a0, double a1, double b0, double b1) {
+    const double LN2 = 0.693147180559945309417232121458;
+    double r;
+    switch (q.metric) {
+    case MT_INNER: r = v; break;
+    case MT_COSINE:
+        r = (a0 == 0.0 && b0 == 0.0) ? 0.0 : ((a0 == 0.0 || b0 == 0.0) ? 1.0 : 1.0 - v * a1 * b1);
+        break;
+    case MT_L2: { double t = a0 - 2.0 * v + b0; return sqrtf((float)(t > 0.0 ? t : 0.0)); }
+    case MT_CORRELATION:
+        r = (a1 == 0.0 || b1 == 0.0) ? 1.0 : 1.0 - (q.k * v - a0 * b0) * a1 * b1;
+        break;
+    case MT_JACCARD: { double u = a0 + b0 - v; r = (u == 0.0) ? 0.0 : 1.0 - v / u; break; }
+    case MT_DICE: { double t = a0 + b0; r = (t == 0.0) ? 0.0 : 1.0 - 2.0 * v / t; break; }
+    case MT_HELLINGER: { double t = 0.5 * (a0 + b0) - v; return sqrtf((float)(t > 0.0 ? t : 0.0)); }
+    case MT_L1:
+    case MT_CANBERRA: { double t = a0 + b0 + v; r = t > 0.0 ? t : 0.0; break; }
+    case MT_MINKOWSKI: {
+        // v: differences on shared columns, s: their share of the norms, w: how many;
+        // a1 / b1 count the entries of the rows: equal supports leave no one-sided part
+        double one_sided = (w == a1 && w == b1) ? 0.0 : (a0 + b0) - s;
+        double t = v + (one_sided > 0.0 ? one_sided : 0.0);
+        float tf = (float)t;
+        return tf == 0.0f ? 0.0f : exp2f(q.inv_p * log2f(tf));
+    }
+    case MT_HAMMING: r = (a0 + b0 + v) / q.k; break;
+    case MT_KL: r = v; break;
+    case MT_JS: { double t = 0.5 * (LN2 * ((a0 + b0) - s) + v); return sqrtf((float)(t > 0.0 ? t : 0.0)); }
+    case MT_CHEBYSHEV: r = v; break;
+    case MT_RUSSELL_RAO: r = (q.k - v) / q.k; break;
+    default: r = 0.0; break;
+    }
+    return (float)r;
+}
+
+}  // namespace spd

@@ -1,0 +1,403 @@
+// Host planner: degree binning of the rows of A and B (see spd_plan.h).
+#include "spd_plan.h"
+
+#include <algorithm>
+#include <numeric>
+
+namespace spd {
+
+namespace {
+
+std::string fmt(const char *what, long long a, long long b = 0) {
+    return std::string(what) + " (" + std::to_string(a) + ", " + std::to_string(b) + ")";
+}
+
+int block_for(uint32_t stage_bytes, int64_t lds_total) {
+    // One to four workgroups per compute unit, sixteen wavefronts in all.
+    int64_t per_cu = lds_total / (int64_t)(stage_bytes + kStaticLds);
+    if (per_cu >= 4) return 256;
+    if (per_cu >= 2) return 512;
+    return 1024;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------
+// B: slabs of 64 lanes
+// ------------------------------------------------------------------------------------
+std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt, BPlan &out) {
+    out = BPlan();
+    if (n_rows < 0) return "negative row count";
+    if (n_rows >= (int64_t)1 << 31) return "more than 2^31-1 rows";
+    const int64_t T = std::max<int64_t>(2, opt.split_len);
+    const int64_t seg_target = std::max<int64_t>(1, T / 2);
+    const int64_t Wn = std::max<int64_t>(kWave, (opt.window / kWave) * kWave);
+    out.n_rows = n_rows;
+    out.nnz = n_rows ? indptr[n_rows] : 0;
+    if (n_rows && indptr[0] != 0) return "indptr[0] != 0";
+    for (int64_t j = 0; j < n_rows; ++j)
+        if (indptr[j + 1] < indptr[j]) return fmt("row pointers decrease at row", j);
+
+    struct Long { int32_t row; int64_t len; int glog; };
+    std::vector<Long> longs;
+    std::vector<int32_t> order;            // short rows, window by window, longest first
+    std::vector<int32_t> window_end;       // prefix positions in `order`
+    order.reserve((size_t)n_rows);
+    std::vector<int32_t> bucket_count((size_t)T + 1);
+    for (int64_t w0 = 0; w0 < n_rows; w0 += Wn) {
+        int64_t w1 = std::min(n_rows, w0 + Wn);
+        std::fill(bucket_count.begin(), bucket_count.end(), 0);
+        for (int64_t j = w0; j < w1; ++j) {
+            int64_t len = indptr[j + 1] - indptr[j];
+            if (len >= T) {
+                int64_t want = (len + seg_target - 1) / seg_target;
+                int glog = 0;
+                while (((int64_t)1 << glog) < want && glog < 6) ++glog;
+                longs.push_back({(int32_t)j, len, glog});
+            } else {
+                ++bucket_count[(size_t)len];
+            }
+        }
+        // counting sort, longest first, stable in j
+        std::vector<int32_t> pos((size_t)T + 1);
+        int32_t acc = 0;
+        for (int64_t l = T - 1; l >= 0; --l) { pos[(size_t)l] = acc; acc += bucket_count[(size_t)l]; }
+        size_t base = order.size();
+        order.resize(base + (size_t)acc);
+        for (int64_t j = w0; j < w1; ++j) {
+            int64_t len = indptr[j + 1] - indptr[j];
+            if (len < T) order[base + (size_t)pos[(size_t)len]++] = (int32_t)j;
+        }
+        window_end.push_back((int32_t)order.size());
+    }
+    std::stable_sort(longs.begin(), longs.end(), [](const Long &a, const Long &b) { return a.glog > b.glog; });
+
+    // count slabs
+    int64_t long_lanes = 0;
+    for (const Long &l : longs) long_lanes += (int64_t)1 << l.glog;
+    int64_t n_long_slabs = (long_lanes + kWave - 1) / kWave;
+    int64_t n_short_slabs = 0;
+    {
+        int32_t prev = 0;
+        for (int32_t e : window_end) { n_short_slabs += (e - prev + kWave - 1) / kWave; prev = e; }
+    }
+    int64_t n_slabs = n_long_slabs + n_short_slabs;
+    if (n_slabs >= ((int64_t)1 << 31) / kWave) return "too many slabs";
+    out.n_slabs = (int32_t)n_slabs;
+    size_t lanes = (size_t)n_slabs * kWave;
+    out.seg_start.assign(lanes, 0);
+    out.seg_len.assign(lanes, 0);
+    out.seg_row.assign(lanes, -1);
+    out.seg_glog.assign(lanes, 0);
+    out.slab_split.assign((size_t)n_slabs, 0);
+
+    size_t lane = 0;
+    for (const Long &l : longs) {
+        int G = 1 << l.glog;
+        int64_t s0 = indptr[l.row];
+        for (int q = 0; q < G; ++q, ++lane) {
+            int64_t lo = l.len * q / G, hi = l.len * (q + 1) / G;
+            out.seg_start[lane] = s0 + lo;
+            out.seg_len[lane] = (int32_t)(hi - lo);
+            out.seg_row[lane] = l.row;
+            out.seg_glog[lane] = (uint8_t)l.glog;
+        }
+        out.slab_split[(lane - 1) / kWave] = 1;
+    }
+    lane = (size_t)n_long_slabs * kWave;
+    {
+        int32_t prev = 0;
+        for (int32_t e : window_end) {
+            for (int32_t t = prev; t < e; ++t, ++lane) {
+                int32_t j = order[(size_t)t];
+                out.seg_start[lane] = indptr[j];
+                out.seg_len[lane] = (int32_t)(indptr[j + 1] - indptr[j]);
+                out.seg_row[lane] = j;
+            }
+            lane = (lane + kWave - 1) / kWave * kWave;
+            prev = e;
+        }
+    }
+    out.slab_base.assign((size_t)n_slabs + 1, 0);
+    out.slab_steps.assign((size_t)n_slabs, 0);
+    for (int64_t s = 0; s < n_slabs; ++s) {
+        int64_t sum = 0;
+        int32_t mx = 0;
+        for (int l = 0; l < kWave; ++l) {
+            int32_t len = out.seg_len[(size_t)s * kWave + l];
+            sum += len;
+            mx = std::max(mx, len);
+        }
+        out.slab_base[(size_t)s + 1] = out.slab_base[(size_t)s] + sum;
+        out.slab_steps[(size_t)s] = mx;
+    }
+    if (out.slab_base[(size_t)n_slabs] != out.nnz) return "internal: packed size != nnz";
+    out.n_chunks = 1;
+    out.chunk_begin = {0, out.n_slabs};
+    return std::string();
+}
+
+void plan_chunks(BPlan &b, int n_groups_total, const PlanOptions &opt) {
+    int64_t total = 0;
+    for (int32_t s : b.slab_steps) total += std::max(1, s);
+    int nc = opt.chunks;
+    if (nc <= 0) {
+        int64_t want = ((int64_t)6 * opt.n_cus + std::max(1, n_groups_total) - 1) / std::max(1, n_groups_total);
+        int64_t cap = std::max<int64_t>(8, total / 256);          // keep chunks worth staging for
+        nc = (int)std::min<int64_t>(std::max<int64_t>(want, 8), cap);
+        nc = (nc + 7) / 8 * 8;
+        nc = std::min(nc, 4096);
+    }
+    b.n_chunks = nc;
+    b.chunk_begin.assign((size_t)nc + 1, b.n_slabs);
+    b.chunk_begin[0] = 0;
+    int64_t run = 0;
+    int c = 1;
+    for (int32_t s = 0; s < b.n_slabs && c < nc; ++s) {
+        run += std::max(1, b.slab_steps[(size_t)s]);
+        while (c < nc && run * nc >= total * c) b.chunk_begin[(size_t)c++] = s + 1;
+    }
+    for (; c < nc; ++c) b.chunk_begin[(size_t)c] = b.n_slabs;
+    b.chunk_begin[(size_t)nc] = b.n_slabs;
+}
+
+namespace {
+
+bool staging_fits(int kind, int R, uint64_t sumlen, uint32_t k, bool cheb, int64_t budget) {
+    if (kind != KIND_STRIP && sumlen > 65534u) return false;      // 16-bit slot ids
+    uint64_t nslots = (kind == KIND_STRIP) ? (uint64_t)k + 1u : sumlen + 1u;
+    if (nslots * (uint64_t)R * 5u > (uint64_t)budget) return false;   // also keeps the 32-bit layout math safe
+    LdsLayout L = lds_layout(kind, R, (uint32_t)sumlen, k, cheb);
+    return (int64_t)L.total <= budget;
+}
+
+}  // namespace
+
+std::string plan_staging(int64_t n_cols, int metric, const PlanOptions &opt, int &kind, int &max_r, uint64_t &dmax) {
+    const bool cheb = metric == MT_CHEBYSHEV;
+    const uint32_t k = (uint32_t)n_cols;
+    max_r = std::min(opt.max_rows, kMaxR);
+    if (metric == MT_JS || metric == MT_MINKOWSKI) max_r = std::min(max_r, 8);   // two fp64 sums per pair
+    if (max_r < 1) max_r = 1;
+    while (max_r & (max_r - 1)) max_r &= max_r - 1;         // power of two
+    if (opt.lds_budget <= (int64_t)kStaticLds + 256) return "lds_budget too small";
+    const int64_t budget = opt.lds_budget - kStaticLds;
+    kind = opt.force_kind;
+    if (kind == KIND_AUTO) {
+        if (staging_fits(KIND_STRIP, std::min(4, max_r), 0, k, cheb, budget)) kind = KIND_STRIP;
+        else if ((int64_t)(k + 1) * 2 <= budget / 3) kind = KIND_SLOT;
+        else kind = KIND_HASH;
+    }
+    if (kind < KIND_STRIP || kind > KIND_HASH) return "bad staging kind";
+    dmax = 0;
+    if (kind == KIND_STRIP) {
+        if (!staging_fits(KIND_STRIP, 1, 0, k, cheb, budget)) return "dense strip does not fit the LDS budget";
+        while (max_r > 1 && !staging_fits(KIND_STRIP, max_r, 0, k, cheb, budget)) max_r /= 2;
+        return std::string();
+    }
+    if (!staging_fits(kind, 1, 1, k, cheb, budget)) return "LDS budget too small to stage a single entry";
+    uint64_t lo = 1, hi = 65534;
+    while (lo < hi) {
+        uint64_t mid = (lo + hi + 1) / 2;
+        if (staging_fits(kind, 1, mid, k, cheb, budget)) lo = mid; else hi = mid - 1;
+    }
+    dmax = lo;
+    return std::string();
+}
+
+// ------------------------------------------------------------------------------------
+// A: groups of R staged rows
+// ------------------------------------------------------------------------------------
+std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int knn_k,
+                   const PlanOptions &opt, APlan &out) {
+    out = APlan();
+    out.n_rows = n_rows;
+    if (n_rows < 0 || n_cols < 0) return "negative size";
+    if (n_rows >= (int64_t)1 << 31 || n_cols >= ((int64_t)1 << 31) - 1) return "more than 2^31-2 rows or columns";
+    if (n_rows && indptr[0] != 0) return "indptr[0] != 0";
+    for (int64_t i = 0; i < n_rows; ++i)
+        if (indptr[i + 1] < indptr[i]) return fmt("row pointers decrease at row", i);
+    const bool cheb = metric == MT_CHEBYSHEV;
+    const uint32_t k = (uint32_t)n_cols;
+    int kind = 0, max_r = 1;
+    uint64_t dmax = 0;
+    {
+        std::string why = plan_staging(n_cols, metric, opt, kind, max_r, dmax);
+        if (!why.empty()) return why;
+    }
+    const int64_t budget = opt.lds_budget - kStaticLds;
+    auto fits = [&](int kd, int R, uint64_t sumlen) { return staging_fits(kd, R, sumlen, k, cheb, budget); };
+
+    auto finish_class = [&](AClass &c) {
+        uint32_t need = 0;
+        for (int g = 0; g < c.n_groups; ++g)
+            need = std::max(need, lds_layout(c.kind, c.R, (uint32_t)c.sumlen[(size_t)g], k, cheb).total);
+        c.block = std::min(block_for(need, opt.lds_budget), scan_max_block(metric_info(metric).op, c.R, knn_k > 0));
+        if (knn_k > 0) {
+            while (c.block > kWave && (int64_t)knn_merge_bytes(c.block, c.R, knn_k) > budget) c.block /= 2;
+            need = std::max(need, knn_merge_bytes(c.block, c.R, knn_k));
+        }
+        c.lds_bytes = (need + 15u) & ~15u;
+    };
+
+    if (kind == KIND_STRIP) {
+        int R = max_r;
+        AClass c;
+        c.R = R; c.kind = KIND_STRIP;
+        c.n_groups = (int)((n_rows + R - 1) / R);
+        c.rows.assign((size_t)c.n_groups * R, ARow{0, 0, -1});
+        c.sumlen.assign((size_t)c.n_groups, 0);
+        for (int64_t i = 0; i < n_rows; ++i) {
+            int64_t len = indptr[i + 1] - indptr[i];
+            if (len > (int64_t)k) return fmt("row longer than the column count", i);
+            c.rows[(size_t)i] = ARow{indptr[i], (int32_t)len, (int32_t)i};
+            c.sumlen[(size_t)(i / R)] += (int32_t)len;
+        }
+        if (c.n_groups) { finish_class(c); out.classes.push_back(std::move(c)); }
+        return std::string();
+    }
+
+    std::vector<ARow> items;
+    items.reserve((size_t)n_rows);
+    for (int64_t i = 0; i < n_rows; ++i) {
+        int64_t len = indptr[i + 1] - indptr[i];
+        if (len > (int64_t)k) return fmt("row longer than the column count", i);
+        if ((uint64_t)len <= dmax) {
+            items.push_back(ARow{indptr[i], (int32_t)len, (int32_t)i});
+        } else {
+            int64_t parts = (len + (int64_t)dmax - 1) / (int64_t)dmax;
+            if (out.n_partial_slots + parts > (1 << 24)) return "too many row slices";
+            out.spilled.push_back(SpilledRow{(int32_t)i, out.n_partial_slots, (int32_t)parts});
+            for (int64_t q = 0; q < parts; ++q) {
+                int64_t lo = len * q / parts, hi = len * (q + 1) / parts;
+                items.push_back(ARow{indptr[i] + lo, (int32_t)(hi - lo), -2 - (out.n_partial_slots++)});
+            }
+        }
+    }
+    std::stable_sort(items.begin(), items.end(), [](const ARow &a, const ARow &b) { return a.len > b.len; });
+
+    AClass by_r[5];                           // R = 16, 8, 4, 2, 1
+    for (int q = 0; q < 5; ++q) { by_r[q].R = 16 >> q; by_r[q].kind = kind; }
+    size_t t = 0;
+    while (t < items.size()) {
+        size_t remaining = items.size() - t;
+        int R = max_r;
+        while (R > 1 && (size_t)(R / 2) >= remaining) R /= 2;
+        for (;; R /= 2) {
+            size_t n = std::min<size_t>((size_t)R, remaining);
+            uint64_t sum = 0;
+            for (size_t q = 0; q < n; ++q) sum += (uint64_t)items[t + q].len;
+            if (fits(kind, R, sum) || R == 1) {
+                if (!fits(kind, R, sum)) return "internal: slice does not fit";
+                int ci = 0;
+                while ((16 >> ci) != R) ++ci;
+                AClass &c = by_r[ci];
+                for (int q = 0; q < R; ++q)
+                    c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1});
+                c.sumlen.push_back((int32_t)sum);
+                ++c.n_groups;
+                t += n;
+                break;
+            }
+        }
+    }
+    for (int q = 0; q < 5; ++q)
+        if (by_r[q].n_groups) { finish_class(by_r[q]); out.classes.push_back(std::move(by_r[q])); }
+    return std::string();
+}
+
+// ------------------------------------------------------------------------------------
+// consistency check of everything the kernels index with
+// ------------------------------------------------------------------------------------
+std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, const int64_t *b_indptr,
+                       int64_t n_cols, int metric, int knn_k, const PlanOptions &opt) {
+    const bool cheb = metric == MT_CHEBYSHEV;
+    const int64_t a_nnz = a.n_rows ? a_indptr[a.n_rows] : 0;
+    std::vector<int64_t> covered((size_t)a.n_rows, 0);
+    std::vector<int64_t> slot_lo((size_t)a.n_partial_slots, -1), slot_hi((size_t)a.n_partial_slots, -1);
+    for (const AClass &c : a.classes) {
+        if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16) return "class R";
+        if ((metric == MT_JS || metric == MT_MINKOWSKI) && c.R > 8) return "two-sum product with R > 8";
+        if (c.kind < KIND_STRIP || c.kind > KIND_HASH) return "class kind";
+        if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";
+        if ((int64_t)c.lds_bytes + kStaticLds > opt.lds_budget) return "class LDS over budget";
+        if ((size_t)c.n_groups * c.R != c.rows.size() || (size_t)c.n_groups != c.sumlen.size()) return "class sizes";
+        if (knn_k > 0 && knn_merge_bytes(c.block, c.R, knn_k) > c.lds_bytes) return "k-NN merge area";
+        if (c.block > scan_max_block(metric_info(metric).op, c.R, knn_k > 0)) return "class block over the kernel's bound";
+        for (int g = 0; g < c.n_groups; ++g) {
+            int64_t sum = 0;
+            for (int r = 0; r < c.R; ++r) {
+                const ARow &row = c.rows[(size_t)g * c.R + r];
+                if (row.len < 0 || row.start < 0 || row.start + row.len > a_nnz) return "A slice out of range";
+                if (row.out == -1) { if (row.len != 0) return "unused lane with entries"; continue; }
+                sum += row.len;
+                if (row.out >= 0) {
+                    if (row.out >= a.n_rows) return "A output row out of range";
+                    if (row.start != a_indptr[row.out] || row.start + row.len != a_indptr[row.out + 1]) return "A row range";
+                    ++covered[(size_t)row.out];
+                } else {
+                    int slot = -2 - row.out;
+                    if (slot < 0 || slot >= a.n_partial_slots) return "partial slot out of range";
+                    if (slot_lo[(size_t)slot] != -1) return "partial slot used twice";
+                    slot_lo[(size_t)slot] = row.start;
+                    slot_hi[(size_t)slot] = row.start + row.len;
+                }
+            }
+            if (sum != c.sumlen[(size_t)g]) return "group sumlen";
+            LdsLayout L = lds_layout(c.kind, c.R, (uint32_t)sum, (uint32_t)n_cols, cheb);
+            if (L.total > c.lds_bytes) return "group LDS over the launch size";
+            if (c.kind != KIND_STRIP && L.nslots > 65535u) return "slot ids over 16 bits";
+        }
+    }
+    for (const SpilledRow &s : a.spilled) {
+        if (s.row < 0 || s.row >= a.n_rows || s.n_slots < 2 || s.first_slot < 0 ||
+            s.first_slot + s.n_slots > a.n_partial_slots) return "spilled row record";
+        int64_t at = a_indptr[s.row];
+        for (int q = 0; q < s.n_slots; ++q) {
+            if (slot_lo[(size_t)(s.first_slot + q)] != at) return "spilled slices not contiguous";
+            at = slot_hi[(size_t)(s.first_slot + q)];
+        }
+        if (at != a_indptr[s.row + 1]) return "spilled slices do not cover the row";
+        ++covered[(size_t)s.row];
+    }
+    for (int64_t i = 0; i < a.n_rows; ++i)
+        if (covered[(size_t)i] != 1) return fmt("A row not covered exactly once", i, covered[(size_t)i]);
+
+    if ((size_t)b.n_slabs + 1 != b.slab_base.size() || (size_t)b.n_slabs != b.slab_steps.size()) return "B slab arrays";
+    size_t lanes = (size_t)b.n_slabs * kWave;
+    if (b.seg_len.size() != lanes || b.seg_row.size() != lanes || b.seg_start.size() != lanes || b.seg_glog.size() != lanes)
+        return "B lane arrays";
+    std::vector<int64_t> next((size_t)b.n_rows);
+    std::vector<uint8_t> seen((size_t)b.n_rows, 0);
+    for (int64_t j = 0; j < b.n_rows; ++j) next[(size_t)j] = b_indptr[j];
+    for (int32_t s = 0; s < b.n_slabs; ++s) {
+        int64_t sum = 0;
+        int32_t mx = 0;
+        for (int l = 0; l < kWave; ++l) {
+            size_t at = (size_t)s * kWave + l;
+            int32_t j = b.seg_row[at], len = b.seg_len[at];
+            int G = 1 << b.seg_glog[at];
+            if (len < 0) return "B negative segment";
+            sum += len; mx = std::max(mx, len);
+            if (j < 0) { if (len != 0 || j != -1) return "B unused lane"; continue; }
+            if (j >= b.n_rows || G > kWave) return "B segment row";
+            if (G > 1 && !b.slab_split[(size_t)s]) return "split row in an unsplit slab";
+            int first = l & ~(G - 1);
+            if (l == first) { if (seen[(size_t)j]) return "B row in two groups"; seen[(size_t)j] = 1; }
+            else if (b.seg_row[(size_t)s * kWave + first] != j) return "B group not aligned";
+            if (b.seg_start[at] != next[(size_t)j]) return "B segments not contiguous";
+            next[(size_t)j] += len;
+            if ((l & (G - 1)) == G - 1 && next[(size_t)j] != b_indptr[j + 1]) return "B segments do not cover the row";
+        }
+        if (b.slab_base[(size_t)s + 1] - b.slab_base[(size_t)s] != sum || b.slab_steps[(size_t)s] != mx) return "B slab sums";
+    }
+    for (int64_t j = 0; j < b.n_rows; ++j)
+        if (!seen[(size_t)j] || next[(size_t)j] != b_indptr[j + 1]) return fmt("B row not covered", j);
+    if (b.n_chunks < 1 || (size_t)b.n_chunks + 1 != b.chunk_begin.size()) return "B chunk arrays";
+    if (b.chunk_begin[0] != 0 || b.chunk_begin[(size_t)b.n_chunks] != b.n_slabs) return "B chunk ends";
+    for (int c = 0; c < b.n_chunks; ++c)
+        if (b.chunk_begin[(size_t)c] > b.chunk_begin[(size_t)c + 1]) return "B chunks not monotone";
+    return std::string();
+}
+
+}  // namespace spd

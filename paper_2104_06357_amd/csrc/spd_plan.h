@@ -1,0 +1,154 @@
+// Host-side plan: how the rows of A are grouped and staged in LDS, and how the rows of B
+// are cut into 64-lane slabs that the wavefronts scan.
+//
+// The paper stages one row of A per block in shared memory - dense when the dimensionality
+// allows it, a hash table when only the degree does, several partitions when neither does
+// (Sections 3.3.2, 3.3.3) - and balances the load over B through a COO row index
+// (Section 3.3).  On an MI355X the 160 KB of LDS per compute unit are spent differently:
+//   * R rows of A (up to 16) are staged together, so that every entry of B that a lane
+//     loads is applied to R rows;
+//   * the staged rows share ONE column map (direct strip, 16-bit column-slot strip, or a
+//     hash table of the union of their columns) in front of a table of R values per
+//     column, so a column of B is looked up once for the R rows;
+//   * rows that do not fit alone are cut into contiguous slices whose partial results are
+//     summed afterwards (the partitions of Section 3.3.3, by column range);
+//   * B is repacked once per call into "slabs" of 64 rows of similar degree, one row per
+//     lane, stored so that the t-th entries of the 64 rows are contiguous.  Each lane
+//     keeps its pairs' sums in registers: no segmented reduction, no atomics.  Rows
+//     longer than `split_len` are cut into 2..64 equal segments that sit in adjacent
+//     lanes and are summed across lanes once, at the end of the slab.
+#pragma once
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "spd_ops.h"
+
+namespace spd {
+
+enum StageKind { KIND_AUTO = 0, KIND_STRIP = 1, KIND_SLOT = 2, KIND_HASH = 3 };
+
+constexpr int kWave = 64;
+constexpr int kMaxR = 16;
+constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
+constexpr int kKnnMaxK = 64;                // fused k-NN: one list entry per lane
+constexpr int kTopRanks = 32;               // Chebyshev: largest entries tracked per staged row
+constexpr uint32_t kStaticLds = 4096;       // upper bound of the kernels' static __shared__ use
+
+struct PlanOptions {
+    int64_t lds_budget = 160 * 1024;        // bytes of LDS per workgroup (static + dynamic)
+    int force_kind = KIND_AUTO;
+    int max_rows = kMaxR;
+    int split_len = 512;
+    int window = 2048;
+    int chunks = 0;
+    int n_cus = 256;
+};
+
+// Sums a pair carries through the slices of a spilled row.
+SPD_HD constexpr int metric_planes(int metric) { return metric == MT_MINKOWSKI ? 3 : (metric == MT_JS ? 2 : 1); }
+
+// Largest workgroup a scan kernel instance may be launched with: the instances that carry
+// the most per-lane state get 256 registers per lane instead of 128.
+SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
+    (void)knn;
+    return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_MINK) && R == 8)) ? 512 : 1024;
+}
+
+// Dynamic-LDS layout of one staged group.  The same function sizes the launch on the host
+// and carves the buffer in the kernel.
+struct LdsLayout {
+    uint32_t nslots;     // rows of the value table (R floats each)
+    uint32_t cap;        // hash capacity (power of two), 0 otherwise
+    uint32_t off_vals, off_map, off_rank, total;
+};
+
+SPD_HD uint32_t pow2_at_least(uint32_t v) {
+    uint32_t c = 16;
+    while (c < v) c <<= 1;
+    return c;
+}
+
+SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool cheb) {
+    LdsLayout L;
+    L.cap = 0;
+    L.nslots = (kind == KIND_STRIP) ? k + 1u : sumlen + 1u;
+    uint32_t off = 0;
+    L.off_vals = off;
+    off += ((L.nslots * (uint32_t)R * 4u) + 15u) & ~15u;
+    L.off_map = off;
+    if (kind == KIND_SLOT) {
+        off += ((k + 1u) * 2u + 15u) & ~15u;
+    } else if (kind == KIND_HASH) {
+        L.cap = pow2_at_least(2u * sumlen);
+        off += L.cap * 8u;
+    }
+    L.off_rank = off;
+    if (cheb) off += ((L.nslots * (uint32_t)R) + 15u) & ~15u;
+    L.total = off;
+    return L;
+}
+
+// One row (or slice of a row) of A staged by a workgroup.
+struct ARow {
+    int64_t start;   // first element in A's CSR arrays
+    int32_t len;     // number of stored entries of the slice
+    int32_t out;     // >= 0: output row i;  -1: unused;  <= -2: partial-result slot (-2 - out)
+};
+
+// One kernel launch: groups of R rows that share the staging kind.
+struct AClass {
+    int R = 0;
+    int kind = 0;
+    int block = 0;              // threads per workgroup
+    uint32_t lds_bytes = 0;     // dynamic LDS of the launch (max over its groups)
+    int n_groups = 0;
+    std::vector<ARow> rows;         // n_groups * R
+    std::vector<int32_t> sumlen;    // n_groups
+};
+
+struct SpilledRow { int32_t row, first_slot, n_slots; };
+
+struct APlan {
+    int64_t n_rows = 0;
+    std::vector<AClass> classes;
+    std::vector<SpilledRow> spilled;
+    int n_partial_slots = 0;
+};
+
+struct BPlan {
+    int64_t n_rows = 0, nnz = 0;
+    int32_t n_slabs = 0;
+    std::vector<int64_t> slab_base;    // n_slabs + 1, offsets into the packed entries
+    std::vector<int32_t> slab_steps;   // n_slabs, longest segment of the slab
+    std::vector<uint8_t> slab_split;   // n_slabs, 1 if the slab holds split rows
+    std::vector<int64_t> seg_start;    // n_slabs*64, first CSR element of the lane's segment
+    std::vector<int32_t> seg_len;      // n_slabs*64
+    std::vector<int32_t> seg_row;      // n_slabs*64, row j of B, -1 for an unused lane
+    std::vector<uint8_t> seg_glog;     // n_slabs*64, log2(lanes the row is split over)
+    int n_chunks = 0;
+    std::vector<int32_t> chunk_begin;  // n_chunks + 1 slab indices
+};
+
+// Staging kind for a column count, the largest number of rows staged together, and the
+// longest slice of a row that fits alone (0 = no limit).  Empty string on success.
+std::string plan_staging(int64_t n_cols, int metric, const PlanOptions &opt, int &kind, int &max_r, uint64_t &dmax);
+
+// Both return an empty string on success, else the reason.
+std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt, BPlan &out);
+std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int knn_k,
+                   const PlanOptions &opt, APlan &out);
+void plan_chunks(BPlan &b, int n_groups_total, const PlanOptions &opt);
+
+// Checks every index a kernel will form from the plan (bounds of segments, slabs, groups,
+// LDS sizes).  Empty string if consistent.
+std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, const int64_t *b_indptr,
+                       int64_t n_cols, int metric, int knn_k, const PlanOptions &opt);
+
+// LDS needed to merge the per-wave k-NN lists of a workgroup (overlays the staging area).
+inline uint32_t knn_merge_bytes(int block, int R, int k) {
+    return (uint32_t)(block / kWave) * (uint32_t)R * (uint32_t)k * 8u;
+}
+
+}  // namespace spd

@@ -1,0 +1,27 @@
+// Routes a scan launch to the translation unit that holds the product's kernels.
+#include "spd_kernels.h"
+
+namespace spd {
+hipError_t launch_scan_dot(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_l1(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_mink(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_canb(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_hamm(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_kl(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_js(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_cheb(hipStream_t, int, int, uint32_t, const ScanArgs &);
+
+hipError_t launch_scan(hipStream_t st, int op, int R, int block, uint32_t lds_bytes, const ScanArgs &args) {
+    switch (op) {
+    case OP_DOT: return launch_scan_dot(st, R, block, lds_bytes, args);
+    case OP_L1: return launch_scan_l1(st, R, block, lds_bytes, args);
+    case OP_MINK: return launch_scan_mink(st, R, block, lds_bytes, args);
+    case OP_CANB: return launch_scan_canb(st, R, block, lds_bytes, args);
+    case OP_HAMM: return launch_scan_hamm(st, R, block, lds_bytes, args);
+    case OP_KL: return launch_scan_kl(st, R, block, lds_bytes, args);
+    case OP_JS: return launch_scan_js(st, R, block, lds_bytes, args);
+    case OP_CHEB: return launch_scan_cheb(st, R, block, lds_bytes, args);
+    default: return hipErrorInvalidValue;
+    }
+}
+}  // namespace spd

@@ -1,0 +1,460 @@
+// The staged-scan kernel: one workgroup stages R rows of A in LDS and sweeps a chunk of
+// B's slabs over them (the hot loop of the paper's Algorithm 3, re-cut for 64-wide
+// wavefronts: one row of B per lane instead of one non-zero per thread, so the segmented
+// scan and the atomic writes of that algorithm disappear).
+//
+// Included once per product (OP) by the spd_scan_op*.hip translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "spd_kernels.h"
+
+namespace spd {
+
+// ------------------------------------------------------------------------------------
+// wavefront helpers (gfx950: 64 lanes)
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t lane_rank_in(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+__device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ bool lex_less(float d1, int j1, float d2, int j2) {
+    return d1 < d2 || (d1 == d2 && j1 < j2);
+}
+
+// Sorted list of the k best (distance, index) pairs of one query row, entry t in lane t.
+struct KnnList {
+    float d;
+    int j;
+    __device__ __forceinline__ void reset() { d = __builtin_huge_valf(); j = 0x7fffffff; }
+    // Every lane may offer one candidate; the list stays sorted by (d, j).
+    __device__ __forceinline__ void offer(float dv, int jv, bool valid, int k) {
+        const int lane = (int)__lane_id();
+        float td = __shfl(d, k - 1);
+        int tj = __shfl(j, k - 1);
+        uint64_t m = __ballot(valid && lex_less(dv, jv, td, tj));
+        while (m) {
+            int src = wave_uniform((int)__builtin_ctzll(m));
+            m &= m - 1;
+            float x = __shfl(dv, src);
+            int xj = __shfl(jv, src);
+            int pos = (int)__popcll(__ballot(lex_less(d, j, x, xj)));   // sorted: a prefix
+            float sd = __shfl_up(d, 1);
+            int sj = __shfl_up(j, 1);
+            if (lane > pos) { d = sd; j = sj; }
+            else if (lane == pos) { d = x; j = xj; }
+        }
+    }
+};
+
+template <typename T> __device__ __forceinline__ T shfl_xor_any(T v, int mask);
+template <> __device__ __forceinline__ double shfl_xor_any<double>(double v, int mask) { return __shfl_xor(v, mask); }
+template <> __device__ __forceinline__ float shfl_xor_any<float>(float v, int mask) { return __shfl_xor(v, mask); }
+template <> __device__ __forceinline__ int shfl_xor_any<int>(int v, int mask) { return __shfl_xor(v, mask); }
+
+template <int OP> __device__ __forceinline__ typename Op<OP>::Acc acc_shfl_xor(const typename Op<OP>::Acc &a, int m);
+#define SPD_ACC_SHFL1(OPID, FIELD)                                                              \
+    template <> __device__ __forceinline__ Op<OPID>::Acc acc_shfl_xor<OPID>(const Op<OPID>::Acc &a, int m) { \
+        Op<OPID>::Acc r; r.FIELD = shfl_xor_any(a.FIELD, m); return r; }
+SPD_ACC_SHFL1(OP_DOT, v)
+SPD_ACC_SHFL1(OP_L1, v)
+SPD_ACC_SHFL1(OP_CANB, v)
+SPD_ACC_SHFL1(OP_HAMM, c)
+SPD_ACC_SHFL1(OP_KL, v)
+SPD_ACC_SHFL1(OP_CHEB, m)
+template <> __device__ __forceinline__ Op<OP_MINK>::Acc acc_shfl_xor<OP_MINK>(const Op<OP_MINK>::Acc &a, int m) {
+    Op<OP_MINK>::Acc r; r.d = __shfl_xor(a.d, m); r.s = __shfl_xor(a.s, m); r.hits = __shfl_xor(a.hits, m); return r;
+}
+template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const Op<OP_JS>::Acc &a, int m) {
+    Op<OP_JS>::Acc r; r.f = __shfl_xor(a.f, m); r.s = __shfl_xor(a.s, m); return r;
+}
+
+// ------------------------------------------------------------------------------------
+// column -> slot of the staged value table
+// ------------------------------------------------------------------------------------
+struct ColumnMap {
+    int kind;
+    const uint16_t *slot16;   // KIND_SLOT: k+1 entries
+    const uint2 *table;       // KIND_HASH: {column, slot}, empty = {kEmptyKey, 0}
+    uint32_t mask, shift;
+    __device__ __forceinline__ uint32_t lookup(uint32_t c) const {
+        if (kind == KIND_STRIP) return c;
+        if (kind == KIND_SLOT) return slot16[c];
+        uint32_t h = (c * 0x9E3779B1u) >> shift;
+        for (;;) {
+            uint2 e = table[h];
+            if (e.x == c) return e.y;          // the idle column is the empty key: slot 0
+            if (e.x == kEmptyKey) return 0u;
+            h = (h + 1u) & mask;
+        }
+    }
+};
+
+template <int R> struct RowVals { float v[R]; };
+
+template <int R> __device__ __forceinline__ RowVals<R> load_vals(const float *vals, uint32_t slot) {
+    RowVals<R> out;
+    const float *p = vals + (size_t)slot * R;
+    if constexpr (R == 1) {
+        out.v[0] = p[0];
+    } else if constexpr (R == 2) {
+        float2 t = *reinterpret_cast<const float2 *>(p);
+        out.v[0] = t.x; out.v[1] = t.y;
+    } else {
+#pragma unroll
+        for (int q = 0; q < R / 4; ++q) {
+            float4 t = *reinterpret_cast<const float4 *>(p + 4 * q);
+            out.v[4 * q] = t.x; out.v[4 * q + 1] = t.y; out.v[4 * q + 2] = t.z; out.v[4 * q + 3] = t.w;
+        }
+    }
+    return out;
+}
+
+// ------------------------------------------------------------------------------------
+// the kernel
+// ------------------------------------------------------------------------------------
+template <int OP, int R, bool KNN>
+__global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(const ScanArgs args) {
+    using O = Op<OP>;
+    using Acc = typename O::Acc;
+    constexpr bool kCheb = (OP == OP_CHEB);
+    extern __shared__ __align__(16) unsigned char dyn[];
+    __shared__ ARow s_rows[R];
+    __shared__ double s_raw[R][2];
+    __shared__ double s_na[R][2];
+    __shared__ double s_wpart[2][16][2];
+    __shared__ int s_ctr;
+    __shared__ float s_top[kCheb ? R * kTopRanks : 1];
+    __shared__ int s_topn[R];
+
+    const int tid = (int)threadIdx.x, nthr = (int)blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nw = nthr >> 6;
+
+    // workgroups that run at the same time on one XCD (ids equal mod 8) share a chunk of B
+    int g, chunk;
+    {
+        int w = (int)blockIdx.x;
+        if ((args.b.n_chunks & 7) == 0) {
+            int t = w >> 3;
+            chunk = (w & 7) + 8 * (t / args.n_groups);
+            g = t % args.n_groups;
+        } else {
+            chunk = w / args.n_groups;
+            g = w % args.n_groups;
+        }
+    }
+    const int slab_begin = args.b.chunk_begin[chunk], slab_end = args.b.chunk_begin[chunk + 1];
+    if (slab_begin >= slab_end) return;
+
+    if (tid < R) s_rows[tid] = args.arows[(size_t)g * R + tid];
+    const uint32_t sumlen = (uint32_t)args.sumlen[g];
+    const LdsLayout L = lds_layout(args.kind, R, sumlen, args.k, kCheb);
+    float *vals = reinterpret_cast<float *>(dyn + L.off_vals);
+    uint16_t *slot16 = reinterpret_cast<uint16_t *>(dyn + L.off_map);
+    uint2 *table = reinterpret_cast<uint2 *>(dyn + L.off_map);
+    unsigned char *rank8 = dyn + L.off_rank;
+    ColumnMap cmap;
+    cmap.kind = args.kind;
+    cmap.slot16 = slot16;
+    cmap.table = table;
+    cmap.mask = L.cap ? L.cap - 1u : 0u;
+    cmap.shift = L.cap ? 32u - (uint32_t)__builtin_ctz(L.cap) : 0u;
+
+    // ---- stage: clear, then insert the R rows one after the other -------------------
+    {
+        uint32_t nv4 = (L.nslots * R + 3u) / 4u;
+        float4 *v4 = reinterpret_cast<float4 *>(vals);
+        for (uint32_t i = tid; i < nv4; i += nthr) v4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (args.kind == KIND_SLOT) {
+            uint32_t nw32 = (args.k + 2u) / 2u;
+            uint32_t *m32 = reinterpret_cast<uint32_t *>(slot16);
+            for (uint32_t i = tid; i < nw32; i += nthr) m32[i] = 0u;
+        } else if (args.kind == KIND_HASH) {
+            for (uint32_t i = tid; i < L.cap; i += nthr) table[i] = make_uint2(kEmptyKey, 0u);
+        }
+        if constexpr (kCheb) {
+            uint32_t nr4 = (L.nslots * R + 3u) / 4u;
+            uint32_t *r32 = reinterpret_cast<uint32_t *>(rank8);
+            for (uint32_t i = tid; i < nr4; i += nthr) r32[i] = 0xFFFFFFFFu;
+        }
+    }
+    __syncthreads();
+    {
+        uint32_t prefix = 0;
+#pragma unroll 1
+        for (int r = 0; r < R; ++r) {
+            const int64_t start = s_rows[r].start;
+            const int len = s_rows[r].len;
+            double s0 = 0.0, s1 = 0.0;
+            for (int qi = tid; qi < len; qi += nthr) {
+                uint32_t c = (uint32_t)args.a_indices[start + qi];
+                float t = transform_value(args.transform, args.a_values[start + qi]);
+                norm_accumulate(args.norm, t, args.q.p, s0, s1);
+                if (t != 0.0f) {                          // a stored zero is absent
+                    if (args.kind == KIND_STRIP) {
+                        vals[(size_t)c * R + r] = t;
+                    } else if (args.kind == KIND_SLOT) {
+                        if (slot16[c] == 0) slot16[c] = (uint16_t)(prefix + (uint32_t)qi + 1u);
+                    } else {
+                        uint32_t h = (c * 0x9E3779B1u) >> cmap.shift;
+                        for (;;) {
+                            uint32_t old = atomicCAS(&table[h].x, kEmptyKey, c);
+                            if (old == kEmptyKey) { table[h].y = prefix + (uint32_t)qi + 1u; break; }
+                            if (old == c) break;           // staged by an earlier row
+                            h = (h + 1u) & cmap.mask;
+                        }
+                    }
+                }
+            }
+            for (int m = 32; m >= 1; m >>= 1) { s0 += __shfl_xor(s0, m); s1 += __shfl_xor(s1, m); }
+            if (lane == 0) { s_wpart[r & 1][wave][0] = s0; s_wpart[r & 1][wave][1] = s1; }
+            __syncthreads();
+            if (tid == 0) {
+                double t0 = 0.0, t1 = 0.0;
+                for (int w = 0; w < nw; ++w) { t0 += s_wpart[r & 1][w][0]; t1 += s_wpart[r & 1][w][1]; }
+                s_raw[r][0] = t0; s_raw[r][1] = t1;
+            }
+            prefix += (uint32_t)len;
+        }
+    }
+    __syncthreads();
+    if (args.kind != KIND_STRIP) {
+#pragma unroll 1
+        for (int r = 0; r < R; ++r) {
+            const int64_t start = s_rows[r].start;
+            const int len = s_rows[r].len;
+            for (int qi = tid; qi < len; qi += nthr) {
+                float t = transform_value(args.transform, args.a_values[start + qi]);
+                if (t != 0.0f) {
+                    uint32_t slot = cmap.lookup((uint32_t)args.a_indices[start + qi]);
+                    vals[(size_t)slot * R + r] = t;
+                }
+            }
+        }
+    }
+    if (tid < R) {
+        double d0, d1;
+        norm_derive(args.q.metric, args.q.k, s_raw[tid][0], s_raw[tid][1], d0, d1);
+        s_na[tid][0] = d0; s_na[tid][1] = d1;
+        int out = s_rows[tid].out;
+        if (out <= -2 && chunk == 0) {
+            args.partial_norms[(size_t)(-2 - out) * 2] = s_raw[tid][0];
+            args.partial_norms[(size_t)(-2 - out) * 2 + 1] = s_raw[tid][1];
+        }
+    }
+    if (tid == 0) s_ctr = slab_begin;
+    __syncthreads();
+
+    if constexpr (kCheb) {
+        // The kTopRanks largest |values| of each staged row, in order, and their ranks
+        // beside the value table: what a row of B leaves unvisited is completed from them.
+        for (int r = wave; r < R; r += nw) {
+            const int64_t start = s_rows[r].start;
+            const int len = s_rows[r].len;
+            float prev_v = __builtin_huge_valf();
+            uint32_t prev_c = 0u;
+            bool first = true;
+            int found = 0;
+            for (int round = 0; round < kTopRanks; ++round) {
+                float best_v = -1.0f;
+                uint32_t best_c = 0xFFFFFFFFu;
+                for (int qi = lane; qi < len; qi += 64) {
+                    float v = fabsf(args.a_values[start + qi]);
+                    uint32_t c = (uint32_t)args.a_indices[start + qi];
+                    bool after_prev = first || v < prev_v || (v == prev_v && c > prev_c);
+                    bool better = v > best_v || (v == best_v && c < best_c);
+                    if (v > 0.0f && after_prev && better) { best_v = v; best_c = c; }
+                }
+                for (int m = 32; m >= 1; m >>= 1) {
+                    float ov = __shfl_xor(best_v, m);
+                    uint32_t oc = (uint32_t)__shfl_xor((int)best_c, m);
+                    if (ov > best_v || (ov == best_v && oc < best_c)) { best_v = ov; best_c = oc; }
+                }
+                if (best_v <= 0.0f) break;
+                if (lane == 0) {
+                    s_top[r * kTopRanks + round] = best_v;
+                    uint32_t slot = cmap.lookup(best_c);
+                    rank8[(size_t)slot * R + r] = (unsigned char)round;
+                }
+                prev_v = best_v; prev_c = best_c; first = false;
+                found = round + 1;
+            }
+            if (lane == 0) s_topn[r] = found;
+        }
+        __syncthreads();
+    }
+
+    // ---- scan: every wavefront takes slabs of the chunk until none is left -----------
+    KnnList lists[KNN ? R : 1];
+    if constexpr (KNN) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) lists[r].reset();
+    }
+    const int64_t n_b = args.b.n_rows;
+
+    for (;;) {
+        int s = 0;
+        if (lane == 0) s = atomicAdd(&s_ctr, 1);
+        s = wave_uniform(s);
+        if (s >= slab_end) break;
+        const size_t at = (size_t)s * kWave + lane;
+        const int row = args.b.seg_row[at];
+        const int len = args.b.seg_len[at];
+        const int steps = wave_uniform(args.b.slab_steps[s]);
+        const bool split = wave_uniform((int)args.b.slab_split[s]) != 0;
+        int64_t off = args.b.slab_base[s];
+        Acc acc[R];
+        uint32_t hit[kCheb ? R : 1];
+#pragma unroll
+        for (int r = 0; r < R; ++r) { O::init(acc[r]); if constexpr (kCheb) hit[r] = 0u; }
+
+        for (int t = 0; t < steps; ++t) {
+            const bool active = t < len;
+            const uint64_t m = __ballot(active);
+            uint2 e = make_uint2(args.padcol, 0u);
+            if (active) e = args.b.packed[off + lane_rank_in(m)];
+            off += __popcll(m);
+            const uint32_t slot = cmap.lookup(e.x);
+            const typename O::Bv bv = O::prep(__uint_as_float(e.y), args.q);
+            const RowVals<R> a = load_vals<R>(vals, slot);
+#pragma unroll
+            for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
+            if constexpr (kCheb) {
+                const unsigned char *rk = rank8 + (size_t)slot * R;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    uint32_t q = rk[r];
+                    hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
+                }
+            }
+        }
+
+        const int glog = args.b.seg_glog[at];
+        if (split) {
+            // rows cut over 2^glog adjacent lanes: sum (max) the lanes of each group
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int step = 0; step < 6; ++step) {
+                    Acc other = acc_shfl_xor<OP>(acc[r], 1 << step);
+                    uint32_t oh = 0u;
+                    if constexpr (kCheb) oh = (uint32_t)__shfl_xor((int)hit[r], 1 << step);
+                    if (step < glog) {
+                        O::combine(acc[r], other);
+                        if constexpr (kCheb) hit[r] |= oh;
+                    }
+                }
+            }
+        }
+        const bool leader = row >= 0 && (lane & ((1 << glog) - 1)) == 0;
+        double nb0 = 0.0, nb1 = 0.0;
+        if (leader) { nb0 = args.b.norms[(size_t)row * 2]; nb1 = args.b.norms[(size_t)row * 2 + 1]; }
+
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int out = s_rows[r].out;           // uniform
+            if (out == -1) continue;
+            double v0 = O::v0(acc[r]), v1 = O::v1(acc[r]);
+            const double v2 = O::v2(acc[r]);
+            if constexpr (kCheb) {
+                if (leader) {
+                    const int topn = s_topn[r];
+                    uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
+                    uint32_t unhit = ~hit[r] & tracked;
+                    float extra = 0.0f;
+                    if (unhit) {
+                        extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
+                    } else if (topn == kTopRanks) {
+                        // every tracked entry was visited: walk the two sorted rows
+                        const int64_t a0 = s_rows[r].start, a1 = a0 + s_rows[r].len;
+                        int64_t bj = args.b_indptr[row];
+                        const int64_t be = args.b_indptr[row + 1];
+                        for (int64_t ai = a0; ai < a1; ++ai) {
+                            int32_t c = args.a_indices[ai];
+                            while (bj < be && args.b_indices[bj] < c) ++bj;
+                            if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
+                        }
+                    }
+                    v0 = fmax(v0, (double)extra);
+                }
+            }
+            if (out >= 0) {
+                float d = finish(args.q, v0, v1, v2, s_na[r][0], s_na[r][1], nb0, nb1);
+                if constexpr (!KNN) {
+                    if (leader) args.out[(size_t)out * (size_t)n_b + (size_t)row] = d;
+                } else {
+                    if (args.q.metric == MT_INNER) d = -d;
+                    lists[r].offer(d, row, leader, args.knn_k);
+                }
+            } else if (leader) {
+                const size_t slot = (size_t)(-2 - out);
+                args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0;
+                if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1;
+                if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2;
+            }
+        }
+    }
+
+    // ---- k-NN: merge the wavefronts' lists, one staged row per wavefront -------------
+    if constexpr (KNN) {
+        const int kk = args.knn_k;
+        __syncthreads();                              // the staging area is dead from here on
+        KnnEntry *area = reinterpret_cast<KnnEntry *>(dyn);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (lane < kk) area[((size_t)wave * R + r) * kk + lane] = KnnEntry{lists[r].d, lists[r].j};
+        __syncthreads();
+        for (int r = wave; r < R; r += nw) {
+            const int out = s_rows[r].out;
+            if (out < 0) continue;
+            KnnList merged;
+            merged.reset();
+            const int total = nw * kk;
+            for (int e0 = 0; e0 < total; e0 += 64) {
+                int e = e0 + lane;
+                bool valid = e < total;
+                KnnEntry c = KnnEntry{0.f, 0};
+                if (valid) c = area[((size_t)(e / kk) * R + r) * kk + (e % kk)];
+                valid = valid && c.j != 0x7fffffff;
+                merged.offer(c.d, c.j, valid, kk);
+            }
+            if (lane < kk)
+                args.knn_part[((size_t)out * args.b.n_chunks + chunk) * kk + lane] = KnnEntry{merged.d, merged.j};
+        }
+    }
+}
+
+template <int OP, int R, bool KNN>
+static hipError_t launch_scan_rk(hipStream_t st, int block, uint32_t lds_bytes, const ScanArgs &args) {
+    if (block > scan_max_block(OP, R, KNN) || block < kWave || (block & (kWave - 1))) return hipErrorInvalidValue;
+    auto kern = spd_scan_kernel<OP, R, KNN>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((size_t)args.n_groups * (size_t)args.b.n_chunks));
+    hipLaunchKernelGGL(kern, grid, dim3((unsigned)block), lds_bytes, st, args);
+    return hipGetLastError();
+}
+
+template <int OP, int R>
+static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, const ScanArgs &args) {
+    if (args.knn_k > 0) return launch_scan_rk<OP, R, true>(st, block, lds_bytes, args);
+    return launch_scan_rk<OP, R, false>(st, block, lds_bytes, args);
+}
+
+template <int OP>
+static hipError_t launch_scan_op(hipStream_t st, int R, int block, uint32_t lds_bytes, const ScanArgs &args) {
+    switch (R) {
+    case 1: return launch_scan_r<OP, 1>(st, block, lds_bytes, args);
+    case 2: return launch_scan_r<OP, 2>(st, block, lds_bytes, args);
+    case 4: return launch_scan_r<OP, 4>(st, block, lds_bytes, args);
+    case 8: return launch_scan_r<OP, 8>(st, block, lds_bytes, args);
+    case 16:
+        if constexpr (OP == OP_JS || OP == OP_MINK) return hipErrorInvalidValue;
+        else return launch_scan_r<OP, 16>(st, block, lds_bytes, args);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace spd

@@ -1,0 +1,315 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C-ABI
+(needs an MI355X; run with -m gpu)."""
+import numpy as np
+import pytest
+
+import oracle
+from gen import synth
+from util import ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, assert_distances_close, assert_knn_matches
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def spd():
+    import paper_2104_06357_amd as lib
+    return lib
+
+
+@pytest.fixture()
+def handle(spd):
+    h = spd.Handle()
+    yield h
+    h.close()
+
+
+@pytest.fixture(scope="module")
+def config0(spd):
+    A, B = synth.workload(0)
+    return A, B, spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+
+
+def _run_pairwise(handle, dA, dB, metric, p=2.0):
+    import torch
+    out = handle.pairwise(dA, dB, metric, p)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _p_of(metric):
+    return 3.0 if metric == "minkowski" else 2.0
+
+
+# ------------------------------------------------------------------ config 0: every pair
+@pytest.mark.parametrize("metric", ALL_METRICS)
+def test_config0_every_pair(handle, config0, metric):
+    A, B, dA, dB = config0
+    print("config0 pairwise", metric, flush=True)
+    got = _run_pairwise(handle, dA, dB, metric, _p_of(metric))
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric), mode="full")
+    assert_distances_close(got, want, metric)
+
+
+@pytest.mark.parametrize("kind", [1, 2, 3])
+@pytest.mark.parametrize("max_rows", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("metric", ["cosine", "l1", "chebyshev", "jensen_shannon", "minkowski", "hamming"])
+def test_config0_every_staging_path(handle, config0, metric, kind, max_rows):
+    """Dense strip, column-slot strip and hash staging, with 1..16 rows of A per workgroup."""
+    A, B, dA, dB = config0
+    print("config0 staging", metric, kind, max_rows, flush=True)
+    handle.set_option("force_kind", kind)
+    handle.set_option("max_rows", max_rows)
+    got = _run_pairwise(handle, dA, dB, metric, _p_of(metric))
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric))
+    assert_distances_close(got, want, "%s kind=%d R=%d" % (metric, kind, max_rows))
+
+
+def _wide_pair(signed):
+    """Two small matrices over 400 columns whose rows have 0..400 entries."""
+    rng = np.random.default_rng(77)
+    out = []
+    for rows in (37, 75):
+        d = np.zeros((rows, 400))
+        for r in range(rows):
+            n = int(rng.choice([0, 3, 40, 129, 150, 280, 300, 400]))
+            cols = rng.choice(400, size=n, replace=False)
+            d[r, cols] = rng.standard_normal(n) if signed else rng.random(n) + 0.01
+        out.append(synth.from_dense(np.asarray(d.astype(np.float32), dtype=np.float64)))
+    return out
+
+
+@pytest.mark.parametrize("metric", ALL_METRICS)
+def test_split_rows_and_sliced_rows(handle, spd, metric):
+    """B rows cut over several lanes (split_len 4) and A rows cut into slices whose partial
+    results are summed afterwards (an 8 KB LDS budget with hash staging holds 128 entries)."""
+    A, B = _wide_pair(metric not in NONNEGATIVE_ONLY)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    print("split+slices", metric, flush=True)
+    plan = spd.host_plan_summary(A["indptr"], B["indptr"], 400, metric, split_len=4, window=64, force_kind=3,
+                                 lds_budget=8192, chunks=3)
+    assert plan["spilled_rows"] > 0 and plan["split_rows"] > 0
+    handle.set_option("split_len", 4)
+    handle.set_option("window", 64)
+    handle.set_option("force_kind", 3)
+    handle.set_option("lds_budget", 8192)
+    handle.set_option("chunks", 3)
+    got = _run_pairwise(handle, dA, dB, metric, _p_of(metric))
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric), mode="full")
+    assert_distances_close(got, want, metric)
+
+
+def _edge_matrices(signed):
+    """Empty rows, single-entry rows, a dense row, duplicates, stored zeros, 130 columns."""
+    rng = np.random.default_rng(99)
+    k = 130
+    d = np.zeros((70, k))
+    for r in range(70):
+        n = [0, 1, 1, 2, 5, 17, 64, 65, 129, 130][r % 10]
+        cols = rng.choice(k, size=n, replace=False)
+        vals = rng.standard_normal(n) if signed else rng.random(n) + 0.01
+        d[r, cols] = vals
+    d[33] = d[4]                       # duplicates
+    d[34] = d[9]
+    d[35] = d[8] * 1.0
+    M = synth.from_dense(np.asarray(d.astype(np.float32), dtype=np.float64))
+    # turn one stored value of row 5 into an explicit zero
+    s = int(M["indptr"][5])
+    M["values"] = M["values"].copy()
+    M["values"][s] = 0.0
+    return M
+
+
+@pytest.mark.parametrize("metric", ALL_METRICS)
+def test_edge_rows_and_self_join(handle, spd, metric):
+    signed = metric not in NONNEGATIVE_ONLY
+    M = _edge_matrices(signed)
+    dM = spd.DeviceCsr.from_host(M)
+    print("edge rows", metric, flush=True)
+    got = _run_pairwise(handle, dM, dM, metric, _p_of(metric))          # A and B alias
+    want = oracle.pairwise(M, M, ORACLE_NAME[metric], _p_of(metric), mode="full")
+    assert_distances_close(got, want, metric)
+    if metric not in ("inner_product", "russell_rao"):
+        assert np.abs(np.diag(got)).max() <= 1e-5, "d(x, x) must vanish"
+    if metric != "kl_divergence":
+        np.testing.assert_allclose(got, got.T, rtol=2e-4, atol=2e-5)
+    # single rows on either side
+    one = synth.slice_rows(M, 6, 7)
+    d1 = spd.DeviceCsr.from_host(one)
+    assert_distances_close(_run_pairwise(handle, d1, dM, metric, _p_of(metric)), want[6:7], metric + " m=1")
+    assert_distances_close(_run_pairwise(handle, dM, d1, metric, _p_of(metric)), want[:, 6:7], metric + " n=1")
+
+
+def test_all_rows_empty(handle, spd):
+    E = synth.from_dense(np.zeros((3, 40)))
+    dE = spd.DeviceCsr.from_host(E)
+    for metric in ALL_METRICS:
+        got = _run_pairwise(handle, dE, dE, metric, 2.0)
+        want = oracle.pairwise(E, E, ORACLE_NAME[metric], 2.0, mode="full")
+        assert_distances_close(got, want, metric)
+
+
+def test_results_are_bitwise_reproducible(handle, config0):
+    A, B, dA, dB = config0
+    for metric in ("l1", "cosine", "jensen_shannon"):
+        a = _run_pairwise(handle, dA, dB, metric)
+        b = _run_pairwise(handle, dA, dB, metric)
+        assert np.array_equal(a, b), metric
+
+
+# ------------------------------------------------------------------ config 1: sampled pairs
+def _sample_rows(csr, n, rng):
+    deg = np.diff(csr["indptr"])
+    order = np.argsort(deg, kind="stable")
+    forced = [order[0], order[-1], order[len(order) // 2]]
+    rest = rng.choice(csr["n_rows"], size=min(n, csr["n_rows"]) - len(forced), replace=False)
+    return np.unique(np.concatenate([forced, rest]))
+
+
+@pytest.fixture(scope="module")
+def config1(spd):
+    A, B = synth.workload(1)
+    return A, B, spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+
+
+@pytest.mark.parametrize("metric", ["l1", "l2_expanded", "cosine", "chebyshev", "minkowski",
+                                    "canberra", "jaccard", "correlation", "hamming"])
+def test_config1_sampled_pairs(handle, config1, metric):
+    A, B, dA, dB = config1
+    print("config1 pairwise", metric, flush=True)
+    rng = np.random.default_rng(1)
+    ra, rb = _sample_rows(A, 64, rng), _sample_rows(B, 2048, rng)
+    got = _run_pairwise(handle, dA, dB, metric, _p_of(metric))
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric), rows_a=ra, rows_b=rb)
+    assert_distances_close(got[np.ix_(ra, rb)], want, metric)
+
+
+@pytest.mark.parametrize("kind", [1, 3])
+def test_config1_other_staging_kinds(handle, config1, kind):
+    A, B, dA, dB = config1
+    print("config1 kind", kind, flush=True)
+    rng = np.random.default_rng(2)
+    ra, rb = _sample_rows(A, 64, rng), _sample_rows(B, 1024, rng)
+    handle.set_option("force_kind", kind)
+    for metric in ("l1", "cosine"):
+        got = _run_pairwise(handle, dA, dB, metric)
+        want = oracle.pairwise(A, B, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
+        assert_distances_close(got[np.ix_(ra, rb)], want, "%s kind %d" % (metric, kind))
+
+
+# ------------------------------------------------------------------ k-NN
+@pytest.mark.parametrize("metric", ALL_METRICS)
+@pytest.mark.parametrize("k", [1, 5, 32, 64])
+def test_config0_knn(handle, config0, metric, k):
+    import torch
+    A, B, dA, dB = config0
+    print("config0 knn", metric, k, flush=True)
+    idx, dist = handle.knn(dA, dB, metric, k, _p_of(metric))
+    torch.cuda.synchronize()
+    rows = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric))
+    assert_knn_matches(idx.cpu().numpy(), dist.cpu().numpy(), rows, k, metric, metric)
+
+
+def test_knn_ties_go_to_the_lower_index(handle, spd):
+    import torch
+    rng = np.random.default_rng(3)
+    base = (rng.random((40, 96)) < 0.1).astype(np.float64)
+    dense = np.concatenate([base, base, base])             # every row three times
+    I = synth.from_dense(dense)
+    Q = synth.from_dense(base)
+    dI, dQ = spd.DeviceCsr.from_host(I), spd.DeviceCsr.from_host(Q)
+    for metric in ("jaccard", "hamming", "dice", "l1"):
+        idx, dist = handle.knn(dQ, dI, metric, 6)
+        torch.cuda.synchronize()
+        want_idx, want_dist = oracle.knn(Q, I, ORACLE_NAME[metric], 6)
+        assert np.array_equal(idx.cpu().numpy(), want_idx), metric
+        assert_distances_close(dist.cpu().numpy(), want_dist, metric)
+
+
+def test_knn_with_sliced_rows_and_split_rows(handle, spd):
+    import torch
+    A, B = _wide_pair(False)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    handle.set_option("split_len", 4)
+    handle.set_option("force_kind", 3)
+    handle.set_option("lds_budget", 8192)
+    for metric in ("l1", "cosine", "inner_product", "jensen_shannon", "minkowski", "chebyshev"):
+        print("knn slices", metric, flush=True)
+        idx, dist = handle.knn(dA, dB, metric, 16, _p_of(metric))
+        torch.cuda.synchronize()
+        rows = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric))
+        assert_knn_matches(idx.cpu().numpy(), dist.cpu().numpy(), rows, 16, metric, metric)
+
+
+def test_config1_knn(handle, config1):
+    import torch
+    A, B, dA, dB = config1
+    rng = np.random.default_rng(4)
+    rq = _sample_rows(A, 24, rng)
+    for metric in ("cosine", "l1"):
+        print("config1 knn", metric, flush=True)
+        idx, dist = handle.knn(dA, dB, metric, 32)
+        torch.cuda.synchronize()
+        rows = oracle.pairwise(A, B, ORACLE_NAME[metric], rows_a=rq)
+        assert_knn_matches(idx.cpu().numpy()[rq], dist.cpu().numpy()[rq], rows, 32, metric, metric)
+
+
+# ------------------------------------------------------------------ the boundary's error paths
+def test_error_statuses(handle, spd, config0):
+    import torch
+    A, B, dA, dB = config0
+    other = spd.DeviceCsr.from_host(synth.from_dense(np.eye(4)))
+    with pytest.raises(spd.SpdError) as e:
+        handle.pairwise(dA, other, "l1", out=torch.empty((256, 4), dtype=torch.float32, device="cuda"))
+    assert e.value.status_name == "SPD_ERR_DIM_MISMATCH"
+    with pytest.raises(spd.SpdError) as e:
+        handle.pairwise(dA, dB, "minkowski", p=0.0)
+    assert e.value.status_name == "SPD_ERR_BAD_P"
+    with pytest.raises(spd.SpdError) as e:
+        handle.pairwise(dA, dB, "minkowski", p=float("nan"))
+    assert e.value.status_name == "SPD_ERR_BAD_P"
+    with pytest.raises(spd.SpdError) as e:
+        handle.pairwise(dA, dB, 99)
+    assert e.value.status_name == "SPD_ERR_BAD_METRIC"
+    for k in (0, 65, 257):
+        with pytest.raises(spd.SpdError) as e:
+            handle.knn(dA, dB, "l1", k)
+        assert e.value.status_name == "SPD_ERR_BAD_K"
+    with pytest.raises(spd.SpdError) as e:
+        handle.set_option("no_such_option", 1)
+    assert e.value.status_name == "SPD_ERR_UNSUPPORTED"
+    # a caller workspace that is too small is reported, a large enough one is used
+    need = handle.workspace_bytes(dA, dB, "l1")
+    handle.set_workspace(torch.empty(256, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(spd.SpdError) as e:
+        handle.pairwise(dA, dB, "l1")
+    assert e.value.status_name == "SPD_ERR_WORKSPACE"
+    handle.set_workspace(torch.empty(need, dtype=torch.uint8, device="cuda"))
+    got = handle.pairwise(dA, dB, "l1")
+    torch.cuda.synchronize()
+    assert_distances_close(got.cpu().numpy(), oracle.pairwise(A, B, "manhattan"), "caller workspace")
+    handle.set_workspace(None)
+
+
+def test_csr_validate(handle, spd, config0):
+    import torch
+    A, B, dA, dB = config0
+    handle.csr_validate(dA)
+    handle.csr_validate(dA, require_nonnegative=True)
+    bad = spd.DeviceCsr(dA.n_rows, dA.n_cols, dA.indptr.clone(), dA.indices.clone(), dA.values.clone())
+    bad.indices[1] = bad.indices[0]                          # columns no longer ascend strictly
+    with pytest.raises(spd.SpdError) as e:
+        handle.csr_validate(bad)
+    assert e.value.status_name == "SPD_ERR_BAD_CSR"
+    bad = spd.DeviceCsr(dA.n_rows, dA.n_cols, dA.indptr.clone(), dA.indices.clone(), dA.values.clone())
+    bad.values[7] = float("inf")
+    with pytest.raises(spd.SpdError):
+        handle.csr_validate(bad)
+    bad = spd.DeviceCsr(dA.n_rows, dA.n_cols, dA.indptr.clone(), dA.indices.clone(), -dA.values)
+    handle.csr_validate(bad)
+    with pytest.raises(spd.SpdError):
+        handle.csr_validate(bad, require_nonnegative=True)
+    bad = spd.DeviceCsr(dA.n_rows, dA.n_cols, dA.indptr.clone(), dA.indices.clone(), dA.values.clone())
+    bad.indptr[5] = bad.indptr[4] - 1
+    with pytest.raises(spd.SpdError):
+        handle.csr_validate(bad)
+    torch.cuda.synchronize()

@@ -1,0 +1,158 @@
+"""The C-ABI library without a GPU: it loads, exports what include/*.h declares, rejects
+bad arguments, and its host logic (planner; shared per-visit arithmetic) is consistent."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2104_06357_amd as spd
+from gen import synth
+from util import ALL_METRICS, ORACLE_NAME, assert_distances_close
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = set()
+    for header in os.listdir(os.path.join(ROOT, "include")):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(spd_[a-z_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = spd.lib()
+    declared = _declared_functions()
+    assert {"spd_create", "spd_destroy", "spd_pairwise", "spd_knn", "spd_workspace_bytes", "spd_set_workspace",
+            "spd_csr_validate", "spd_set_option", "spd_last_error", "spd_metric_name", "spd_version",
+            "spd_host_pair_value", "spd_host_plan_summary"} <= set(declared)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert b"gfx950" in L.spd_version()
+    for i, name in enumerate(spd.METRICS):
+        assert L.spd_metric_name(i).decode() == name
+
+
+def test_null_handle_and_missing_gpu_fail_loudly():
+    L = spd.lib()
+    assert L.spd_pairwise(None, None, None, 0, 2.0, None) == 1          # SPD_ERR_NULL
+    assert L.spd_knn(None, None, None, 0, 2.0, 1, None, None) == 1
+    assert L.spd_destroy(None) == 1
+    import torch
+    if not torch.cuda.is_available():
+        h = ctypes.c_void_p()
+        assert L.spd_create(ctypes.byref(h), None) == 8                   # SPD_ERR_HIP: no CPU fallback
+        assert not h
+        with pytest.raises(RuntimeError):
+            spd.Handle()
+
+
+def test_host_pair_value_argument_checks():
+    c = np.array([1], dtype=np.int32); v = np.array([1.0], dtype=np.float32)
+    with pytest.raises(spd.SpdError) as e:
+        spd.host_pair_value("minkowski", 0.0, 4, c, v, c, v)
+    assert e.value.status_name == "SPD_ERR_BAD_P"
+    with pytest.raises(spd.SpdError) as e:
+        spd.host_pair_value(99, 2.0, 4, c, v, c, v)
+    assert e.value.status_name == "SPD_ERR_BAD_METRIC"
+
+
+@pytest.mark.parametrize("metric", ALL_METRICS)
+def test_single_sweep_arithmetic_matches_the_oracle(metric):
+    """The products g(a, b), norms and expansion functions the kernels run, evaluated on
+    the host for single pairs: the union family's one-sweep form (norms plus corrections on
+    the intersection) and the expanded forms equal the oracle's plain definitions."""
+    A, B = synth.workload(0)
+    ra, rb = np.arange(0, 256, 7), np.arange(0, 256, 5)
+    for p in ((0.5, 1.0, 3.0) if metric == "minkowski" else (2.0,)):
+        want = oracle.pairwise(A, B, ORACLE_NAME[metric], p, rows_a=ra, rows_b=rb)
+        got = np.empty_like(want)
+        for x, i in enumerate(ra):
+            a0, a1 = A["indptr"][i], A["indptr"][i + 1]
+            for y, j in enumerate(rb):
+                b0, b1 = B["indptr"][j], B["indptr"][j + 1]
+                got[x, y] = spd.host_pair_value(metric, p, A["n_cols"], A["indices"][a0:a1], A["values"][a0:a1],
+                                                B["indices"][b0:b1], B["values"][b0:b1])
+        assert_distances_close(got, want, "%s p=%g" % (metric, p))
+
+
+@pytest.mark.parametrize("metric", ALL_METRICS)
+def test_single_sweep_arithmetic_identical_and_signed_rows(metric):
+    rng = np.random.default_rng(5)
+    signed = metric not in ("hellinger", "kl_divergence", "jensen_shannon")
+    k = 300
+    rows = []
+    for _ in range(6):
+        cols = np.sort(rng.choice(k, size=rng.integers(1, 120), replace=False)).astype(np.int32)
+        vals = (rng.standard_normal(cols.size) if signed else rng.random(cols.size) + 0.01) * 40.0
+        rows.append((cols, vals.astype(np.float32)))
+    rows.append((np.empty(0, np.int32), np.empty(0, np.float32)))            # an empty row
+    rows.append((rows[0][0].copy(), rows[0][1].copy()))                      # a duplicate of row 0
+    half = rows[1][1].copy(); half[::2] = rows[1][1][::2] * np.float32(1.0000001)
+    rows.append((rows[1][0].copy(), half))                                   # a near duplicate of row 1
+    dense = np.zeros((len(rows), k))
+    for r, (c, v) in enumerate(rows):
+        dense[r, c] = v
+    M = synth.from_dense(dense)
+    want = oracle.pairwise(M, M, ORACLE_NAME[metric], 3.0)
+    got = np.array([[spd.host_pair_value(metric, 3.0, k, ca, va, cb, vb) for cb, vb in rows] for ca, va in rows])
+    assert_distances_close(got, want, metric)
+
+
+def test_planner_paths_and_thresholds():
+    A, B = synth.workload(1, 0.2)
+    auto = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine")
+    assert all(c["kind"] == 2 for c in auto["classes"])                      # 20,000 columns: slot strip
+    assert auto["packed_entries"] == B["indptr"][-1] and auto["spilled_rows"] == 0
+    for kind in (1, 3):
+        s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine", force_kind=kind)
+        assert all(c["kind"] == kind for c in s["classes"])
+    small, _ = synth.workload(0)
+    s = spd.host_plan_summary(small["indptr"], small["indptr"], small["n_cols"], "l1")
+    assert [c["kind"] for c in s["classes"]] == [1] and s["classes"][0]["R"] == 16
+    # a tight LDS budget forces slices (partitions) of the long rows
+    s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "l1", force_kind=3, lds_budget=16384)
+    assert s["spilled_rows"] > 0 and s["partial_slots"] >= 2 * s["spilled_rows"]
+    assert all(c["lds_bytes"] + 4096 <= 16384 for c in s["classes"])
+    # rows at the split threshold: 511 stays whole, 512 is cut
+    for length, split in ((511, 0), (512, 1), (513, 1)):
+        ip = np.array([0, length], dtype=np.int64)
+        s = spd.host_plan_summary(ip, ip, 4096, "l1", force_kind=3)
+        assert s["split_rows"] == split, (length, s)
+    # Jensen-Shannon keeps at most 8 rows per group
+    s = spd.host_plan_summary(small["indptr"], small["indptr"], small["n_cols"], "jensen_shannon")
+    assert max(c["R"] for c in s["classes"]) == 8
+    # the fused k-NN needs room to merge the wavefronts' lists
+    s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine", k_neighbors=64)
+    for c in s["classes"]:
+        assert c["lds_bytes"] >= (c["block"] // 64) * c["R"] * 64 * 8
+
+
+def test_planner_rejects_bad_row_pointers():
+    good = np.array([0, 2, 5], dtype=np.int64)
+    bad = np.array([0, 3, 2], dtype=np.int64)
+    with pytest.raises(spd.SpdError):
+        spd.host_plan_summary(bad, good, 16, "l1")
+    with pytest.raises(spd.SpdError):
+        spd.host_plan_summary(good, bad, 16, "l1")
+    with pytest.raises(spd.SpdError):
+        spd.host_plan_summary(np.array([0, 40], dtype=np.int64), good, 16, "l1")   # row longer than k
+
+
+@pytest.mark.parametrize("config,scale", [(2, 0.02), (3, 0.01), (4, 0.02)])
+def test_planner_on_the_large_shapes(config, scale):
+    A, B = synth.workload(config, scale)
+    metric = {2: "cosine", 3: "jensen_shannon", 4: "jaccard"}[config]
+    s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], metric, k_neighbors=32 if config == 4 else 0)
+    assert s["packed_entries"] == B["indptr"][-1]
+    expected_kind = {2: 3, 3: 2, 4: 3}[config]                               # hash / slot strip / hash
+    assert all(c["kind"] == expected_kind for c in s["classes"]), s
+    if config == 3:
+        # the 16-bit column-slot strip leaves room for a whole 12,000-entry row; a hash table does not
+        assert s["spilled_rows"] == 0
+        h = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], metric, force_kind=3)
+        assert h["spilled_rows"] >= 1 and h["partial_slots"] >= 2

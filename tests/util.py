@@ -1,0 +1,60 @@
+"""Helpers shared by the tests: metric naming on the two sides and the tolerance rule."""
+import numpy as np
+
+# library metric name -> oracle metric name (the two sides keep their own vocabularies)
+ORACLE_NAME = {
+    "inner_product": "inner_product", "cosine": "cosine", "l2_expanded": "euclidean",
+    "correlation": "correlation", "jaccard": "jaccard", "dice": "dice", "hellinger": "hellinger",
+    "l1": "manhattan", "chebyshev": "chebyshev", "minkowski": "minkowski", "canberra": "canberra",
+    "hamming": "hamming", "kl_divergence": "kl_divergence", "jensen_shannon": "jensen_shannon",
+    "russell_rao": "russell_rao",
+}
+ALL_METRICS = tuple(ORACLE_NAME)
+NONNEGATIVE_ONLY = ("hellinger", "kl_divergence", "jensen_shannon")
+
+REL_TOL = 1e-4      # max relative error of an fp32 distance
+ABS_TOL = 1e-5      # absolute error allowed near zero
+
+
+def tolerance(oracle_values):
+    return np.maximum(REL_TOL * np.abs(oracle_values), ABS_TOL)
+
+
+def assert_distances_close(got, want, what=""):
+    """|got - want| <= max(1e-4 |want|, 1e-5) element by element (got fp32, want fp64)."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    assert np.all(np.isfinite(got)), what + ": non-finite result"
+    excess = np.abs(got - want) / tolerance(want)
+    worst = np.unravel_index(np.argmax(excess), excess.shape) if excess.size else None
+    assert excess.size == 0 or excess.max() <= 1.0, (
+        "%s: worst error %.3g x tolerance at %s (got %.9g, want %.9g)"
+        % (what, excess.max(), worst, got[worst], want[worst]))
+
+
+def assert_knn_matches(idx, dist, oracle_rows, k, metric, what=""):
+    """Exact index parity except at ties within tolerance.
+
+    `oracle_rows` is the full fp64 distance row of every query (m, n).  The returned
+    distances must match the oracle's at the returned indices; the list must be ordered
+    by (distance, index); and wherever the index differs from the oracle's choice, the
+    two candidates' oracle distances must be within tolerance of each other (a tie)."""
+    idx = np.asarray(idx); dist = np.asarray(dist, dtype=np.float64)
+    m, n = oracle_rows.shape
+    key = -oracle_rows if metric == "inner_product" else oracle_rows
+    for r in range(m):
+        order = np.lexsort((np.arange(n), key[r]))[:k]
+        assert len(set(idx[r].tolist())) == k, "%s: duplicate neighbours in row %d" % (what, r)
+        assert idx[r].min() >= 0 and idx[r].max() < n
+        assert_distances_close(dist[r], oracle_rows[r, idx[r]], "%s row %d distances" % (what, r))
+        gk = -dist[r] if metric == "inner_product" else dist[r]
+        for t in range(k - 1):
+            assert gk[t] < gk[t + 1] or (gk[t] == gk[t + 1] and idx[r, t] < idx[r, t + 1]), \
+                "%s: row %d not ordered at %d" % (what, r, t)
+        diff = np.nonzero(idx[r] != order)[0]
+        for t in diff:
+            a, b = oracle_rows[r, idx[r, t]], oracle_rows[r, order[t]]
+            assert abs(a - b) <= 2.0 * max(REL_TOL * abs(b), ABS_TOL), \
+                "%s: row %d position %d: index %d (%.9g) instead of %d (%.9g)" % (
+                    what, r, t, idx[r, t], a, order[t], b)
