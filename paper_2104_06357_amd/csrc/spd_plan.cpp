@@ -245,12 +245,12 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         AClass c;
         c.R = R; c.kind = KIND_STRIP;
         c.n_groups = (int)((n_rows + R - 1) / R);
-        c.rows.assign((size_t)c.n_groups * R, ARow{0, 0, -1});
+        c.rows.assign((size_t)c.n_groups * R, ARow{0, 0, -1, kRowFirst | kRowLast, 0});
         c.sumlen.assign((size_t)c.n_groups, 0);
         for (int64_t i = 0; i < n_rows; ++i) {
             int64_t len = indptr[i + 1] - indptr[i];
             if (len > (int64_t)k) return fmt("row longer than the column count", i);
-            c.rows[(size_t)i] = ARow{indptr[i], (int32_t)len, (int32_t)i};
+            c.rows[(size_t)i] = ARow{indptr[i], (int32_t)len, (int32_t)i, kRowFirst | kRowLast, 0};
             c.sumlen[(size_t)(i / R)] += (int32_t)len;
         }
         if (c.n_groups) { finish_class(c); out.classes.push_back(std::move(c)); }
@@ -263,14 +263,15 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         int64_t len = indptr[i + 1] - indptr[i];
         if (len > (int64_t)k) return fmt("row longer than the column count", i);
         if ((uint64_t)len <= dmax) {
-            items.push_back(ARow{indptr[i], (int32_t)len, (int32_t)i});
+            items.push_back(ARow{indptr[i], (int32_t)len, (int32_t)i, kRowFirst | kRowLast, 0});
         } else {
             int64_t parts = (len + (int64_t)dmax - 1) / (int64_t)dmax;
             if (out.n_partial_slots + parts > (1 << 24)) return "too many row slices";
             out.spilled.push_back(SpilledRow{(int32_t)i, out.n_partial_slots, (int32_t)parts});
             for (int64_t q = 0; q < parts; ++q) {
                 int64_t lo = len * q / parts, hi = len * (q + 1) / parts;
-                items.push_back(ARow{indptr[i] + lo, (int32_t)(hi - lo), -2 - (out.n_partial_slots++)});
+                uint32_t fl = (q == 0 ? kRowFirst : 0u) | (q == parts - 1 ? kRowLast : 0u);
+                items.push_back(ARow{indptr[i] + lo, (int32_t)(hi - lo), -2 - (out.n_partial_slots++), fl, 0});
             }
         }
     }
@@ -293,7 +294,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 while ((16 >> ci) != R) ++ci;
                 AClass &c = by_r[ci];
                 for (int q = 0; q < R; ++q)
-                    c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1});
+                    c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});
                 c.sumlen.push_back((int32_t)sum);
                 ++c.n_groups;
                 t += n;
@@ -315,6 +316,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
     const int64_t a_nnz = a.n_rows ? a_indptr[a.n_rows] : 0;
     std::vector<int64_t> covered((size_t)a.n_rows, 0);
     std::vector<int64_t> slot_lo((size_t)a.n_partial_slots, -1), slot_hi((size_t)a.n_partial_slots, -1);
+    std::vector<uint32_t> slot_flags((size_t)a.n_partial_slots, 0);
     for (const AClass &c : a.classes) {
         if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16) return "class R";
         if ((metric == MT_JS || metric == MT_MINKOWSKI) && c.R > 8) return "two-sum product with R > 8";
@@ -334,11 +336,14 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
                 if (row.out >= 0) {
                     if (row.out >= a.n_rows) return "A output row out of range";
                     if (row.start != a_indptr[row.out] || row.start + row.len != a_indptr[row.out + 1]) return "A row range";
+                    if (row.flags != (kRowFirst | kRowLast)) return "whole row without both end flags";
                     ++covered[(size_t)row.out];
                 } else {
                     int slot = -2 - row.out;
                     if (slot < 0 || slot >= a.n_partial_slots) return "partial slot out of range";
                     if (slot_lo[(size_t)slot] != -1) return "partial slot used twice";
+                    if (row.len < 1) return "empty slice";
+                    slot_flags[(size_t)slot] = row.flags;
                     slot_lo[(size_t)slot] = row.start;
                     slot_hi[(size_t)slot] = row.start + row.len;
                 }
@@ -355,6 +360,8 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
         int64_t at = a_indptr[s.row];
         for (int q = 0; q < s.n_slots; ++q) {
             if (slot_lo[(size_t)(s.first_slot + q)] != at) return "spilled slices not contiguous";
+            uint32_t want = (q == 0 ? kRowFirst : 0u) | (q == s.n_slots - 1 ? kRowLast : 0u);
+            if (slot_flags[(size_t)(s.first_slot + q)] != want) return "spilled slice end flags";
             at = slot_hi[(size_t)(s.first_slot + q)];
         }
         if (at != a_indptr[s.row + 1]) return "spilled slices do not cover the row";

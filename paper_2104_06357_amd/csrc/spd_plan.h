@@ -95,7 +95,10 @@ struct ARow {
     int64_t start;   // first element in A's CSR arrays
     int32_t len;     // number of stored entries of the slice
     int32_t out;     // >= 0: output row i;  -1: unused;  <= -2: partial-result slot (-2 - out)
+    uint32_t flags;  // bit 0: holds the first entry of its row, bit 1: holds the last one
+    uint32_t reserved;
 };
+constexpr uint32_t kRowFirst = 1u, kRowLast = 2u;
 
 // One kernel launch: groups of R rows that share the staging kind.
 struct AClass {

@@ -127,6 +127,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     __shared__ int s_ctr;
     __shared__ float s_top[kCheb ? R * kTopRanks : 1];
     __shared__ int s_topn[R];
+    __shared__ uint32_t s_clo[kCheb ? R : 1], s_cspan[kCheb ? R : 1];   // column range a slice answers for
 
     const int tid = (int)threadIdx.x, nthr = (int)blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nw = nthr >> 6;
@@ -145,7 +146,18 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         }
     }
     const int slab_begin = args.b.chunk_begin[chunk], slab_end = args.b.chunk_begin[chunk + 1];
-    if (slab_begin >= slab_end) return;
+    if (slab_begin >= slab_end) {
+        if constexpr (KNN) {
+            // an empty chunk still owns its place in the candidate lists: mark it unused
+            for (int e = tid; e < R * args.knn_k; e += nthr) {
+                const int out = args.arows[(size_t)g * R + e / args.knn_k].out;
+                if (out >= 0)
+                    args.knn_part[((size_t)out * args.b.n_chunks + chunk) * args.knn_k + e % args.knn_k] =
+                        KnnEntry{__builtin_huge_valf(), 0x7fffffff};
+            }
+        }
+        return;
+    }
 
     if (tid < R) s_rows[tid] = args.arows[(size_t)g * R + tid];
     const uint32_t sumlen = (uint32_t)args.sumlen[g];
@@ -244,6 +256,18 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         }
     }
     if (tid == 0) s_ctr = slab_begin;
+    if constexpr (kCheb) {
+        // With sum() = max a column that a slice of a row does not store still counts
+        // (|0 - b|), so each slice answers only for the columns from its first entry up to
+        // the next slice's first entry (the partition membership test of Section 3.3.3).
+        if (tid < R) {
+            const ARow rw = s_rows[tid];
+            uint32_t lo = (rw.flags & kRowFirst) ? 0u : (uint32_t)args.a_indices[rw.start];
+            uint32_t hi = (rw.flags & kRowLast) ? 0xFFFFFFFFu : (uint32_t)args.a_indices[rw.start + rw.len] - 1u;
+            s_clo[tid] = lo;
+            s_cspan[tid] = hi - lo;
+        }
+    }
     __syncthreads();
 
     if constexpr (kCheb) {
@@ -318,8 +342,14 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
             const uint32_t slot = cmap.lookup(e.x);
             const typename O::Bv bv = O::prep(__uint_as_float(e.y), args.q);
             const RowVals<R> a = load_vals<R>(vals, slot);
+            if constexpr (kCheb) {
 #pragma unroll
-            for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
+                for (int r = 0; r < R; ++r)
+                    if (e.x - s_clo[r] <= s_cspan[r]) O::visit(acc[r], a.v[r], bv, args.q);
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
+            }
             if constexpr (kCheb) {
                 const unsigned char *rk = rank8 + (size_t)slot * R;
 #pragma unroll

@@ -129,7 +129,8 @@ def test_edge_rows_and_self_join(handle, spd, metric):
     want = oracle.pairwise(M, M, ORACLE_NAME[metric], _p_of(metric), mode="full")
     assert_distances_close(got, want, metric)
     if metric not in ("inner_product", "russell_rao"):
-        assert np.abs(np.diag(got)).max() <= 1e-5, "d(x, x) must vanish"
+        defined = np.abs(np.diag(want)) < 1e-9   # a row without variance has correlation distance 1
+        assert defined.sum() >= 55 and np.abs(np.diag(got)[defined]).max() <= 1e-5, "d(x, x) must vanish"
     if metric != "kl_divergence":
         np.testing.assert_allclose(got, got.T, rtol=2e-4, atol=2e-5)
     # single rows on either side
