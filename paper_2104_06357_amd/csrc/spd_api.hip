@@ -191,21 +191,16 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
     why = plan_b(b_ip, n, h->opt, bp);
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
-    int groups_total = 0;
-    for (const AClass &c : ap.classes) groups_total += c.n_groups;
-    plan_chunks(bp, groups_total, h->opt);
+    for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
     why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, knn_k, h->opt);
     if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
-    for (const AClass &c : ap.classes)
-        if ((int64_t)c.n_groups * bp.n_chunks >= ((int64_t)1 << 31))
-            return fail(h, SPD_ERR_UNSUPPORTED, "launch grid beyond 2^31 workgroups");
 
     // ---- scratch layout ---------------------------------------------------------------
     const int planes = metric_planes((int)metric);
     const size_t lanes = (size_t)bp.n_slabs * kWave;
     Carver cv;
     Upload up;
-    const size_t o_packed = cv.take((size_t)bp.nnz * 8);
+    const size_t o_packed = cv.take((size_t)bp.slab_base[(size_t)bp.n_slabs] * 8);
     const size_t o_norms = cv.take((size_t)n * 16);
     const size_t o_slab_base = cv.take(bp.slab_base.size() * 8);
     const size_t o_slab_steps = cv.take(bp.slab_steps.size() * 4);
@@ -214,7 +209,6 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     const size_t o_seg_len = cv.take(lanes * 4);
     const size_t o_seg_row = cv.take(lanes * 4);
     const size_t o_seg_glog = cv.take(lanes);
-    const size_t o_chunks = cv.take(bp.chunk_begin.size() * 4);
     up.add(o_slab_base, bp.slab_base.data(), bp.slab_base.size() * 8);
     up.add(o_slab_steps, bp.slab_steps.data(), bp.slab_steps.size() * 4);
     up.add(o_slab_split, bp.slab_split.data(), bp.slab_split.size());
@@ -222,29 +216,40 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     up.add(o_seg_len, bp.seg_len.data(), lanes * 4);
     up.add(o_seg_row, bp.seg_row.data(), lanes * 4);
     up.add(o_seg_glog, bp.seg_glog.data(), lanes);
-    up.add(o_chunks, bp.chunk_begin.data(), bp.chunk_begin.size() * 4);
-    std::vector<size_t> o_rows(ap.classes.size()), o_sumlen(ap.classes.size());
+    std::vector<size_t> o_rows(ap.classes.size()), o_sumlen(ap.classes.size()), o_chunks(ap.classes.size());
     for (size_t ci = 0; ci < ap.classes.size(); ++ci) {
         const AClass &c = ap.classes[ci];
         o_rows[ci] = cv.take(c.rows.size() * sizeof(ARow));
         o_sumlen[ci] = cv.take(c.sumlen.size() * 4);
+        o_chunks[ci] = cv.take(c.chunk_begin.size() * 4);
         up.add(o_rows[ci], c.rows.data(), c.rows.size() * sizeof(ARow));
         up.add(o_sumlen[ci], c.sumlen.data(), c.sumlen.size() * 4);
+        up.add(o_chunks[ci], c.chunk_begin.data(), c.chunk_begin.size() * 4);
     }
     const size_t o_spilled = cv.take(ap.spilled.size() * sizeof(SpilledRow));
     up.add(o_spilled, ap.spilled.data(), ap.spilled.size() * sizeof(SpilledRow));
     const size_t o_partial = cv.take((size_t)ap.n_partial_slots * planes * (size_t)n * 8);
     const size_t o_partial_norms = cv.take((size_t)ap.n_partial_slots * 16);
-    std::vector<uint8_t> is_spilled;
-    size_t o_knn_part = 0, o_is_spilled = 0;
+    // k-NN: every (row, chunk of its launch) owns a list of k candidates
+    std::vector<int64_t> knn_row_off;
+    std::vector<int32_t> knn_row_lists;
+    size_t o_knn_part = 0, o_knn_off = 0, o_knn_lists = 0;
     if (knn_k > 0) {
-        o_knn_part = cv.take((size_t)m * bp.n_chunks * knn_k * sizeof(KnnEntry));
-        if (!ap.spilled.empty()) {
-            is_spilled.assign((size_t)m, 0);
-            for (const SpilledRow &s : ap.spilled) is_spilled[(size_t)s.row] = 1;
-            o_is_spilled = cv.take((size_t)m);
-            up.add(o_is_spilled, is_spilled.data(), (size_t)m);
-        }
+        knn_row_off.assign((size_t)m, 0);
+        knn_row_lists.assign((size_t)m, 0);                // 0 lists: a spilled row
+        int64_t entries = 0;
+        for (const AClass &c : ap.classes)
+            for (const ARow &r : c.rows)
+                if (r.out >= 0) {
+                    knn_row_off[(size_t)r.out] = entries;
+                    knn_row_lists[(size_t)r.out] = c.n_chunks;
+                    entries += (int64_t)c.n_chunks * knn_k;
+                }
+        o_knn_part = cv.take((size_t)entries * sizeof(KnnEntry));
+        o_knn_off = cv.take((size_t)m * 8);
+        o_knn_lists = cv.take((size_t)m * 4);
+        up.add(o_knn_off, knn_row_off.data(), (size_t)m * 8);
+        up.add(o_knn_lists, knn_row_lists.data(), (size_t)m * 4);
     }
     st = ensure_workspace(h, cv.off);
     if (st != SPD_OK) return st;
@@ -277,11 +282,11 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     bd.seg_row = reinterpret_cast<const int32_t *>(ws + o_seg_row);
     bd.seg_glog = ws + o_seg_glog;
     bd.norms = reinterpret_cast<const double *>(ws + o_norms);
-    bd.chunk_begin = reinterpret_cast<const int32_t *>(ws + o_chunks);
     bd.n_slabs = bp.n_slabs;
-    bd.n_chunks = bp.n_chunks;
     bd.n_rows = n;
 
+    // every launch of a call stages the same way: one pad column serves them all
+    const uint32_t padcol = (!ap.classes.empty() && ap.classes[0].kind == KIND_HASH) ? kEmptyKey : (uint32_t)A->n_cols;
     OpParams q;
     q.p = p;
     q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : 1.0f;
@@ -292,7 +297,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     {
         LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, (bp.n_slabs + 3) / 4);
         e = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd, reinterpret_cast<uint2 *>(ws + o_packed),
-                          reinterpret_cast<double *>(ws + o_norms), (int)metric, mi.transform, mi.norm, q.p, q.k);
+                          reinterpret_cast<double *>(ws + o_norms), (int)metric, mi.transform, mi.norm, q.p, q.k,
+                          padcol);
         if (e != hipSuccess) return hip_fail(h, e, "pack kernel");
         lt.done();
     }
@@ -305,6 +311,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         sa.arows = reinterpret_cast<const ARow *>(ws + o_rows[ci]);
         sa.sumlen = reinterpret_cast<const int32_t *>(ws + o_sumlen[ci]);
         sa.n_groups = c.n_groups;
+        sa.chunk_begin = reinterpret_cast<const int32_t *>(ws + o_chunks[ci]);
+        sa.n_chunks = c.n_chunks;
         sa.b_indptr = B->indptr;
         sa.b_indices = B->indices;
         sa.b = bd;
@@ -313,16 +321,17 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         sa.transform = mi.transform;
         sa.norm = mi.norm;
         sa.k = (uint32_t)A->n_cols;
-        sa.padcol = (c.kind == KIND_HASH) ? kEmptyKey : (uint32_t)A->n_cols;
+        sa.padcol = padcol;
         sa.out = out;
         sa.partial = reinterpret_cast<double *>(ws + o_partial);
         sa.partial_norms = reinterpret_cast<double *>(ws + o_partial_norms);
         sa.planes = planes;
         sa.knn_k = knn_k;
         sa.knn_part = reinterpret_cast<KnnEntry *>(ws + o_knn_part);
+        sa.knn_row_off = reinterpret_cast<const int64_t *>(ws + o_knn_off);
         int64_t live_rows = 0;
         for (const ARow &r : c.rows) live_rows += (r.out != -1);
-        LaunchTimer lt(h, "scan", c.R, c.kind, c.block, c.lds_bytes, live_rows, (int64_t)c.n_groups * bp.n_chunks);
+        LaunchTimer lt(h, "scan", c.R, c.kind, c.block, c.lds_bytes, live_rows, (int64_t)c.n_groups * c.n_chunks);
         e = launch_scan(h->stream, mi.op, c.R, c.block, c.lds_bytes, sa);
         if (e != hipSuccess) return hip_fail(h, e, "scan kernel");
         lt.done();
@@ -349,9 +358,10 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     }
     if (knn_k > 0) {
         LaunchTimer lt(h, "knn_merge", 0, 0, 0, 0, m, (m + 3) / 4);
-        e = launch_knn_merge(h->stream, reinterpret_cast<const KnnEntry *>(ws + o_knn_part), m, bp.n_chunks, knn_k,
-                             ap.spilled.empty() ? nullptr : ws + o_is_spilled, metric == SPD_INNER_PRODUCT ? 1 : 0,
-                             out_idx, out_dist);
+        e = launch_knn_merge(h->stream, reinterpret_cast<const KnnEntry *>(ws + o_knn_part),
+                             reinterpret_cast<const int64_t *>(ws + o_knn_off),
+                             reinterpret_cast<const int32_t *>(ws + o_knn_lists), m, knn_k,
+                             metric == SPD_INNER_PRODUCT ? 1 : 0, out_idx, out_dist);
         if (e != hipSuccess) return hip_fail(h, e, "k-NN merge kernel");
         lt.done();
     }
@@ -407,12 +417,10 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     const size_t window = (size_t)std::max(64, o.window);
     size_t slabs = n / 64 + n / window + (n + 4 * (size_t)B->nnz / seg_target) / 64 + 4;
     size_t lanes = slabs * 64;
-    size_t chunks = 4096;
-    {
-        size_t groups_min = std::max<size_t>(1, (m + 15) / 16);
-        size_t want = ((size_t)6 * (size_t)o.n_cus + groups_min - 1) / groups_min;
-        chunks = o.chunks > 0 ? (size_t)o.chunks : std::min<size_t>(4096, (std::max<size_t>(want, 8) + 7) / 8 * 8);
-    }
+    // at most 15 launches (5 group sizes x 3 occupancies), each cutting B at most 4096 times and
+    // never into more than 4 workgroups per slot of the chip plus one per group
+    const size_t launches = 15;
+    const size_t chunk_words = launches * 4097;
     // rows of A that do not fit alone are cut into slices of at least 1/2 of the largest
     // slice the budget admits; 512 entries is a floor for any budget the planner accepts
     size_t slices = 2 * (size_t)A->nnz / 512 + 2;
@@ -420,15 +428,23 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     size_t planes = (size_t)metric_planes((int)metric);
     size_t total = 0;
     auto add = [&](size_t b) { total += align256(b); };
-    add((size_t)B->nnz * 8); add(n * 16); add((slabs + 1) * 8); add(slabs * 4); add(slabs);
-    add(lanes * 8); add(lanes * 4); add(lanes * 4); add(lanes); add((chunks + 1) * 4);
+    // padded slabs: at most 64 idle entries per step of the longest row of each window, one per
+    // lane of a split row, and the rounding of each group of split rows
+    size_t padded = (size_t)B->nnz + (size_t)B->nnz * 64 / (size_t)std::max(2, o.split_len) +
+                    64 * (size_t)std::max(2, o.split_len) * (n / window + 8) + 64 * slabs;
+    add(padded * 8); add(n * 16); add((slabs + 1) * 8); add(slabs * 4); add(slabs);
+    add(lanes * 8); add(lanes * 4); add(lanes * 4); add(lanes); add(chunk_words * 4); total += launches * 256;
     add((m + slices + 16 * 6) * sizeof(ARow)); add((m + slices + 6) * 4); total += 12 * 256;
     add(slices * sizeof(SpilledRow));
     // partial results exist only for sliced rows; a row needs slicing only above ~9,000 entries
     size_t sliced_rows_max = (size_t)A->nnz / 4096 + 1;
     size_t partial_slots = std::min(slices, 2 * sliced_rows_max + (size_t)A->nnz / 4096);
     add(partial_slots * planes * n * 8); add(partial_slots * 16);
-    if (k_neighbors > 0) { add(m * chunks * (size_t)k_neighbors * sizeof(KnnEntry)); add(m); }
+    if (k_neighbors > 0) {
+        size_t lists = o.chunks > 0 ? (m + 16 * launches) * (size_t)o.chunks
+                                    : launches * 16 * (16 * (size_t)o.n_cus + 1) + m + 16 * launches;
+        add(lists * (size_t)k_neighbors * sizeof(KnnEntry)); add(m * 8); add(m * 4);
+    }
     *bytes = total;
     return SPD_OK;
 }

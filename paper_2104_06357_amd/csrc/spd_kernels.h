@@ -11,7 +11,7 @@ struct KnnEntry { float d; int32_t j; };
 
 // Device-resident copy of a BPlan plus the repacked entries and the row norms of B.
 struct BDevice {
-    const uint2 *packed;          // nnz entries {column, value bits}, slab by slab
+    const uint2 *packed;          // entries {column, value bits}: slab_base[s] + t*64 + lane
     const int64_t *slab_base;     // n_slabs + 1
     const int32_t *slab_steps;    // n_slabs
     const uint8_t *slab_split;    // n_slabs
@@ -20,8 +20,7 @@ struct BDevice {
     const int32_t *seg_row;       // lanes
     const uint8_t *seg_glog;      // lanes
     const double *norms;          // n_rows * 2, derived norms
-    const int32_t *chunk_begin;   // n_chunks + 1
-    int32_t n_slabs, n_chunks;
+    int32_t n_slabs;
     int64_t n_rows;
 };
 
@@ -32,6 +31,8 @@ struct ScanArgs {
     const ARow *arows;            // n_groups * R
     const int32_t *sumlen;        // n_groups
     int32_t n_groups;
+    const int32_t *chunk_begin;   // n_chunks + 1 slab indices: how this launch cuts B
+    int32_t n_chunks;
     // B (original CSR, for the Chebyshev completion of fully covered rows)
     const int64_t *b_indptr;
     const int32_t *b_indices;
@@ -47,7 +48,8 @@ struct ScanArgs {
     double *partial_norms;        // [slot][2] raw sums
     int32_t planes;               // 1, or 2 for Jensen-Shannon
     int32_t knn_k;                // 0: pairwise
-    KnnEntry *knn_part;           // k-NN: [row][chunk][k]
+    KnnEntry *knn_part;           // k-NN: candidate lists, knn_row_off[row] + chunk * k + t
+    const int64_t *knn_row_off;   // per output row
 };
 
 struct FinalizeArgs {
@@ -67,11 +69,11 @@ struct FinalizeArgs {
 
 hipError_t launch_pack_b(hipStream_t st, const int64_t *b_indptr, const int32_t *b_indices, const float *b_values,
                          const BDevice &b, uint2 *packed_out, double *norms_out, int metric, int transform,
-                         int norm, float p, double k);
+                         int norm, float p, double k, uint32_t padcol);
 hipError_t launch_scan(hipStream_t st, int op, int R, int block, uint32_t lds_bytes, const ScanArgs &args);
 hipError_t launch_finalize(hipStream_t st, const FinalizeArgs &args);
-hipError_t launch_knn_merge(hipStream_t st, const KnnEntry *part, int64_t n_rows, int n_chunks, int k,
-                            const uint8_t *row_is_spilled, int negate, int64_t *out_idx, float *out_dist);
+hipError_t launch_knn_merge(hipStream_t st, const KnnEntry *part, const int64_t *row_off, const int32_t *row_lists,
+                            int64_t n_rows, int k, int negate, int64_t *out_idx, float *out_dist);
 hipError_t launch_validate(hipStream_t st, const int64_t *indptr, const int32_t *indices, const float *values,
                            int64_t n_rows, int64_t n_cols, int64_t nnz, int require_nonnegative, int32_t *flag);
 hipError_t set_scan_lds_limit(uint32_t bytes);

@@ -10,14 +10,16 @@ namespace spd {
 
 // ------------------------------------------------------------------------------------
 // B: CSR -> slabs.  One wavefront per slab, one segment per lane; the t-th entries of
-// the lanes that still have one are written side by side, so the scan reads them back
-// with one coalesced load per step.  The lane also sums its part of the row norm.
+// the 64 lanes are written side by side (a lane whose segment has ended writes the pad
+// column), so the scan reads them back with one coalesced load per step.  The lane also
+// sums its part of the row norm.
 // ------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restrict__ b_indptr,
                                                          const int32_t *__restrict__ b_indices,
                                                          const float *__restrict__ b_values, BDevice b,
                                                          uint2 *__restrict__ packed, double *__restrict__ norms,
-                                                         int metric, int transform, int norm, float p, double k) {
+                                                         int metric, int transform, int norm, float p, double k,
+                                                         uint32_t padcol) {
     const int lane = (int)threadIdx.x & 63;
     const int s = (int)blockIdx.x * 4 + ((int)threadIdx.x >> 6);
     if (s >= b.n_slabs) return;
@@ -27,17 +29,16 @@ __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restri
     const int row = b.seg_row[at];
     const int glog = b.seg_glog[at];
     const int steps = b.slab_steps[s];
-    int64_t off = b.slab_base[s];
+    uint2 *dst = packed + b.slab_base[s] + lane;
     double s0 = 0.0, s1 = 0.0;
     for (int t = 0; t < steps; ++t) {
-        const bool active = t < len;
-        const uint64_t m = __ballot(active);
-        if (active) {
+        uint2 e = make_uint2(padcol, 0u);
+        if (t < len) {
             float v = transform_value(transform, b_values[start + t]);
             norm_accumulate(norm, v, p, s0, s1);
-            packed[off + lane_rank_in(m)] = make_uint2((uint32_t)b_indices[start + t], __float_as_uint(v));
+            e = make_uint2((uint32_t)b_indices[start + t], __float_as_uint(v));
         }
-        off += __popcll(m);
+        dst[(size_t)t * kWave] = e;
     }
     if (b.slab_split[s]) {
 #pragma unroll
@@ -56,11 +57,11 @@ __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restri
 
 hipError_t launch_pack_b(hipStream_t st, const int64_t *b_indptr, const int32_t *b_indices, const float *b_values,
                          const BDevice &b, uint2 *packed_out, double *norms_out, int metric, int transform,
-                         int norm, float p, double k) {
+                         int norm, float p, double k, uint32_t padcol) {
     if (b.n_slabs <= 0) return hipSuccess;
     dim3 grid((unsigned)((b.n_slabs + 3) / 4));
     hipLaunchKernelGGL(spd_pack_b_kernel, grid, dim3(256), 0, st, b_indptr, b_indices, b_values, b, packed_out,
-                       norms_out, metric, transform, norm, p, k);
+                       norms_out, metric, transform, norm, p, k, padcol);
     return hipGetLastError();
 }
 
@@ -154,19 +155,20 @@ hipError_t launch_finalize(hipStream_t st, const FinalizeArgs &args) {
 // ------------------------------------------------------------------------------------
 // k-NN: one wavefront per query row merges the lists its chunks produced.
 // ------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) spd_knn_merge_kernel(const KnnEntry *__restrict__ part, int64_t n_rows,
-                                                            int n_chunks, int k,
-                                                            const uint8_t *__restrict__ row_is_spilled, int negate,
-                                                            int64_t *__restrict__ out_idx,
+__global__ void __launch_bounds__(256) spd_knn_merge_kernel(const KnnEntry *__restrict__ part,
+                                                            const int64_t *__restrict__ row_off,
+                                                            const int32_t *__restrict__ row_lists, int64_t n_rows,
+                                                            int k, int negate, int64_t *__restrict__ out_idx,
                                                             float *__restrict__ out_dist) {
     const int lane = (int)threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + ((int)threadIdx.x >> 6);
     if (row >= n_rows) return;
-    if (row_is_spilled && row_is_spilled[row]) return;     // written by the finalize kernel
+    const int lists = row_lists[row];
+    if (lists <= 0) return;                                // a spilled row: written by the finalize kernel
     KnnList merged;
     merged.reset();
-    const int total = n_chunks * k;
-    const KnnEntry *src = part + (size_t)row * (size_t)total;
+    const int total = lists * k;
+    const KnnEntry *src = part + row_off[row];
     for (int e0 = 0; e0 < total; e0 += 64) {
         int e = e0 + lane;
         bool valid = e < total;
@@ -181,12 +183,12 @@ __global__ void __launch_bounds__(256) spd_knn_merge_kernel(const KnnEntry *__re
     }
 }
 
-hipError_t launch_knn_merge(hipStream_t st, const KnnEntry *part, int64_t n_rows, int n_chunks, int k,
-                            const uint8_t *row_is_spilled, int negate, int64_t *out_idx, float *out_dist) {
+hipError_t launch_knn_merge(hipStream_t st, const KnnEntry *part, const int64_t *row_off, const int32_t *row_lists,
+                            int64_t n_rows, int k, int negate, int64_t *out_idx, float *out_dist) {
     if (n_rows <= 0) return hipSuccess;
     dim3 grid((unsigned)((n_rows + 3) / 4));
-    hipLaunchKernelGGL(spd_knn_merge_kernel, grid, dim3(256), 0, st, part, n_rows, n_chunks, k, row_is_spilled,
-                       negate, out_idx, out_dist);
+    hipLaunchKernelGGL(spd_knn_merge_kernel, grid, dim3(256), 0, st, part, row_off, row_lists, n_rows, k, negate,
+                       out_idx, out_dist);
     return hipGetLastError();
 }
 

@@ -70,7 +70,10 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
         }
         window_end.push_back((int32_t)order.size());
     }
-    std::stable_sort(longs.begin(), longs.end(), [](const Long &a, const Long &b) { return a.glog > b.glog; });
+    // groups of equal size side by side, and within them segments of similar length
+    std::stable_sort(longs.begin(), longs.end(), [](const Long &a, const Long &b) {
+        return a.glog != b.glog ? a.glog > b.glog : a.len > b.len;
+    });
 
     // count slabs
     int64_t long_lanes = 0;
@@ -120,45 +123,55 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     }
     out.slab_base.assign((size_t)n_slabs + 1, 0);
     out.slab_steps.assign((size_t)n_slabs, 0);
+    // a slab stores steps x 64 entries: entry t of lane l at slab_base + t*64 + l, lanes whose
+    // segment is shorter are padded with a column that no row stages
     for (int64_t s = 0; s < n_slabs; ++s) {
-        int64_t sum = 0;
         int32_t mx = 0;
-        for (int l = 0; l < kWave; ++l) {
-            int32_t len = out.seg_len[(size_t)s * kWave + l];
-            sum += len;
-            mx = std::max(mx, len);
-        }
-        out.slab_base[(size_t)s + 1] = out.slab_base[(size_t)s] + sum;
+        for (int l = 0; l < kWave; ++l) mx = std::max(mx, out.seg_len[(size_t)s * kWave + l]);
+        out.slab_base[(size_t)s + 1] = out.slab_base[(size_t)s] + (int64_t)mx * kWave;
         out.slab_steps[(size_t)s] = mx;
     }
-    if (out.slab_base[(size_t)n_slabs] != out.nnz) return "internal: packed size != nnz";
-    out.n_chunks = 1;
-    out.chunk_begin = {0, out.n_slabs};
     return std::string();
 }
 
-void plan_chunks(BPlan &b, int n_groups_total, const PlanOptions &opt) {
+void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
     int64_t total = 0;
-    for (int32_t s : b.slab_steps) total += std::max(1, s);
+    int64_t longest = 1;
+    for (int32_t s : b.slab_steps) { total += std::max(1, s); longest = std::max<int64_t>(longest, s); }
+    const int waves = std::max(1, c.block / kWave);
     int nc = opt.chunks;
     if (nc <= 0) {
-        int64_t want = ((int64_t)6 * opt.n_cus + std::max(1, n_groups_total) - 1) / std::max(1, n_groups_total);
-        int64_t cap = std::max<int64_t>(8, total / 256);          // keep chunks worth staging for
-        nc = (int)std::min<int64_t>(std::max<int64_t>(want, 8), cap);
-        nc = (nc + 7) / 8 * 8;
-        nc = std::min(nc, 4096);
+        // Model of the launch time in slab steps: workgroups run in rounds over the chip's
+        // slots; each stages its rows, then its wavefronts share the chunk's slabs, the
+        // last one finishing up to half a slab after the others.
+        const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(opt.lds_budget / ((int64_t)c.lds_bytes + kStaticLds),
+                                                                      (int64_t)16 / waves));
+        const int64_t slots = (int64_t)opt.n_cus * per_cu;
+        const double stage = 24.0;
+        // more workgroups than four per slot buy nothing
+        const int64_t useful = 4 * slots / std::max(1, c.n_groups) + 1;
+        const int max_nc = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(4096, useful), b.n_slabs / waves));
+        double best = -1.0;
+        nc = 1;
+        for (int cand = 1; cand <= max_nc; cand = cand < 8 ? cand + 1 : cand + 8) {
+            int64_t wgs = (int64_t)c.n_groups * cand;
+            double rounds = (double)((wgs + slots - 1) / slots);
+            double per_wg = stage + (double)total / cand / waves + 0.5 * (double)longest;
+            double t = rounds * per_wg;
+            if (best < 0.0 || t < best * 0.98) { best = t; nc = cand; }
+        }
     }
-    b.n_chunks = nc;
-    b.chunk_begin.assign((size_t)nc + 1, b.n_slabs);
-    b.chunk_begin[0] = 0;
+    c.n_chunks = nc;
+    c.chunk_begin.assign((size_t)nc + 1, b.n_slabs);
+    c.chunk_begin[0] = 0;
     int64_t run = 0;
-    int c = 1;
-    for (int32_t s = 0; s < b.n_slabs && c < nc; ++s) {
+    int at = 1;
+    for (int32_t s = 0; s < b.n_slabs && at < nc; ++s) {
         run += std::max(1, b.slab_steps[(size_t)s]);
-        while (c < nc && run * nc >= total * c) b.chunk_begin[(size_t)c++] = s + 1;
+        while (at < nc && run * nc >= total * at) c.chunk_begin[(size_t)at++] = s + 1;
     }
-    for (; c < nc; ++c) b.chunk_begin[(size_t)c] = b.n_slabs;
-    b.chunk_begin[(size_t)nc] = b.n_slabs;
+    for (; at < nc; ++at) c.chunk_begin[(size_t)at] = b.n_slabs;
+    c.chunk_begin[(size_t)nc] = b.n_slabs;
 }
 
 namespace {
@@ -277,8 +290,11 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     }
     std::stable_sort(items.begin(), items.end(), [](const ARow &a, const ARow &b) { return a.len > b.len; });
 
-    AClass by_r[5];                           // R = 16, 8, 4, 2, 1
-    for (int q = 0; q < 5; ++q) { by_r[q].R = 16 >> q; by_r[q].kind = kind; }
+    // one launch per (R, workgroups per compute unit): groups that need little LDS are not
+    // held to the occupancy of the heaviest ones
+    AClass by_key[5][3];                      // R = 16, 8, 4, 2, 1  x  block 256 / 512 / 1024
+    for (int q = 0; q < 5; ++q)
+        for (int b = 0; b < 3; ++b) { by_key[q][b].R = 16 >> q; by_key[q][b].kind = kind; }
     size_t t = 0;
     while (t < items.size()) {
         size_t remaining = items.size() - t;
@@ -292,7 +308,9 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 if (!fits(kind, R, sum)) return "internal: slice does not fit";
                 int ci = 0;
                 while ((16 >> ci) != R) ++ci;
-                AClass &c = by_r[ci];
+                uint32_t need = lds_layout(kind, R, (uint32_t)sum, k, cheb).total;
+                int blk = block_for(need, opt.lds_budget);
+                AClass &c = by_key[ci][blk == 256 ? 0 : (blk == 512 ? 1 : 2)];
                 for (int q = 0; q < R; ++q)
                     c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});
                 c.sumlen.push_back((int32_t)sum);
@@ -303,7 +321,8 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         }
     }
     for (int q = 0; q < 5; ++q)
-        if (by_r[q].n_groups) { finish_class(by_r[q]); out.classes.push_back(std::move(by_r[q])); }
+        for (int b = 0; b < 3; ++b)
+            if (by_key[q][b].n_groups) { finish_class(by_key[q][b]); out.classes.push_back(std::move(by_key[q][b])); }
     return std::string();
 }
 
@@ -376,6 +395,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
         return "B lane arrays";
     std::vector<int64_t> next((size_t)b.n_rows);
     std::vector<uint8_t> seen((size_t)b.n_rows, 0);
+    int64_t total_entries = 0;
     for (int64_t j = 0; j < b.n_rows; ++j) next[(size_t)j] = b_indptr[j];
     for (int32_t s = 0; s < b.n_slabs; ++s) {
         int64_t sum = 0;
@@ -396,14 +416,20 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
             next[(size_t)j] += len;
             if ((l & (G - 1)) == G - 1 && next[(size_t)j] != b_indptr[j + 1]) return "B segments do not cover the row";
         }
-        if (b.slab_base[(size_t)s + 1] - b.slab_base[(size_t)s] != sum || b.slab_steps[(size_t)s] != mx) return "B slab sums";
+        if (b.slab_base[(size_t)s + 1] - b.slab_base[(size_t)s] != (int64_t)mx * kWave || b.slab_steps[(size_t)s] != mx)
+            return "B slab sizes";
+        total_entries += sum;
     }
     for (int64_t j = 0; j < b.n_rows; ++j)
         if (!seen[(size_t)j] || next[(size_t)j] != b_indptr[j + 1]) return fmt("B row not covered", j);
-    if (b.n_chunks < 1 || (size_t)b.n_chunks + 1 != b.chunk_begin.size()) return "B chunk arrays";
-    if (b.chunk_begin[0] != 0 || b.chunk_begin[(size_t)b.n_chunks] != b.n_slabs) return "B chunk ends";
-    for (int c = 0; c < b.n_chunks; ++c)
-        if (b.chunk_begin[(size_t)c] > b.chunk_begin[(size_t)c + 1]) return "B chunks not monotone";
+    if (total_entries != b.nnz) return "B entries != nnz";
+    for (const AClass &c : a.classes) {
+        if (c.n_chunks < 1 || (size_t)c.n_chunks + 1 != c.chunk_begin.size()) return "chunk arrays";
+        if (c.chunk_begin[0] != 0 || c.chunk_begin[(size_t)c.n_chunks] != b.n_slabs) return "chunk ends";
+        for (int q = 0; q < c.n_chunks; ++q)
+            if (c.chunk_begin[(size_t)q] > c.chunk_begin[(size_t)q + 1]) return "chunks not monotone";
+        if ((int64_t)c.n_groups * c.n_chunks >= ((int64_t)1 << 31)) return "launch grid beyond 2^31 workgroups";
+    }
     return std::string();
 }
 

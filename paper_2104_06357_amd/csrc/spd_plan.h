@@ -13,7 +13,8 @@
 //   * rows that do not fit alone are cut into contiguous slices whose partial results are
 //     summed afterwards (the partitions of Section 3.3.3, by column range);
 //   * B is repacked once per call into "slabs" of 64 rows of similar degree, one row per
-//     lane, stored so that the t-th entries of the 64 rows are contiguous.  Each lane
+//     lane, stored so that the t-th entries of the 64 rows are contiguous (shorter rows
+//     padded with a column that stages nothing).  Each lane
 //     keeps its pairs' sums in registers: no segmented reduction, no atomics.  Rows
 //     longer than `split_len` are cut into 2..64 equal segments that sit in adjacent
 //     lanes and are summed across lanes once, at the end of the slab.
@@ -40,7 +41,7 @@ struct PlanOptions {
     int64_t lds_budget = 160 * 1024;        // bytes of LDS per workgroup (static + dynamic)
     int force_kind = KIND_AUTO;
     int max_rows = kMaxR;
-    int split_len = 512;
+    int split_len = 128;
     int window = 2048;
     int chunks = 0;
     int n_cus = 256;
@@ -109,6 +110,8 @@ struct AClass {
     int n_groups = 0;
     std::vector<ARow> rows;         // n_groups * R
     std::vector<int32_t> sumlen;    // n_groups
+    int n_chunks = 0;               // how this launch cuts B's slabs (plan_chunks)
+    std::vector<int32_t> chunk_begin;   // n_chunks + 1 slab indices
 };
 
 struct SpilledRow { int32_t row, first_slot, n_slots; };
@@ -123,15 +126,13 @@ struct APlan {
 struct BPlan {
     int64_t n_rows = 0, nnz = 0;
     int32_t n_slabs = 0;
-    std::vector<int64_t> slab_base;    // n_slabs + 1, offsets into the packed entries
+    std::vector<int64_t> slab_base;    // n_slabs + 1, offsets into the packed entries (64 * steps each)
     std::vector<int32_t> slab_steps;   // n_slabs, longest segment of the slab
     std::vector<uint8_t> slab_split;   // n_slabs, 1 if the slab holds split rows
     std::vector<int64_t> seg_start;    // n_slabs*64, first CSR element of the lane's segment
     std::vector<int32_t> seg_len;      // n_slabs*64
     std::vector<int32_t> seg_row;      // n_slabs*64, row j of B, -1 for an unused lane
     std::vector<uint8_t> seg_glog;     // n_slabs*64, log2(lanes the row is split over)
-    int n_chunks = 0;
-    std::vector<int32_t> chunk_begin;  // n_chunks + 1 slab indices
 };
 
 // Staging kind for a column count, the largest number of rows staged together, and the
@@ -142,7 +143,9 @@ std::string plan_staging(int64_t n_cols, int metric, const PlanOptions &opt, int
 std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt, BPlan &out);
 std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int knn_k,
                    const PlanOptions &opt, APlan &out);
-void plan_chunks(BPlan &b, int n_groups_total, const PlanOptions &opt);
+// Cuts B's slabs into chunks for one launch: enough workgroups to fill the chip, yet chunks
+// long enough that a workgroup's wavefronts stay evenly loaded and staging is amortised.
+void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt);
 
 // Checks every index a kernel will form from the plan (bounds of segments, slabs, groups,
 // LDS sizes).  Empty string if consistent.

@@ -3,7 +3,7 @@
 // wavefronts: one row of B per lane instead of one non-zero per thread, so the segmented
 // scan and the atomic writes of that algorithm disappear).
 //
-// Included once per product (OP) by the spd_scan_op*.hip translation units.
+// Included once per product (OP) by the spd_scan_op_*.hip translation units.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -24,17 +24,20 @@ __device__ __forceinline__ bool lex_less(float d1, int j1, float d2, int j2) {
 }
 
 // Sorted list of the k best (distance, index) pairs of one query row, entry t in lane t.
+// (tau_d, tau_j) caches entry k-1, the bar a candidate has to beat.
 struct KnnList {
-    float d;
-    int j;
-    __device__ __forceinline__ void reset() { d = __builtin_huge_valf(); j = 0x7fffffff; }
+    float d, tau_d;
+    int j, tau_j;
+    __device__ __forceinline__ void reset() {
+        d = tau_d = __builtin_huge_valf();
+        j = tau_j = 0x7fffffff;
+    }
     // Every lane may offer one candidate; the list stays sorted by (d, j).
     __device__ __forceinline__ void offer(float dv, int jv, bool valid, int k) {
+        uint64_t m = __ballot(valid && lex_less(dv, jv, tau_d, tau_j));
+        if (m == 0) return;
         const int lane = (int)__lane_id();
-        float td = __shfl(d, k - 1);
-        int tj = __shfl(j, k - 1);
-        uint64_t m = __ballot(valid && lex_less(dv, jv, td, tj));
-        while (m) {
+        do {
             int src = wave_uniform((int)__builtin_ctzll(m));
             m &= m - 1;
             float x = __shfl(dv, src);
@@ -44,7 +47,9 @@ struct KnnList {
             int sj = __shfl_up(j, 1);
             if (lane > pos) { d = sd; j = sj; }
             else if (lane == pos) { d = x; j = xj; }
-        }
+        } while (m);
+        tau_d = __shfl(d, k - 1);
+        tau_j = __shfl(j, k - 1);
     }
 };
 
@@ -73,21 +78,24 @@ template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const 
 // ------------------------------------------------------------------------------------
 // column -> slot of the staged value table
 // ------------------------------------------------------------------------------------
-struct ColumnMap {
-    int kind;
+template <int KIND> struct ColumnMap {
     const uint16_t *slot16;   // KIND_SLOT: k+1 entries
     const uint2 *table;       // KIND_HASH: {column, slot}, empty = {kEmptyKey, 0}
     uint32_t mask, shift;
-    __device__ __forceinline__ uint32_t lookup(uint32_t c) const {
-        if (kind == KIND_STRIP) return c;
-        if (kind == KIND_SLOT) return slot16[c];
-        uint32_t h = (c * 0x9E3779B1u) >> shift;
+    __device__ __forceinline__ uint32_t home(uint32_t c) const { return (c * 0x9E3779B1u) >> shift; }
+    // Continues a hash lookup whose first probe `e` (at `h`) did not settle it.
+    __device__ __forceinline__ uint32_t resolve(uint32_t c, uint32_t h, uint2 e) const {
         for (;;) {
-            uint2 e = table[h];
             if (e.x == c) return e.y;          // the idle column is the empty key: slot 0
             if (e.x == kEmptyKey) return 0u;
             h = (h + 1u) & mask;
+            e = table[h];
         }
+    }
+    __device__ __forceinline__ uint32_t lookup(uint32_t c) const {
+        if constexpr (KIND == KIND_STRIP) return c;
+        else if constexpr (KIND == KIND_SLOT) return slot16[c];
+        else { uint32_t h = home(c); return resolve(c, h, table[h]); }
     }
 };
 
@@ -111,19 +119,21 @@ template <int R> __device__ __forceinline__ RowVals<R> load_vals(const float *va
     return out;
 }
 
+constexpr int kScanUnroll = 4;     // steps of a slab fetched ahead as one block
+
 // ------------------------------------------------------------------------------------
 // the kernel
 // ------------------------------------------------------------------------------------
-template <int OP, int R, bool KNN>
+template <int OP, int R, int KIND, bool KNN>
 __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(const ScanArgs args) {
     using O = Op<OP>;
     using Acc = typename O::Acc;
     constexpr bool kCheb = (OP == OP_CHEB);
+    constexpr int U = kScanUnroll;
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ ARow s_rows[R];
-    __shared__ double s_raw[R][2];
+    __shared__ uint32_t s_prefix[R + 1];
     __shared__ double s_na[R][2];
-    __shared__ double s_wpart[2][16][2];
     __shared__ int s_ctr;
     __shared__ float s_top[kCheb ? R * kTopRanks : 1];
     __shared__ int s_topn[R];
@@ -136,7 +146,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     int g, chunk;
     {
         int w = (int)blockIdx.x;
-        if ((args.b.n_chunks & 7) == 0) {
+        if ((args.n_chunks & 7) == 0) {
             int t = w >> 3;
             chunk = (w & 7) + 8 * (t / args.n_groups);
             g = t % args.n_groups;
@@ -145,14 +155,14 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
             g = w % args.n_groups;
         }
     }
-    const int slab_begin = args.b.chunk_begin[chunk], slab_end = args.b.chunk_begin[chunk + 1];
+    const int slab_begin = args.chunk_begin[chunk], slab_end = args.chunk_begin[chunk + 1];
     if (slab_begin >= slab_end) {
         if constexpr (KNN) {
             // an empty chunk still owns its place in the candidate lists: mark it unused
             for (int e = tid; e < R * args.knn_k; e += nthr) {
                 const int out = args.arows[(size_t)g * R + e / args.knn_k].out;
                 if (out >= 0)
-                    args.knn_part[((size_t)out * args.b.n_chunks + chunk) * args.knn_k + e % args.knn_k] =
+                    args.knn_part[args.knn_row_off[out] + (size_t)chunk * args.knn_k + e % args.knn_k] =
                         KnnEntry{__builtin_huge_valf(), 0x7fffffff};
             }
         }
@@ -161,28 +171,28 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 
     if (tid < R) s_rows[tid] = args.arows[(size_t)g * R + tid];
     const uint32_t sumlen = (uint32_t)args.sumlen[g];
-    const LdsLayout L = lds_layout(args.kind, R, sumlen, args.k, kCheb);
+    const LdsLayout L = lds_layout(KIND, R, sumlen, args.k, kCheb);
     float *vals = reinterpret_cast<float *>(dyn + L.off_vals);
     uint16_t *slot16 = reinterpret_cast<uint16_t *>(dyn + L.off_map);
     uint2 *table = reinterpret_cast<uint2 *>(dyn + L.off_map);
     unsigned char *rank8 = dyn + L.off_rank;
-    ColumnMap cmap;
-    cmap.kind = args.kind;
+    ColumnMap<KIND> cmap;
     cmap.slot16 = slot16;
     cmap.table = table;
     cmap.mask = L.cap ? L.cap - 1u : 0u;
     cmap.shift = L.cap ? 32u - (uint32_t)__builtin_ctz(L.cap) : 0u;
 
-    // ---- stage: clear, then insert the R rows one after the other -------------------
+    // ---- stage ------------------------------------------------------------------------
+    // 1. clear the value table and the column map
     {
         uint32_t nv4 = (L.nslots * R + 3u) / 4u;
         float4 *v4 = reinterpret_cast<float4 *>(vals);
         for (uint32_t i = tid; i < nv4; i += nthr) v4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (args.kind == KIND_SLOT) {
+        if constexpr (KIND == KIND_SLOT) {
             uint32_t nw32 = (args.k + 2u) / 2u;
             uint32_t *m32 = reinterpret_cast<uint32_t *>(slot16);
             for (uint32_t i = tid; i < nw32; i += nthr) m32[i] = 0u;
-        } else if (args.kind == KIND_HASH) {
+        } else if constexpr (KIND == KIND_HASH) {
             for (uint32_t i = tid; i < L.cap; i += nthr) table[i] = make_uint2(kEmptyKey, 0u);
         }
         if constexpr (kCheb) {
@@ -192,70 +202,68 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         }
     }
     __syncthreads();
-    {
-        uint32_t prefix = 0;
-#pragma unroll 1
-        for (int r = 0; r < R; ++r) {
-            const int64_t start = s_rows[r].start;
-            const int len = s_rows[r].len;
-            double s0 = 0.0, s1 = 0.0;
-            for (int qi = tid; qi < len; qi += nthr) {
-                uint32_t c = (uint32_t)args.a_indices[start + qi];
-                float t = transform_value(args.transform, args.a_values[start + qi]);
-                norm_accumulate(args.norm, t, args.q.p, s0, s1);
-                if (t != 0.0f) {                          // a stored zero is absent
-                    if (args.kind == KIND_STRIP) {
-                        vals[(size_t)c * R + r] = t;
-                    } else if (args.kind == KIND_SLOT) {
-                        if (slot16[c] == 0) slot16[c] = (uint16_t)(prefix + (uint32_t)qi + 1u);
-                    } else {
-                        uint32_t h = (c * 0x9E3779B1u) >> cmap.shift;
-                        for (;;) {
-                            uint32_t old = atomicCAS(&table[h].x, kEmptyKey, c);
-                            if (old == kEmptyKey) { table[h].y = prefix + (uint32_t)qi + 1u; break; }
-                            if (old == c) break;           // staged by an earlier row
-                            h = (h + 1u) & cmap.mask;
-                        }
-                    }
-                }
+    if (tid == 0) {
+        uint32_t acc = 0;
+        for (int r = 0; r < R; ++r) { s_prefix[r] = acc; acc += (uint32_t)s_rows[r].len; }
+        s_prefix[R] = acc;
+        s_ctr = slab_begin;
+    }
+    // 2. row norms: one wavefront per row, summed in a fixed order (Section 3.4)
+    for (int r = wave; r < R; r += nw) {
+        const int64_t start = s_rows[r].start;
+        const int len = s_rows[r].len;
+        double s0 = 0.0, s1 = 0.0;
+        for (int qi = lane; qi < len; qi += 64)
+            norm_accumulate(args.norm, transform_value(args.transform, args.a_values[start + qi]), args.q.p, s0, s1);
+        for (int m = 32; m >= 1; m >>= 1) { s0 += __shfl_xor(s0, m); s1 += __shfl_xor(s1, m); }
+        if (lane == 0) {
+            double d0, d1;
+            norm_derive(args.q.metric, args.q.k, s0, s1, d0, d1);
+            s_na[r][0] = d0; s_na[r][1] = d1;
+            const int out = s_rows[r].out;
+            if (out <= -2 && chunk == 0) {
+                args.partial_norms[(size_t)(-2 - out) * 2] = s0;
+                args.partial_norms[(size_t)(-2 - out) * 2 + 1] = s1;
             }
-            for (int m = 32; m >= 1; m >>= 1) { s0 += __shfl_xor(s0, m); s1 += __shfl_xor(s1, m); }
-            if (lane == 0) { s_wpart[r & 1][wave][0] = s0; s_wpart[r & 1][wave][1] = s1; }
-            __syncthreads();
-            if (tid == 0) {
-                double t0 = 0.0, t1 = 0.0;
-                for (int w = 0; w < nw; ++w) { t0 += s_wpart[r & 1][w][0]; t1 += s_wpart[r & 1][w][1]; }
-                s_raw[r][0] = t0; s_raw[r][1] = t1;
-            }
-            prefix += (uint32_t)len;
         }
     }
     __syncthreads();
-    if (args.kind != KIND_STRIP) {
-#pragma unroll 1
-        for (int r = 0; r < R; ++r) {
-            const int64_t start = s_rows[r].start;
-            const int len = s_rows[r].len;
-            for (int qi = tid; qi < len; qi += nthr) {
-                float t = transform_value(args.transform, args.a_values[start + qi]);
-                if (t != 0.0f) {
-                    uint32_t slot = cmap.lookup((uint32_t)args.a_indices[start + qi]);
-                    vals[(size_t)slot * R + r] = t;
+    // 3. every stored entry of the R rows claims a slot for its column.  Two rows that share
+    //    a column may both write: either slot id will do, the fill below reads the winner.
+    const uint32_t total = s_prefix[R];
+    if constexpr (KIND != KIND_STRIP) {
+        for (uint32_t e = tid; e < total; e += nthr) {
+            int r = 0;
+#pragma unroll
+            for (int q = 1; q < R; ++q) r += (e >= s_prefix[q]) ? 1 : 0;
+            const int64_t at = s_rows[r].start + (e - s_prefix[r]);
+            const float t = transform_value(args.transform, args.a_values[at]);
+            if (t != 0.0f) {                              // a stored zero is absent
+                const uint32_t c = (uint32_t)args.a_indices[at];
+                if constexpr (KIND == KIND_SLOT) {
+                    if (slot16[c] == 0) slot16[c] = (uint16_t)(e + 1u);
+                } else {
+                    uint32_t h = cmap.home(c);
+                    for (;;) {
+                        uint32_t old = atomicCAS(&table[h].x, kEmptyKey, c);
+                        if (old == kEmptyKey) { table[h].y = e + 1u; break; }
+                        if (old == c) break;
+                        h = (h + 1u) & cmap.mask;
+                    }
                 }
             }
         }
+        __syncthreads();
     }
-    if (tid < R) {
-        double d0, d1;
-        norm_derive(args.q.metric, args.q.k, s_raw[tid][0], s_raw[tid][1], d0, d1);
-        s_na[tid][0] = d0; s_na[tid][1] = d1;
-        int out = s_rows[tid].out;
-        if (out <= -2 && chunk == 0) {
-            args.partial_norms[(size_t)(-2 - out) * 2] = s_raw[tid][0];
-            args.partial_norms[(size_t)(-2 - out) * 2 + 1] = s_raw[tid][1];
-        }
+    // 4. fill the value table
+    for (uint32_t e = tid; e < total; e += nthr) {
+        int r = 0;
+#pragma unroll
+        for (int q = 1; q < R; ++q) r += (e >= s_prefix[q]) ? 1 : 0;
+        const int64_t at = s_rows[r].start + (e - s_prefix[r]);
+        const float t = transform_value(args.transform, args.a_values[at]);
+        if (t != 0.0f) vals[(size_t)cmap.lookup((uint32_t)args.a_indices[at]) * R + r] = t;
     }
-    if (tid == 0) s_ctr = slab_begin;
     if constexpr (kCheb) {
         // With sum() = max a column that a slice of a row does not store still counts
         // (|0 - b|), so each slice answers only for the columns from its first entry up to
@@ -298,8 +306,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                 if (best_v <= 0.0f) break;
                 if (lane == 0) {
                     s_top[r * kTopRanks + round] = best_v;
-                    uint32_t slot = cmap.lookup(best_c);
-                    rank8[(size_t)slot * R + r] = (unsigned char)round;
+                    rank8[(size_t)cmap.lookup(best_c) * R + r] = (unsigned char)round;
                 }
                 prev_v = best_v; prev_c = best_c; first = false;
                 found = round + 1;
@@ -324,38 +331,66 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         if (s >= slab_end) break;
         const size_t at = (size_t)s * kWave + lane;
         const int row = args.b.seg_row[at];
-        const int len = args.b.seg_len[at];
         const int steps = wave_uniform(args.b.slab_steps[s]);
         const bool split = wave_uniform((int)args.b.slab_split[s]) != 0;
-        int64_t off = args.b.slab_base[s];
+        const uint2 *__restrict__ pk = args.b.packed + args.b.slab_base[s] + lane;
         Acc acc[R];
         uint32_t hit[kCheb ? R : 1];
 #pragma unroll
         for (int r = 0; r < R; ++r) { O::init(acc[r]); if constexpr (kCheb) hit[r] = 0u; }
 
-        for (int t = 0; t < steps; ++t) {
-            const bool active = t < len;
-            const uint64_t m = __ballot(active);
-            uint2 e = make_uint2(args.padcol, 0u);
-            if (active) e = args.b.packed[off + lane_rank_in(m)];
-            off += __popcll(m);
-            const uint32_t slot = cmap.lookup(e.x);
-            const typename O::Bv bv = O::prep(__uint_as_float(e.y), args.q);
-            const RowVals<R> a = load_vals<R>(vals, slot);
-            if constexpr (kCheb) {
+        // Entry t of lane l sits at pk[t*64 + l]: one coalesced load per step, fetched U steps
+        // ahead of its use (past the slab's end the last step is simply read again).
+        uint2 nxt[U];
+        auto fetch_block = [&](int t_first) {
 #pragma unroll
-                for (int r = 0; r < R; ++r)
-                    if (e.x - s_clo[r] <= s_cspan[r]) O::visit(acc[r], a.v[r], bv, args.q);
-            } else {
-#pragma unroll
-                for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
+            for (int u = 0; u < U; ++u) {
+                const int t = min(t_first + u, steps - 1);
+                nxt[u] = pk[(size_t)t * kWave];
             }
+        };
+        auto visit_step = [&](const uint2 entry, const uint32_t slot) {
+            const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
+            const RowVals<R> a = load_vals<R>(vals, slot);
             if constexpr (kCheb) {
                 const unsigned char *rk = rank8 + (size_t)slot * R;
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
+                    if (entry.x - s_clo[r] <= s_cspan[r]) O::visit(acc[r], a.v[r], bv, args.q);
                     uint32_t q = rk[r];
                     hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
+            }
+        };
+        if (steps > 0) {
+            fetch_block(0);
+            for (int t0 = 0; t0 < steps; t0 += U) {
+                uint2 cur[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+                fetch_block(t0 + U);
+                uint32_t slot[U];
+                if constexpr (KIND == KIND_HASH) {
+                    uint32_t h[U];
+                    uint2 e[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) { h[u] = cmap.home(cur[u].x); e[u] = table[h[u]]; }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) slot[u] = cmap.resolve(cur[u].x, h[u], e[u]);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) slot[u] = cmap.lookup(cur[u].x);
+                }
+                if (t0 + U <= steps) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) visit_step(cur[u], slot[u]);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (t0 + u < steps) visit_step(cur[u], slot[u]);
                 }
             }
         }
@@ -383,7 +418,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int out = s_rows[r].out;           // uniform
+            const int out = wave_uniform(s_rows[r].out);
             if (out == -1) continue;
             double v0 = O::v0(acc[r]), v1 = O::v1(acc[r]);
             const double v2 = O::v2(acc[r]);
@@ -440,37 +475,48 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
             if (out < 0) continue;
             KnnList merged;
             merged.reset();
-            const int total = nw * kk;
-            for (int e0 = 0; e0 < total; e0 += 64) {
+            const int total_e = nw * kk;
+            for (int e0 = 0; e0 < total_e; e0 += 64) {
                 int e = e0 + lane;
-                bool valid = e < total;
+                bool valid = e < total_e;
                 KnnEntry c = KnnEntry{0.f, 0};
                 if (valid) c = area[((size_t)(e / kk) * R + r) * kk + (e % kk)];
                 valid = valid && c.j != 0x7fffffff;
                 merged.offer(c.d, c.j, valid, kk);
             }
             if (lane < kk)
-                args.knn_part[((size_t)out * args.b.n_chunks + chunk) * kk + lane] = KnnEntry{merged.d, merged.j};
+                args.knn_part[args.knn_row_off[out] + (size_t)chunk * kk + lane] = KnnEntry{merged.d, merged.j};
         }
     }
 }
 
-template <int OP, int R, bool KNN>
-static hipError_t launch_scan_rk(hipStream_t st, int block, uint32_t lds_bytes, const ScanArgs &args) {
+template <int OP, int R, int KIND, bool KNN>
+static hipError_t launch_scan_rkk(hipStream_t st, int block, uint32_t lds_bytes, const ScanArgs &args) {
     if (block > scan_max_block(OP, R, KNN) || block < kWave || (block & (kWave - 1))) return hipErrorInvalidValue;
-    auto kern = spd_scan_kernel<OP, R, KNN>;
+    auto kern = spd_scan_kernel<OP, R, KIND, KNN>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((size_t)args.n_groups * (size_t)args.b.n_chunks));
+    dim3 grid((unsigned)((size_t)args.n_groups * (size_t)args.n_chunks));
     hipLaunchKernelGGL(kern, grid, dim3((unsigned)block), lds_bytes, st, args);
     return hipGetLastError();
 }
 
 template <int OP, int R>
 static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, const ScanArgs &args) {
-    if (args.knn_k > 0) return launch_scan_rk<OP, R, true>(st, block, lds_bytes, args);
-    return launch_scan_rk<OP, R, false>(st, block, lds_bytes, args);
+    const bool knn = args.knn_k > 0;
+    switch (args.kind) {
+    case KIND_STRIP:
+        return knn ? launch_scan_rkk<OP, R, KIND_STRIP, true>(st, block, lds_bytes, args)
+                   : launch_scan_rkk<OP, R, KIND_STRIP, false>(st, block, lds_bytes, args);
+    case KIND_SLOT:
+        return knn ? launch_scan_rkk<OP, R, KIND_SLOT, true>(st, block, lds_bytes, args)
+                   : launch_scan_rkk<OP, R, KIND_SLOT, false>(st, block, lds_bytes, args);
+    case KIND_HASH:
+        return knn ? launch_scan_rkk<OP, R, KIND_HASH, true>(st, block, lds_bytes, args)
+                   : launch_scan_rkk<OP, R, KIND_HASH, false>(st, block, lds_bytes, args);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 template <int OP>

@@ -102,9 +102,7 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
     std::string why = plan_a(a_indptr, a_rows, n_cols, (int)metric, k_neighbors, opt, ap);
     if (why.empty()) why = plan_b(b_indptr, b_rows, opt, bp);
     if (why.empty()) {
-        int groups = 0;
-        for (const AClass &c : ap.classes) groups += c.n_groups;
-        plan_chunks(bp, groups, opt);
+        for (AClass &c : ap.classes) plan_chunks(bp, c, opt);
         why = plan_check(ap, bp, a_indptr, b_indptr, n_cols, (int)metric, k_neighbors, opt);
     }
     std::string js = "{";
@@ -120,8 +118,9 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
         for (int32_t s : c.sumlen) max_sum = std::max<int64_t>(max_sum, s);
         char buf[256];
         std::snprintf(buf, sizeof buf,
-                      "%s{\"R\": %d, \"kind\": %d, \"block\": %d, \"lds_bytes\": %u, \"groups\": %d, \"max_sumlen\": %lld}",
-                      i ? ", " : "", c.R, c.kind, c.block, c.lds_bytes, c.n_groups, (long long)max_sum);
+                      "%s{\"R\": %d, \"kind\": %d, \"block\": %d, \"lds_bytes\": %u, \"groups\": %d, \"max_sumlen\": %lld, "
+                      "\"chunks\": %d}",
+                      i ? ", " : "", c.R, c.kind, c.block, c.lds_bytes, c.n_groups, (long long)max_sum, c.n_chunks);
         js += buf;
     }
     int64_t split_rows = 0, max_steps = 0, total_steps = 0;
@@ -131,9 +130,9 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
     char buf[512];
     std::snprintf(buf, sizeof buf,
                   "], \"spilled_rows\": %zu, \"partial_slots\": %d, \"slabs\": %d, \"split_rows\": %lld, "
-                  "\"max_slab_steps\": %lld, \"total_slab_steps\": %lld, \"packed_entries\": %lld, \"chunks\": %d}",
+                  "\"max_slab_steps\": %lld, \"total_slab_steps\": %lld, \"packed_entries\": %lld}",
                   ap.spilled.size(), ap.n_partial_slots, bp.n_slabs, (long long)split_rows, (long long)max_steps,
-                  (long long)total_steps, (long long)bp.nnz, bp.n_chunks);
+                  (long long)total_steps, (long long)bp.nnz);
     js += buf;
     std::snprintf(json, cap, "%s", js.c_str());
     return js.size() < cap ? SPD_OK : SPD_ERR_WORKSPACE;

@@ -118,8 +118,8 @@ def test_planner_paths_and_thresholds():
     s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "l1", force_kind=3, lds_budget=16384)
     assert s["spilled_rows"] > 0 and s["partial_slots"] >= 2 * s["spilled_rows"]
     assert all(c["lds_bytes"] + 4096 <= 16384 for c in s["classes"])
-    # rows at the split threshold: 511 stays whole, 512 is cut
-    for length, split in ((511, 0), (512, 1), (513, 1)):
+    # rows at the split threshold: 127 stays whole, 128 is cut
+    for length, split in ((127, 0), (128, 1), (129, 1)):
         ip = np.array([0, length], dtype=np.int64)
         s = spd.host_plan_summary(ip, ip, 4096, "l1", force_kind=3)
         assert s["split_rows"] == split, (length, s)
