@@ -1,0 +1,119 @@
+"""Parity at the full sizes of BASELINE configs 2-4 (needs an MI355X; run with -m gpu).
+
+The library runs a whole query tile against the whole index, exactly as a user would call
+it; the oracle then recomputes a seeded sample of the outputs one by one (always including
+the rows of smallest, median and largest degree), or, for k-NN, the full distance rows of
+a sample of queries.
+"""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+from gen import synth
+from util import ORACLE_NAME, assert_distances_close, assert_knn_matches
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def spd():
+    import paper_2104_06357_amd as lib
+    return lib
+
+
+def _extremes_and_sample(csr, n, rng, extra=()):
+    deg = np.diff(csr["indptr"])
+    order = np.argsort(deg, kind="stable")
+    forced = [order[0], order[-1], order[len(order) // 2], *extra]
+    rest = rng.choice(csr["n_rows"], size=max(0, n - len(forced)), replace=False)
+    return np.unique(np.concatenate([np.asarray(forced, dtype=np.int64), rest]))
+
+
+def _gather(out, rows, cols):
+    import torch
+    r = torch.as_tensor(rows, device=out.device)
+    c = torch.as_tensor(cols, device=out.device)
+    return out.index_select(0, r).index_select(1, c).cpu().numpy()
+
+
+def _timed(label, fn):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    out = fn()
+    torch.cuda.synchronize()
+    print("%s: %.1f ms" % (label, 1e3 * (time.perf_counter() - t0)), flush=True)
+    return out
+
+
+def test_config2_bag_of_words_tile(spd):
+    """1,024 queries (one output tile of 1.2 GB) against the 300,000-row index."""
+    import torch
+    Q, I = synth.workload(2)
+    rng = np.random.default_rng(2)
+    tile_rows = _extremes_and_sample(Q, 1024, rng)
+    tile = synth.take_rows(Q, tile_rows)
+    dQ, dI = spd.DeviceCsr.from_host(tile), spd.DeviceCsr.from_host(I)
+    h = spd.Handle()
+    out = torch.empty((tile["n_rows"], I["n_rows"]), dtype=torch.float32, device="cuda")
+    ra = _extremes_and_sample(tile, 64, rng)
+    rb = _extremes_and_sample(I, 2048, rng)
+    for metric in ("cosine", "inner_product", "hellinger"):
+        _timed("config2 " + metric, lambda: h.pairwise(dQ, dI, metric, out=out))
+        want = oracle.pairwise(tile, I, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
+        assert_distances_close(_gather(out, ra, rb), want, "config2 " + metric)
+    # rows are L2-normalised: cosine distance = 1 - inner product (a property at any size)
+    cos = h.pairwise(dQ, dI, "cosine", out=out).index_select(0, torch.as_tensor(ra, device="cuda")).clone()
+    ip = h.pairwise(dQ, dI, "inner_product", out=out).index_select(0, torch.as_tensor(ra, device="cuda"))
+    assert float((cos + ip - 1.0).abs().max()) < 2e-6
+    h.close()
+
+
+def test_config3_count_matrix_tile(spd):
+    """A 4,096-row query tile of the 65,536-row self-join, union-family metrics."""
+    import torch
+    M, _ = synth.workload(3)
+    deg = np.diff(M["indptr"])
+    heavy = np.nonzero(deg > 10_240)[0]
+    assert heavy.size >= 8
+    rng = np.random.default_rng(3)
+    tile_rows = _extremes_and_sample(M, 4096, rng, extra=heavy[:8])
+    tile = synth.take_rows(M, tile_rows)
+    dQ, dM = spd.DeviceCsr.from_host(tile), spd.DeviceCsr.from_host(M)
+    h = spd.Handle()
+    out = torch.empty((tile["n_rows"], M["n_rows"]), dtype=torch.float32, device="cuda")
+    heavy_in_tile = np.nonzero(np.isin(tile_rows, heavy))[0]
+    ra = _extremes_and_sample(tile, 64, rng, extra=heavy_in_tile)
+    # index sample: extremes, the heavy rows, and the tile's own rows (the self-join diagonal)
+    rb = _extremes_and_sample(M, 2048, rng, extra=list(heavy) + list(tile_rows[ra]))
+    for metric in ("kl_divergence", "jensen_shannon", "canberra", "l1"):
+        _timed("config3 " + metric, lambda: h.pairwise(dQ, dM, metric, out=out))
+        want = oracle.pairwise(tile, M, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
+        assert_distances_close(_gather(out, ra, rb), want, "config3 " + metric)
+    # the same rows through hash staging: the >10,240-entry rows are cut into slices
+    h.set_option("force_kind", 3)
+    plan = spd.host_plan_summary(tile["indptr"], M["indptr"], M["n_cols"], "l1", force_kind=3)
+    assert plan["spilled_rows"] >= 8
+    _timed("config3 l1 (hash staging)", lambda: h.pairwise(dQ, dM, "l1", out=out))
+    want = oracle.pairwise(tile, M, "manhattan", rows_a=ra, rows_b=rb)
+    assert_distances_close(_gather(out, ra, rb), want, "config3 l1 with slices")
+    h.close()
+
+
+def test_config4_binary_knn(spd):
+    """4,096 binary queries against 500,000 index rows over 2^20 columns, fused top-32."""
+    import torch
+    Q, I = synth.workload(4)
+    dQ, dI = spd.DeviceCsr.from_host(Q), spd.DeviceCsr.from_host(I)
+    h = spd.Handle()
+    rng = np.random.default_rng(4)
+    rq = _extremes_and_sample(Q, 24, rng)
+    plan = spd.host_plan_summary(Q["indptr"], I["indptr"], Q["n_cols"], "jaccard", k_neighbors=32)
+    print("config4 plan: spilled rows %d, slabs %d" % (plan["spilled_rows"], plan["slabs"]), flush=True)
+    for metric in ("jaccard", "dice", "hamming"):
+        idx, dist = _timed("config4 knn " + metric, lambda: h.knn(dQ, dI, metric, 32))
+        rows = oracle.pairwise(Q, I, ORACLE_NAME[metric], rows_a=rq)
+        assert_knn_matches(idx.cpu().numpy()[rq], dist.cpu().numpy()[rq], rows, 32, metric, "config4 " + metric)
+    h.close()
