@@ -123,6 +123,7 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *   "split_len"   B rows at least this long are split over several lanes
  *   "window"      B rows per degree-sorting window
  *   "chunks"      number of B chunks (0 = automatic)
+ *   "check_plan"  1: verify every index the kernels will form from the plan before launching
  *   "profile"     1: bracket every kernel launch with HIP events (see spd_profile_read)
  * Unknown names or values out of range return SPD_ERR_UNSUPPORTED. */
 spd_status spd_set_option(spd_handle *handle, const char *name, int64_t value);

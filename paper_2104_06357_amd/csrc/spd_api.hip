@@ -2,7 +2,9 @@
 // layout, and the sequence of launches of one spd_pairwise / spd_knn call.
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cmath>
+#include <cstdlib>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -28,6 +30,7 @@ struct spd_handle {
     size_t own_ws_bytes = 0;
     int32_t *flag = nullptr;     // device word for spd_csr_validate
     bool profile = false;
+    bool check_plan = false;     // full consistency check of every plan before launching
     struct Timed { spd_kernel_time rec; hipEvent_t start, stop; };
     std::vector<Timed> timed;    // launches of the last call (profile mode)
     std::vector<hipEvent_t> event_pool;
@@ -160,6 +163,15 @@ struct Upload {
 spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, int knn_k,
                float *out, int64_t *out_idx, float *out_dist) {
     const int64_t m = A->n_rows, n = B->n_rows;
+    static const bool host_times = std::getenv("SPD_HOST_TIMES") != nullptr;
+    auto now = [] { return std::chrono::steady_clock::now(); };
+    auto t_begin = now();
+    auto lap = [&](const char *what) {
+        if (!host_times) return;
+        auto t = now();
+        std::fprintf(stderr, "[spd host] %-12s %8.1f us\n", what, std::chrono::duration<double, std::micro>(t - t_begin).count());
+        t_begin = t;
+    };
     for (auto &t : h->timed) { h->event_pool.push_back(t.start); h->event_pool.push_back(t.stop); }
     h->timed.clear();
     if (m == 0 || n == 0) return SPD_OK;
@@ -182,6 +194,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     e = hipStreamSynchronize(h->stream);
     if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
     if (a_ip[m] != A->nnz || b_ip[n] != B->nnz) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
+    lap("indptr d2h");
 
     // ---- plan -------------------------------------------------------------------------
     const MetricInfo mi = metric_info((int)metric);
@@ -191,17 +204,24 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
     why = plan_b(b_ip, n, h->opt, bp);
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
+    lap("plan a+b");
     for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
-    why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, knn_k, h->opt);
-    if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
+    lap("chunks");
+    if (h->check_plan) {
+        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, knn_k, h->opt);
+        if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
+    }
+    for (const AClass &c : ap.classes)
+        if ((int64_t)c.n_groups * c.n_chunks >= ((int64_t)1 << 31) || (int64_t)c.lds_bytes + kStaticLds > h->opt.lds_budget)
+            return fail(h, SPD_ERR_UNSUPPORTED, "internal: launch outside the device limits");
+    lap("plan check");
 
     // ---- scratch layout ---------------------------------------------------------------
     const int planes = metric_planes((int)metric);
     const size_t lanes = (size_t)bp.n_slabs * kWave;
     Carver cv;
     Upload up;
-    const size_t o_packed = cv.take((size_t)bp.slab_base[(size_t)bp.n_slabs] * 8);
-    const size_t o_norms = cv.take((size_t)n * 16);
+    // (1) the plan region: everything the host uploads, contiguous, so that one copy moves it
     const size_t o_slab_base = cv.take(bp.slab_base.size() * 8);
     const size_t o_slab_steps = cv.take(bp.slab_steps.size() * 4);
     const size_t o_slab_split = cv.take(bp.slab_split.size());
@@ -228,49 +248,50 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     }
     const size_t o_spilled = cv.take(ap.spilled.size() * sizeof(SpilledRow));
     up.add(o_spilled, ap.spilled.data(), ap.spilled.size() * sizeof(SpilledRow));
-    const size_t o_partial = cv.take((size_t)ap.n_partial_slots * planes * (size_t)n * 8);
-    const size_t o_partial_norms = cv.take((size_t)ap.n_partial_slots * 16);
     // k-NN: every (row, chunk of its launch) owns a list of k candidates
     std::vector<int64_t> knn_row_off;
     std::vector<int32_t> knn_row_lists;
-    size_t o_knn_part = 0, o_knn_off = 0, o_knn_lists = 0;
+    size_t o_knn_off = 0, o_knn_lists = 0;
+    int64_t knn_entries = 0;
     if (knn_k > 0) {
         knn_row_off.assign((size_t)m, 0);
         knn_row_lists.assign((size_t)m, 0);                // 0 lists: a spilled row
-        int64_t entries = 0;
         for (const AClass &c : ap.classes)
             for (const ARow &r : c.rows)
                 if (r.out >= 0) {
-                    knn_row_off[(size_t)r.out] = entries;
+                    knn_row_off[(size_t)r.out] = knn_entries;
                     knn_row_lists[(size_t)r.out] = c.n_chunks;
-                    entries += (int64_t)c.n_chunks * knn_k;
+                    knn_entries += (int64_t)c.n_chunks * knn_k;
                 }
-        o_knn_part = cv.take((size_t)entries * sizeof(KnnEntry));
         o_knn_off = cv.take((size_t)m * 8);
         o_knn_lists = cv.take((size_t)m * 4);
         up.add(o_knn_off, knn_row_off.data(), (size_t)m * 8);
         up.add(o_knn_lists, knn_row_lists.data(), (size_t)m * 4);
     }
+    // (2) what the kernels produce
+    const size_t o_packed = cv.take((size_t)bp.slab_base[(size_t)bp.n_slabs] * 8);
+    const size_t o_norms = cv.take((size_t)n * 16);
+    const size_t o_partial = cv.take((size_t)ap.n_partial_slots * planes * (size_t)n * 8);
+    const size_t o_partial_norms = cv.take((size_t)ap.n_partial_slots * 16);
+    const size_t o_knn_part = cv.take((size_t)knn_entries * sizeof(KnnEntry));
     st = ensure_workspace(h, cv.off);
     if (st != SPD_OK) return st;
     unsigned char *ws = reinterpret_cast<unsigned char *>(h->ws);
 
-    // ---- upload the plan (through pinned memory, so the copies are asynchronous) --------
-    size_t blob = 0;
-    for (auto &pt : up.parts) blob += align256(pt.second.second);
-    st = ensure_pinned(h, blob);
-    if (st != SPD_OK) return st;
+    // ---- upload the plan: one copy of one pinned blob that mirrors the scratch layout ----
     {
-        unsigned char *pin = reinterpret_cast<unsigned char *>(h->pinned);
-        size_t at = 0;
-        for (auto &pt : up.parts) {
-            std::memcpy(pin + at, pt.second.first, pt.second.second);
-            e = hipMemcpyAsync(ws + pt.first, pin + at, pt.second.second, hipMemcpyHostToDevice, h->stream);
+        size_t lo = cv.off, hi = 0;
+        for (auto &pt : up.parts) { lo = std::min(lo, pt.first); hi = std::max(hi, pt.first + pt.second.second); }
+        if (hi > lo) {
+            st = ensure_pinned(h, hi - lo);
+            if (st != SPD_OK) return st;
+            unsigned char *pin = reinterpret_cast<unsigned char *>(h->pinned);
+            for (auto &pt : up.parts) std::memcpy(pin + (pt.first - lo), pt.second.first, pt.second.second);
+            e = hipMemcpyAsync(ws + lo, pin, hi - lo, hipMemcpyHostToDevice, h->stream);
             if (e != hipSuccess) return hip_fail(h, e, "upload of the plan");
-            at += align256(pt.second.second);
         }
     }
-
+    lap("upload");
     // ---- launches ---------------------------------------------------------------------
     BDevice bd;
     bd.packed = reinterpret_cast<const uint2 *>(ws + o_packed);
@@ -356,6 +377,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         if (e != hipSuccess) return hip_fail(h, e, "finalize kernel");
         lt.done();
     }
+    lap("launches");
     if (knn_k > 0) {
         LaunchTimer lt(h, "knn_merge", 0, 0, 0, 0, m, (m + 3) / 4);
         e = launch_knn_merge(h->stream, reinterpret_cast<const KnnEntry *>(ws + o_knn_part),
@@ -528,6 +550,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "chunks") {
         if (value < 0 || value > 4096) return fail(h, SPD_ERR_UNSUPPORTED, "chunks must lie in [0, 4096]");
         o.chunks = (int)value;
+    } else if (s == "check_plan") {
+        if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "check_plan must be 0 or 1");
+        h->check_plan = value != 0;
     } else if (s == "profile") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "profile must be 0 or 1");
         h->profile = value != 0;

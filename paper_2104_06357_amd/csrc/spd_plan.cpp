@@ -43,7 +43,7 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     std::vector<int32_t> order;            // short rows, window by window, longest first
     std::vector<int32_t> window_end;       // prefix positions in `order`
     order.reserve((size_t)n_rows);
-    std::vector<int32_t> bucket_count((size_t)T + 1);
+    std::vector<int32_t> bucket_count((size_t)T + 1), pos((size_t)T + 1);
     for (int64_t w0 = 0; w0 < n_rows; w0 += Wn) {
         int64_t w1 = std::min(n_rows, w0 + Wn);
         std::fill(bucket_count.begin(), bucket_count.end(), 0);
@@ -59,7 +59,6 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
             }
         }
         // counting sort, longest first, stable in j
-        std::vector<int32_t> pos((size_t)T + 1);
         int32_t acc = 0;
         for (int64_t l = T - 1; l >= 0; --l) { pos[(size_t)l] = acc; acc += bucket_count[(size_t)l]; }
         size_t base = order.size();
@@ -288,13 +287,23 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
             }
         }
     }
-    std::stable_sort(items.begin(), items.end(), [](const ARow &a, const ARow &b) { return a.len > b.len; });
+    {   // counting sort by length, longest first, stable
+        int32_t max_len = 0;
+        for (const ARow &r : items) max_len = std::max(max_len, r.len);
+        std::vector<uint32_t> start((size_t)max_len + 2, 0);
+        for (const ARow &r : items) ++start[(size_t)(max_len - r.len) + 1];
+        for (size_t q = 1; q < start.size(); ++q) start[q] += start[q - 1];
+        std::vector<ARow> sorted(items.size());
+        for (const ARow &r : items) sorted[start[(size_t)(max_len - r.len)]++] = r;
+        items.swap(sorted);
+    }
 
     // one launch per (R, workgroups per compute unit): groups that need little LDS are not
     // held to the occupancy of the heaviest ones
     AClass by_key[5][3];                      // R = 16, 8, 4, 2, 1  x  block 256 / 512 / 1024
     for (int q = 0; q < 5; ++q)
         for (int b = 0; b < 3; ++b) { by_key[q][b].R = 16 >> q; by_key[q][b].kind = kind; }
+    for (int q = 0; q < 5; ++q) by_key[q][1].rows.reserve(items.size() + 16);
     size_t t = 0;
     while (t < items.size()) {
         size_t remaining = items.size() - t;

@@ -40,7 +40,7 @@ constexpr uint32_t kStaticLds = 4096;       // upper bound of the kernels' stati
 struct PlanOptions {
     int64_t lds_budget = 160 * 1024;        // bytes of LDS per workgroup (static + dynamic)
     int force_kind = KIND_AUTO;
-    int max_rows = kMaxR;
+    int max_rows = 8;                       // 16 halves the wavefronts a compute unit can hold
     int split_len = 128;
     int window = 2048;
     int chunks = 0;

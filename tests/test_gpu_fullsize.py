@@ -57,6 +57,7 @@ def test_config2_bag_of_words_tile(spd):
     tile = synth.take_rows(Q, tile_rows)
     dQ, dI = spd.DeviceCsr.from_host(tile), spd.DeviceCsr.from_host(I)
     h = spd.Handle()
+    h.set_option("check_plan", 1)
     out = torch.empty((tile["n_rows"], I["n_rows"]), dtype=torch.float32, device="cuda")
     ra = _extremes_and_sample(tile, 64, rng)
     rb = _extremes_and_sample(I, 2048, rng)
@@ -83,6 +84,7 @@ def test_config3_count_matrix_tile(spd):
     tile = synth.take_rows(M, tile_rows)
     dQ, dM = spd.DeviceCsr.from_host(tile), spd.DeviceCsr.from_host(M)
     h = spd.Handle()
+    h.set_option("check_plan", 1)
     out = torch.empty((tile["n_rows"], M["n_rows"]), dtype=torch.float32, device="cuda")
     heavy_in_tile = np.nonzero(np.isin(tile_rows, heavy))[0]
     ra = _extremes_and_sample(tile, 64, rng, extra=heavy_in_tile)
@@ -108,6 +110,7 @@ def test_config4_binary_knn(spd):
     Q, I = synth.workload(4)
     dQ, dI = spd.DeviceCsr.from_host(Q), spd.DeviceCsr.from_host(I)
     h = spd.Handle()
+    h.set_option("check_plan", 1)
     rng = np.random.default_rng(4)
     rq = _extremes_and_sample(Q, 24, rng)
     plan = spd.host_plan_summary(Q["indptr"], I["indptr"], Q["n_cols"], "jaccard", k_neighbors=32)

@@ -19,6 +19,7 @@ def spd():
 @pytest.fixture()
 def handle(spd):
     h = spd.Handle()
+    h.set_option("check_plan", 1)
     yield h
     h.close()
 

@@ -113,7 +113,7 @@ def test_planner_paths_and_thresholds():
         assert all(c["kind"] == kind for c in s["classes"])
     small, _ = synth.workload(0)
     s = spd.host_plan_summary(small["indptr"], small["indptr"], small["n_cols"], "l1")
-    assert [c["kind"] for c in s["classes"]] == [1] and s["classes"][0]["R"] == 16
+    assert [c["kind"] for c in s["classes"]] == [1] and s["classes"][0]["R"] == 8
     # a tight LDS budget forces slices (partitions) of the long rows
     s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "l1", force_kind=3, lds_budget=16384)
     assert s["spilled_rows"] > 0 and s["partial_slots"] >= 2 * s["spilled_rows"]
