@@ -30,7 +30,11 @@ struct spd_handle {
     size_t own_ws_bytes = 0;
     int32_t *flag = nullptr;     // device word for spd_csr_validate
     bool profile = false;
-    bool check_plan = false;     // full consistency check of every plan before launching
+    bool check_plan = false;
+    bool multi_stream = false;   // option "side_streams": small launches run beside the large one
+    static constexpr int kSideStreams = 3;
+    hipStream_t side[kSideStreams] = {nullptr, nullptr, nullptr};
+    hipEvent_t fork_event = nullptr, join_event[kSideStreams] = {nullptr, nullptr, nullptr};     // full consistency check of every plan before launching
     struct Timed { spd_kernel_time rec; hipEvent_t start, stop; };
     std::vector<Timed> timed;    // launches of the last call (profile mode)
     std::vector<hipEvent_t> event_pool;
@@ -133,8 +137,10 @@ struct LaunchTimer {
     spd_handle *h;
     bool on;
     spd_handle::Timed t;
-    LaunchTimer(spd_handle *hh, const char *name, int R, int kind, int block, uint32_t lds, int64_t a_rows, int64_t wgs)
-        : h(hh), on(hh->profile) {
+    hipStream_t stream;
+    LaunchTimer(spd_handle *hh, const char *name, int R, int kind, int block, uint32_t lds, int64_t a_rows, int64_t wgs,
+                hipStream_t st = nullptr)
+        : h(hh), on(hh->profile), stream(st ? st : hh->stream) {
         if (!on) return;
         std::memset(&t.rec, 0, sizeof t.rec);
         std::snprintf(t.rec.name, sizeof t.rec.name, "%s", name);
@@ -145,11 +151,11 @@ struct LaunchTimer {
             return hipEventCreate(&e) == hipSuccess;
         };
         if (!get(t.start) || !get(t.stop)) { on = false; return; }
-        (void)hipEventRecord(t.start, h->stream);
+        (void)hipEventRecord(t.start, stream);
     }
     void done() {
         if (!on) return;
-        (void)hipEventRecord(t.stop, h->stream);
+        (void)hipEventRecord(t.stop, stream);
         h->timed.push_back(t);
     }
 };
@@ -324,7 +330,43 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         lt.done();
     }
 
-    for (size_t ci = 0; ci < ap.classes.size(); ++ci) {
+    // The launch with the most work stays on the caller's stream; the others go round-robin
+    // to side streams that fork after the repack and join before whatever follows, so that
+    // launches too small to fill the chip overlap with the large one.
+    size_t main_class = 0;
+    std::vector<int> lane_of(ap.classes.size(), -1);        // -1: caller's stream
+    int side_used = 0;
+    {
+        int64_t best = -1;
+        for (size_t ci = 0; ci < ap.classes.size(); ++ci) {
+            int64_t work = (int64_t)ap.classes[ci].n_groups * ap.classes[ci].R;
+            if (work > best) { best = work; main_class = ci; }
+        }
+        if (h->multi_stream && ap.classes.size() > 1) {
+            for (int q = 0; q < spd_handle::kSideStreams; ++q) {
+                if (!h->side[q] && hipStreamCreateWithFlags(&h->side[q], hipStreamNonBlocking) != hipSuccess) { h->side[q] = nullptr; break; }
+                if (!h->join_event[q] && hipEventCreateWithFlags(&h->join_event[q], hipEventDisableTiming) != hipSuccess) break;
+                side_used = q + 1;
+            }
+            if (!h->fork_event && hipEventCreateWithFlags(&h->fork_event, hipEventDisableTiming) != hipSuccess) side_used = 0;
+        }
+        if (side_used > 0) {
+            e = hipEventRecord(h->fork_event, h->stream);
+            if (e != hipSuccess) return hip_fail(h, e, "hipEventRecord");
+            for (int q = 0; q < side_used; ++q) {
+                e = hipStreamWaitEvent(h->side[q], h->fork_event, 0);
+                if (e != hipSuccess) return hip_fail(h, e, "hipStreamWaitEvent");
+            }
+            int next = 0;
+            for (size_t ci = 0; ci < ap.classes.size(); ++ci)
+                if (ci != main_class) { lane_of[ci] = next; next = (next + 1) % side_used; }
+        }
+    }
+    std::vector<size_t> launch_order;
+    for (size_t ci = 0; ci < ap.classes.size(); ++ci) if (ci != main_class) launch_order.push_back(ci);
+    if (!ap.classes.empty()) launch_order.push_back(main_class);
+    for (size_t ci : launch_order) {
+        hipStream_t st_launch = lane_of[ci] >= 0 ? h->side[lane_of[ci]] : h->stream;
         const AClass &c = ap.classes[ci];
         ScanArgs sa;
         sa.a_indices = A->indices;
@@ -352,10 +394,18 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         sa.knn_row_off = reinterpret_cast<const int64_t *>(ws + o_knn_off);
         int64_t live_rows = 0;
         for (const ARow &r : c.rows) live_rows += (r.out != -1);
-        LaunchTimer lt(h, "scan", c.R, c.kind, c.block, c.lds_bytes, live_rows, (int64_t)c.n_groups * c.n_chunks);
-        e = launch_scan(h->stream, mi.op, c.R, c.block, c.lds_bytes, sa);
+        LaunchTimer lt(h, "scan", c.R, c.kind, c.block, c.lds_bytes, live_rows, (int64_t)c.n_groups * c.n_chunks,
+                       st_launch);
+        e = launch_scan(st_launch, mi.op, c.R, c.block, c.lds_bytes, sa);
         if (e != hipSuccess) return hip_fail(h, e, "scan kernel");
         lt.done();
+    }
+
+    for (int q = 0; q < side_used; ++q) {
+        e = hipEventRecord(h->join_event[q], h->side[q]);
+        if (e != hipSuccess) return hip_fail(h, e, "hipEventRecord");
+        e = hipStreamWaitEvent(h->stream, h->join_event[q], 0);
+        if (e != hipSuccess) return hip_fail(h, e, "hipStreamWaitEvent");
     }
 
     if (!ap.spilled.empty()) {
@@ -424,6 +474,11 @@ spd_status spd_destroy(spd_handle *h) {
     if (h->flag) (void)hipFree(h->flag);
     for (auto &t : h->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
     for (hipEvent_t ev : h->event_pool) (void)hipEventDestroy(ev);
+    for (int q = 0; q < spd_handle::kSideStreams; ++q) {
+        if (h->side[q]) { (void)hipStreamSynchronize(h->side[q]); (void)hipStreamDestroy(h->side[q]); }
+        if (h->join_event[q]) (void)hipEventDestroy(h->join_event[q]);
+    }
+    if (h->fork_event) (void)hipEventDestroy(h->fork_event);
     delete h;
     return SPD_OK;
 }
@@ -550,6 +605,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "chunks") {
         if (value < 0 || value > 4096) return fail(h, SPD_ERR_UNSUPPORTED, "chunks must lie in [0, 4096]");
         o.chunks = (int)value;
+    } else if (s == "side_streams") {
+        if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must be 0 or 1");
+        h->multi_stream = value != 0;
     } else if (s == "check_plan") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "check_plan must be 0 or 1");
         h->check_plan = value != 0;
