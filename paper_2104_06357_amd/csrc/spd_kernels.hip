@@ -118,7 +118,7 @@ __global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArg
             d = finalize_one(a, sr, j, na0, na1);
             if (a.q.metric == MT_INNER) d = -d;
         }
-        list.offer(d, (int)j, valid, kk);
+        list.offer(d, (int)j, valid, kk, __builtin_huge_valf());
     }
     if (lane < kk) s_area[wave * kk + lane] = KnnEntry{list.d, list.j};
     __syncthreads();
@@ -132,7 +132,7 @@ __global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArg
             KnnEntry c = KnnEntry{0.f, 0};
             if (valid) c = s_area[e];
             valid = valid && c.j != 0x7fffffff;
-            merged.offer(c.d, c.j, valid, kk);
+            merged.offer(c.d, c.j, valid, kk, __builtin_huge_valf());
         }
         if (lane < kk) {
             a.out_idx[(size_t)sr.row * kk + lane] = (int64_t)merged.j;
@@ -175,7 +175,7 @@ __global__ void __launch_bounds__(256) spd_knn_merge_kernel(const KnnEntry *__re
         KnnEntry c = KnnEntry{0.f, 0};
         if (valid) c = src[e];
         valid = valid && c.j != 0x7fffffff;
-        merged.offer(c.d, c.j, valid, k);
+        merged.offer(c.d, c.j, valid, k, __builtin_huge_valf());
     }
     if (lane < k) {
         out_idx[(size_t)row * k + lane] = (int64_t)merged.j;

@@ -67,11 +67,41 @@ struct OpParams {
     int metric;
 };
 
+// log2, exp2 and x/y as the kernels use them: the hardware's transcendental units on the device
+// (v_log_f32, v_exp_f32, v_rcp_f32: about 1 ulp, far inside the 1e-4 tolerance), libm on the
+// host (test hooks only).
+SPD_HD float fast_log2(float x) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_logf(x);
+#else
+    return log2f(x);
+#endif
+}
+SPD_HD float fast_exp2(float x) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_exp2f(x);
+#else
+    return exp2f(x);
+#endif
+}
+SPD_HD float fast_div(float x, float y) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return x * __builtin_amdgcn_rcpf(y);
+#else
+    return x / y;
+#endif
+}
+
 // |v|^p in fp32.  The same function feeds the row norm F and the per-visit product, so
-// the terms that have to cancel are bit-identical (pow_abs(0) == 0).
+// the terms that have to cancel are bit-identical (pow_abs(0) == 0).  Small integer
+// degrees are plain products.
 SPD_HD float pow_abs(float v, float p) {
     float a = fabsf(v);
-    return a == 0.0f ? 0.0f : exp2f(p * log2f(a));
+    if (p == 1.0f) return a;
+    if (p == 2.0f) return a * a;
+    if (p == 3.0f) return a * a * a;
+    if (p == 4.0f) { float q = a * a; return q * q; }
+    return a == 0.0f ? 0.0f : fast_exp2(p * fast_log2(a));
 }
 
 SPD_HD float transform_value(int tr, float v) {
@@ -166,7 +196,7 @@ template <> struct Op<OP_CANB> {
     SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
         bool hit = (a != 0.0f) && (b.b != 0.0f);
-        float ratio = fabsf(a - b.b) / (fabsf(a) + fabsf(b.b));   // NaN only when !hit
+        float ratio = fast_div(fabsf(a - b.b), hit ? fabsf(a) + fabsf(b.b) : 1.0f);
         x.v += hit ? (double)ratio - 2.0 : 0.0;                   // each one-sided column counts 1
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
@@ -190,6 +220,8 @@ template <> struct Op<OP_HAMM> {
     SPD_HD static double v2(const Acc &) { return 0.0; }
 };
 
+// KL: a log(a/b) = ln 2 * a log2(a/b) on shared columns, with a correctly rounded quotient so
+// that equal entries give exactly 0; the factor ln 2 is applied once, by finish().
 template <> struct Op<OP_KL> {
     struct Acc { double v; };
     struct Bv { float b; };
@@ -197,7 +229,7 @@ template <> struct Op<OP_KL> {
     SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
         bool hit = (a > 0.0f) && (b.b > 0.0f);
-        float t = a * logf(hit ? a / b.b : 1.0f);
+        float t = a * fast_log2(hit ? a / b.b : 1.0f);
         x.v += hit ? (double)t : 0.0;
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
@@ -206,9 +238,12 @@ template <> struct Op<OP_KL> {
     SPD_HD static double v2(const Acc &) { return 0.0; }
 };
 
-// Jensen-Shannon: f(a,b) = a log(2a/(a+b)) + b log(2b/(a+b)) on shared columns (exactly 0
-// for a == b); a one-sided column adds its value times log 2, which the finish step takes
-// from the row sums minus `s`, the sum of the values seen on shared columns.
+// Jensen-Shannon: on a shared column, with u = a/(a+b),
+//   a log(2a/(a+b)) + b log(2b/(a+b)) = ln 2 [ a log2(2u) + b log2(2(1-u)) ],
+// exactly 0 for a == b (u = 1/2 exactly, 2u = 1) and accurate when a is close to b (the two
+// logarithms are then small and each is formed directly).  The bracket is accumulated; the
+// factor ln 2 is applied by finish().  A one-sided column adds its value times log 2, which
+// finish() takes from the row sums minus `s`, the sum of the values seen on shared columns.
 template <> struct Op<OP_JS> {
     struct Acc { double f, s; };
     struct Bv { float b; double db; };
@@ -216,9 +251,10 @@ template <> struct Op<OP_JS> {
     SPD_HD static Bv prep(float b, const OpParams &) { return {b, (double)b}; }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
         bool hit = (a > 0.0f) && (b.b > 0.0f);
-        float r = hit ? 2.0f / (a + b.b) : 1.0f;
-        float aa = hit ? a : 0.5f, bb = hit ? b.b : 0.5f;
-        float t = aa * logf(aa * r) + bb * logf(bb * r);
+        float aa = hit ? a : 1.0f, bb = hit ? b.b : 1.0f;
+        float sum = aa + bb;
+        float u = aa / sum;                              // correctly rounded: 1/2 for aa == bb
+        float t = aa * fast_log2(2.0f * u) + bb * fast_log2(2.0f * (1.0f - u));
         x.f += hit ? (double)t : 0.0;
         x.s += hit ? (double)a + b.db : 0.0;
     }
@@ -265,11 +301,13 @@ SPD_HD float finish(const OpParams &q, double v, double s, double w, double a0, 
         double one_sided = (w == a1 && w == b1) ? 0.0 : (a0 + b0) - s;
         double t = v + (one_sided > 0.0 ? one_sided : 0.0);
         float tf = (float)t;
-        return tf == 0.0f ? 0.0f : exp2f(q.inv_p * log2f(tf));
+        if (q.p == 1.0f) return tf;
+        if (q.p == 2.0f) return sqrtf(tf);
+        return tf == 0.0f ? 0.0f : fast_exp2(q.inv_p * fast_log2(tf));
     }
     case MT_HAMMING: r = (a0 + b0 + v) / q.k; break;
-    case MT_KL: r = v; break;
-    case MT_JS: { double t = 0.5 * (LN2 * ((a0 + b0) - s) + v); return sqrtf((float)(t > 0.0 ? t : 0.0)); }
+    case MT_KL: r = LN2 * v; break;
+    case MT_JS: { double t = 0.5 * LN2 * (((a0 + b0) - s) + v); return sqrtf((float)(t > 0.0 ? t : 0.0)); }
     case MT_CHEBYSHEV: r = v; break;
     case MT_RUSSELL_RAO: r = (q.k - v) / q.k; break;
     default: r = 0.0; break;

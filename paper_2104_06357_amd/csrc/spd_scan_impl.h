@@ -23,6 +23,18 @@ __device__ __forceinline__ bool lex_less(float d1, int j1, float d2, int j2) {
     return d1 < d2 || (d1 == d2 && j1 < j2);
 }
 
+// Order-preserving map float -> uint32 (for an LDS atomicMin over distances of any sign).
+__device__ __forceinline__ uint32_t float_order_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float float_from_order_key(uint32_t u) {
+    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
+}
+
+// Lane l receives lane l-1's value (lane 0 keeps its own): DPP wavefront shift right by one.
+__device__ __forceinline__ int wave_shr1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x138, 0xf, 0xf, false); }
+
 // Sorted list of the k best (distance, index) pairs of one query row, entry t in lane t.
 // (tau_d, tau_j) caches entry k-1, the bar a candidate has to beat.
 struct KnnList {
@@ -32,24 +44,31 @@ struct KnnList {
         d = tau_d = __builtin_huge_valf();
         j = tau_j = 0x7fffffff;
     }
-    // Every lane may offer one candidate; the list stays sorted by (d, j).
-    __device__ __forceinline__ void offer(float dv, int jv, bool valid, int k) {
-        uint64_t m = __ballot(valid && lex_less(dv, jv, tau_d, tau_j));
-        if (m == 0) return;
+    __device__ __forceinline__ bool full() const { return tau_j != 0x7fffffff; }
+    // Every lane may offer one candidate; the list stays sorted by (d, j).  `bound` is any
+    // upper bound of the final k-th distance known from elsewhere (candidates above it are
+    // dropped unseen).  Returns true if the list changed.
+    __device__ __forceinline__ bool offer(float dv, int jv, bool valid, int k, float bound) {
+        uint64_t m = __ballot(valid && dv <= bound && lex_less(dv, jv, tau_d, tau_j));
+        if (m == 0) return false;
         const int lane = (int)__lane_id();
+        bool changed = false;
         do {
-            int src = wave_uniform((int)__builtin_ctzll(m));
+            const int src = (int)__builtin_ctzll(m);                 // wavefront-uniform
             m &= m - 1;
-            float x = __shfl(dv, src);
-            int xj = __shfl(jv, src);
-            int pos = (int)__popcll(__ballot(lex_less(d, j, x, xj)));   // sorted: a prefix
-            float sd = __shfl_up(d, 1);
-            int sj = __shfl_up(j, 1);
+            const float x = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(dv), src));
+            const int xj = __builtin_amdgcn_readlane(jv, src);
+            if (!lex_less(x, xj, tau_d, tau_j)) continue;            // the list improved meanwhile
+            const int pos = (int)__popcll(__ballot(lex_less(d, j, x, xj)));   // sorted: a prefix
+            const float sd = __int_as_float(wave_shr1(__float_as_int(d)));
+            const int sj = wave_shr1(j);
             if (lane > pos) { d = sd; j = sj; }
             else if (lane == pos) { d = x; j = xj; }
+            tau_d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d), k - 1));
+            tau_j = __builtin_amdgcn_readlane(j, k - 1);
+            changed = true;
         } while (m);
-        tau_d = __shfl(d, k - 1);
-        tau_j = __shfl(j, k - 1);
+        return changed;
     }
 };
 
@@ -135,6 +154,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     __shared__ uint32_t s_prefix[R + 1];
     __shared__ double s_na[R][2];
     __shared__ int s_ctr;
+    __shared__ uint32_t s_tau[KNN ? R : 1];      // k-NN: smallest k-th distance any wavefront holds, per row
     __shared__ float s_top[kCheb ? R * kTopRanks : 1];
     __shared__ int s_topn[R];
     __shared__ uint32_t s_clo[kCheb ? R : 1], s_cspan[kCheb ? R : 1];   // column range a slice answers for
@@ -207,6 +227,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         for (int r = 0; r < R; ++r) { s_prefix[r] = acc; acc += (uint32_t)s_rows[r].len; }
         s_prefix[R] = acc;
         s_ctr = slab_begin;
+    }
+    if constexpr (KNN) {
+        if (tid < R) s_tau[tid] = float_order_key(__builtin_huge_valf());
     }
     // 2. row norms: one wavefront per row, summed in a fixed order (Section 3.4)
     for (int r = wave; r < R; r += nw) {
@@ -450,7 +473,10 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                     if (leader) args.out[(size_t)out * (size_t)n_b + (size_t)row] = d;
                 } else {
                     if (args.q.metric == MT_INNER) d = -d;
-                    lists[r].offer(d, row, leader, args.knn_k);
+                    // a full list of any wavefront bounds the workgroup's k-th distance from above
+                    const float bound = float_from_order_key(s_tau[r]);
+                    if (lists[r].offer(d, row, leader, args.knn_k, bound) && lists[r].full() && lane == 0)
+                        atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
                 }
             } else if (leader) {
                 const size_t slot = (size_t)(-2 - out);
@@ -482,7 +508,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                 KnnEntry c = KnnEntry{0.f, 0};
                 if (valid) c = area[((size_t)(e / kk) * R + r) * kk + (e % kk)];
                 valid = valid && c.j != 0x7fffffff;
-                merged.offer(c.d, c.j, valid, kk);
+                merged.offer(c.d, c.j, valid, kk, __builtin_huge_valf());
             }
             if (lane < kk)
                 args.knn_part[args.knn_row_off[out] + (size_t)chunk * kk + lane] = KnnEntry{merged.d, merged.j};
