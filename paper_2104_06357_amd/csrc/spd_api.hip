@@ -381,6 +381,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         sa.b = bd;
         sa.q = q;
         sa.kind = c.kind;
+        sa.hscale = c.hscale;
         sa.transform = mi.transform;
         sa.norm = mi.norm;
         sa.k = (uint32_t)A->n_cols;
@@ -508,7 +509,7 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     // padded slabs: at most 64 idle entries per step of the longest row of each window, one per
     // lane of a split row, and the rounding of each group of split rows
     size_t padded = (size_t)B->nnz + (size_t)B->nnz * 64 / (size_t)std::max(2, o.split_len) +
-                    64 * (size_t)std::max(2, o.split_len) * (n / window + 8) + 64 * slabs;
+                    64 * (size_t)std::max(2, o.split_len) * (n / window + 8) + 64 * (size_t)kScanUnroll * slabs;
     add(padded * 8); add(n * 16); add((slabs + 1) * 8); add(slabs * 4); add(slabs);
     add(lanes * 8); add(lanes * 4); add(lanes * 4); add(lanes); add(chunk_words * 4); total += launches * 256;
     add((m + slices + 16 * 6) * sizeof(ARow)); add((m + slices + 6) * 4); total += 12 * 256;

@@ -40,6 +40,7 @@ struct ScanArgs {
     // what to compute
     OpParams q;
     int32_t kind, transform, norm;
+    int32_t hscale;               // hash staging: log2 of table entries per staged entry
     uint32_t k;                   // columns
     uint32_t padcol;              // column an idle lane looks up (maps to the zero row)
     // results

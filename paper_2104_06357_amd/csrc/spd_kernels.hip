@@ -116,7 +116,7 @@ __global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArg
         float d = 0.f;
         if (valid) {
             d = finalize_one(a, sr, j, na0, na1);
-            if (a.q.metric == MT_INNER) d = -d;
+            if (a.q.metric == MT_INNER) d = 0.0f - d;
         }
         list.offer(d, (int)j, valid, kk, __builtin_huge_valf());
     }

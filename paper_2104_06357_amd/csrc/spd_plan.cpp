@@ -123,10 +123,12 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     out.slab_base.assign((size_t)n_slabs + 1, 0);
     out.slab_steps.assign((size_t)n_slabs, 0);
     // a slab stores steps x 64 entries: entry t of lane l at slab_base + t*64 + l, lanes whose
-    // segment is shorter are padded with a column that no row stages
+    // segment is shorter are padded with a column that no row stages; steps is a whole
+    // number of scan blocks
     for (int64_t s = 0; s < n_slabs; ++s) {
         int32_t mx = 0;
         for (int l = 0; l < kWave; ++l) mx = std::max(mx, out.seg_len[(size_t)s * kWave + l]);
+        mx = (mx + kScanUnroll - 1) / kScanUnroll * kScanUnroll;
         out.slab_base[(size_t)s + 1] = out.slab_base[(size_t)s] + (int64_t)mx * kWave;
         out.slab_steps[(size_t)s] = mx;
     }
@@ -179,7 +181,7 @@ bool staging_fits(int kind, int R, uint64_t sumlen, uint32_t k, bool cheb, int64
     if (kind != KIND_STRIP && sumlen > 65534u) return false;      // 16-bit slot ids
     uint64_t nslots = (kind == KIND_STRIP) ? (uint64_t)k + 1u : sumlen + 1u;
     if (nslots * (uint64_t)R * 5u > (uint64_t)budget) return false;   // also keeps the 32-bit layout math safe
-    LdsLayout L = lds_layout(kind, R, (uint32_t)sumlen, k, cheb);
+    LdsLayout L = lds_layout(kind, R, (uint32_t)sumlen, k, cheb, 1);
     return (int64_t)L.total <= budget;
 }
 
@@ -241,9 +243,23 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     auto fits = [&](int kd, int R, uint64_t sumlen) { return staging_fits(kd, R, sumlen, k, cheb, budget); };
 
     auto finish_class = [&](AClass &c) {
-        uint32_t need = 0;
-        for (int g = 0; g < c.n_groups; ++g)
-            need = std::max(need, lds_layout(c.kind, c.R, (uint32_t)c.sumlen[(size_t)g], k, cheb).total);
+        auto need_at = [&](int hs) {
+            uint32_t need = 0;
+            for (int g = 0; g < c.n_groups; ++g)
+                need = std::max(need, lds_layout(c.kind, c.R, (uint32_t)c.sumlen[(size_t)g], k, cheb, hs).total);
+            return need;
+        };
+        uint32_t need = need_at(1);
+        c.hscale = 1;
+        if (c.kind == KIND_HASH) {
+            // a sparser table shortens the probe sequences: take the sparsest one that
+            // leaves the launch as many workgroups per compute unit as it has now
+            const int now = block_for(need, opt.lds_budget);
+            for (int hs = 3; hs >= 2; --hs) {
+                uint32_t wider = need_at(hs);
+                if ((int64_t)wider <= budget && block_for(wider, opt.lds_budget) == now) { c.hscale = hs; need = wider; break; }
+            }
+        }
         c.block = std::min(block_for(need, opt.lds_budget), scan_max_block(metric_info(metric).op, c.R, knn_k > 0));
         if (knn_k > 0) {
             while (c.block > kWave && (int64_t)knn_merge_bytes(c.block, c.R, knn_k) > budget) c.block /= 2;
@@ -317,7 +333,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 if (!fits(kind, R, sum)) return "internal: slice does not fit";
                 int ci = 0;
                 while ((16 >> ci) != R) ++ci;
-                uint32_t need = lds_layout(kind, R, (uint32_t)sum, k, cheb).total;
+                uint32_t need = lds_layout(kind, R, (uint32_t)sum, k, cheb, 1).total;
                 int blk = block_for(need, opt.lds_budget);
                 AClass &c = by_key[ci][blk == 256 ? 0 : (blk == 512 ? 1 : 2)];
                 for (int q = 0; q < R; ++q)
@@ -377,7 +393,9 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
                 }
             }
             if (sum != c.sumlen[(size_t)g]) return "group sumlen";
-            LdsLayout L = lds_layout(c.kind, c.R, (uint32_t)sum, (uint32_t)n_cols, cheb);
+            if (c.hscale < 1 || c.hscale > 3) return "class hash scale";
+            LdsLayout L = lds_layout(c.kind, c.R, (uint32_t)sum, (uint32_t)n_cols, cheb, c.hscale);
+            if (c.kind == KIND_HASH && (L.cap < 2u * (uint32_t)sum || L.cap < 16u)) return "hash table too full";
             if (L.total > c.lds_bytes) return "group LDS over the launch size";
             if (c.kind != KIND_STRIP && L.nslots > 65535u) return "slot ids over 16 bits";
         }
@@ -425,6 +443,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
             next[(size_t)j] += len;
             if ((l & (G - 1)) == G - 1 && next[(size_t)j] != b_indptr[j + 1]) return "B segments do not cover the row";
         }
+        mx = (mx + kScanUnroll - 1) / kScanUnroll * kScanUnroll;
         if (b.slab_base[(size_t)s + 1] - b.slab_base[(size_t)s] != (int64_t)mx * kWave || b.slab_steps[(size_t)s] != mx)
             return "B slab sizes";
         total_entries += sum;

@@ -31,6 +31,7 @@ namespace spd {
 enum StageKind { KIND_AUTO = 0, KIND_STRIP = 1, KIND_SLOT = 2, KIND_HASH = 3 };
 
 constexpr int kWave = 64;
+constexpr int kScanUnroll = 4;              // a slab is scanned in blocks of this many steps
 constexpr int kMaxR = 16;
 constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
 constexpr int kKnnMaxK = 64;                // fused k-NN: one list entry per lane
@@ -61,7 +62,7 @@ SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
 // and carves the buffer in the kernel.
 struct LdsLayout {
     uint32_t nslots;     // rows of the value table (R floats each)
-    uint32_t cap;        // hash capacity (power of two), 0 otherwise
+    uint32_t cap;        // hash capacity in entries (power of two, two entries per bucket), 0 otherwise
     uint32_t off_vals, off_map, off_rank, total;
 };
 
@@ -71,7 +72,8 @@ SPD_HD uint32_t pow2_at_least(uint32_t v) {
     return c;
 }
 
-SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool cheb) {
+// `hscale`: the hash table holds at least sumlen << hscale entries (1..3: load <= 1/2, 1/4, 1/8).
+SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool cheb, int hscale) {
     LdsLayout L;
     L.cap = 0;
     L.nslots = (kind == KIND_STRIP) ? k + 1u : sumlen + 1u;
@@ -82,7 +84,7 @@ SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool c
     if (kind == KIND_SLOT) {
         off += ((k + 1u) * 2u + 15u) & ~15u;
     } else if (kind == KIND_HASH) {
-        L.cap = pow2_at_least(2u * sumlen);
+        L.cap = pow2_at_least(sumlen << hscale);
         off += L.cap * 8u;
     }
     L.off_rank = off;
@@ -105,6 +107,7 @@ constexpr uint32_t kRowFirst = 1u, kRowLast = 2u;
 struct AClass {
     int R = 0;
     int kind = 0;
+    int hscale = 1;             // KIND_HASH: log2 of table entries per staged entry
     int block = 0;              // threads per workgroup
     uint32_t lds_bytes = 0;     // dynamic LDS of the launch (max over its groups)
     int n_groups = 0;
@@ -127,7 +130,7 @@ struct BPlan {
     int64_t n_rows = 0, nnz = 0;
     int32_t n_slabs = 0;
     std::vector<int64_t> slab_base;    // n_slabs + 1, offsets into the packed entries (64 * steps each)
-    std::vector<int32_t> slab_steps;   // n_slabs, longest segment of the slab
+    std::vector<int32_t> slab_steps;   // n_slabs, longest segment of the slab rounded up to whole blocks
     std::vector<uint8_t> slab_split;   // n_slabs, 1 if the slab holds split rows
     std::vector<int64_t> seg_start;    // n_slabs*64, first CSR element of the lane's segment
     std::vector<int32_t> seg_len;      // n_slabs*64

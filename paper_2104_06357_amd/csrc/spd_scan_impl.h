@@ -35,6 +35,69 @@ __device__ __forceinline__ float float_from_order_key(uint32_t u) {
 // Lane l receives lane l-1's value (lane 0 keeps its own): DPP wavefront shift right by one.
 __device__ __forceinline__ int wave_shr1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x138, 0xf, 0xf, false); }
 
+// (distance, index) as one integer whose order is the lexicographic order of the pair.
+__device__ __forceinline__ uint64_t knn_key(float d, int j) {
+    return ((uint64_t)float_order_key(d + 0.0f) << 32) | (uint32_t)j;     // -0 counts as +0
+}
+constexpr int kKnnBulkFrom = 8;     // candidates in one offer from which they are sorted rather than inserted one by one
+
+// Lanes whose bit is set keep the smaller key of a compare-exchange at distance J while
+// blocks of K lanes are being merged (K = 128: every block ascending).
+constexpr uint64_t bitonic_keep_min(int K, int J, bool descending) {
+    uint64_t m = 0;
+    for (int l = 0; l < 64; ++l) {
+        bool up = ((l & K) == 0) != descending;
+        if (((l & J) == 0) == up) m |= (uint64_t)1 << l;
+    }
+    return m;
+}
+
+// Value of lane l ^ J.  Within a row of 16 lanes the exchange is a DPP move (no trip through
+// the LDS crossbar): quad permutes for 1 and 2, a rotation by 8, and for 4 two shifts that
+// each write the banks of four lanes they are right for.
+template <int J> __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
+    const int x = (int)v;
+    if constexpr (J == 1) return (uint32_t)__builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, false);        // quad_perm [1,0,3,2]
+    else if constexpr (J == 2) return (uint32_t)__builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+    else if constexpr (J == 4) {
+        int t = __builtin_amdgcn_mov_dpp(x, 0x104, 0xf, 0x5, false);             // row_shl:4 -> lanes 0-3, 8-11 read l+4
+        return (uint32_t)__builtin_amdgcn_update_dpp(t, x, 0x114, 0xf, 0xA, false);   // row_shr:4 -> lanes 4-7, 12-15 read l-4
+    } else if constexpr (J == 8) return (uint32_t)__builtin_amdgcn_mov_dpp(x, 0x128, 0xf, 0xf, false);  // row_ror:8
+    else return (uint32_t)__shfl_xor(x, J);
+}
+
+template <int K, int J, bool DESC> __device__ __forceinline__ uint64_t bitonic_step(uint64_t mine, int lane) {
+    constexpr uint64_t keep = bitonic_keep_min(K, J, DESC);
+    const uint32_t lo = lane_xor<J>((uint32_t)mine);
+    const uint32_t hi = lane_xor<J>((uint32_t)(mine >> 32));
+    const uint64_t other = ((uint64_t)hi << 32) | lo;
+    // take the other key where (other < mine) == keep: the lane pattern is a constant mask
+    (void)lane;
+    const bool take = __builtin_amdgcn_inverse_ballot_w64(__builtin_amdgcn_ballot_w64(other < mine) ^ ~keep);
+    return take ? other : mine;
+}
+
+// Sorts one key per lane over the wavefront, descending (bitonic network, 21 steps).
+__device__ __forceinline__ uint64_t wave_sort_desc(uint64_t x, int lane) {
+    x = bitonic_step<2, 1, true>(x, lane);
+    x = bitonic_step<4, 2, true>(x, lane);  x = bitonic_step<4, 1, true>(x, lane);
+    x = bitonic_step<8, 4, true>(x, lane);  x = bitonic_step<8, 2, true>(x, lane);  x = bitonic_step<8, 1, true>(x, lane);
+    x = bitonic_step<16, 8, true>(x, lane); x = bitonic_step<16, 4, true>(x, lane); x = bitonic_step<16, 2, true>(x, lane);
+    x = bitonic_step<16, 1, true>(x, lane);
+    x = bitonic_step<32, 16, true>(x, lane); x = bitonic_step<32, 8, true>(x, lane); x = bitonic_step<32, 4, true>(x, lane);
+    x = bitonic_step<32, 2, true>(x, lane);  x = bitonic_step<32, 1, true>(x, lane);
+    x = bitonic_step<64, 32, true>(x, lane); x = bitonic_step<64, 16, true>(x, lane); x = bitonic_step<64, 8, true>(x, lane);
+    x = bitonic_step<64, 4, true>(x, lane);  x = bitonic_step<64, 2, true>(x, lane);  x = bitonic_step<64, 1, true>(x, lane);
+    return x;
+}
+// Sorts a bitonic sequence of 64 keys ascending (6 steps).
+__device__ __forceinline__ uint64_t wave_merge_asc(uint64_t x, int lane) {
+    x = bitonic_step<128, 32, false>(x, lane); x = bitonic_step<128, 16, false>(x, lane);
+    x = bitonic_step<128, 8, false>(x, lane);  x = bitonic_step<128, 4, false>(x, lane);
+    x = bitonic_step<128, 2, false>(x, lane);  x = bitonic_step<128, 1, false>(x, lane);
+    return x;
+}
+
 // Sorted list of the k best (distance, index) pairs of one query row, entry t in lane t.
 // (tau_d, tau_j) caches entry k-1, the bar a candidate has to beat.
 struct KnnList {
@@ -49,9 +112,24 @@ struct KnnList {
     // upper bound of the final k-th distance known from elsewhere (candidates above it are
     // dropped unseen).  Returns true if the list changed.
     __device__ __forceinline__ bool offer(float dv, int jv, bool valid, int k, float bound) {
-        uint64_t m = __ballot(valid && dv <= bound && lex_less(dv, jv, tau_d, tau_j));
+        const bool pass = valid && dv <= bound && lex_less(dv, jv, tau_d, tau_j);
+        uint64_t m = __ballot(pass);
         if (m == 0) return false;
         const int lane = (int)__lane_id();
+        if (__popcll(m) >= kKnnBulkFrom) {
+            // many candidates: sort them descending, take the lane-wise minimum with the
+            // ascending list (the 64 smallest of both, a bitonic sequence), sort that
+            const uint64_t unused = knn_key(__builtin_huge_valf(), 0x7fffffff);
+            uint64_t c = wave_sort_desc(pass ? knn_key(dv, jv) : unused, lane);
+            const uint64_t mine = knn_key(d, j);
+            c = wave_merge_asc(c < mine ? c : mine, lane);
+            if (lane >= k) c = unused;
+            d = float_from_order_key((uint32_t)(c >> 32));
+            j = (int)(uint32_t)c;
+            tau_d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d), k - 1));
+            tau_j = __builtin_amdgcn_readlane(j, k - 1);
+            return true;
+        }
         bool changed = false;
         do {
             const int src = (int)__builtin_ctzll(m);                 // wavefront-uniform
@@ -97,16 +175,21 @@ template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const 
 // ------------------------------------------------------------------------------------
 // column -> slot of the staged value table
 // ------------------------------------------------------------------------------------
+// The hash table is an array of buckets of two {column, slot} entries, read with one
+// 16-byte LDS load.  An entry is claimed in the first free place of its home bucket, else
+// of the next bucket, and entries are never removed: a bucket whose second place is empty
+// ends every probe sequence that reaches it.
 template <int KIND> struct ColumnMap {
     const uint16_t *slot16;   // KIND_SLOT: k+1 entries
-    const uint2 *table;       // KIND_HASH: {column, slot}, empty = {kEmptyKey, 0}
-    uint32_t mask, shift;
+    const uint4 *table;       // KIND_HASH: buckets {column, slot, column, slot}, empty = {kEmptyKey, 0}
+    uint32_t mask, shift;     // over buckets
     __device__ __forceinline__ uint32_t home(uint32_t c) const { return (c * 0x9E3779B1u) >> shift; }
-    // Continues a hash lookup whose first probe `e` (at `h`) did not settle it.
-    __device__ __forceinline__ uint32_t resolve(uint32_t c, uint32_t h, uint2 e) const {
+    // Continues a hash lookup from its first bucket `e` (at `h`).
+    __device__ __forceinline__ uint32_t resolve(uint32_t c, uint32_t h, uint4 e) const {
         for (;;) {
             if (e.x == c) return e.y;          // the idle column is the empty key: slot 0
-            if (e.x == kEmptyKey) return 0u;
+            if (e.z == c) return e.w;
+            if (e.z == kEmptyKey) return 0u;
             h = (h + 1u) & mask;
             e = table[h];
         }
@@ -138,7 +221,6 @@ template <int R> __device__ __forceinline__ RowVals<R> load_vals(const float *va
     return out;
 }
 
-constexpr int kScanUnroll = 4;     // steps of a slab fetched ahead as one block
 
 // ------------------------------------------------------------------------------------
 // the kernel
@@ -191,16 +273,16 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 
     if (tid < R) s_rows[tid] = args.arows[(size_t)g * R + tid];
     const uint32_t sumlen = (uint32_t)args.sumlen[g];
-    const LdsLayout L = lds_layout(KIND, R, sumlen, args.k, kCheb);
+    const LdsLayout L = lds_layout(KIND, R, sumlen, args.k, kCheb, args.hscale);
     float *vals = reinterpret_cast<float *>(dyn + L.off_vals);
     uint16_t *slot16 = reinterpret_cast<uint16_t *>(dyn + L.off_map);
-    uint2 *table = reinterpret_cast<uint2 *>(dyn + L.off_map);
+    uint4 *table = reinterpret_cast<uint4 *>(dyn + L.off_map);
     unsigned char *rank8 = dyn + L.off_rank;
     ColumnMap<KIND> cmap;
     cmap.slot16 = slot16;
     cmap.table = table;
-    cmap.mask = L.cap ? L.cap - 1u : 0u;
-    cmap.shift = L.cap ? 32u - (uint32_t)__builtin_ctz(L.cap) : 0u;
+    cmap.mask = L.cap ? L.cap / 2u - 1u : 0u;
+    cmap.shift = L.cap ? 33u - (uint32_t)__builtin_ctz(L.cap) : 0u;
 
     // ---- stage ------------------------------------------------------------------------
     // 1. clear the value table and the column map
@@ -213,7 +295,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
             uint32_t *m32 = reinterpret_cast<uint32_t *>(slot16);
             for (uint32_t i = tid; i < nw32; i += nthr) m32[i] = 0u;
         } else if constexpr (KIND == KIND_HASH) {
-            for (uint32_t i = tid; i < L.cap; i += nthr) table[i] = make_uint2(kEmptyKey, 0u);
+            for (uint32_t i = tid; i < L.cap / 2u; i += nthr) table[i] = make_uint4(kEmptyKey, 0u, kEmptyKey, 0u);
         }
         if constexpr (kCheb) {
             uint32_t nr4 = (L.nslots * R + 3u) / 4u;
@@ -270,6 +352,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                     for (;;) {
                         uint32_t old = atomicCAS(&table[h].x, kEmptyKey, c);
                         if (old == kEmptyKey) { table[h].y = e + 1u; break; }
+                        if (old == c) break;
+                        old = atomicCAS(&table[h].z, kEmptyKey, c);
+                        if (old == kEmptyKey) { table[h].w = e + 1u; break; }
                         if (old == c) break;
                         h = (h + 1u) & cmap.mask;
                     }
@@ -362,15 +447,14 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 #pragma unroll
         for (int r = 0; r < R; ++r) { O::init(acc[r]); if constexpr (kCheb) hit[r] = 0u; }
 
-        // Entry t of lane l sits at pk[t*64 + l]: one coalesced load per step, fetched U steps
-        // ahead of its use (past the slab's end the last step is simply read again).
+        // Entry t of lane l sits at pk[t*64 + l]: one coalesced load per step, fetched a block
+        // of U steps ahead of its use.  The plan pads every slab to whole blocks (with the
+        // column that stages nothing), so the loop has no tail.
         uint2 nxt[U];
         auto fetch_block = [&](int t_first) {
+            const uint2 *__restrict__ src = pk + (size_t)t_first * kWave;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = min(t_first + u, steps - 1);
-                nxt[u] = pk[(size_t)t * kWave];
-            }
+            for (int u = 0; u < U; ++u) nxt[u] = src[u * kWave];
         };
         auto visit_step = [&](const uint2 entry, const uint32_t slot) {
             const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
@@ -394,11 +478,11 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                 uint2 cur[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) cur[u] = nxt[u];
-                fetch_block(t0 + U);
+                fetch_block(min(t0 + U, steps - U));      // the last block is simply read again
                 uint32_t slot[U];
                 if constexpr (KIND == KIND_HASH) {
                     uint32_t h[U];
-                    uint2 e[U];
+                    uint4 e[U];
 #pragma unroll
                     for (int u = 0; u < U; ++u) { h[u] = cmap.home(cur[u].x); e[u] = table[h[u]]; }
 #pragma unroll
@@ -407,14 +491,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 #pragma unroll
                     for (int u = 0; u < U; ++u) slot[u] = cmap.lookup(cur[u].x);
                 }
-                if (t0 + U <= steps) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) visit_step(cur[u], slot[u]);
-                } else {
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (t0 + u < steps) visit_step(cur[u], slot[u]);
-                }
+                for (int u = 0; u < U; ++u) visit_step(cur[u], slot[u]);
             }
         }
 
@@ -472,7 +550,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                 if constexpr (!KNN) {
                     if (leader) args.out[(size_t)out * (size_t)n_b + (size_t)row] = d;
                 } else {
-                    if (args.q.metric == MT_INNER) d = -d;
+                    if (args.q.metric == MT_INNER) d = 0.0f - d;       // never -0: keys order by bit pattern
                     // a full list of any wavefront bounds the workgroup's k-th distance from above
                     const float bound = float_from_order_key(s_tau[r]);
                     if (lists[r].offer(d, row, leader, args.knn_k, bound) && lists[r].full() && lane == 0)
