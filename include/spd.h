@@ -125,7 +125,7 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *   "chunks"      number of B chunks (0 = automatic)
  *   "side_streams" 1: launches too small to fill the chip run on internal side streams beside
  *                 the large one, forked and joined with events so that the handle's stream
- *                 still orders the whole call (default 0: everything on the handle's stream)
+ *                 still orders the whole call (default 1; 0: everything on the handle's stream)
  *   "check_plan"  1: verify every index the kernels will form from the plan before launching
  *   "profile"     1: bracket every kernel launch with HIP events (see spd_profile_read)
  * Unknown names or values out of range return SPD_ERR_UNSUPPORTED. */

@@ -31,13 +31,17 @@ struct spd_handle {
     int32_t *flag = nullptr;     // device word for spd_csr_validate
     bool profile = false;
     bool check_plan = false;
-    bool multi_stream = false;   // option "side_streams": small launches run beside the large one
+    bool multi_stream = true;    // option "side_streams": small launches run beside the large one
     static constexpr int kSideStreams = 3;
     hipStream_t side[kSideStreams] = {nullptr, nullptr, nullptr};
     hipEvent_t fork_event = nullptr, join_event[kSideStreams] = {nullptr, nullptr, nullptr};     // full consistency check of every plan before launching
     struct Timed { spd_kernel_time rec; hipEvent_t start, stop; };
     std::vector<Timed> timed;    // launches of the last call (profile mode)
     std::vector<hipEvent_t> event_pool;
+    APlan plan_of_a;             // kept between calls: the planner reuses their buffers
+    BPlan plan_of_b;
+    std::vector<int64_t> knn_row_off;
+    std::vector<int32_t> knn_row_lists;
 };
 
 namespace {
@@ -187,7 +191,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     // ---- row pointers to the host ---------------------------------------------------
     const bool same = A->indptr == B->indptr && m == n;
     size_t ip_bytes = (size_t)(m + 1) * 8 + (same ? 0 : (size_t)(n + 1) * 8);
-    spd_status st = ensure_pinned(h, ip_bytes);
+    // (sized for the two plan uploads as well, which follow the row pointers in the buffer)
+    spd_status st = ensure_pinned(h, ip_bytes + 32 * ((size_t)n + 4096) + 48 * ((size_t)m + 4096));
     if (st != SPD_OK) return st;
     int64_t *a_ip = reinterpret_cast<int64_t *>(h->pinned);
     int64_t *b_ip = same ? a_ip : a_ip + (m + 1);
@@ -202,32 +207,32 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     if (a_ip[m] != A->nnz || b_ip[n] != B->nnz) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
     lap("indptr d2h");
 
-    // ---- plan -------------------------------------------------------------------------
+    // ---- B first: plan it, upload its plan and start the repack, so that the device is
+    //      busy while the host plans A -----------------------------------------------------
     const MetricInfo mi = metric_info((int)metric);
-    APlan ap;
-    BPlan bp;
-    std::string why = plan_a(a_ip, m, A->n_cols, (int)metric, knn_k, h->opt, ap);
-    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
-    why = plan_b(b_ip, n, h->opt, bp);
+    APlan &ap = h->plan_of_a;
+    BPlan &bp = h->plan_of_b;
+    std::string why = plan_b(b_ip, n, h->opt, bp);
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
-    lap("plan a+b");
-    for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
-    lap("chunks");
-    if (h->check_plan) {
-        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, knn_k, h->opt);
-        if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
-    }
-    for (const AClass &c : ap.classes)
-        if ((int64_t)c.n_groups * c.n_chunks >= ((int64_t)1 << 31) || (int64_t)c.lds_bytes + kStaticLds > h->opt.lds_budget)
-            return fail(h, SPD_ERR_UNSUPPORTED, "internal: launch outside the device limits");
-    lap("plan check");
+    lap("plan b");
+    int a_kind = 0, a_max_r = 1;
+    uint64_t a_dmax = 0;
+    why = plan_staging(A->n_cols, (int)metric, h->opt, a_kind, a_max_r, a_dmax);
+    if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "A: " + why);
+    // every launch of a call stages the same way: one pad column serves them all
+    const uint32_t padcol = a_kind == KIND_HASH ? kEmptyKey : (uint32_t)A->n_cols;
+    OpParams q;
+    q.p = p;
+    q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : 1.0f;
+    q.k = (double)A->n_cols;
+    q.metric = (int)metric;
+    if (metric != SPD_MINKOWSKI) q.p = 1.0f;
 
-    // ---- scratch layout ---------------------------------------------------------------
     const int planes = metric_planes((int)metric);
     const size_t lanes = (size_t)bp.n_slabs * kWave;
     Carver cv;
-    Upload up;
-    // (1) the plan region: everything the host uploads, contiguous, so that one copy moves it
+    // (1) B's plan, contiguous so that one copy moves it, then what the repack produces
+    Upload up_b;
     const size_t o_slab_base = cv.take(bp.slab_base.size() * 8);
     const size_t o_slab_steps = cv.take(bp.slab_steps.size() * 4);
     const size_t o_slab_split = cv.take(bp.slab_split.size());
@@ -235,13 +240,89 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     const size_t o_seg_len = cv.take(lanes * 4);
     const size_t o_seg_row = cv.take(lanes * 4);
     const size_t o_seg_glog = cv.take(lanes);
-    up.add(o_slab_base, bp.slab_base.data(), bp.slab_base.size() * 8);
-    up.add(o_slab_steps, bp.slab_steps.data(), bp.slab_steps.size() * 4);
-    up.add(o_slab_split, bp.slab_split.data(), bp.slab_split.size());
-    up.add(o_seg_start, bp.seg_start.data(), lanes * 8);
-    up.add(o_seg_len, bp.seg_len.data(), lanes * 4);
-    up.add(o_seg_row, bp.seg_row.data(), lanes * 4);
-    up.add(o_seg_glog, bp.seg_glog.data(), lanes);
+    up_b.add(o_slab_base, bp.slab_base.data(), bp.slab_base.size() * 8);
+    up_b.add(o_slab_steps, bp.slab_steps.data(), bp.slab_steps.size() * 4);
+    up_b.add(o_slab_split, bp.slab_split.data(), bp.slab_split.size());
+    up_b.add(o_seg_start, bp.seg_start.data(), lanes * 8);
+    up_b.add(o_seg_len, bp.seg_len.data(), lanes * 4);
+    up_b.add(o_seg_row, bp.seg_row.data(), lanes * 4);
+    up_b.add(o_seg_glog, bp.seg_glog.data(), lanes);
+    const size_t b_plan_end = cv.off;
+    const size_t o_packed = cv.take((size_t)bp.slab_base[(size_t)bp.n_slabs] * 8);
+    const size_t o_norms = cv.take((size_t)n * 16);
+    const size_t b_end = cv.off;
+    {
+        // room for A's part as well, from the documented bound, so that the scratch does not
+        // have to move once the repack has been started (checked again below)
+        size_t guess = 0;
+        if (!h->ws_external && spd_workspace_bytes(h, A, B, metric, knn_k, &guess) != SPD_OK) guess = 0;
+        st = ensure_workspace(h, std::max(b_end, guess));
+        if (st != SPD_OK) return st;
+    }
+    // pinned staging: [row pointers | B's plan | A's plan]
+    const size_t pin_b = align256(ip_bytes);
+    const size_t pin_a = pin_b + align256(b_plan_end);
+    if (h->pinned_bytes < pin_a + (size_t)m * (sizeof(ARow) + 16) + (64 << 10)) {
+        // growing the pinned buffer moves it: keep the row pointers
+        std::vector<unsigned char> keep(ip_bytes);
+        std::memcpy(keep.data(), h->pinned, ip_bytes);
+        st = ensure_pinned(h, pin_a + (size_t)m * (sizeof(ARow) + 16) + (64 << 10));
+        if (st != SPD_OK) return st;
+        std::memcpy(h->pinned, keep.data(), ip_bytes);
+        a_ip = reinterpret_cast<int64_t *>(h->pinned);
+        b_ip = same ? a_ip : a_ip + (m + 1);
+    }
+    BDevice bd;
+    auto stage_b = [&]() -> spd_status {
+        unsigned char *ws = reinterpret_cast<unsigned char *>(h->ws);
+        unsigned char *pin = reinterpret_cast<unsigned char *>(h->pinned) + pin_b;
+        for (auto &pt : up_b.parts) std::memcpy(pin + pt.first, pt.second.first, pt.second.second);
+        if (b_plan_end) {
+            hipError_t err = hipMemcpyAsync(ws, pin, b_plan_end, hipMemcpyHostToDevice, h->stream);
+            if (err != hipSuccess) return hip_fail(h, err, "upload of B's plan");
+        }
+        bd.packed = reinterpret_cast<const uint2 *>(ws + o_packed);
+        bd.slab_base = reinterpret_cast<const int64_t *>(ws + o_slab_base);
+        bd.slab_steps = reinterpret_cast<const int32_t *>(ws + o_slab_steps);
+        bd.slab_split = ws + o_slab_split;
+        bd.seg_start = reinterpret_cast<const int64_t *>(ws + o_seg_start);
+        bd.seg_len = reinterpret_cast<const int32_t *>(ws + o_seg_len);
+        bd.seg_row = reinterpret_cast<const int32_t *>(ws + o_seg_row);
+        bd.seg_glog = ws + o_seg_glog;
+        bd.norms = reinterpret_cast<const double *>(ws + o_norms);
+        bd.n_slabs = bp.n_slabs;
+        bd.n_rows = n;
+        LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, (bp.n_slabs + 3) / 4);
+        hipError_t err = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd,
+                                       reinterpret_cast<uint2 *>(ws + o_packed), reinterpret_cast<double *>(ws + o_norms),
+                                       (int)metric, mi.transform, mi.norm, q.p, q.k, padcol);
+        if (err != hipSuccess) return hip_fail(h, err, "pack kernel");
+        lt.done();
+        return SPD_OK;
+    };
+    st = stage_b();
+    if (st != SPD_OK) return st;
+    lap("stage b");
+
+    // ---- A, while the repack runs -------------------------------------------------------
+    why = plan_a(a_ip, m, A->n_cols, (int)metric, knn_k, h->opt, ap);
+    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
+    lap("plan a");
+    for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
+    lap("chunks");
+    if (h->check_plan) {
+        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, knn_k, h->opt);
+        if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
+    }
+    for (const AClass &c : ap.classes)
+        if ((int64_t)c.n_groups * c.n_chunks >= ((int64_t)1 << 31) || (int64_t)c.lds_bytes + kStaticLds > h->opt.lds_budget ||
+            c.kind != a_kind)
+            return fail(h, SPD_ERR_UNSUPPORTED, "internal: launch outside the device limits");
+    lap("plan check");
+
+    // (2) A's plan, contiguous again, then what the scans produce
+    Upload up;
+    const size_t a_plan_begin = cv.off;
     std::vector<size_t> o_rows(ap.classes.size()), o_sumlen(ap.classes.size()), o_chunks(ap.classes.size());
     for (size_t ci = 0; ci < ap.classes.size(); ++ci) {
         const AClass &c = ap.classes[ci];
@@ -255,8 +336,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     const size_t o_spilled = cv.take(ap.spilled.size() * sizeof(SpilledRow));
     up.add(o_spilled, ap.spilled.data(), ap.spilled.size() * sizeof(SpilledRow));
     // k-NN: every (row, chunk of its launch) owns a list of k candidates
-    std::vector<int64_t> knn_row_off;
-    std::vector<int32_t> knn_row_lists;
+    std::vector<int64_t> &knn_row_off = h->knn_row_off;
+    std::vector<int32_t> &knn_row_lists = h->knn_row_lists;
     size_t o_knn_off = 0, o_knn_lists = 0;
     int64_t knn_entries = 0;
     if (knn_k > 0) {
@@ -274,61 +355,32 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         up.add(o_knn_off, knn_row_off.data(), (size_t)m * 8);
         up.add(o_knn_lists, knn_row_lists.data(), (size_t)m * 4);
     }
-    // (2) what the kernels produce
-    const size_t o_packed = cv.take((size_t)bp.slab_base[(size_t)bp.n_slabs] * 8);
-    const size_t o_norms = cv.take((size_t)n * 16);
+    const size_t a_plan_end = cv.off;
     const size_t o_partial = cv.take((size_t)ap.n_partial_slots * planes * (size_t)n * 8);
     const size_t o_partial_norms = cv.take((size_t)ap.n_partial_slots * 16);
     const size_t o_knn_part = cv.take((size_t)knn_entries * sizeof(KnnEntry));
-    st = ensure_workspace(h, cv.off);
-    if (st != SPD_OK) return st;
-    unsigned char *ws = reinterpret_cast<unsigned char *>(h->ws);
-
-    // ---- upload the plan: one copy of one pinned blob that mirrors the scratch layout ----
-    {
-        size_t lo = cv.off, hi = 0;
-        for (auto &pt : up.parts) { lo = std::min(lo, pt.first); hi = std::max(hi, pt.first + pt.second.second); }
-        if (hi > lo) {
-            st = ensure_pinned(h, hi - lo);
-            if (st != SPD_OK) return st;
-            unsigned char *pin = reinterpret_cast<unsigned char *>(h->pinned);
-            for (auto &pt : up.parts) std::memcpy(pin + (pt.first - lo), pt.second.first, pt.second.second);
-            e = hipMemcpyAsync(ws + lo, pin, hi - lo, hipMemcpyHostToDevice, h->stream);
-            if (e != hipSuccess) return hip_fail(h, e, "upload of the plan");
+    if (cv.off > h->ws_bytes || pin_a + (a_plan_end - a_plan_begin) > h->pinned_bytes) {
+        // the bound was too small after all: growing waits for the repack, discards it and
+        // runs it again in the new buffers
+        st = ensure_workspace(h, cv.off);
+        if (st != SPD_OK) return st;
+        st = ensure_pinned(h, pin_a + (a_plan_end - a_plan_begin));
+        if (st != SPD_OK) return st;
+        if (h->profile && !h->timed.empty()) {
+            h->event_pool.push_back(h->timed.back().start); h->event_pool.push_back(h->timed.back().stop);
+            h->timed.pop_back();
         }
+        st = stage_b();
+        if (st != SPD_OK) return st;
     }
-    lap("upload");
-    // ---- launches ---------------------------------------------------------------------
-    BDevice bd;
-    bd.packed = reinterpret_cast<const uint2 *>(ws + o_packed);
-    bd.slab_base = reinterpret_cast<const int64_t *>(ws + o_slab_base);
-    bd.slab_steps = reinterpret_cast<const int32_t *>(ws + o_slab_steps);
-    bd.slab_split = ws + o_slab_split;
-    bd.seg_start = reinterpret_cast<const int64_t *>(ws + o_seg_start);
-    bd.seg_len = reinterpret_cast<const int32_t *>(ws + o_seg_len);
-    bd.seg_row = reinterpret_cast<const int32_t *>(ws + o_seg_row);
-    bd.seg_glog = ws + o_seg_glog;
-    bd.norms = reinterpret_cast<const double *>(ws + o_norms);
-    bd.n_slabs = bp.n_slabs;
-    bd.n_rows = n;
-
-    // every launch of a call stages the same way: one pad column serves them all
-    const uint32_t padcol = (!ap.classes.empty() && ap.classes[0].kind == KIND_HASH) ? kEmptyKey : (uint32_t)A->n_cols;
-    OpParams q;
-    q.p = p;
-    q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : 1.0f;
-    q.k = (double)A->n_cols;
-    q.metric = (int)metric;
-    if (metric != SPD_MINKOWSKI) q.p = 1.0f;
-
-    {
-        LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, (bp.n_slabs + 3) / 4);
-        e = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd, reinterpret_cast<uint2 *>(ws + o_packed),
-                          reinterpret_cast<double *>(ws + o_norms), (int)metric, mi.transform, mi.norm, q.p, q.k,
-                          padcol);
-        if (e != hipSuccess) return hip_fail(h, e, "pack kernel");
-        lt.done();
+    unsigned char *ws = reinterpret_cast<unsigned char *>(h->ws);
+    if (a_plan_end > a_plan_begin) {
+        unsigned char *pin = reinterpret_cast<unsigned char *>(h->pinned) + pin_a;
+        for (auto &pt : up.parts) std::memcpy(pin + (pt.first - a_plan_begin), pt.second.first, pt.second.second);
+        e = hipMemcpyAsync(ws + a_plan_begin, pin, a_plan_end - a_plan_begin, hipMemcpyHostToDevice, h->stream);
+        if (e != hipSuccess) return hip_fail(h, e, "upload of A's plan");
     }
+    lap("upload a");
 
     // The launch with the most work stays on the caller's stream; the others go round-robin
     // to side streams that fork after the repack and join before whatever follows, so that

@@ -92,6 +92,15 @@ SPD_HD float fast_div(float x, float y) {
 #endif
 }
 
+// Median of (a, b, 0): the one of a and b nearer to zero when they have the same sign, else 0.
+SPD_HD float median_with_zero(float a, float b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_fmed3f(a, b, 0.0f);
+#else
+    return fmaxf(fminf(a, b), fminf(fmaxf(a, b), 0.0f));
+#endif
+}
+
 // |v|^p in fp32.  The same function feeds the row norm F and the per-visit product, so
 // the terms that have to cancel are bit-identical (pow_abs(0) == 0).  Small integer
 // degrees are plain products.
@@ -154,17 +163,18 @@ template <> struct Op<OP_DOT> {
     SPD_HD static double v2(const Acc &) { return 0.0; }
 };
 
+// |a - b| - |a| - |b| is -2 min(|a|, |b|) when a and b have the same sign and 0 otherwise
+// (also when a == 0): the sum keeps c = |median(a, b, 0)|, which is exact in fp32.
 template <> struct Op<OP_L1> {
     struct Acc { double v; };
-    struct Bv { double db, adb; };
+    struct Bv { float b; };
     SPD_HD static void init(Acc &x) { x.v = 0.0; }
-    SPD_HD static Bv prep(float b, const OpParams &) { return {(double)b, fabs((double)b)}; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
-        double da = (double)a;
-        x.v += (fabs(da - b.db) - fabs(da)) - b.adb;   // 0 when a == 0
+        x.v += (double)fabsf(median_with_zero(a, b.b));
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
-    SPD_HD static double v0(const Acc &x) { return x.v; }
+    SPD_HD static double v0(const Acc &x) { return -2.0 * x.v; }
     SPD_HD static double v1(const Acc &) { return 0.0; }
     SPD_HD static double v2(const Acc &) { return 0.0; }
 };

@@ -26,7 +26,7 @@ int block_for(uint32_t stage_bytes, int64_t lds_total) {
 // B: slabs of 64 lanes
 // ------------------------------------------------------------------------------------
 std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt, BPlan &out) {
-    out = BPlan();
+    out.n_rows = 0; out.nnz = 0; out.n_slabs = 0;
     if (n_rows < 0) return "negative row count";
     if (n_rows >= (int64_t)1 << 31) return "more than 2^31-1 rows";
     const int64_t T = std::max<int64_t>(2, opt.split_len);
@@ -38,12 +38,14 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     for (int64_t j = 0; j < n_rows; ++j)
         if (indptr[j + 1] < indptr[j]) return fmt("row pointers decrease at row", j);
 
-    struct Long { int32_t row; int64_t len; int glog; };
-    std::vector<Long> longs;
-    std::vector<int32_t> order;            // short rows, window by window, longest first
-    std::vector<int32_t> window_end;       // prefix positions in `order`
+    using Long = BPlan::LongRow;
+    std::vector<Long> &longs = out.longs;
+    std::vector<int32_t> &order = out.order;            // short rows, window by window, longest first
+    std::vector<int32_t> &window_end = out.window_end;  // prefix positions in `order`
+    std::vector<int32_t> &bucket_count = out.bucket_count, &pos = out.pos;
+    longs.clear(); order.clear(); window_end.clear();
     order.reserve((size_t)n_rows);
-    std::vector<int32_t> bucket_count((size_t)T + 1), pos((size_t)T + 1);
+    bucket_count.assign((size_t)T + 1, 0); pos.assign((size_t)T + 1, 0);
     for (int64_t w0 = 0; w0 < n_rows; w0 += Wn) {
         int64_t w1 = std::min(n_rows, w0 + Wn);
         std::fill(bucket_count.begin(), bucket_count.end(), 0);
@@ -224,7 +226,13 @@ std::string plan_staging(int64_t n_cols, int metric, const PlanOptions &opt, int
 // ------------------------------------------------------------------------------------
 std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int knn_k,
                    const PlanOptions &opt, APlan &out) {
-    out = APlan();
+    // take the buffers of the previous plan back before anything else
+    if (out.pool.size() != 16) out.pool.assign(16, AClass());
+    for (AClass &c : out.classes) { const int slot = c.pool_slot; out.pool[(size_t)slot] = std::move(c); }
+    out.classes.clear();
+    out.spilled.clear();
+    out.n_partial_slots = 0;
+    for (AClass &c : out.pool) { c.rows.clear(); c.sumlen.clear(); c.chunk_begin.clear(); c.n_groups = 0; c.n_chunks = 0; c.hscale = 1; }
     out.n_rows = n_rows;
     if (n_rows < 0 || n_cols < 0) return "negative size";
     if (n_rows >= (int64_t)1 << 31 || n_cols >= ((int64_t)1 << 31) - 1) return "more than 2^31-2 rows or columns";
@@ -270,7 +278,8 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
 
     if (kind == KIND_STRIP) {
         int R = max_r;
-        AClass c;
+        AClass &c = out.pool[15];
+        c.pool_slot = 15;
         c.R = R; c.kind = KIND_STRIP;
         c.n_groups = (int)((n_rows + R - 1) / R);
         c.rows.assign((size_t)c.n_groups * R, ARow{0, 0, -1, kRowFirst | kRowLast, 0});
@@ -285,7 +294,8 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         return std::string();
     }
 
-    std::vector<ARow> items;
+    std::vector<ARow> &items = out.items;
+    items.clear();
     items.reserve((size_t)n_rows);
     for (int64_t i = 0; i < n_rows; ++i) {
         int64_t len = indptr[i + 1] - indptr[i];
@@ -306,20 +316,26 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     {   // counting sort by length, longest first, stable
         int32_t max_len = 0;
         for (const ARow &r : items) max_len = std::max(max_len, r.len);
-        std::vector<uint32_t> start((size_t)max_len + 2, 0);
+        std::vector<uint32_t> &start = out.sort_start;
+        start.assign((size_t)max_len + 2, 0);
         for (const ARow &r : items) ++start[(size_t)(max_len - r.len) + 1];
         for (size_t q = 1; q < start.size(); ++q) start[q] += start[q - 1];
-        std::vector<ARow> sorted(items.size());
+        std::vector<ARow> &sorted = out.sorted;
+        sorted.resize(items.size());
         for (const ARow &r : items) sorted[start[(size_t)(max_len - r.len)]++] = r;
         items.swap(sorted);
     }
 
     // one launch per (R, workgroups per compute unit): groups that need little LDS are not
     // held to the occupancy of the heaviest ones
-    AClass by_key[5][3];                      // R = 16, 8, 4, 2, 1  x  block 256 / 512 / 1024
+    AClass *by_key[5][3];                     // R = 16, 8, 4, 2, 1  x  block 256 / 512 / 1024
     for (int q = 0; q < 5; ++q)
-        for (int b = 0; b < 3; ++b) { by_key[q][b].R = 16 >> q; by_key[q][b].kind = kind; }
-    for (int q = 0; q < 5; ++q) by_key[q][1].rows.reserve(items.size() + 16);
+        for (int b = 0; b < 3; ++b) {
+            by_key[q][b] = &out.pool[(size_t)(q * 3 + b)];
+            by_key[q][b]->pool_slot = q * 3 + b;
+            by_key[q][b]->R = 16 >> q;
+            by_key[q][b]->kind = kind;
+        }
     size_t t = 0;
     while (t < items.size()) {
         size_t remaining = items.size() - t;
@@ -335,7 +351,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 while ((16 >> ci) != R) ++ci;
                 uint32_t need = lds_layout(kind, R, (uint32_t)sum, k, cheb, 1).total;
                 int blk = block_for(need, opt.lds_budget);
-                AClass &c = by_key[ci][blk == 256 ? 0 : (blk == 512 ? 1 : 2)];
+                AClass &c = *by_key[ci][blk == 256 ? 0 : (blk == 512 ? 1 : 2)];
                 for (int q = 0; q < R; ++q)
                     c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});
                 c.sumlen.push_back((int32_t)sum);
@@ -347,7 +363,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     }
     for (int q = 0; q < 5; ++q)
         for (int b = 0; b < 3; ++b)
-            if (by_key[q][b].n_groups) { finish_class(by_key[q][b]); out.classes.push_back(std::move(by_key[q][b])); }
+            if (by_key[q][b]->n_groups) { finish_class(*by_key[q][b]); out.classes.push_back(std::move(*by_key[q][b])); }
     return std::string();
 }
 

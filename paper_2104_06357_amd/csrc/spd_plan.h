@@ -115,6 +115,7 @@ struct AClass {
     std::vector<int32_t> sumlen;    // n_groups
     int n_chunks = 0;               // how this launch cuts B's slabs (plan_chunks)
     std::vector<int32_t> chunk_begin;   // n_chunks + 1 slab indices
+    int pool_slot = 0;              // where the planner keeps this class's buffers between calls
 };
 
 struct SpilledRow { int32_t row, first_slot, n_slots; };
@@ -124,6 +125,11 @@ struct APlan {
     std::vector<AClass> classes;
     std::vector<SpilledRow> spilled;
     int n_partial_slots = 0;
+    // buffers the planner reuses from call to call (a plan object that is planned into
+    // again allocates nothing once it has seen the largest input)
+    std::vector<AClass> pool;
+    std::vector<ARow> items, sorted;
+    std::vector<uint32_t> sort_start;
 };
 
 struct BPlan {
@@ -136,6 +142,10 @@ struct BPlan {
     std::vector<int32_t> seg_len;      // n_slabs*64
     std::vector<int32_t> seg_row;      // n_slabs*64, row j of B, -1 for an unused lane
     std::vector<uint8_t> seg_glog;     // n_slabs*64, log2(lanes the row is split over)
+    // planner scratch, kept between calls
+    struct LongRow { int32_t row; int64_t len; int glog; };
+    std::vector<LongRow> longs;
+    std::vector<int32_t> order, window_end, bucket_count, pos;
 };
 
 // Staging kind for a column count, the largest number of rows staged together, and the
