@@ -236,7 +236,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     __shared__ uint32_t s_prefix[R + 1];
     __shared__ double s_na[R][2];
     __shared__ int s_ctr;
-    __shared__ uint32_t s_tau[KNN ? R : 1];      // k-NN: smallest k-th distance any wavefront holds, per row
+    __shared__ uint32_t s_tau[KNN ? R : 1];      // k-NN: an upper bound of the workgroup's k-th distance, per row
+    __shared__ uint32_t s_share[KNN ? R * 16 : 1];   // k-NN: each wavefront's ceil(k / wavefronts)-th distance, per row
     __shared__ float s_top[kCheb ? R * kTopRanks : 1];
     __shared__ int s_topn[R];
     __shared__ uint32_t s_clo[kCheb ? R : 1], s_cspan[kCheb ? R : 1];   // column range a slice answers for
@@ -312,6 +313,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     }
     if constexpr (KNN) {
         if (tid < R) s_tau[tid] = float_order_key(__builtin_huge_valf());
+        if (tid < R * 16) s_share[tid] = float_order_key(__builtin_huge_valf());
     }
     // 2. row norms: one wavefront per row, summed in a fixed order (Section 3.4)
     for (int r = wave; r < R; r += nw) {
@@ -444,17 +446,17 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         const uint2 *__restrict__ pk = args.b.packed + args.b.slab_base[s] + lane;
         Acc acc[R];
         uint32_t hit[kCheb ? R : 1];
+        bool lists_changed = false;
 #pragma unroll
         for (int r = 0; r < R; ++r) { O::init(acc[r]); if constexpr (kCheb) hit[r] = 0u; }
 
         // Entry t of lane l sits at pk[t*64 + l]: one coalesced load per step, fetched a block
         // of U steps ahead of its use.  The plan pads every slab to whole blocks (with the
         // column that stages nothing), so the loop has no tail.
-        uint2 nxt[U];
-        auto fetch_block = [&](int t_first) {
+        auto fetch_block = [&](uint2 (&into)[U], int t_first) {
             const uint2 *__restrict__ src = pk + (size_t)t_first * kWave;
 #pragma unroll
-            for (int u = 0; u < U; ++u) nxt[u] = src[u * kWave];
+            for (int u = 0; u < U; ++u) into[u] = src[u * kWave];
         };
         auto visit_step = [&](const uint2 entry, const uint32_t slot) {
             const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
@@ -472,27 +474,38 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                 for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
             }
         };
+        auto visit_block = [&](const uint2 (&cur)[U]) {
+            uint32_t slot[U];
+            if constexpr (KIND == KIND_HASH) {
+                uint32_t h[U];
+                uint4 e[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) { h[u] = cmap.home(cur[u].x); e[u] = table[h[u]]; }
+#pragma unroll
+                for (int u = 0; u < U; ++u) slot[u] = cmap.resolve(cur[u].x, h[u], e[u]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) slot[u] = cmap.lookup(cur[u].x);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) visit_step(cur[u], slot[u]);
+        };
         if (steps > 0) {
-            fetch_block(0);
-            for (int t0 = 0; t0 < steps; t0 += U) {
-                uint2 cur[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
-                fetch_block(min(t0 + U, steps - U));      // the last block is simply read again
-                uint32_t slot[U];
-                if constexpr (KIND == KIND_HASH) {
-                    uint32_t h[U];
-                    uint4 e[U];
-#pragma unroll
-                    for (int u = 0; u < U; ++u) { h[u] = cmap.home(cur[u].x); e[u] = table[h[u]]; }
-#pragma unroll
-                    for (int u = 0; u < U; ++u) slot[u] = cmap.resolve(cur[u].x, h[u], e[u]);
-                } else {
-#pragma unroll
-                    for (int u = 0; u < U; ++u) slot[u] = cmap.lookup(cur[u].x);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) visit_step(cur[u], slot[u]);
+            // two register sets take turns: while one block is worked on, the next one is in
+            // flight (past the slab's end the last block is simply read again)
+            uint2 even[U], odd[U];
+            fetch_block(even, 0);
+            for (int t0 = 0;;) {
+                fetch_block(odd, min(t0 + U, steps - U));
+                __builtin_amdgcn_sched_barrier(0);        // keep the loads ahead of the arithmetic
+                visit_block(even);
+                t0 += U;
+                if (t0 >= steps) break;
+                fetch_block(even, min(t0 + U, steps - U));
+                __builtin_amdgcn_sched_barrier(0);
+                visit_block(odd);
+                t0 += U;
+                if (t0 >= steps) break;
             }
         }
 
@@ -553,14 +566,39 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                     if (args.q.metric == MT_INNER) d = 0.0f - d;       // never -0: keys order by bit pattern
                     // a full list of any wavefront bounds the workgroup's k-th distance from above
                     const float bound = float_from_order_key(s_tau[r]);
-                    if (lists[r].offer(d, row, leader, args.knn_k, bound) && lists[r].full() && lane == 0)
-                        atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
+                    if (lists[r].offer(d, row, leader, args.knn_k, bound)) {
+                        lists_changed = true;
+                        if (lists[r].full() && lane == 0) atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
+                    }
                 }
             } else if (leader) {
                 const size_t slot = (size_t)(-2 - out);
                 args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0;
                 if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1;
                 if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2;
+            }
+        }
+        if constexpr (KNN) {
+            // The wavefronts' lists hold different rows of B.  Once every wavefront holds at
+            // least q = ceil(k / wavefronts) entries, the largest of their q-th distances has k
+            // entries at or below it: a bound on the k-th distance that is far tighter than any
+            // single list's own.  (What is read here may be out of date: then it is only looser.)
+            if (lists_changed) {
+                const int q = (args.knn_k + nw - 1) / nw - 1;
+                float mine = 0.0f;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const float qd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lists[r].d), q));
+                    if (lane == r) mine = qd;
+                }
+                if (lane < R) s_share[lane * 16 + wave] = float_order_key(mine);
+                for (int base = 0; base < R * nw; base += kWave) {
+                    const int e = base + lane;
+                    const int r = e / nw, w = e % nw;
+                    uint32_t key = r < R ? s_share[r * 16 + w] : 0u;
+                    for (int m = 1; m < nw; m <<= 1) key = max(key, (uint32_t)__shfl_xor((int)key, m));
+                    if (r < R && w == 0 && key < s_tau[r]) atomicMin(&s_tau[r], key);
+                }
             }
         }
     }
@@ -579,14 +617,31 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
             if (out < 0) continue;
             KnnList merged;
             merged.reset();
-            const int total_e = nw * kk;
-            for (int e0 = 0; e0 < total_e; e0 += 64) {
-                int e = e0 + lane;
-                bool valid = e < total_e;
-                KnnEntry c = KnnEntry{0.f, 0};
-                if (valid) c = area[((size_t)(e / kk) * R + r) * kk + (e % kk)];
-                valid = valid && c.j != 0x7fffffff;
-                merged.offer(c.d, c.j, valid, kk, __builtin_huge_valf());
+            if (kk <= 32) {
+                // the lists are sorted: the running best ascending in the low lanes and the next
+                // list descending in the high lanes form a bitonic sequence, six steps sort it
+                const uint64_t unused = knn_key(__builtin_huge_valf(), 0x7fffffff);
+                uint64_t best = unused;
+                if (lane < kk) { const KnnEntry c = area[(size_t)r * kk + lane]; best = knn_key(c.d, c.j); }
+                for (int w = 1; w < nw; ++w) {
+                    const int t = 63 - lane;
+                    uint64_t x = best;
+                    if (t < kk) { const KnnEntry c = area[((size_t)w * R + r) * kk + t]; x = knn_key(c.d, c.j); }
+                    x = wave_merge_asc(x, lane);
+                    best = lane < kk ? x : unused;
+                }
+                merged.d = float_from_order_key((uint32_t)(best >> 32));
+                merged.j = (int)(uint32_t)best;
+            } else {
+                const int total_e = nw * kk;
+                for (int e0 = 0; e0 < total_e; e0 += 64) {
+                    int e = e0 + lane;
+                    bool valid = e < total_e;
+                    KnnEntry c = KnnEntry{0.f, 0};
+                    if (valid) c = area[((size_t)(e / kk) * R + r) * kk + (e % kk)];
+                    valid = valid && c.j != 0x7fffffff;
+                    merged.offer(c.d, c.j, valid, kk, __builtin_huge_valf());
+                }
             }
             if (lane < kk)
                 args.knn_part[args.knn_row_off[out] + (size_t)chunk * kk + lane] = KnnEntry{merged.d, merged.j};
