@@ -14,7 +14,7 @@ struct BDevice {
     const uint2 *packed;          // entries {column, value bits}: slab_base[s] + t*64 + lane
     const int64_t *slab_base;     // n_slabs + 1
     const int32_t *slab_steps;    // n_slabs
-    const uint8_t *slab_split;    // n_slabs
+    const uint8_t *slab_split;    // n_slabs, largest seg_glog of the slab
     const int64_t *seg_start;     // lanes
     const int32_t *seg_len;       // lanes
     const int32_t *seg_row;       // lanes

@@ -39,7 +39,7 @@ enum MetricId {
 
 struct MetricInfo { int op, transform, norm; };
 
-SPD_HD MetricInfo metric_info(int metric) {
+SPD_HD constexpr MetricInfo metric_info(int metric) {
     switch (metric) {
     case MT_INNER:       return {OP_DOT, TR_ID, NORM_NONE};
     case MT_COSINE:      return {OP_DOT, TR_ID, NORM_SUMSQ};
@@ -288,24 +288,34 @@ template <> struct Op<OP_CHEB> {
 
 // Expansion function (Table 1, "Expansion" column, and the closing steps of the union
 // family).  v, s, w: the accumulated sums; a0,a1 / b0,b1: derived norms of the two rows.
-SPD_HD float finish(const OpParams &q, double v, double s, double w, double a0, double a1, double b0, double b1) {
+// The metric is a template argument so that a kernel can pick the formula once per slab
+// instead of once per pair.
+template <int MT>
+SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a0, double a1, double b0, double b1) {
     const double LN2 = 0.693147180559945309417232121458;
-    double r;
-    switch (q.metric) {
-    case MT_INNER: r = v; break;
-    case MT_COSINE:
-        r = (a0 == 0.0 && b0 == 0.0) ? 0.0 : ((a0 == 0.0 || b0 == 0.0) ? 1.0 : 1.0 - v * a1 * b1);
-        break;
-    case MT_L2: { double t = a0 - 2.0 * v + b0; return sqrtf((float)(t > 0.0 ? t : 0.0)); }
-    case MT_CORRELATION:
-        r = (a1 == 0.0 || b1 == 0.0) ? 1.0 : 1.0 - (q.k * v - a0 * b0) * a1 * b1;
-        break;
-    case MT_JACCARD: { double u = a0 + b0 - v; r = (u == 0.0) ? 0.0 : 1.0 - v / u; break; }
-    case MT_DICE: { double t = a0 + b0; r = (t == 0.0) ? 0.0 : 1.0 - 2.0 * v / t; break; }
-    case MT_HELLINGER: { double t = 0.5 * (a0 + b0) - v; return sqrtf((float)(t > 0.0 ? t : 0.0)); }
-    case MT_L1:
-    case MT_CANBERRA: { double t = a0 + b0 + v; r = t > 0.0 ? t : 0.0; break; }
-    case MT_MINKOWSKI: {
+    (void)s; (void)w; (void)a0; (void)a1; (void)b0; (void)b1; (void)q;
+    if constexpr (MT == MT_INNER || MT == MT_CHEBYSHEV) {
+        return (float)v;
+    } else if constexpr (MT == MT_COSINE) {
+        return (float)((a0 == 0.0 && b0 == 0.0) ? 0.0 : ((a0 == 0.0 || b0 == 0.0) ? 1.0 : 1.0 - v * a1 * b1));
+    } else if constexpr (MT == MT_L2) {
+        double t = a0 - 2.0 * v + b0;
+        return sqrtf((float)(t > 0.0 ? t : 0.0));
+    } else if constexpr (MT == MT_CORRELATION) {
+        return (float)((a1 == 0.0 || b1 == 0.0) ? 1.0 : 1.0 - (q.k * v - a0 * b0) * a1 * b1);
+    } else if constexpr (MT == MT_JACCARD) {
+        double u = a0 + b0 - v;
+        return (float)((u == 0.0) ? 0.0 : 1.0 - v / u);
+    } else if constexpr (MT == MT_DICE) {
+        double t = a0 + b0;
+        return (float)((t == 0.0) ? 0.0 : 1.0 - 2.0 * v / t);
+    } else if constexpr (MT == MT_HELLINGER) {
+        double t = 0.5 * (a0 + b0) - v;
+        return sqrtf((float)(t > 0.0 ? t : 0.0));
+    } else if constexpr (MT == MT_L1 || MT == MT_CANBERRA) {
+        double t = a0 + b0 + v;
+        return (float)(t > 0.0 ? t : 0.0);
+    } else if constexpr (MT == MT_MINKOWSKI) {
         // v: differences on shared columns, s: their share of the norms, w: how many;
         // a1 / b1 count the entries of the rows: equal supports leave no one-sided part
         double one_sided = (w == a1 && w == b1) ? 0.0 : (a0 + b0) - s;
@@ -314,15 +324,45 @@ SPD_HD float finish(const OpParams &q, double v, double s, double w, double a0, 
         if (q.p == 1.0f) return tf;
         if (q.p == 2.0f) return sqrtf(tf);
         return tf == 0.0f ? 0.0f : fast_exp2(q.inv_p * fast_log2(tf));
+    } else if constexpr (MT == MT_HAMMING) {
+        return (float)((a0 + b0 + v) / q.k);
+    } else if constexpr (MT == MT_KL) {
+        return (float)(LN2 * v);
+    } else if constexpr (MT == MT_JS) {
+        double t = 0.5 * LN2 * (((a0 + b0) - s) + v);
+        return sqrtf((float)(t > 0.0 ? t : 0.0));
+    } else if constexpr (MT == MT_RUSSELL_RAO) {
+        return (float)((q.k - v) / q.k);
+    } else {
+        return 0.0f;
     }
-    case MT_HAMMING: r = (a0 + b0 + v) / q.k; break;
-    case MT_KL: r = LN2 * v; break;
-    case MT_JS: { double t = 0.5 * LN2 * (((a0 + b0) - s) + v); return sqrtf((float)(t > 0.0 ? t : 0.0)); }
-    case MT_CHEBYSHEV: r = v; break;
-    case MT_RUSSELL_RAO: r = (q.k - v) / q.k; break;
-    default: r = 0.0; break;
+}
+
+template <int MT> struct MetricTag { static constexpr int value = MT; };
+
+// Calls f(MetricTag<m>) for the metric `metric`, which must be one computed by product OP
+// (the others are not instantiated: a kernel of one product carries only its own formulas).
+template <int OP, typename F> SPD_HD void for_metric_of(int metric, F &&f) {
+#define SPD_CASE(M) case M: if constexpr (metric_info(M).op == OP) f(MetricTag<M>{}); break;
+    switch (metric) {
+        SPD_CASE(MT_INNER) SPD_CASE(MT_COSINE) SPD_CASE(MT_L2) SPD_CASE(MT_CORRELATION) SPD_CASE(MT_JACCARD)
+        SPD_CASE(MT_DICE) SPD_CASE(MT_HELLINGER) SPD_CASE(MT_L1) SPD_CASE(MT_CHEBYSHEV) SPD_CASE(MT_MINKOWSKI)
+        SPD_CASE(MT_CANBERRA) SPD_CASE(MT_HAMMING) SPD_CASE(MT_KL) SPD_CASE(MT_JS) SPD_CASE(MT_RUSSELL_RAO)
+    default: break;
     }
-    return (float)r;
+#undef SPD_CASE
+}
+
+// The same with the metric known only at run time.
+SPD_HD float finish(const OpParams &q, double v, double s, double w, double a0, double a1, double b0, double b1) {
+    switch (q.metric) {
+#define SPD_CASE(M) case M: return finish_as<M>(q, v, s, w, a0, a1, b0, b1);
+        SPD_CASE(MT_INNER) SPD_CASE(MT_COSINE) SPD_CASE(MT_L2) SPD_CASE(MT_CORRELATION) SPD_CASE(MT_JACCARD)
+        SPD_CASE(MT_DICE) SPD_CASE(MT_HELLINGER) SPD_CASE(MT_L1) SPD_CASE(MT_CHEBYSHEV) SPD_CASE(MT_MINKOWSKI)
+        SPD_CASE(MT_CANBERRA) SPD_CASE(MT_HAMMING) SPD_CASE(MT_KL) SPD_CASE(MT_JS) SPD_CASE(MT_RUSSELL_RAO)
+#undef SPD_CASE
+    default: return 0.0f;
+    }
 }
 
 }  // namespace spd

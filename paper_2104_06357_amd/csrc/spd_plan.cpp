@@ -106,7 +106,8 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
             out.seg_row[lane] = l.row;
             out.seg_glog[lane] = (uint8_t)l.glog;
         }
-        out.slab_split[(lane - 1) / kWave] = 1;
+        uint8_t &deepest = out.slab_split[(lane - 1) / kWave];
+        deepest = std::max<uint8_t>(deepest, (uint8_t)l.glog);
     }
     lane = (size_t)n_long_slabs * kWave;
     {

@@ -137,7 +137,7 @@ struct BPlan {
     int32_t n_slabs = 0;
     std::vector<int64_t> slab_base;    // n_slabs + 1, offsets into the packed entries (64 * steps each)
     std::vector<int32_t> slab_steps;   // n_slabs, longest segment of the slab rounded up to whole blocks
-    std::vector<uint8_t> slab_split;   // n_slabs, 1 if the slab holds split rows
+    std::vector<uint8_t> slab_split;   // n_slabs, largest log2(lanes per row) in the slab: 0 = no split rows
     std::vector<int64_t> seg_start;    // n_slabs*64, first CSR element of the lane's segment
     std::vector<int32_t> seg_len;      // n_slabs*64
     std::vector<int32_t> seg_row;      // n_slabs*64, row j of B, -1 for an unused lane

@@ -150,6 +150,20 @@ struct KnnList {
     }
 };
 
+// c ? b : a on any plain struct, word by word (selects, no branch).
+template <typename T> __device__ __forceinline__ T select_words(bool c, const T &a, const T &b) {
+    static_assert(sizeof(T) % 4 == 0, "whole words");
+    constexpr int N = (int)(sizeof(T) / 4);
+    uint32_t wa[N], wb[N];
+    __builtin_memcpy(wa, &a, sizeof(T));
+    __builtin_memcpy(wb, &b, sizeof(T));
+#pragma unroll
+    for (int i = 0; i < N; ++i) wa[i] = c ? wb[i] : wa[i];
+    T out;
+    __builtin_memcpy(&out, wa, sizeof(T));
+    return out;
+}
+
 template <typename T> __device__ __forceinline__ T shfl_xor_any(T v, int mask);
 template <> __device__ __forceinline__ double shfl_xor_any<double>(double v, int mask) { return __shfl_xor(v, mask); }
 template <> __device__ __forceinline__ float shfl_xor_any<float>(float v, int mask) { return __shfl_xor(v, mask); }
@@ -203,24 +217,31 @@ template <int KIND> struct ColumnMap {
 
 template <int R> struct RowVals { float v[R]; };
 
-template <int R> __device__ __forceinline__ RowVals<R> load_vals(const float *vals, uint32_t slot) {
+// The value table is kept in planes of four staged rows: plane q holds, for every slot, the
+// values of rows 4q .. 4q+3 in 16 bytes.  A wavefront's 16-byte reads at random slots then
+// fall on all LDS banks alike (rows of 32 or 64 bytes would start on every other or every
+// fourth bank group only and halve or quarter the rate).
+template <int R> __device__ __forceinline__ uint32_t vals_index(uint32_t slot, int r, uint32_t nslots) {
+    if constexpr (R <= 4) return slot * R + (uint32_t)r;
+    else return ((uint32_t)(r >> 2) * nslots + slot) * 4u + (uint32_t)(r & 3);
+}
+
+template <int R> __device__ __forceinline__ RowVals<R> load_vals(const float *vals, uint32_t slot, uint32_t nslots) {
     RowVals<R> out;
-    const float *p = vals + (size_t)slot * R;
     if constexpr (R == 1) {
-        out.v[0] = p[0];
+        out.v[0] = vals[slot];
     } else if constexpr (R == 2) {
-        float2 t = *reinterpret_cast<const float2 *>(p);
+        float2 t = *reinterpret_cast<const float2 *>(vals + (size_t)slot * 2);
         out.v[0] = t.x; out.v[1] = t.y;
     } else {
 #pragma unroll
         for (int q = 0; q < R / 4; ++q) {
-            float4 t = *reinterpret_cast<const float4 *>(p + 4 * q);
+            float4 t = *reinterpret_cast<const float4 *>(vals + ((size_t)q * nslots + slot) * 4);
             out.v[4 * q] = t.x; out.v[4 * q + 1] = t.y; out.v[4 * q + 2] = t.z; out.v[4 * q + 3] = t.w;
         }
     }
     return out;
 }
-
 
 // ------------------------------------------------------------------------------------
 // the kernel
@@ -372,7 +393,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         for (int q = 1; q < R; ++q) r += (e >= s_prefix[q]) ? 1 : 0;
         const int64_t at = s_rows[r].start + (e - s_prefix[r]);
         const float t = transform_value(args.transform, args.a_values[at]);
-        if (t != 0.0f) vals[(size_t)cmap.lookup((uint32_t)args.a_indices[at]) * R + r] = t;
+        if (t != 0.0f) vals[vals_index<R>(cmap.lookup((uint32_t)args.a_indices[at]), r, L.nslots)] = t;
     }
     if constexpr (kCheb) {
         // With sum() = max a column that a slice of a row does not store still counts
@@ -442,7 +463,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         const size_t at = (size_t)s * kWave + lane;
         const int row = args.b.seg_row[at];
         const int steps = wave_uniform(args.b.slab_steps[s]);
-        const bool split = wave_uniform((int)args.b.slab_split[s]) != 0;
+        const int split_depth = wave_uniform((int)args.b.slab_split[s]);   // deepest split of a row in the slab
         const uint2 *__restrict__ pk = args.b.packed + args.b.slab_base[s] + lane;
         Acc acc[R];
         uint32_t hit[kCheb ? R : 1];
@@ -460,7 +481,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         };
         auto visit_step = [&](const uint2 entry, const uint32_t slot) {
             const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
-            const RowVals<R> a = load_vals<R>(vals, slot);
+            const RowVals<R> a = load_vals<R>(vals, slot, L.nslots);
             if constexpr (kCheb) {
                 const unsigned char *rk = rank8 + (size_t)slot * R;
 #pragma unroll
@@ -510,18 +531,20 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         }
 
         const int glog = args.b.seg_glog[at];
-        if (split) {
+        if (split_depth > 0) {
             // rows cut over 2^glog adjacent lanes: sum (max) the lanes of each group
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int step = 0; step < 6; ++step) {
+                if (step >= split_depth) break;
+                const bool mine = step < glog;
 #pragma unroll
-                for (int step = 0; step < 6; ++step) {
-                    Acc other = acc_shfl_xor<OP>(acc[r], 1 << step);
-                    uint32_t oh = 0u;
-                    if constexpr (kCheb) oh = (uint32_t)__shfl_xor((int)hit[r], 1 << step);
-                    if (step < glog) {
-                        O::combine(acc[r], other);
-                        if constexpr (kCheb) hit[r] |= oh;
+                for (int r = 0; r < R; ++r) {
+                    Acc merged = acc[r];
+                    O::combine(merged, acc_shfl_xor<OP>(acc[r], 1 << step));
+                    acc[r] = select_words(mine, acc[r], merged);
+                    if constexpr (kCheb) {
+                        const uint32_t oh = (uint32_t)__shfl_xor((int)hit[r], 1 << step);
+                        hit[r] |= mine ? oh : 0u;
                     }
                 }
             }
@@ -530,54 +553,75 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         double nb0 = 0.0, nb1 = 0.0;
         if (leader) { nb0 = args.b.norms[(size_t)row * 2]; nb1 = args.b.norms[(size_t)row * 2 + 1]; }
 
+        // the expansion function is picked once per slab, not once per pair
+        for_metric_of<OP>(args.q.metric, [&](auto metric_tag) {
+            constexpr int MT = decltype(metric_tag)::value;
+            double v0[R], v1[R], v2[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int out = wave_uniform(s_rows[r].out);
-            if (out == -1) continue;
-            double v0 = O::v0(acc[r]), v1 = O::v1(acc[r]);
-            const double v2 = O::v2(acc[r]);
+            for (int r = 0; r < R; ++r) { v0[r] = O::v0(acc[r]); v1[r] = O::v1(acc[r]); v2[r] = O::v2(acc[r]); }
             if constexpr (kCheb) {
-                if (leader) {
-                    const int topn = s_topn[r];
-                    uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
-                    uint32_t unhit = ~hit[r] & tracked;
-                    float extra = 0.0f;
-                    if (unhit) {
-                        extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
-                    } else if (topn == kTopRanks) {
-                        // every tracked entry was visited: walk the two sorted rows
-                        const int64_t a0 = s_rows[r].start, a1 = a0 + s_rows[r].len;
-                        int64_t bj = args.b_indptr[row];
-                        const int64_t be = args.b_indptr[row + 1];
-                        for (int64_t ai = a0; ai < a1; ++ai) {
-                            int32_t c = args.a_indices[ai];
-                            while (bj < be && args.b_indices[bj] < c) ++bj;
-                            if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (wave_uniform(s_rows[r].out) == -1) continue;
+                    if (leader) {
+                        const int topn = s_topn[r];
+                        uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
+                        uint32_t unhit = ~hit[r] & tracked;
+                        float extra = 0.0f;
+                        if (unhit) {
+                            extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
+                        } else if (topn == kTopRanks) {
+                            // every tracked entry was visited: walk the two sorted rows
+                            const int64_t a0 = s_rows[r].start, a1 = a0 + s_rows[r].len;
+                            int64_t bj = args.b_indptr[row];
+                            const int64_t be = args.b_indptr[row + 1];
+                            for (int64_t ai = a0; ai < a1; ++ai) {
+                                int32_t c = args.a_indices[ai];
+                                while (bj < be && args.b_indices[bj] < c) ++bj;
+                                if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
+                            }
                         }
+                        v0[r] = fmax(v0[r], (double)extra);
                     }
-                    v0 = fmax(v0, (double)extra);
                 }
             }
-            if (out >= 0) {
-                float d = finish(args.q, v0, v1, v2, s_na[r][0], s_na[r][1], nb0, nb1);
-                if constexpr (!KNN) {
-                    if (leader) args.out[(size_t)out * (size_t)n_b + (size_t)row] = d;
-                } else {
-                    if (args.q.metric == MT_INNER) d = 0.0f - d;       // never -0: keys order by bit pattern
-                    // a full list of any wavefront bounds the workgroup's k-th distance from above
+            float dist[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                dist[r] = finish_as<MT>(args.q, v0[r], v1[r], v2[r], s_na[r][0], s_na[r][1], nb0, nb1);
+            if constexpr (!KNN) {
+                if (leader) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const int out = wave_uniform(s_rows[r].out);
+                        if (out >= 0) args.out[(size_t)out * (size_t)n_b + (size_t)row] = dist[r];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (wave_uniform(s_rows[r].out) < 0) continue;
+                    float d = dist[r];
+                    if constexpr (MT == MT_INNER) d = 0.0f - d;       // never -0: keys order by bit pattern
                     const float bound = float_from_order_key(s_tau[r]);
                     if (lists[r].offer(d, row, leader, args.knn_k, bound)) {
                         lists_changed = true;
                         if (lists[r].full() && lane == 0) atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
                     }
                 }
-            } else if (leader) {
-                const size_t slot = (size_t)(-2 - out);
-                args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0;
-                if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1;
-                if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2;
             }
-        }
+            if (leader) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int out = wave_uniform(s_rows[r].out);
+                    if (out > -2) continue;
+                    const size_t slot = (size_t)(-2 - out);
+                    args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0[r];
+                    if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1[r];
+                    if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2[r];
+                }
+            }
+        });
         if constexpr (KNN) {
             // The wavefronts' lists hold different rows of B.  Once every wavefront holds at
             // least q = ceil(k / wavefronts) entries, the largest of their q-th distances has k
