@@ -18,6 +18,10 @@ __device__ __forceinline__ uint32_t lane_rank_in(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 __device__ __forceinline__ int wave_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ double wave_uniform_f64(double v) {
+    const int lo = __builtin_amdgcn_readfirstlane(__double2loint(v)), hi = __builtin_amdgcn_readfirstlane(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
 
 __device__ __forceinline__ bool lex_less(float d1, int j1, float d2, int j2) {
     return d1 < d2 || (d1 == d2 && j1 < j2);
@@ -447,6 +451,16 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         __syncthreads();
     }
 
+    // what the epilogue of every slab needs of the staged rows, once, in scalar registers
+    int row_out[R];
+    double row_na0[R], row_na1[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        row_out[r] = wave_uniform(s_rows[r].out);
+        row_na0[r] = wave_uniform_f64(s_na[r][0]);
+        row_na1[r] = wave_uniform_f64(s_na[r][1]);
+    }
+
     // ---- scan: every wavefront takes slabs of the chunk until none is left -----------
     KnnList lists[KNN ? R : 1];
     if constexpr (KNN) {
@@ -553,75 +567,75 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         double nb0 = 0.0, nb1 = 0.0;
         if (leader) { nb0 = args.b.norms[(size_t)row * 2]; nb1 = args.b.norms[(size_t)row * 2 + 1]; }
 
+        double v0[R], v1[R], v2[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) { v0[r] = O::v0(acc[r]); v1[r] = O::v1(acc[r]); v2[r] = O::v2(acc[r]); }
+        if constexpr (kCheb) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (row_out[r] == -1) continue;
+                if (leader) {
+                    const int topn = s_topn[r];
+                    uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
+                    uint32_t unhit = ~hit[r] & tracked;
+                    float extra = 0.0f;
+                    if (unhit) {
+                        extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
+                    } else if (topn == kTopRanks) {
+                        // every tracked entry was visited: walk the two sorted rows
+                        const int64_t a0 = s_rows[r].start, a1 = a0 + s_rows[r].len;
+                        int64_t bj = args.b_indptr[row];
+                        const int64_t be = args.b_indptr[row + 1];
+                        for (int64_t ai = a0; ai < a1; ++ai) {
+                            int32_t c = args.a_indices[ai];
+                            while (bj < be && args.b_indices[bj] < c) ++bj;
+                            if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
+                        }
+                    }
+                    v0[r] = fmax(v0[r], (double)extra);
+                }
+            }
+        }
         // the expansion function is picked once per slab, not once per pair
+        float dist[R];
         for_metric_of<OP>(args.q.metric, [&](auto metric_tag) {
             constexpr int MT = decltype(metric_tag)::value;
-            double v0[R], v1[R], v2[R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) { v0[r] = O::v0(acc[r]); v1[r] = O::v1(acc[r]); v2[r] = O::v2(acc[r]); }
-            if constexpr (kCheb) {
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if (wave_uniform(s_rows[r].out) == -1) continue;
-                    if (leader) {
-                        const int topn = s_topn[r];
-                        uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
-                        uint32_t unhit = ~hit[r] & tracked;
-                        float extra = 0.0f;
-                        if (unhit) {
-                            extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
-                        } else if (topn == kTopRanks) {
-                            // every tracked entry was visited: walk the two sorted rows
-                            const int64_t a0 = s_rows[r].start, a1 = a0 + s_rows[r].len;
-                            int64_t bj = args.b_indptr[row];
-                            const int64_t be = args.b_indptr[row + 1];
-                            for (int64_t ai = a0; ai < a1; ++ai) {
-                                int32_t c = args.a_indices[ai];
-                                while (bj < be && args.b_indices[bj] < c) ++bj;
-                                if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
-                            }
-                        }
-                        v0[r] = fmax(v0[r], (double)extra);
-                    }
-                }
+            for (int r = 0; r < R; ++r) {
+                dist[r] = finish_as<MT>(args.q, v0[r], v1[r], v2[r], row_na0[r], row_na1[r], nb0, nb1);
+                if constexpr (KNN && MT == MT_INNER) dist[r] = 0.0f - dist[r];   // largest first; never -0: keys order by bit pattern
             }
-            float dist[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                dist[r] = finish_as<MT>(args.q, v0[r], v1[r], v2[r], s_na[r][0], s_na[r][1], nb0, nb1);
-            if constexpr (!KNN) {
-                if (leader) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const int out = wave_uniform(s_rows[r].out);
-                        if (out >= 0) args.out[(size_t)out * (size_t)n_b + (size_t)row] = dist[r];
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if (wave_uniform(s_rows[r].out) < 0) continue;
-                    float d = dist[r];
-                    if constexpr (MT == MT_INNER) d = 0.0f - d;       // never -0: keys order by bit pattern
-                    const float bound = float_from_order_key(s_tau[r]);
-                    if (lists[r].offer(d, row, leader, args.knn_k, bound)) {
-                        lists_changed = true;
-                        if (lists[r].full() && lane == 0) atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
-                    }
-                }
-            }
+        });
+        if constexpr (!KNN) {
             if (leader) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const int out = wave_uniform(s_rows[r].out);
-                    if (out > -2) continue;
-                    const size_t slot = (size_t)(-2 - out);
-                    args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0[r];
-                    if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1[r];
-                    if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2[r];
+                    const int out = row_out[r];
+                    if (out >= 0) args.out[(size_t)out * (size_t)n_b + (size_t)row] = dist[r];
                 }
             }
-        });
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (row_out[r] < 0) continue;
+                const float bound = float_from_order_key(s_tau[r]);
+                if (lists[r].offer(dist[r], row, leader, args.knn_k, bound)) {
+                    lists_changed = true;
+                    if (lists[r].full() && lane == 0) atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
+                }
+            }
+        }
+        if (leader) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int out = row_out[r];
+                if (out > -2) continue;
+                const size_t slot = (size_t)(-2 - out);
+                args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0[r];
+                if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1[r];
+                if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2[r];
+            }
+        }
         if constexpr (KNN) {
             // The wavefronts' lists hold different rows of B.  Once every wavefront holds at
             // least q = ceil(k / wavefronts) entries, the largest of their q-th distances has k
@@ -705,33 +719,43 @@ static hipError_t launch_scan_rkk(hipStream_t st, int block, uint32_t lds_bytes,
     return hipGetLastError();
 }
 
-template <int OP, int R>
+// WHICH: 0 = pairwise instances only, 1 = fused k-NN instances only, 2 = both (a product whose
+// instances take long to compile is spread over two translation units).
+template <int OP, int R, int WHICH>
 static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, const ScanArgs &args) {
     const bool knn = args.knn_k > 0;
-    switch (args.kind) {
-    case KIND_STRIP:
-        return knn ? launch_scan_rkk<OP, R, KIND_STRIP, true>(st, block, lds_bytes, args)
-                   : launch_scan_rkk<OP, R, KIND_STRIP, false>(st, block, lds_bytes, args);
-    case KIND_SLOT:
-        return knn ? launch_scan_rkk<OP, R, KIND_SLOT, true>(st, block, lds_bytes, args)
-                   : launch_scan_rkk<OP, R, KIND_SLOT, false>(st, block, lds_bytes, args);
-    case KIND_HASH:
-        return knn ? launch_scan_rkk<OP, R, KIND_HASH, true>(st, block, lds_bytes, args)
-                   : launch_scan_rkk<OP, R, KIND_HASH, false>(st, block, lds_bytes, args);
-    default: return hipErrorInvalidValue;
+    if ((knn && WHICH == 0) || (!knn && WHICH == 1)) return hipErrorInvalidValue;
+    if constexpr (WHICH != 0) {
+        if (knn) {
+            switch (args.kind) {
+            case KIND_STRIP: return launch_scan_rkk<OP, R, KIND_STRIP, true>(st, block, lds_bytes, args);
+            case KIND_SLOT: return launch_scan_rkk<OP, R, KIND_SLOT, true>(st, block, lds_bytes, args);
+            case KIND_HASH: return launch_scan_rkk<OP, R, KIND_HASH, true>(st, block, lds_bytes, args);
+            default: return hipErrorInvalidValue;
+            }
+        }
     }
+    if constexpr (WHICH != 1) {
+        switch (args.kind) {
+        case KIND_STRIP: return launch_scan_rkk<OP, R, KIND_STRIP, false>(st, block, lds_bytes, args);
+        case KIND_SLOT: return launch_scan_rkk<OP, R, KIND_SLOT, false>(st, block, lds_bytes, args);
+        case KIND_HASH: return launch_scan_rkk<OP, R, KIND_HASH, false>(st, block, lds_bytes, args);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    return hipErrorInvalidValue;
 }
 
-template <int OP>
+template <int OP, int WHICH = 2>
 static hipError_t launch_scan_op(hipStream_t st, int R, int block, uint32_t lds_bytes, const ScanArgs &args) {
     switch (R) {
-    case 1: return launch_scan_r<OP, 1>(st, block, lds_bytes, args);
-    case 2: return launch_scan_r<OP, 2>(st, block, lds_bytes, args);
-    case 4: return launch_scan_r<OP, 4>(st, block, lds_bytes, args);
-    case 8: return launch_scan_r<OP, 8>(st, block, lds_bytes, args);
+    case 1: return launch_scan_r<OP, 1, WHICH>(st, block, lds_bytes, args);
+    case 2: return launch_scan_r<OP, 2, WHICH>(st, block, lds_bytes, args);
+    case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
+    case 8: return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
     case 16:
         if constexpr (OP == OP_JS || OP == OP_MINK) return hipErrorInvalidValue;
-        else return launch_scan_r<OP, 16>(st, block, lds_bytes, args);
+        else return launch_scan_r<OP, 16, WHICH>(st, block, lds_bytes, args);
     default: return hipErrorInvalidValue;
     }
 }
