@@ -123,6 +123,8 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *   "split_len"   B rows at least this long are split over several lanes
  *   "window"      B rows per degree-sorting window
  *   "chunks"      number of B chunks (0 = automatic)
+ *   "waves_per_cu" wavefronts a launch aims to keep on a compute unit: 8, 16 or 32
+ *                 (0 = automatic: 32, or 16 for the fused k-NN kernels)
  *   "side_streams" 1: launches too small to fill the chip run on internal side streams beside
  *                 the large one, forked and joined with events so that the handle's stream
  *                 still orders the whole call (default 1; 0: everything on the handle's stream)

@@ -658,6 +658,10 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "chunks") {
         if (value < 0 || value > 4096) return fail(h, SPD_ERR_UNSUPPORTED, "chunks must lie in [0, 4096]");
         o.chunks = (int)value;
+    } else if (s == "waves_per_cu") {
+        if (value != 0 && value != 8 && value != 16 && value != 32)
+            return fail(h, SPD_ERR_UNSUPPORTED, "waves_per_cu must be 0 (automatic), 8, 16 or 32");
+        o.waves_per_cu = (int)value;
     } else if (s == "side_streams") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must be 0 or 1");
         h->multi_stream = value != 0;

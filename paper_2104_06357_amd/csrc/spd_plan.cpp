@@ -12,12 +12,13 @@ std::string fmt(const char *what, long long a, long long b = 0) {
     return std::string(what) + " (" + std::to_string(a) + ", " + std::to_string(b) + ")";
 }
 
-int block_for(uint32_t stage_bytes, int64_t lds_total) {
-    // One to four workgroups per compute unit, sixteen wavefronts in all.
-    int64_t per_cu = lds_total / (int64_t)(stage_bytes + kStaticLds);
-    if (per_cu >= 4) return 256;
-    if (per_cu >= 2) return 512;
-    return 1024;
+int block_for(uint32_t stage_bytes, int64_t lds_total, int waves_per_cu) {
+    // As many workgroups per compute unit as the LDS holds (at most eight), sized so that
+    // together they bring `waves_per_cu` wavefronts.
+    int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(8, lds_total / (int64_t)(stage_bytes + kStaticLds)));
+    int block = 64;
+    while (block < 1024 && (int64_t)block * per_cu < (int64_t)waves_per_cu * 64) block *= 2;
+    return std::max(block, 256);
 }
 
 }  // namespace
@@ -149,7 +150,7 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
         // slots; each stages its rows, then its wavefronts share the chunk's slabs, the
         // last one finishing up to half a slab after the others.
         const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(opt.lds_budget / ((int64_t)c.lds_bytes + kStaticLds),
-                                                                      (int64_t)16 / waves));
+                                                                      (int64_t)32 / waves));
         const int64_t slots = (int64_t)opt.n_cus * per_cu;
         const double stage = 24.0;
         // more workgroups than four per slot buy nothing
@@ -250,6 +251,8 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     }
     const int64_t budget = opt.lds_budget - kStaticLds;
     auto fits = [&](int kd, int R, uint64_t sumlen) { return staging_fits(kd, R, sumlen, k, cheb, budget); };
+    // the fused k-NN instances hold more registers per lane: fewer of their wavefronts fit
+    const int want_waves = opt.waves_per_cu > 0 ? opt.waves_per_cu : (knn_k > 0 ? 16 : 32);
 
     auto finish_class = [&](AClass &c) {
         auto need_at = [&](int hs) {
@@ -263,13 +266,13 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         if (c.kind == KIND_HASH) {
             // a sparser table shortens the probe sequences: take the sparsest one that
             // leaves the launch as many workgroups per compute unit as it has now
-            const int now = block_for(need, opt.lds_budget);
+            const int now = block_for(need, opt.lds_budget, want_waves);
             for (int hs = 3; hs >= 2; --hs) {
                 uint32_t wider = need_at(hs);
-                if ((int64_t)wider <= budget && block_for(wider, opt.lds_budget) == now) { c.hscale = hs; need = wider; break; }
+                if ((int64_t)wider <= budget && block_for(wider, opt.lds_budget, want_waves) == now) { c.hscale = hs; need = wider; break; }
             }
         }
-        c.block = std::min(block_for(need, opt.lds_budget), scan_max_block(metric_info(metric).op, c.R, knn_k > 0));
+        c.block = std::min(block_for(need, opt.lds_budget, want_waves), scan_max_block(metric_info(metric).op, c.R, knn_k > 0));
         if (knn_k > 0) {
             while (c.block > kWave && (int64_t)knn_merge_bytes(c.block, c.R, knn_k) > budget) c.block /= 2;
             need = std::max(need, knn_merge_bytes(c.block, c.R, knn_k));
@@ -351,7 +354,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 int ci = 0;
                 while ((16 >> ci) != R) ++ci;
                 uint32_t need = lds_layout(kind, R, (uint32_t)sum, k, cheb, 1).total;
-                int blk = block_for(need, opt.lds_budget);
+                int blk = block_for(need, opt.lds_budget, want_waves);
                 AClass &c = *by_key[ci][blk == 256 ? 0 : (blk == 512 ? 1 : 2)];
                 for (int q = 0; q < R; ++q)
                     c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});

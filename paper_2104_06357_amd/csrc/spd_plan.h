@@ -46,6 +46,7 @@ struct PlanOptions {
     int window = 2048;
     int chunks = 0;
     int n_cus = 256;
+    int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32, or 16 for k-NN)
 };
 
 // Sums a pair carries through the slices of a spilled row.
