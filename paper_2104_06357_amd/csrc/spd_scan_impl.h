@@ -195,27 +195,29 @@ template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const 
 // ------------------------------------------------------------------------------------
 // The hash table is an array of buckets of two {column, slot} entries, read with one
 // 16-byte LDS load.  An entry is claimed in the first free place of its home bucket, else
-// of the next bucket, and entries are never removed: a bucket whose second place is empty
-// ends every probe sequence that reaches it.
+// of the next bucket, and entries are never removed.  While the table is built the longest
+// such walk is recorded: a lookup reads exactly that many buckets from its home bucket on,
+// the same number in every lane, with no branch (a column that was never staged, and the
+// idle column, which is the empty key, come out as slot 0).
 template <int KIND> struct ColumnMap {
     const uint16_t *slot16;   // KIND_SLOT: k+1 entries
     const uint4 *table;       // KIND_HASH: buckets {column, slot, column, slot}, empty = {kEmptyKey, 0}
     uint32_t mask, shift;     // over buckets
+    int reach;                // KIND_HASH: buckets a lookup reads (at least 1)
     __device__ __forceinline__ uint32_t home(uint32_t c) const { return (c * 0x9E3779B1u) >> shift; }
-    // Continues a hash lookup from its first bucket `e` (at `h`).
-    __device__ __forceinline__ uint32_t resolve(uint32_t c, uint32_t h, uint4 e) const {
-        for (;;) {
-            if (e.x == c) return e.y;          // the idle column is the empty key: slot 0
-            if (e.z == c) return e.w;
-            if (e.z == kEmptyKey) return 0u;
-            h = (h + 1u) & mask;
-            e = table[h];
-        }
+    __device__ __forceinline__ static uint32_t match(uint32_t c, uint4 e, uint32_t slot) {
+        slot = (e.x == c) ? e.y : slot;
+        return (e.z == c) ? e.w : slot;
+    }
+    // Buckets after the home bucket.
+    __device__ __forceinline__ uint32_t beyond(uint32_t c, uint32_t h, uint32_t slot) const {
+        for (int i = 1; i < reach; ++i) slot = match(c, table[(h + (uint32_t)i) & mask], slot);
+        return slot;
     }
     __device__ __forceinline__ uint32_t lookup(uint32_t c) const {
         if constexpr (KIND == KIND_STRIP) return c;
         else if constexpr (KIND == KIND_SLOT) return slot16[c];
-        else { uint32_t h = home(c); return resolve(c, h, table[h]); }
+        else { uint32_t h = home(c); return beyond(c, h, match(c, table[h], 0u)); }
     }
 };
 
@@ -261,6 +263,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     __shared__ uint32_t s_prefix[R + 1];
     __shared__ double s_na[R][2];
     __shared__ int s_ctr;
+    __shared__ int s_reach;                      // hash staging: buckets the longest insertion walked
     __shared__ uint32_t s_tau[KNN ? R : 1];      // k-NN: an upper bound of the workgroup's k-th distance, per row
     __shared__ uint32_t s_share[KNN ? R * 16 : 1];   // k-NN: each wavefront's ceil(k / wavefronts)-th distance, per row
     __shared__ float s_top[kCheb ? R * kTopRanks : 1];
@@ -309,6 +312,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     cmap.table = table;
     cmap.mask = L.cap ? L.cap / 2u - 1u : 0u;
     cmap.shift = L.cap ? 33u - (uint32_t)__builtin_ctz(L.cap) : 0u;
+    cmap.reach = 1;
 
     // ---- stage ------------------------------------------------------------------------
     // 1. clear the value table and the column map
@@ -335,6 +339,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         for (int r = 0; r < R; ++r) { s_prefix[r] = acc; acc += (uint32_t)s_rows[r].len; }
         s_prefix[R] = acc;
         s_ctr = slab_begin;
+        s_reach = 1;
     }
     if constexpr (KNN) {
         if (tid < R) s_tau[tid] = float_order_key(__builtin_huge_valf());
@@ -376,7 +381,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                     if (slot16[c] == 0) slot16[c] = (uint16_t)(e + 1u);
                 } else {
                     uint32_t h = cmap.home(c);
-                    for (;;) {
+                    int walked = 1;
+                    for (;; ++walked) {
                         uint32_t old = atomicCAS(&table[h].x, kEmptyKey, c);
                         if (old == kEmptyKey) { table[h].y = e + 1u; break; }
                         if (old == c) break;
@@ -385,10 +391,12 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                         if (old == c) break;
                         h = (h + 1u) & cmap.mask;
                     }
+                    if (walked > 1) atomicMax(&s_reach, walked);
                 }
             }
         }
         __syncthreads();
+        if constexpr (KIND == KIND_HASH) cmap.reach = wave_uniform(s_reach);
     }
     // 4. fill the value table
     for (uint32_t e = tid; e < total; e += nthr) {
@@ -517,7 +525,13 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 #pragma unroll
                 for (int u = 0; u < U; ++u) { h[u] = cmap.home(cur[u].x); e[u] = table[h[u]]; }
 #pragma unroll
-                for (int u = 0; u < U; ++u) slot[u] = cmap.resolve(cur[u].x, h[u], e[u]);
+                for (int u = 0; u < U; ++u) slot[u] = ColumnMap<KIND>::match(cur[u].x, e[u], 0u);
+                for (int i = 1; i < cmap.reach; ++i) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) e[u] = table[(h[u] + (uint32_t)i) & cmap.mask];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) slot[u] = ColumnMap<KIND>::match(cur[u].x, e[u], slot[u]);
+                }
             } else {
 #pragma unroll
                 for (int u = 0; u < U; ++u) slot[u] = cmap.lookup(cur[u].x);
