@@ -119,10 +119,14 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
 /* Planner knobs, mainly for tests that need to reach a particular staging path:
  *   "lds_budget"  bytes of LDS a workgroup may use (default: the device limit)
  *   "force_kind"  0 auto, 1 dense strip, 2 column-slot strip, 3 hash
- *   "max_rows"    largest number of A rows staged together (1, 2, 4, 8 or 16)
+ *   "max_rows"    largest number of A rows staged together (1, 2, 4, 8 or 16; the set metrics,
+ *                 whose rows take a byte each in the staged table, stage four times as many,
+ *                 up to 32, or 16 with fused k-NN)
  *   "split_len"   B rows at least this long are split over several lanes
  *   "window"      B rows per degree-sorting window
  *   "chunks"      number of B chunks (0 = automatic)
+ *   "byte_counters" 1 (default): Jaccard, Dice and Russell-Rao count shared columns in byte lanes,
+ *                 four staged rows to the 32-bit word; 0: through the dot product of 0/1 values
  *   "waves_per_cu" wavefronts a launch aims to keep on a compute unit: 8, 16 or 32
  *                 (0 = automatic: 32, or 16 for the fused k-NN kernels)
  *   "side_streams" 1: launches too small to fill the chip run on internal side streams beside

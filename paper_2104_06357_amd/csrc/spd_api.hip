@@ -31,6 +31,7 @@ struct spd_handle {
     int32_t *flag = nullptr;     // device word for spd_csr_validate
     bool profile = false;
     bool check_plan = false;
+    bool no_byte_counters = false;   // option "byte_counters" 0: set metrics through the dot product
     bool multi_stream = true;    // option "side_streams": small launches run beside the large one
     static constexpr int kSideStreams = 3;
     hipStream_t side[kSideStreams] = {nullptr, nullptr, nullptr};
@@ -215,9 +216,12 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     std::string why = plan_b(b_ip, n, h->opt, bp);
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
     lap("plan b");
-    int a_kind = 0, a_max_r = 1;
+    // the set metrics count shared columns in byte lanes, or (option) as a dot product of 0/1 values
+    int op = mi.op;
+    if (op == OP_CNT && h->no_byte_counters) op = OP_DOT;
+    int a_kind = 0, a_max_r = 1, a_min_r = 1;
     uint64_t a_dmax = 0;
-    why = plan_staging(A->n_cols, (int)metric, h->opt, a_kind, a_max_r, a_dmax);
+    why = plan_staging(A->n_cols, (int)metric, op, knn_k > 0, h->opt, a_kind, a_max_r, a_min_r, a_dmax);
     if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "A: " + why);
     // every launch of a call stages the same way: one pad column serves them all
     const uint32_t padcol = a_kind == KIND_HASH ? kEmptyKey : (uint32_t)A->n_cols;
@@ -305,13 +309,13 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     lap("stage b");
 
     // ---- A, while the repack runs -------------------------------------------------------
-    why = plan_a(a_ip, m, A->n_cols, (int)metric, knn_k, h->opt, ap);
+    why = plan_a(a_ip, m, A->n_cols, (int)metric, op, knn_k, h->opt, ap);
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
     lap("plan a");
     for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
     lap("chunks");
     if (h->check_plan) {
-        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, knn_k, h->opt);
+        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, op, knn_k, h->opt);
         if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
     }
     for (const AClass &c : ap.classes)
@@ -449,7 +453,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         for (const ARow &r : c.rows) live_rows += (r.out != -1);
         LaunchTimer lt(h, "scan", c.R, c.kind, c.block, c.lds_bytes, live_rows, (int64_t)c.n_groups * c.n_chunks,
                        st_launch);
-        e = launch_scan(st_launch, mi.op, c.R, c.block, c.lds_bytes, sa);
+        e = launch_scan(st_launch, op, c.R, c.block, c.lds_bytes, sa);
         if (e != hipSuccess) return hip_fail(h, e, "scan kernel");
         lt.done();
     }
@@ -658,6 +662,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "chunks") {
         if (value < 0 || value > 4096) return fail(h, SPD_ERR_UNSUPPORTED, "chunks must lie in [0, 4096]");
         o.chunks = (int)value;
+    } else if (s == "byte_counters") {
+        if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "byte_counters must be 0 or 1");
+        h->no_byte_counters = value == 0;
     } else if (s == "waves_per_cu") {
         if (value != 0 && value != 8 && value != 16 && value != 32)
             return fail(h, SPD_ERR_UNSUPPORTED, "waves_per_cu must be 0 (automatic), 8, 16 or 32");

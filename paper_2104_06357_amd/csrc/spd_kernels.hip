@@ -36,7 +36,9 @@ __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restri
         if (t < len) {
             float v = transform_value(transform, b_values[start + t]);
             norm_accumulate(norm, v, p, s0, s1);
-            e = make_uint2((uint32_t)b_indices[start + t], __float_as_uint(v));
+            // a stored zero of a set metric is absent: it takes the column that stages nothing
+            const uint32_t col = (transform == TR_NONZERO && v == 0.0f) ? padcol : (uint32_t)b_indices[start + t];
+            e = make_uint2(col, __float_as_uint(v));
         }
         dst[(size_t)t * kWave] = e;
     }

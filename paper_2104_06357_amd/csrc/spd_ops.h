@@ -27,7 +27,7 @@
 
 namespace spd {
 
-enum OpId { OP_DOT = 0, OP_L1, OP_MINK, OP_CANB, OP_HAMM, OP_KL, OP_JS, OP_CHEB, OP_COUNT };
+enum OpId { OP_DOT = 0, OP_L1, OP_MINK, OP_CANB, OP_HAMM, OP_KL, OP_JS, OP_CHEB, OP_CNT, OP_COUNT };
 enum Transform { TR_ID = 0, TR_SQRT, TR_NONZERO };
 enum NormKind { NORM_NONE = 0, NORM_SUMSQ, NORM_SUM_SUMSQ, NORM_SUM, NORM_SUM_ABS, NORM_SUM_POW, NORM_NNZ };
 
@@ -45,8 +45,8 @@ SPD_HD constexpr MetricInfo metric_info(int metric) {
     case MT_COSINE:      return {OP_DOT, TR_ID, NORM_SUMSQ};
     case MT_L2:          return {OP_DOT, TR_ID, NORM_SUMSQ};
     case MT_CORRELATION: return {OP_DOT, TR_ID, NORM_SUM_SUMSQ};
-    case MT_JACCARD:     return {OP_DOT, TR_NONZERO, NORM_SUM};
-    case MT_DICE:        return {OP_DOT, TR_NONZERO, NORM_SUM};
+    case MT_JACCARD:     return {OP_CNT, TR_NONZERO, NORM_SUM};
+    case MT_DICE:        return {OP_CNT, TR_NONZERO, NORM_SUM};
     case MT_HELLINGER:   return {OP_DOT, TR_SQRT, NORM_SUMSQ};
     case MT_L1:          return {OP_L1, TR_ID, NORM_SUM_ABS};
     case MT_CHEBYSHEV:   return {OP_CHEB, TR_ID, NORM_NONE};
@@ -55,7 +55,7 @@ SPD_HD constexpr MetricInfo metric_info(int metric) {
     case MT_HAMMING:     return {OP_HAMM, TR_ID, NORM_NNZ};
     case MT_KL:          return {OP_KL, TR_ID, NORM_NONE};
     case MT_JS:          return {OP_JS, TR_ID, NORM_SUM};
-    case MT_RUSSELL_RAO: return {OP_DOT, TR_NONZERO, NORM_NONE};
+    case MT_RUSSELL_RAO: return {OP_CNT, TR_NONZERO, NORM_NONE};
     default:             return {-1, 0, 0};
     }
 }
@@ -230,6 +230,23 @@ template <> struct Op<OP_HAMM> {
     SPD_HD static double v2(const Acc &) { return 0.0; }
 };
 
+// Set metrics: the number of shared columns.  The scan kernel counts it for many staged
+// rows at a time in byte lanes of 32-bit words (one byte of the staged table per row); this
+// form, one pair at a time, serves the host.
+template <> struct Op<OP_CNT> {
+    struct Acc { int c; };
+    struct Bv { float b; };
+    SPD_HD static void init(Acc &x) { x.c = 0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
+        x.c += ((a != 0.0f) && (b.b != 0.0f)) ? 1 : 0;
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.c += y.c; }
+    SPD_HD static double v0(const Acc &x) { return (double)x.c; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
 // KL: a log(a/b) = ln 2 * a log2(a/b) on shared columns, with a correctly rounded quotient so
 // that equal entries give exactly 0; the factor ln 2 is applied once, by finish().
 template <> struct Op<OP_KL> {
@@ -304,11 +321,15 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
     } else if constexpr (MT == MT_CORRELATION) {
         return (float)((a1 == 0.0 || b1 == 0.0) ? 1.0 : 1.0 - (q.k * v - a0 * b0) * a1 * b1);
     } else if constexpr (MT == MT_JACCARD) {
+        // counts below 2^24 are exact in fp32 and one fp32 quotient is well inside the
+        // tolerance: the 64-bit division is kept for rows beyond that
         double u = a0 + b0 - v;
-        return (float)((u == 0.0) ? 0.0 : 1.0 - v / u);
+        if (u < 16777216.0) { float uf = (float)u; return uf == 0.0f ? 0.0f : 1.0f - fast_div((float)v, uf); }
+        return (float)(1.0 - v / u);
     } else if constexpr (MT == MT_DICE) {
         double t = a0 + b0;
-        return (float)((t == 0.0) ? 0.0 : 1.0 - 2.0 * v / t);
+        if (t < 8388608.0) { float tf = (float)t; return tf == 0.0f ? 0.0f : 1.0f - fast_div(2.0f * (float)v, tf); }
+        return (float)(1.0 - 2.0 * v / t);
     } else if constexpr (MT == MT_HELLINGER) {
         double t = 0.5 * (a0 + b0) - v;
         return sqrtf((float)(t > 0.0 ? t : 0.0));
@@ -340,10 +361,16 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
 
 template <int MT> struct MetricTag { static constexpr int value = MT; };
 
-// Calls f(MetricTag<m>) for the metric `metric`, which must be one computed by product OP
+// The product that computes a metric, and OP_DOT for the set metrics too (a dot product of
+// 0/1 values counts the shared columns: the route the option "byte_counters" 0 selects).
+SPD_HD constexpr bool op_serves(int op, int metric) {
+    return metric_info(metric).op == op || (op == OP_DOT && metric_info(metric).op == OP_CNT);
+}
+
+// Calls f(MetricTag<m>) for the metric `metric`, which must be one that product OP serves
 // (the others are not instantiated: a kernel of one product carries only its own formulas).
 template <int OP, typename F> SPD_HD void for_metric_of(int metric, F &&f) {
-#define SPD_CASE(M) case M: if constexpr (metric_info(M).op == OP) f(MetricTag<M>{}); break;
+#define SPD_CASE(M) case M: if constexpr (op_serves(OP, M)) f(MetricTag<M>{}); break;
     switch (metric) {
         SPD_CASE(MT_INNER) SPD_CASE(MT_COSINE) SPD_CASE(MT_L2) SPD_CASE(MT_CORRELATION) SPD_CASE(MT_JACCARD)
         SPD_CASE(MT_DICE) SPD_CASE(MT_HELLINGER) SPD_CASE(MT_L1) SPD_CASE(MT_CHEBYSHEV) SPD_CASE(MT_MINKOWSKI)

@@ -191,33 +191,41 @@ bool staging_fits(int kind, int R, uint64_t sumlen, uint32_t k, bool cheb, int64
 
 }  // namespace
 
-std::string plan_staging(int64_t n_cols, int metric, const PlanOptions &opt, int &kind, int &max_r, uint64_t &dmax) {
+std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const PlanOptions &opt, int &kind, int &max_r,
+                         int &min_r, uint64_t &dmax) {
     const bool cheb = metric == MT_CHEBYSHEV;
     const uint32_t k = (uint32_t)n_cols;
-    max_r = std::min(opt.max_rows, kMaxR);
+    max_r = std::min(opt.max_rows, 16);
     if (metric == MT_JS || metric == MT_MINKOWSKI) max_r = std::min(max_r, 8);   // two fp64 sums per pair
     if (max_r < 1) max_r = 1;
     while (max_r & (max_r - 1)) max_r &= max_r - 1;         // power of two
+    min_r = 1;
+    if (op == OP_CNT) {
+        // a byte per row: four rows to the word, and the k-NN lists bound the registers
+        min_r = 4;
+        max_r = std::min(4 * max_r, knn ? 16 : 32);
+    }
+    auto words = [&](int R) { return table_words(op, R); };
     if (opt.lds_budget <= (int64_t)kStaticLds + 256) return "lds_budget too small";
     const int64_t budget = opt.lds_budget - kStaticLds;
     kind = opt.force_kind;
     if (kind == KIND_AUTO) {
-        if (staging_fits(KIND_STRIP, std::min(4, max_r), 0, k, cheb, budget)) kind = KIND_STRIP;
+        if (staging_fits(KIND_STRIP, words(std::min(4 * min_r, max_r)), 0, k, cheb, budget)) kind = KIND_STRIP;
         else if ((int64_t)(k + 1) * 2 <= budget / 3) kind = KIND_SLOT;
         else kind = KIND_HASH;
     }
     if (kind < KIND_STRIP || kind > KIND_HASH) return "bad staging kind";
     dmax = 0;
     if (kind == KIND_STRIP) {
-        if (!staging_fits(KIND_STRIP, 1, 0, k, cheb, budget)) return "dense strip does not fit the LDS budget";
-        while (max_r > 1 && !staging_fits(KIND_STRIP, max_r, 0, k, cheb, budget)) max_r /= 2;
+        if (!staging_fits(KIND_STRIP, words(min_r), 0, k, cheb, budget)) return "dense strip does not fit the LDS budget";
+        while (max_r > min_r && !staging_fits(KIND_STRIP, words(max_r), 0, k, cheb, budget)) max_r /= 2;
         return std::string();
     }
-    if (!staging_fits(kind, 1, 1, k, cheb, budget)) return "LDS budget too small to stage a single entry";
+    if (!staging_fits(kind, words(min_r), 1, k, cheb, budget)) return "LDS budget too small to stage a single entry";
     uint64_t lo = 1, hi = 65534;
     while (lo < hi) {
         uint64_t mid = (lo + hi + 1) / 2;
-        if (staging_fits(kind, 1, mid, k, cheb, budget)) lo = mid; else hi = mid - 1;
+        if (staging_fits(kind, words(min_r), mid, k, cheb, budget)) lo = mid; else hi = mid - 1;
     }
     dmax = lo;
     return std::string();
@@ -226,10 +234,11 @@ std::string plan_staging(int64_t n_cols, int metric, const PlanOptions &opt, int
 // ------------------------------------------------------------------------------------
 // A: groups of R staged rows
 // ------------------------------------------------------------------------------------
-std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int knn_k,
+std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int op, int knn_k,
                    const PlanOptions &opt, APlan &out) {
     // take the buffers of the previous plan back before anything else
-    if (out.pool.size() != 16) out.pool.assign(16, AClass());
+    constexpr size_t kPool = 6 * 3 + 1;       // 6 group sizes x 3 occupancies, and the dense strip's one class
+    if (out.pool.size() != kPool) out.pool.assign(kPool, AClass());
     for (AClass &c : out.classes) { const int slot = c.pool_slot; out.pool[(size_t)slot] = std::move(c); }
     out.classes.clear();
     out.spilled.clear();
@@ -243,14 +252,14 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         if (indptr[i + 1] < indptr[i]) return fmt("row pointers decrease at row", i);
     const bool cheb = metric == MT_CHEBYSHEV;
     const uint32_t k = (uint32_t)n_cols;
-    int kind = 0, max_r = 1;
+    int kind = 0, max_r = 1, min_r = 1;
     uint64_t dmax = 0;
     {
-        std::string why = plan_staging(n_cols, metric, opt, kind, max_r, dmax);
+        std::string why = plan_staging(n_cols, metric, op, knn_k > 0, opt, kind, max_r, min_r, dmax);
         if (!why.empty()) return why;
     }
     const int64_t budget = opt.lds_budget - kStaticLds;
-    auto fits = [&](int kd, int R, uint64_t sumlen) { return staging_fits(kd, R, sumlen, k, cheb, budget); };
+    auto fits = [&](int kd, int R, uint64_t sumlen) { return staging_fits(kd, table_words(op, R), sumlen, k, cheb, budget); };
     // the fused k-NN instances hold more registers per lane: fewer of their wavefronts fit
     const int want_waves = opt.waves_per_cu > 0 ? opt.waves_per_cu : (knn_k > 0 ? 16 : 32);
 
@@ -258,7 +267,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         auto need_at = [&](int hs) {
             uint32_t need = 0;
             for (int g = 0; g < c.n_groups; ++g)
-                need = std::max(need, lds_layout(c.kind, c.R, (uint32_t)c.sumlen[(size_t)g], k, cheb, hs).total);
+                need = std::max(need, lds_layout(c.kind, table_words(op, c.R), (uint32_t)c.sumlen[(size_t)g], k, cheb, hs).total);
             return need;
         };
         uint32_t need = need_at(1);
@@ -272,7 +281,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 if ((int64_t)wider <= budget && block_for(wider, opt.lds_budget, want_waves) == now) { c.hscale = hs; need = wider; break; }
             }
         }
-        c.block = std::min(block_for(need, opt.lds_budget, want_waves), scan_max_block(metric_info(metric).op, c.R, knn_k > 0));
+        c.block = std::min(block_for(need, opt.lds_budget, want_waves), scan_max_block(op, c.R, knn_k > 0));
         if (knn_k > 0) {
             while (c.block > kWave && (int64_t)knn_merge_bytes(c.block, c.R, knn_k) > budget) c.block /= 2;
             need = std::max(need, knn_merge_bytes(c.block, c.R, knn_k));
@@ -282,8 +291,8 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
 
     if (kind == KIND_STRIP) {
         int R = max_r;
-        AClass &c = out.pool[15];
-        c.pool_slot = 15;
+        AClass &c = out.pool[kPool - 1];
+        c.pool_slot = (int)kPool - 1;
         c.R = R; c.kind = KIND_STRIP;
         c.n_groups = (int)((n_rows + R - 1) / R);
         c.rows.assign((size_t)c.n_groups * R, ARow{0, 0, -1, kRowFirst | kRowLast, 0});
@@ -332,28 +341,30 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
 
     // one launch per (R, workgroups per compute unit): groups that need little LDS are not
     // held to the occupancy of the heaviest ones
-    AClass *by_key[5][3];                     // R = 16, 8, 4, 2, 1  x  block 256 / 512 / 1024
-    for (int q = 0; q < 5; ++q)
+    AClass *by_key[6][3];                     // R = 32, 16, 8, 4, 2, 1  x  block 256 / 512 / 1024
+    for (int q = 0; q < 6; ++q)
         for (int b = 0; b < 3; ++b) {
             by_key[q][b] = &out.pool[(size_t)(q * 3 + b)];
             by_key[q][b]->pool_slot = q * 3 + b;
-            by_key[q][b]->R = 16 >> q;
+            by_key[q][b]->R = 32 >> q;
             by_key[q][b]->kind = kind;
         }
     size_t t = 0;
     while (t < items.size()) {
         size_t remaining = items.size() - t;
         int R = max_r;
-        while (R > 1 && (size_t)(R / 2) >= remaining) R /= 2;
+        while (R > min_r && (size_t)(R / 2) >= remaining) R /= 2;
         for (;; R /= 2) {
             size_t n = std::min<size_t>((size_t)R, remaining);
             uint64_t sum = 0;
             for (size_t q = 0; q < n; ++q) sum += (uint64_t)items[t + q].len;
-            if (fits(kind, R, sum) || R == 1) {
+            if (fits(kind, R, sum) || R == min_r) {
+                // the smallest group may have to leave places empty (longest items come first)
+                while (n > 1 && !fits(kind, R, sum)) sum -= (uint64_t)items[t + --n].len;
                 if (!fits(kind, R, sum)) return "internal: slice does not fit";
                 int ci = 0;
-                while ((16 >> ci) != R) ++ci;
-                uint32_t need = lds_layout(kind, R, (uint32_t)sum, k, cheb, 1).total;
+                while ((32 >> ci) != R) ++ci;
+                uint32_t need = lds_layout(kind, table_words(op, R), (uint32_t)sum, k, cheb, 1).total;
                 int blk = block_for(need, opt.lds_budget, want_waves);
                 AClass &c = *by_key[ci][blk == 256 ? 0 : (blk == 512 ? 1 : 2)];
                 for (int q = 0; q < R; ++q)
@@ -365,7 +376,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
             }
         }
     }
-    for (int q = 0; q < 5; ++q)
+    for (int q = 0; q < 6; ++q)
         for (int b = 0; b < 3; ++b)
             if (by_key[q][b]->n_groups) { finish_class(*by_key[q][b]); out.classes.push_back(std::move(*by_key[q][b])); }
     return std::string();
@@ -375,21 +386,22 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
 // consistency check of everything the kernels index with
 // ------------------------------------------------------------------------------------
 std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, const int64_t *b_indptr,
-                       int64_t n_cols, int metric, int knn_k, const PlanOptions &opt) {
+                       int64_t n_cols, int metric, int op, int knn_k, const PlanOptions &opt) {
     const bool cheb = metric == MT_CHEBYSHEV;
     const int64_t a_nnz = a.n_rows ? a_indptr[a.n_rows] : 0;
     std::vector<int64_t> covered((size_t)a.n_rows, 0);
     std::vector<int64_t> slot_lo((size_t)a.n_partial_slots, -1), slot_hi((size_t)a.n_partial_slots, -1);
     std::vector<uint32_t> slot_flags((size_t)a.n_partial_slots, 0);
     for (const AClass &c : a.classes) {
-        if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16) return "class R";
+        if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16 && c.R != 32) return "class R";
+        if (op == OP_CNT ? (c.R < 4 || (knn_k > 0 && c.R > 16)) : c.R > 16) return "class R outside the product's range";
         if ((metric == MT_JS || metric == MT_MINKOWSKI) && c.R > 8) return "two-sum product with R > 8";
         if (c.kind < KIND_STRIP || c.kind > KIND_HASH) return "class kind";
         if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";
         if ((int64_t)c.lds_bytes + kStaticLds > opt.lds_budget) return "class LDS over budget";
         if ((size_t)c.n_groups * c.R != c.rows.size() || (size_t)c.n_groups != c.sumlen.size()) return "class sizes";
         if (knn_k > 0 && knn_merge_bytes(c.block, c.R, knn_k) > c.lds_bytes) return "k-NN merge area";
-        if (c.block > scan_max_block(metric_info(metric).op, c.R, knn_k > 0)) return "class block over the kernel's bound";
+        if (c.block > scan_max_block(op, c.R, knn_k > 0)) return "class block over the kernel's bound";
         for (int g = 0; g < c.n_groups; ++g) {
             int64_t sum = 0;
             for (int r = 0; r < c.R; ++r) {
@@ -414,7 +426,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
             }
             if (sum != c.sumlen[(size_t)g]) return "group sumlen";
             if (c.hscale < 1 || c.hscale > 3) return "class hash scale";
-            LdsLayout L = lds_layout(c.kind, c.R, (uint32_t)sum, (uint32_t)n_cols, cheb, c.hscale);
+            LdsLayout L = lds_layout(c.kind, table_words(op, c.R), (uint32_t)sum, (uint32_t)n_cols, cheb, c.hscale);
             if (c.kind == KIND_HASH && (L.cap < 2u * (uint32_t)sum || L.cap < 16u)) return "hash table too full";
             if (L.total > c.lds_bytes) return "group LDS over the launch size";
             if (c.kind != KIND_STRIP && L.nslots > 65535u) return "slot ids over 16 bits";
@@ -437,6 +449,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
         if (covered[(size_t)i] != 1) return fmt("A row not covered exactly once", i, covered[(size_t)i]);
 
     if ((size_t)b.n_slabs + 1 != b.slab_base.size() || (size_t)b.n_slabs != b.slab_steps.size()) return "B slab arrays";
+
     size_t lanes = (size_t)b.n_slabs * kWave;
     if (b.seg_len.size() != lanes || b.seg_row.size() != lanes || b.seg_start.size() != lanes || b.seg_glog.size() != lanes)
         return "B lane arrays";

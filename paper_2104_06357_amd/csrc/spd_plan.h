@@ -32,7 +32,7 @@ enum StageKind { KIND_AUTO = 0, KIND_STRIP = 1, KIND_SLOT = 2, KIND_HASH = 3 };
 
 constexpr int kWave = 64;
 constexpr int kScanUnroll = 4;              // a slab is scanned in blocks of this many steps
-constexpr int kMaxR = 16;
+constexpr int kMaxR = 32;                   // 32 only for the set metrics (one byte per staged row)
 constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
 constexpr int kKnnMaxK = 64;                // fused k-NN: one list entry per lane
 constexpr int kTopRanks = 32;               // Chebyshev: largest entries tracked per staged row
@@ -49,18 +49,23 @@ struct PlanOptions {
     int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32, or 16 for k-NN)
 };
 
+// 4-byte words a slot of the staged value table holds for R rows: one fp32 per row, or one
+// byte per row for the set metrics.
+SPD_HD constexpr int table_words(int op, int R) { return op == OP_CNT ? (R + 3) / 4 : R; }
+constexpr int kCntMaxSteps = 252;           // byte counters are folded into 32-bit counts at least this often
+
 // Sums a pair carries through the slices of a spilled row.
 SPD_HD constexpr int metric_planes(int metric) { return metric == MT_MINKOWSKI ? 3 : (metric == MT_JS ? 2 : 1); }
 
 // Largest workgroup a scan kernel instance may be launched with: the instances that carry
 // the most per-lane state get 256 registers per lane instead of 128.
 SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
-    (void)knn;
+    if (op == OP_CNT) return (knn && R >= 16) ? 512 : 1024;
     return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_MINK) && R == 8)) ? 512 : 1024;
 }
 
 // Dynamic-LDS layout of one staged group.  The same function sizes the launch on the host
-// and carves the buffer in the kernel.
+// and carves the buffer in the kernel.  `R` here is table_words(op, rows).
 struct LdsLayout {
     uint32_t nslots;     // rows of the value table (R floats each)
     uint32_t cap;        // hash capacity in entries (power of two, two entries per bucket), 0 otherwise
@@ -151,11 +156,13 @@ struct BPlan {
 
 // Staging kind for a column count, the largest number of rows staged together, and the
 // longest slice of a row that fits alone (0 = no limit).  Empty string on success.
-std::string plan_staging(int64_t n_cols, int metric, const PlanOptions &opt, int &kind, int &max_r, uint64_t &dmax);
+// `op` is the product whose kernels will run (the metric's own, or OP_DOT standing in for OP_CNT).
+std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const PlanOptions &opt, int &kind, int &max_r,
+                         int &min_r, uint64_t &dmax);
 
 // Both return an empty string on success, else the reason.
 std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt, BPlan &out);
-std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int knn_k,
+std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int op, int knn_k,
                    const PlanOptions &opt, APlan &out);
 // Cuts B's slabs into chunks for one launch: enough workgroups to fill the chip, yet chunks
 // long enough that a workgroup's wavefronts stay evenly loaded and staging is amortised.
@@ -164,7 +171,7 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt);
 // Checks every index a kernel will form from the plan (bounds of segments, slabs, groups,
 // LDS sizes).  Empty string if consistent.
 std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, const int64_t *b_indptr,
-                       int64_t n_cols, int metric, int knn_k, const PlanOptions &opt);
+                       int64_t n_cols, int metric, int op, int knn_k, const PlanOptions &opt);
 
 // LDS needed to merge the per-wave k-NN lists of a workgroup (overlays the staging area).
 inline uint32_t knn_merge_bytes(int block, int R, int k) {

@@ -4,6 +4,8 @@
 namespace spd {
 hipError_t launch_scan_dot(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_dot_knn(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_cnt(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_cnt_knn(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_l1(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_mink(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_canb(hipStream_t, int, int, uint32_t, const ScanArgs &);
@@ -17,6 +19,9 @@ hipError_t launch_scan(hipStream_t st, int op, int R, int block, uint32_t lds_by
     case OP_DOT:
         return args.knn_k > 0 ? launch_scan_dot_knn(st, R, block, lds_bytes, args)
                               : launch_scan_dot(st, R, block, lds_bytes, args);
+    case OP_CNT:
+        return args.knn_k > 0 ? launch_scan_cnt_knn(st, R, block, lds_bytes, args)
+                              : launch_scan_cnt(st, R, block, lds_bytes, args);
     case OP_L1: return launch_scan_l1(st, R, block, lds_bytes, args);
     case OP_MINK: return launch_scan_mink(st, R, block, lds_bytes, args);
     case OP_CANB: return launch_scan_canb(st, R, block, lds_bytes, args);

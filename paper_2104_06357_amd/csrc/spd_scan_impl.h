@@ -181,6 +181,7 @@ SPD_ACC_SHFL1(OP_DOT, v)
 SPD_ACC_SHFL1(OP_L1, v)
 SPD_ACC_SHFL1(OP_CANB, v)
 SPD_ACC_SHFL1(OP_HAMM, c)
+SPD_ACC_SHFL1(OP_CNT, c)
 SPD_ACC_SHFL1(OP_KL, v)
 SPD_ACC_SHFL1(OP_CHEB, m)
 template <> __device__ __forceinline__ Op<OP_MINK>::Acc acc_shfl_xor<OP_MINK>(const Op<OP_MINK>::Acc &a, int m) {
@@ -257,6 +258,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     using O = Op<OP>;
     using Acc = typename O::Acc;
     constexpr bool kCheb = (OP == OP_CHEB);
+    constexpr bool kCnt = (OP == OP_CNT);          // set metrics: one byte of the table per staged row
+    constexpr int W = table_words(OP, R);          // 4-byte words per slot of the value table
+    static_assert(!kCnt || (R % 4 == 0), "byte counters come four to the word");
     constexpr int U = kScanUnroll;
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ ARow s_rows[R];
@@ -302,7 +306,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 
     if (tid < R) s_rows[tid] = args.arows[(size_t)g * R + tid];
     const uint32_t sumlen = (uint32_t)args.sumlen[g];
-    const LdsLayout L = lds_layout(KIND, R, sumlen, args.k, kCheb, args.hscale);
+    const LdsLayout L = lds_layout(KIND, W, sumlen, args.k, kCheb, args.hscale);
     float *vals = reinterpret_cast<float *>(dyn + L.off_vals);
     uint16_t *slot16 = reinterpret_cast<uint16_t *>(dyn + L.off_map);
     uint4 *table = reinterpret_cast<uint4 *>(dyn + L.off_map);
@@ -317,7 +321,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     // ---- stage ------------------------------------------------------------------------
     // 1. clear the value table and the column map
     {
-        uint32_t nv4 = (L.nslots * R + 3u) / 4u;
+        uint32_t nv4 = (L.nslots * W + 3u) / 4u;
         float4 *v4 = reinterpret_cast<float4 *>(vals);
         for (uint32_t i = tid; i < nv4; i += nthr) v4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         if constexpr (KIND == KIND_SLOT) {
@@ -343,7 +347,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     }
     if constexpr (KNN) {
         if (tid < R) s_tau[tid] = float_order_key(__builtin_huge_valf());
-        if (tid < R * 16) s_share[tid] = float_order_key(__builtin_huge_valf());
+        for (int e = tid; e < R * 16; e += nthr) s_share[e] = float_order_key(__builtin_huge_valf());
     }
     // 2. row norms: one wavefront per row, summed in a fixed order (Section 3.4)
     for (int r = wave; r < R; r += nw) {
@@ -405,7 +409,12 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         for (int q = 1; q < R; ++q) r += (e >= s_prefix[q]) ? 1 : 0;
         const int64_t at = s_rows[r].start + (e - s_prefix[r]);
         const float t = transform_value(args.transform, args.a_values[at]);
-        if (t != 0.0f) vals[vals_index<R>(cmap.lookup((uint32_t)args.a_indices[at]), r, L.nslots)] = t;
+        if (t != 0.0f) {
+            const uint32_t slot = cmap.lookup((uint32_t)args.a_indices[at]);
+            if constexpr (kCnt)      // byte r & 3 of word r >> 2 of the slot
+                reinterpret_cast<unsigned char *>(vals)[(size_t)vals_index<W>(slot, r >> 2, L.nslots) * 4 + (r & 3)] = 1;
+            else vals[vals_index<R>(slot, r, L.nslots)] = t;
+        }
     }
     if constexpr (kCheb) {
         // With sum() = max a column that a slice of a row does not store still counts
@@ -489,9 +498,14 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         const uint2 *__restrict__ pk = args.b.packed + args.b.slab_base[s] + lane;
         Acc acc[R];
         uint32_t hit[kCheb ? R : 1];
+        uint32_t counts[kCnt ? W : 1];            // set metrics: four byte counters to the word
         bool lists_changed = false;
 #pragma unroll
         for (int r = 0; r < R; ++r) { O::init(acc[r]); if constexpr (kCheb) hit[r] = 0u; }
+        if constexpr (kCnt) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) counts[w] = 0u;
+        }
 
         // Entry t of lane l sits at pk[t*64 + l]: one coalesced load per step, fetched a block
         // of U steps ahead of its use.  The plan pads every slab to whole blocks (with the
@@ -502,22 +516,46 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
             for (int u = 0; u < U; ++u) into[u] = src[u * kWave];
         };
         auto visit_step = [&](const uint2 entry, const uint32_t slot) {
-            const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
-            const RowVals<R> a = load_vals<R>(vals, slot, L.nslots);
-            if constexpr (kCheb) {
-                const unsigned char *rk = rank8 + (size_t)slot * R;
+            if constexpr (kCnt) {
+                // the slot's R bytes are 0 or 1: adding its words counts the shared columns of all
+                // R rows at once
+                const RowVals<W> a = load_vals<W>(vals, slot, L.nslots);
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if (entry.x - s_clo[r] <= s_cspan[r]) O::visit(acc[r], a.v[r], bv, args.q);
-                    uint32_t q = rk[r];
-                    hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
-                }
+                for (int w = 0; w < W; ++w) counts[w] += __float_as_uint(a.v[w]);
             } else {
+                const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
+                const RowVals<R> a = load_vals<R>(vals, slot, L.nslots);
+                if constexpr (kCheb) {
+                    const unsigned char *rk = rank8 + (size_t)slot * R;
 #pragma unroll
-                for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
+                    for (int r = 0; r < R; ++r) {
+                        if (entry.x - s_clo[r] <= s_cspan[r]) O::visit(acc[r], a.v[r], bv, args.q);
+                        uint32_t q = rk[r];
+                        hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
+                }
+            }
+        };
+        // Byte counters hold up to 255: they are folded into the pairs' 32-bit counts before a
+        // byte can overflow, and at the end of the slab.
+        int unfolded = 0;
+        auto fold_counts = [&]() {
+            if constexpr (kCnt) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) acc[r].c += (int)((counts[r >> 2] >> (8 * (r & 3))) & 0xffu);
+#pragma unroll
+                for (int w = 0; w < W; ++w) counts[w] = 0u;
+                unfolded = 0;
             }
         };
         auto visit_block = [&](const uint2 (&cur)[U]) {
+            if constexpr (kCnt) {
+                if (unfolded > kCntMaxSteps - U) fold_counts();
+                unfolded += U;
+            }
             uint32_t slot[U];
             if constexpr (KIND == KIND_HASH) {
                 uint32_t h[U];
@@ -558,6 +596,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
             }
         }
 
+        if constexpr (kCnt) fold_counts();
         const int glog = args.b.seg_glog[at];
         if (split_depth > 0) {
             // rows cut over 2^glog adjacent lanes: sum (max) the lanes of each group
@@ -581,73 +620,81 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
         double nb0 = 0.0, nb1 = 0.0;
         if (leader) { nb0 = args.b.norms[(size_t)row * 2]; nb1 = args.b.norms[(size_t)row * 2 + 1]; }
 
-        double v0[R], v1[R], v2[R];
+        // The rows are finished eight at a time (all at once would keep the sums and distances of
+        // up to 32 rows in registers together).
+        constexpr int RB = R < 8 ? R : 8;
 #pragma unroll
-        for (int r = 0; r < R; ++r) { v0[r] = O::v0(acc[r]); v1[r] = O::v1(acc[r]); v2[r] = O::v2(acc[r]); }
-        if constexpr (kCheb) {
+        for (int r0 = 0; r0 < R; r0 += RB) {
+            double v0[RB], v1[RB], v2[RB];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (row_out[r] == -1) continue;
-                if (leader) {
-                    const int topn = s_topn[r];
-                    uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
-                    uint32_t unhit = ~hit[r] & tracked;
-                    float extra = 0.0f;
-                    if (unhit) {
-                        extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
-                    } else if (topn == kTopRanks) {
-                        // every tracked entry was visited: walk the two sorted rows
-                        const int64_t a0 = s_rows[r].start, a1 = a0 + s_rows[r].len;
-                        int64_t bj = args.b_indptr[row];
-                        const int64_t be = args.b_indptr[row + 1];
-                        for (int64_t ai = a0; ai < a1; ++ai) {
-                            int32_t c = args.a_indices[ai];
-                            while (bj < be && args.b_indices[bj] < c) ++bj;
-                            if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
+            for (int i = 0; i < RB; ++i) { v0[i] = O::v0(acc[r0 + i]); v1[i] = O::v1(acc[r0 + i]); v2[i] = O::v2(acc[r0 + i]); }
+            if constexpr (kCheb) {
+#pragma unroll
+                for (int i = 0; i < RB; ++i) {
+                    const int r = r0 + i;
+                    if (row_out[r] == -1) continue;
+                    if (leader) {
+                        const int topn = s_topn[r];
+                        uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
+                        uint32_t unhit = ~hit[r] & tracked;
+                        float extra = 0.0f;
+                        if (unhit) {
+                            extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
+                        } else if (topn == kTopRanks) {
+                            // every tracked entry was visited: walk the two sorted rows
+                            const int64_t a0 = s_rows[r].start, a1 = a0 + s_rows[r].len;
+                            int64_t bj = args.b_indptr[row];
+                            const int64_t be = args.b_indptr[row + 1];
+                            for (int64_t ai = a0; ai < a1; ++ai) {
+                                int32_t c = args.a_indices[ai];
+                                while (bj < be && args.b_indices[bj] < c) ++bj;
+                                if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
+                            }
                         }
+                        v0[i] = fmax(v0[i], (double)extra);
                     }
-                    v0[r] = fmax(v0[r], (double)extra);
                 }
             }
-        }
-        // the expansion function is picked once per slab, not once per pair
-        float dist[R];
-        for_metric_of<OP>(args.q.metric, [&](auto metric_tag) {
-            constexpr int MT = decltype(metric_tag)::value;
+            // the expansion function is picked once per eight rows, not once per pair
+            float dist[RB];
+            for_metric_of<OP>(args.q.metric, [&](auto metric_tag) {
+                constexpr int MT = decltype(metric_tag)::value;
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                dist[r] = finish_as<MT>(args.q, v0[r], v1[r], v2[r], row_na0[r], row_na1[r], nb0, nb1);
-                if constexpr (KNN && MT == MT_INNER) dist[r] = 0.0f - dist[r];   // largest first; never -0: keys order by bit pattern
+                for (int i = 0; i < RB; ++i) {
+                    dist[i] = finish_as<MT>(args.q, v0[i], v1[i], v2[i], row_na0[r0 + i], row_na1[r0 + i], nb0, nb1);
+                    if constexpr (KNN && MT == MT_INNER) dist[i] = 0.0f - dist[i];   // largest first; never -0: keys order by bit pattern
+                }
+            });
+            if constexpr (!KNN) {
+                if (leader) {
+#pragma unroll
+                    for (int i = 0; i < RB; ++i) {
+                        const int out = row_out[r0 + i];
+                        if (out >= 0) args.out[(size_t)out * (size_t)n_b + (size_t)row] = dist[i];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < RB; ++i) {
+                    const int r = r0 + i;
+                    if (row_out[r] < 0) continue;
+                    const float bound = float_from_order_key(s_tau[r]);
+                    if (lists[r].offer(dist[i], row, leader, args.knn_k, bound)) {
+                        lists_changed = true;
+                        if (lists[r].full() && lane == 0) atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
+                    }
+                }
             }
-        });
-        if constexpr (!KNN) {
             if (leader) {
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const int out = row_out[r];
-                    if (out >= 0) args.out[(size_t)out * (size_t)n_b + (size_t)row] = dist[r];
+                for (int i = 0; i < RB; ++i) {
+                    const int out = row_out[r0 + i];
+                    if (out > -2) continue;
+                    const size_t slot = (size_t)(-2 - out);
+                    args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0[i];
+                    if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1[i];
+                    if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2[i];
                 }
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (row_out[r] < 0) continue;
-                const float bound = float_from_order_key(s_tau[r]);
-                if (lists[r].offer(dist[r], row, leader, args.knn_k, bound)) {
-                    lists_changed = true;
-                    if (lists[r].full() && lane == 0) atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
-                }
-            }
-        }
-        if (leader) {
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int out = row_out[r];
-                if (out > -2) continue;
-                const size_t slot = (size_t)(-2 - out);
-                args.partial[(slot * args.planes) * (size_t)n_b + (size_t)row] = v0[r];
-                if (args.planes >= 2) args.partial[(slot * args.planes + 1) * (size_t)n_b + (size_t)row] = v1[r];
-                if (args.planes == 3) args.partial[(slot * 3 + 2) * (size_t)n_b + (size_t)row] = v2[r];
             }
         }
         if constexpr (KNN) {
@@ -762,15 +809,28 @@ static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, c
 
 template <int OP, int WHICH = 2>
 static hipError_t launch_scan_op(hipStream_t st, int R, int block, uint32_t lds_bytes, const ScanArgs &args) {
-    switch (R) {
-    case 1: return launch_scan_r<OP, 1, WHICH>(st, block, lds_bytes, args);
-    case 2: return launch_scan_r<OP, 2, WHICH>(st, block, lds_bytes, args);
-    case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
-    case 8: return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
-    case 16:
-        if constexpr (OP == OP_JS || OP == OP_MINK) return hipErrorInvalidValue;
-        else return launch_scan_r<OP, 16, WHICH>(st, block, lds_bytes, args);
-    default: return hipErrorInvalidValue;
+    if constexpr (OP == OP_CNT) {
+        // four rows to the word of the table; 32 rows only without the k-NN lists
+        switch (R) {
+        case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
+        case 8: return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
+        case 16: return launch_scan_r<OP, 16, WHICH>(st, block, lds_bytes, args);
+        case 32:
+            if constexpr (WHICH == 0) return launch_scan_r<OP, 32, WHICH>(st, block, lds_bytes, args);
+            else return hipErrorInvalidValue;
+        default: return hipErrorInvalidValue;
+        }
+    } else {
+        switch (R) {
+        case 1: return launch_scan_r<OP, 1, WHICH>(st, block, lds_bytes, args);
+        case 2: return launch_scan_r<OP, 2, WHICH>(st, block, lds_bytes, args);
+        case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
+        case 8: return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
+        case 16:
+            if constexpr (OP == OP_JS || OP == OP_MINK) return hipErrorInvalidValue;
+            else return launch_scan_r<OP, 16, WHICH>(st, block, lds_bytes, args);
+        default: return hipErrorInvalidValue;
+        }
     }
 }
 

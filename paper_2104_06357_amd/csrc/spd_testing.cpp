@@ -59,6 +59,7 @@ spd_status spd_host_pair_value(spd_metric metric, float p, int64_t n_cols, const
     double v0 = 0, v1 = 0, v2 = 0;
     switch (mi.op) {
     case OP_DOT:  pair_sums<OP_DOT>(q, mi.transform, a_cols, a_vals, a_len, b_cols, b_vals, b_len, v0, v1, v2); break;
+    case OP_CNT:  pair_sums<OP_CNT>(q, mi.transform, a_cols, a_vals, a_len, b_cols, b_vals, b_len, v0, v1, v2); break;
     case OP_L1:   pair_sums<OP_L1>(q, mi.transform, a_cols, a_vals, a_len, b_cols, b_vals, b_len, v0, v1, v2); break;
     case OP_MINK: pair_sums<OP_MINK>(q, mi.transform, a_cols, a_vals, a_len, b_cols, b_vals, b_len, v0, v1, v2); break;
     case OP_CANB: pair_sums<OP_CANB>(q, mi.transform, a_cols, a_vals, a_len, b_cols, b_vals, b_len, v0, v1, v2); break;
@@ -99,11 +100,12 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
     }
     APlan ap;
     BPlan bp;
-    std::string why = plan_a(a_indptr, a_rows, n_cols, (int)metric, k_neighbors, opt, ap);
-    if (why.empty()) why = plan_b(b_indptr, b_rows, opt, bp);
+    std::string why = plan_b(b_indptr, b_rows, opt, bp);
+    int op = metric_info((int)metric).op;
+    if (why.empty()) why = plan_a(a_indptr, a_rows, n_cols, (int)metric, op, k_neighbors, opt, ap);
     if (why.empty()) {
         for (AClass &c : ap.classes) plan_chunks(bp, c, opt);
-        why = plan_check(ap, bp, a_indptr, b_indptr, n_cols, (int)metric, k_neighbors, opt);
+        why = plan_check(ap, bp, a_indptr, b_indptr, n_cols, (int)metric, op, k_neighbors, opt);
     }
     std::string js = "{";
     if (!why.empty()) {
