@@ -121,7 +121,7 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *   "force_kind"  0 auto, 1 dense strip, 2 column-slot strip, 3 hash
  *   "max_rows"    largest number of A rows staged together (1, 2, 4, 8 or 16; the set metrics,
  *                 whose rows take a byte each in the staged table, stage four times as many,
- *                 up to 32, or 16 with fused k-NN)
+ *                 up to 32; with fused k-NN 8, or 16 for max_rows = 16)
  *   "split_len"   B rows at least this long are split over several lanes
  *   "window"      B rows per degree-sorting window
  *   "chunks"      number of B chunks (0 = automatic)

@@ -296,7 +296,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         bd.norms = reinterpret_cast<const double *>(ws + o_norms);
         bd.n_slabs = bp.n_slabs;
         bd.n_rows = n;
-        LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, (bp.n_slabs + 3) / 4);
+        LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, bp.n_slabs);
         hipError_t err = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd,
                                        reinterpret_cast<uint2 *>(ws + o_packed), reinterpret_cast<double *>(ws + o_norms),
                                        (int)metric, mi.transform, mi.norm, q.p, q.k, padcol);

@@ -14,15 +14,22 @@ namespace spd {
 // column), so the scan reads them back with one coalesced load per step.  The lane also
 // sums its part of the row norm.
 // ------------------------------------------------------------------------------------
+constexpr int kPackTile = 16;       // steps of a slab that pass through LDS together
+
 __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restrict__ b_indptr,
                                                          const int32_t *__restrict__ b_indices,
                                                          const float *__restrict__ b_values, BDevice b,
                                                          uint2 *__restrict__ packed, double *__restrict__ norms,
                                                          int metric, int transform, int norm, float p, double k,
                                                          uint32_t padcol) {
-    const int lane = (int)threadIdx.x & 63;
-    const int s = (int)blockIdx.x * 4 + ((int)threadIdx.x >> 6);
-    if (s >= b.n_slabs) return;
+    // One workgroup per slab, its four wavefronts taking the slab's tiles of 16 steps in turn.
+    // The CSR rows are read along the rows (16 consecutive entries of a row per quarter
+    // wavefront: a cache line) into an LDS tile and written out along the steps (the 64 lanes'
+    // entries of one step are 512 contiguous bytes): both sides coalesced.
+    __shared__ uint2 s_tile[4][kPackTile][kWave];
+    __shared__ double s_sums[4][kWave][2];
+    const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
+    const int s = (int)blockIdx.x;
     const size_t at = (size_t)s * kWave + lane;
     const int64_t start = b.seg_start[at];
     const int len = b.seg_len[at];
@@ -30,18 +37,50 @@ __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restri
     const int glog = b.seg_glog[at];
     const int steps = b.slab_steps[s];
     uint2 *dst = packed + b.slab_base[s] + lane;
+    uint2 (*tile)[kWave] = s_tile[wave];
+    const int quarter = lane / kPackTile, within = lane % kPackTile;
     double s0 = 0.0, s1 = 0.0;
-    for (int t = 0; t < steps; ++t) {
-        uint2 e = make_uint2(padcol, 0u);
-        if (t < len) {
-            float v = transform_value(transform, b_values[start + t]);
-            norm_accumulate(norm, v, p, s0, s1);
-            // a stored zero of a set metric is absent: it takes the column that stages nothing
-            const uint32_t col = (transform == TR_NONZERO && v == 0.0f) ? padcol : (uint32_t)b_indices[start + t];
-            e = make_uint2(col, __float_as_uint(v));
+    for (int t0 = wave * kPackTile; t0 < steps; t0 += 4 * kPackTile) {
+        // fixed trip counts, so that all of a tile's loads are in flight together
+        uint2 got[kPackTile];
+#pragma unroll
+        for (int i = 0; i < kPackTile; ++i) {
+            const int r = i * (kWave / kPackTile) + quarter;
+            const int rl = __shfl(len, r);
+            const int64_t rs = __shfl(start, r);
+            const int t = t0 + within;
+            got[i] = make_uint2(padcol, 0u);
+            if (t < rl) {
+                const float v = transform_value(transform, b_values[rs + t]);
+                // a stored zero of a set metric is absent: it takes the column that stages nothing
+                const uint32_t col = (transform == TR_NONZERO && v == 0.0f) ? padcol : (uint32_t)b_indices[rs + t];
+                got[i] = make_uint2(col, __float_as_uint(v));
+            }
         }
-        dst[(size_t)t * kWave] = e;
+#pragma unroll
+        for (int i = 0; i < kPackTile; ++i) tile[within][i * (kWave / kPackTile) + quarter] = got[i];
+        __builtin_amdgcn_wave_barrier();
+        const int nt = min(kPackTile, steps - t0);
+#pragma unroll
+        for (int tt = 0; tt < kPackTile; ++tt) {
+            if (tt < nt) {
+                uint2 e = make_uint2(padcol, 0u);
+                if (t0 + tt < len) {
+                    e = tile[tt][lane];
+                    norm_accumulate(norm, __uint_as_float(e.y), p, s0, s1);
+                }
+                dst[(size_t)(t0 + tt) * kWave] = e;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
     }
+    // the wavefronts' shares of each row's sums, added in a fixed order
+    s_sums[wave][lane][0] = s0;
+    s_sums[wave][lane][1] = s1;
+    __syncthreads();
+    if (wave != 0) return;
+    s0 = (s_sums[0][lane][0] + s_sums[1][lane][0]) + (s_sums[2][lane][0] + s_sums[3][lane][0]);
+    s1 = (s_sums[0][lane][1] + s_sums[1][lane][1]) + (s_sums[2][lane][1] + s_sums[3][lane][1]);
     if (b.slab_split[s]) {
 #pragma unroll
         for (int step = 0; step < 6; ++step) {
@@ -61,7 +100,7 @@ hipError_t launch_pack_b(hipStream_t st, const int64_t *b_indptr, const int32_t 
                          const BDevice &b, uint2 *packed_out, double *norms_out, int metric, int transform,
                          int norm, float p, double k, uint32_t padcol) {
     if (b.n_slabs <= 0) return hipSuccess;
-    dim3 grid((unsigned)((b.n_slabs + 3) / 4));
+    dim3 grid((unsigned)b.n_slabs);
     hipLaunchKernelGGL(spd_pack_b_kernel, grid, dim3(256), 0, st, b_indptr, b_indices, b_values, b, packed_out,
                        norms_out, metric, transform, norm, p, k, padcol);
     return hipGetLastError();

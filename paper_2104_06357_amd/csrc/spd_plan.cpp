@@ -201,9 +201,10 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
     while (max_r & (max_r - 1)) max_r &= max_r - 1;         // power of two
     min_r = 1;
     if (op == OP_CNT) {
-        // a byte per row: four rows to the word, and the k-NN lists bound the registers
+        // a byte per row: four rows to the word; with the k-NN lists in registers as well, 8 rows
+        // run faster than 16 (which max_rows = 16 still selects)
         min_r = 4;
-        max_r = std::min(4 * max_r, knn ? 16 : 32);
+        max_r = std::min(4 * max_r, knn ? (opt.max_rows > 8 ? 16 : 8) : 32);
     }
     auto words = [&](int R) { return table_words(op, R); };
     if (opt.lds_budget <= (int64_t)kStaticLds + 256) return "lds_budget too small";
