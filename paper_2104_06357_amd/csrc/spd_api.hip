@@ -547,7 +547,8 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     if (A->n_rows < 0 || B->n_rows < 0 || A->nnz < 0 || B->nnz < 0 || A->n_cols != B->n_cols) return SPD_ERR_DIM_MISMATCH;
     const PlanOptions &o = h->opt;
     const size_t m = (size_t)A->n_rows, n = (size_t)B->n_rows;
-    const size_t seg_target = (size_t)std::max(1, std::max(2, o.split_len) / 2);
+    const int split_len = split_len_for(o, B->nnz);
+    const size_t seg_target = (size_t)std::max(1, std::max(2, split_len) / 2);
     const size_t window = (size_t)std::max(64, o.window);
     size_t slabs = n / 64 + n / window + (n + 4 * (size_t)B->nnz / seg_target) / 64 + 4;
     size_t lanes = slabs * 64;
@@ -564,8 +565,8 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     auto add = [&](size_t b) { total += align256(b); };
     // padded slabs: at most 64 idle entries per step of the longest row of each window, one per
     // lane of a split row, and the rounding of each group of split rows
-    size_t padded = (size_t)B->nnz + (size_t)B->nnz * 64 / (size_t)std::max(2, o.split_len) +
-                    64 * (size_t)std::max(2, o.split_len) * (n / window + 8) + 64 * (size_t)kScanUnroll * slabs;
+    size_t padded = (size_t)B->nnz + (size_t)B->nnz * 64 / (size_t)std::max(2, split_len) +
+                    64 * (size_t)std::max(2, split_len) * (n / window + 8) + 64 * (size_t)kScanUnroll * slabs;
     add(padded * 8); add(n * 16); add((slabs + 1) * 8); add(slabs * 4); add(slabs);
     add(lanes * 8); add(lanes * 4); add(lanes * 4); add(lanes); add(chunk_words * 4); total += launches * 256;
     add((m + slices + 16 * 6) * sizeof(ARow)); add((m + slices + 6) * 4); total += 12 * 256;
@@ -654,7 +655,8 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
             return fail(h, SPD_ERR_UNSUPPORTED, "max_rows must be 1, 2, 4, 8 or 16");
         o.max_rows = (int)value;
     } else if (s == "split_len") {
-        if (value < 2 || value > (1 << 20)) return fail(h, SPD_ERR_UNSUPPORTED, "split_len must lie in [2, 2^20]");
+        if (value != 0 && (value < 2 || value > (1 << 20)))
+            return fail(h, SPD_ERR_UNSUPPORTED, "split_len must be 0 (automatic) or lie in [2, 2^20]");
         o.split_len = (int)value;
     } else if (s == "window") {
         if (value < 64 || value > (1 << 24)) return fail(h, SPD_ERR_UNSUPPORTED, "window must lie in [64, 2^24]");

@@ -30,7 +30,7 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     out.n_rows = 0; out.nnz = 0; out.n_slabs = 0;
     if (n_rows < 0) return "negative row count";
     if (n_rows >= (int64_t)1 << 31) return "more than 2^31-1 rows";
-    const int64_t T = std::max<int64_t>(2, opt.split_len);
+    const int64_t T = std::max<int64_t>(2, split_len_for(opt, n_rows > 0 ? indptr[n_rows] : 0));
     const int64_t seg_target = std::max<int64_t>(1, T / 2);
     const int64_t Wn = std::max<int64_t>(kWave, (opt.window / kWave) * kWave);
     out.n_rows = n_rows;
@@ -53,9 +53,9 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
         for (int64_t j = w0; j < w1; ++j) {
             int64_t len = indptr[j + 1] - indptr[j];
             if (len >= T) {
-                int64_t want = (len + seg_target - 1) / seg_target;
-                int glog = 0;
-                while (((int64_t)1 << glog) < want && glog < 6) ++glog;
+                // the fewest lanes (a power of two, at most 64) whose segments are at most seg_target long
+                int glog = 1;
+                while (glog < 6 && (seg_target << glog) < len) ++glog;
                 longs.push_back({(int32_t)j, len, glog});
             } else {
                 ++bucket_count[(size_t)len];
@@ -72,10 +72,24 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
         }
         window_end.push_back((int32_t)order.size());
     }
-    // groups of equal size side by side, and within them segments of similar length
-    std::stable_sort(longs.begin(), longs.end(), [](const Long &a, const Long &b) {
-        return a.glog != b.glog ? a.glog > b.glog : a.len > b.len;
-    });
+    // groups of equal size side by side, and within them segments of similar length: a stable
+    // counting sort by (lanes per row, segment length), both descending.  Segments longer than
+    // the last bucket belong to rows that fill a slab alone, so their order costs no padding.
+    if (longs.size() > 1) {
+        constexpr int kSegBuckets = 1024;
+        auto key_of = [&](const Long &l) {
+            int64_t seg = (l.len + ((int64_t)1 << l.glog) - 1) >> l.glog;
+            int sb = (int)std::min<int64_t>(seg, kSegBuckets - 1);
+            return (6 - l.glog) * kSegBuckets + (kSegBuckets - 1 - sb);      // ascending key = descending order
+        };
+        std::vector<int32_t> &count = out.bucket_count;       // reused below only per window: free here
+        count.assign((size_t)7 * kSegBuckets + 1, 0);
+        for (const Long &l : longs) ++count[(size_t)key_of(l) + 1];
+        for (size_t q = 1; q < count.size(); ++q) count[q] += count[q - 1];
+        out.longs_sorted.resize(longs.size());
+        for (const Long &l : longs) out.longs_sorted[(size_t)count[(size_t)key_of(l)]++] = l;
+        longs.swap(out.longs_sorted);
+    }
 
     // count slabs
     int64_t long_lanes = 0;
@@ -90,37 +104,51 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     if (n_slabs >= ((int64_t)1 << 31) / kWave) return "too many slabs";
     out.n_slabs = (int32_t)n_slabs;
     size_t lanes = (size_t)n_slabs * kWave;
-    out.seg_start.assign(lanes, 0);
-    out.seg_len.assign(lanes, 0);
-    out.seg_row.assign(lanes, -1);
-    out.seg_glog.assign(lanes, 0);
+    // every lane is written exactly once below (the arrays keep their size from call to call)
+    out.seg_start.resize(lanes);
+    out.seg_len.resize(lanes);
+    out.seg_row.resize(lanes);
+    out.seg_glog.resize(lanes);
     out.slab_split.assign((size_t)n_slabs, 0);
+    int64_t *const seg_start = out.seg_start.data();
+    int32_t *const seg_len = out.seg_len.data();
+    int32_t *const seg_row = out.seg_row.data();
+    uint8_t *const seg_glog = out.seg_glog.data();
+    auto idle = [&](size_t from, size_t to) {
+        for (size_t q = from; q < to; ++q) { seg_start[q] = 0; seg_len[q] = 0; seg_row[q] = -1; seg_glog[q] = 0; }
+    };
 
     size_t lane = 0;
     for (const Long &l : longs) {
-        int G = 1 << l.glog;
-        int64_t s0 = indptr[l.row];
+        const int G = 1 << l.glog;
+        const int64_t s0 = indptr[l.row];
+        int64_t lo = 0;
         for (int q = 0; q < G; ++q, ++lane) {
-            int64_t lo = l.len * q / G, hi = l.len * (q + 1) / G;
-            out.seg_start[lane] = s0 + lo;
-            out.seg_len[lane] = (int32_t)(hi - lo);
-            out.seg_row[lane] = l.row;
-            out.seg_glog[lane] = (uint8_t)l.glog;
+            const int64_t hi = (l.len * (q + 1)) >> l.glog;        // equal shares, the remainder spread
+            seg_start[lane] = s0 + lo;
+            seg_len[lane] = (int32_t)(hi - lo);
+            seg_row[lane] = l.row;
+            seg_glog[lane] = (uint8_t)l.glog;
+            lo = hi;
         }
         uint8_t &deepest = out.slab_split[(lane - 1) / kWave];
         deepest = std::max<uint8_t>(deepest, (uint8_t)l.glog);
     }
+    idle(lane, (size_t)n_long_slabs * kWave);
     lane = (size_t)n_long_slabs * kWave;
     {
         int32_t prev = 0;
         for (int32_t e : window_end) {
             for (int32_t t = prev; t < e; ++t, ++lane) {
                 int32_t j = order[(size_t)t];
-                out.seg_start[lane] = indptr[j];
-                out.seg_len[lane] = (int32_t)(indptr[j + 1] - indptr[j]);
-                out.seg_row[lane] = j;
+                seg_start[lane] = indptr[j];
+                seg_len[lane] = (int32_t)(indptr[j + 1] - indptr[j]);
+                seg_row[lane] = j;
+                seg_glog[lane] = 0;
             }
-            lane = (lane + kWave - 1) / kWave * kWave;
+            const size_t end = (lane + kWave - 1) / kWave * kWave;
+            idle(lane, end);
+            lane = end;
             prev = e;
         }
     }

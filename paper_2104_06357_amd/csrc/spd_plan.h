@@ -42,7 +42,7 @@ struct PlanOptions {
     int64_t lds_budget = 160 * 1024;        // bytes of LDS per workgroup (static + dynamic)
     int force_kind = KIND_AUTO;
     int max_rows = 8;                       // 16 halves the wavefronts a compute unit can hold
-    int split_len = 128;
+    int split_len = 0;                      // 0: by the size of B (see split_len_for)
     int window = 2048;
     int chunks = 0;
     int n_cus = 256;
@@ -53,6 +53,13 @@ struct PlanOptions {
 // byte per row for the set metrics.
 SPD_HD constexpr int table_words(int op, int R) { return op == OP_CNT ? (R + 3) / 4 : R; }
 constexpr int kCntMaxSteps = 252;           // byte counters are folded into 32-bit counts at least this often
+
+// Rows of B at least this long are cut over several lanes.  Long segments amortise what a slab
+// costs beside its steps; a small B needs many short slabs to keep every wavefront busy.
+inline int split_len_for(const PlanOptions &opt, int64_t nnz_b) {
+    if (opt.split_len > 0) return opt.split_len;
+    return nnz_b >= ((int64_t)4 << 20) ? 512 : 256;
+}
 
 // Sums a pair carries through the slices of a spilled row.
 SPD_HD constexpr int metric_planes(int metric) { return metric == MT_MINKOWSKI ? 3 : (metric == MT_JS ? 2 : 1); }
@@ -150,7 +157,7 @@ struct BPlan {
     std::vector<uint8_t> seg_glog;     // n_slabs*64, log2(lanes the row is split over)
     // planner scratch, kept between calls
     struct LongRow { int32_t row; int64_t len; int glog; };
-    std::vector<LongRow> longs;
+    std::vector<LongRow> longs, longs_sorted;
     std::vector<int32_t> order, window_end, bucket_count, pos;
 };
 

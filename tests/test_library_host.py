@@ -118,11 +118,20 @@ def test_planner_paths_and_thresholds():
     s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "l1", force_kind=3, lds_budget=16384)
     assert s["spilled_rows"] > 0 and s["partial_slots"] >= 2 * s["spilled_rows"]
     assert all(c["lds_bytes"] + 4096 <= 16384 for c in s["classes"])
-    # rows at the split threshold: 127 stays whole, 128 is cut
-    for length, split in ((127, 0), (128, 1), (129, 1)):
+    # rows at the split threshold (256 for a small B, or the option): one below stays whole
+    for length, split in ((255, 0), (256, 1), (257, 1)):
         ip = np.array([0, length], dtype=np.int64)
         s = spd.host_plan_summary(ip, ip, 4096, "l1", force_kind=3)
         assert s["split_rows"] == split, (length, s)
+    for length, split in ((127, 0), (128, 1), (129, 1)):
+        ip = np.array([0, length], dtype=np.int64)
+        s = spd.host_plan_summary(ip, ip, 4096, "l1", force_kind=3, split_len=128)
+        assert s["split_rows"] == split, (length, s)
+    # a B of 2^22 stored entries or more is cut at 512
+    ip = np.arange(0, 511 * 8300, 511, dtype=np.int64)
+    assert spd.host_plan_summary(ip[:2], ip, 4096, "l1", force_kind=3)["split_rows"] == 0
+    ip = np.arange(0, 512 * 8300, 512, dtype=np.int64)
+    assert spd.host_plan_summary(ip[:2], ip, 4096, "l1", force_kind=3)["split_rows"] == 8299
     # Jensen-Shannon keeps at most 8 rows per group
     s = spd.host_plan_summary(small["indptr"], small["indptr"], small["n_cols"], "jensen_shannon")
     assert max(c["R"] for c in s["classes"]) == 8
