@@ -7,7 +7,11 @@
 #include <cstdlib>
 #include <cstdio>
 #include <cstring>
+#include <condition_variable>
+#include <functional>
+#include <mutex>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/spd.h"
@@ -15,6 +19,47 @@
 #include "spd_plan.h"
 
 using namespace spd;
+
+// A helper thread that runs one job at a time beside the caller's thread (the plan of A is
+// made there while the caller plans B, uploads its plan and starts the repack).
+class Helper {
+public:
+    ~Helper() {
+        if (!th_.joinable()) return;
+        { std::lock_guard<std::mutex> g(m_); quit_ = true; }
+        cv_.notify_all();
+        th_.join();
+    }
+    void post(std::function<void()> job) {
+        if (!th_.joinable()) th_ = std::thread([this] { loop(); });
+        { std::lock_guard<std::mutex> g(m_); job_ = std::move(job); pending_ = true; done_ = false; }
+        cv_.notify_all();
+    }
+    void wait() {
+        std::unique_lock<std::mutex> g(m_);
+        cv_.wait(g, [this] { return done_; });
+    }
+private:
+    void loop() {
+        std::unique_lock<std::mutex> g(m_);
+        for (;;) {
+            cv_.wait(g, [this] { return pending_ || quit_; });
+            if (quit_) return;
+            std::function<void()> job = std::move(job_);
+            pending_ = false;
+            g.unlock();
+            job();
+            g.lock();
+            done_ = true;
+            cv_.notify_all();
+        }
+    }
+    std::thread th_;
+    std::mutex m_;
+    std::condition_variable cv_;
+    std::function<void()> job_;
+    bool pending_ = false, done_ = true, quit_ = false;
+};
 
 struct spd_handle {
     hipStream_t stream = nullptr;
@@ -41,6 +86,7 @@ struct spd_handle {
     std::vector<hipEvent_t> event_pool;
     APlan plan_of_a;             // kept between calls: the planner reuses their buffers
     BPlan plan_of_b;
+    Helper helper;
     std::vector<int64_t> knn_row_off;
     std::vector<int32_t> knn_row_lists;
 };
@@ -213,12 +259,25 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     const MetricInfo mi = metric_info((int)metric);
     APlan &ap = h->plan_of_a;
     BPlan &bp = h->plan_of_b;
-    std::string why = plan_b(b_ip, n, h->opt, bp);
-    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
-    lap("plan b");
     // the set metrics count shared columns in byte lanes, or (option) as a dot product of 0/1 values
     int op = mi.op;
     if (op == OP_CNT && h->no_byte_counters) op = OP_DOT;
+    // A is planned on the helper thread meanwhile; every way out of this function waits for it
+    std::string why_a;
+    {
+        const int64_t *a_rows_ptr = a_ip;
+        h->helper.post([&why_a, &ap, h, a_rows_ptr, m, A, metric, op, knn_k] {
+            try {
+                why_a = plan_a(a_rows_ptr, m, A->n_cols, (int)metric, op, knn_k, h->opt, ap);
+            } catch (const std::exception &ex) {
+                why_a = std::string("planning failed: ") + ex.what();
+            }
+        });
+    }
+    struct WaitForHelper { Helper &w; ~WaitForHelper() { w.wait(); } } wait_for_helper{h->helper};
+    std::string why = plan_b(b_ip, n, h->opt, bp);
+    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
+    lap("plan b");
     int a_kind = 0, a_max_r = 1, a_min_r = 1;
     uint64_t a_dmax = 0;
     why = plan_staging(A->n_cols, (int)metric, op, knn_k > 0, h->opt, a_kind, a_max_r, a_min_r, a_dmax);
@@ -267,7 +326,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     const size_t pin_b = align256(ip_bytes);
     const size_t pin_a = pin_b + align256(b_plan_end);
     if (h->pinned_bytes < pin_a + (size_t)m * (sizeof(ARow) + 16) + (64 << 10)) {
-        // growing the pinned buffer moves it: keep the row pointers
+        // growing the pinned buffer moves it: let the helper finish reading, keep the row pointers
+        h->helper.wait();
         std::vector<unsigned char> keep(ip_bytes);
         std::memcpy(keep.data(), h->pinned, ip_bytes);
         st = ensure_pinned(h, pin_a + (size_t)m * (sizeof(ARow) + 16) + (64 << 10));
@@ -309,9 +369,10 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     lap("stage b");
 
     // ---- A, while the repack runs -------------------------------------------------------
-    why = plan_a(a_ip, m, A->n_cols, (int)metric, op, knn_k, h->opt, ap);
+    h->helper.wait();
+    why = why_a;
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
-    lap("plan a");
+    lap("wait for plan a");
     for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
     lap("chunks");
     if (h->check_plan) {
