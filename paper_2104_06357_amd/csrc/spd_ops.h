@@ -321,14 +321,15 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
     } else if constexpr (MT == MT_CORRELATION) {
         return (float)((a1 == 0.0 || b1 == 0.0) ? 1.0 : 1.0 - (q.k * v - a0 * b0) * a1 * b1);
     } else if constexpr (MT == MT_JACCARD) {
-        // counts below 2^24 are exact in fp32 and one fp32 quotient is well inside the
-        // tolerance: the 64-bit division is kept for rows beyond that
+        // counts below 2^24 are exact in fp32, and a correctly rounded fp32 quotient is well inside
+        // the tolerance and the same for equal ratios (pairs that tie exactly stay tied): the
+        // 64-bit division is kept for rows beyond that
         double u = a0 + b0 - v;
-        if (u < 16777216.0) { float uf = (float)u; return uf == 0.0f ? 0.0f : 1.0f - fast_div((float)v, uf); }
+        if (u < 16777216.0) { float uf = (float)u; return uf == 0.0f ? 0.0f : 1.0f - (float)v / uf; }
         return (float)(1.0 - v / u);
     } else if constexpr (MT == MT_DICE) {
         double t = a0 + b0;
-        if (t < 8388608.0) { float tf = (float)t; return tf == 0.0f ? 0.0f : 1.0f - fast_div(2.0f * (float)v, tf); }
+        if (t < 8388608.0) { float tf = (float)t; return tf == 0.0f ? 0.0f : 1.0f - (2.0f * (float)v) / tf; }
         return (float)(1.0 - 2.0 * v / t);
     } else if constexpr (MT == MT_HELLINGER) {
         double t = 0.5 * (a0 + b0) - v;

@@ -53,9 +53,11 @@ def test_config0_every_pair(handle, config0, metric):
 
 @pytest.mark.parametrize("kind", [1, 2, 3])
 @pytest.mark.parametrize("max_rows", [1, 2, 4, 8, 16])
-@pytest.mark.parametrize("metric", ["cosine", "l1", "chebyshev", "jensen_shannon", "minkowski", "hamming"])
+@pytest.mark.parametrize("metric", ["cosine", "l1", "chebyshev", "jensen_shannon", "minkowski", "hamming",
+                                    "jaccard", "russell_rao"])
 def test_config0_every_staging_path(handle, config0, metric, kind, max_rows):
-    """Dense strip, column-slot strip and hash staging, with 1..16 rows of A per workgroup."""
+    """Dense strip, column-slot strip and hash staging, with 1..16 rows of A per workgroup
+    (4..32 for the set metrics, which stage a byte per row)."""
     A, B, dA, dB = config0
     print("config0 staging", metric, kind, max_rows, flush=True)
     handle.set_option("force_kind", kind)
@@ -97,6 +99,46 @@ def test_split_rows_and_sliced_rows(handle, spd, metric):
     got = _run_pairwise(handle, dA, dB, metric, _p_of(metric))
     want = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric), mode="full")
     assert_distances_close(got, want, metric)
+
+
+def _long_rows_pair():
+    """Rows of up to 900 entries over 1,000 columns: with splitting switched off a slab has
+    far more than 255 steps, so the byte counters of the set metrics are folded on the way."""
+    rng = np.random.default_rng(78)
+    out = []
+    for rows in (21, 70):
+        d = np.zeros((rows, 1000))
+        for r in range(rows):
+            n = int(rng.choice([0, 3, 250, 256, 300, 700, 900]))
+            cols = rng.choice(1000, size=n, replace=False)
+            d[r, cols] = rng.random(n) + 0.01
+        out.append(synth.from_dense(np.asarray(d.astype(np.float32), dtype=np.float64)))
+    return out
+
+
+@pytest.mark.parametrize("byte_counters", [1, 0])
+@pytest.mark.parametrize("metric", ["jaccard", "dice", "russell_rao"])
+def test_set_metrics_both_routes_and_long_slabs(handle, spd, metric, byte_counters):
+    """Jaccard, Dice and Russell-Rao through the byte counters and through the dot product of
+    0/1 values, on slabs of up to 900 steps, pairwise and fused k-NN."""
+    import torch
+    A, B = _long_rows_pair()
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    print("set metric", metric, "byte_counters", byte_counters, flush=True)
+    handle.set_option("byte_counters", byte_counters)
+    handle.set_option("split_len", 1 << 20)
+    plan = spd.host_plan_summary(A["indptr"], B["indptr"], 1000, metric, split_len=1 << 20)
+    assert plan["split_rows"] == 0 and plan["max_slab_steps"] >= 900
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], mode="full")
+    for kind in (2, 3):
+        handle.set_option("force_kind", kind)
+        assert_distances_close(_run_pairwise(handle, dA, dB, metric), want, "%s kind %d" % (metric, kind))
+        idx, dist = handle.knn(dA, dB, metric, 8)
+        torch.cuda.synchronize()
+        assert_knn_matches(idx.cpu().numpy(), dist.cpu().numpy(), want, 8, metric, "%s kind %d" % (metric, kind))
+    # and with rows of B cut over lanes again
+    handle.set_option("split_len", 64)
+    assert_distances_close(_run_pairwise(handle, dA, dB, metric), want, metric + " split")
 
 
 def _edge_matrices(signed):
@@ -234,7 +276,7 @@ def test_knn_with_sliced_rows_and_split_rows(handle, spd):
     handle.set_option("split_len", 4)
     handle.set_option("force_kind", 3)
     handle.set_option("lds_budget", 8192)
-    for metric in ("l1", "cosine", "inner_product", "jensen_shannon", "minkowski", "chebyshev"):
+    for metric in ("l1", "cosine", "inner_product", "jensen_shannon", "minkowski", "chebyshev", "jaccard"):
         print("knn slices", metric, flush=True)
         idx, dist = handle.knn(dA, dB, metric, 16, _p_of(metric))
         torch.cuda.synchronize()
