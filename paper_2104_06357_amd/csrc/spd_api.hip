@@ -407,7 +407,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     int64_t knn_entries = 0;
     if (knn_k > 0) {
         knn_row_off.assign((size_t)m, 0);
-        knn_row_lists.assign((size_t)m, 0);                // 0 lists: a spilled row
+        knn_row_lists.assign((size_t)m, 0);
         for (const AClass &c : ap.classes)
             for (const ARow &r : c.rows)
                 if (r.out >= 0) {
@@ -415,6 +415,13 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
                     knn_row_lists[(size_t)r.out] = c.n_chunks;
                     knn_entries += (int64_t)c.n_chunks * knn_k;
                 }
+        // a spilled row: one list per tile of columns its finalize kernel walks
+        const int64_t tiles = (n + kFinalizeTile - 1) / kFinalizeTile;
+        for (const SpilledRow &sr : ap.spilled) {
+            knn_row_off[(size_t)sr.row] = knn_entries;
+            knn_row_lists[(size_t)sr.row] = (int32_t)tiles;
+            knn_entries += tiles * knn_k;
+        }
         o_knn_off = cv.take((size_t)m * 8);
         o_knn_lists = cv.take((size_t)m * 4);
         up.add(o_knn_off, knn_row_off.data(), (size_t)m * 8);
@@ -538,8 +545,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         fa.q = q;
         fa.out = out;
         fa.knn_k = knn_k;
-        fa.out_idx = out_idx;
-        fa.out_dist = out_dist;
+        fa.knn_part = reinterpret_cast<KnnEntry *>(ws + o_knn_part);
+        fa.knn_row_off = reinterpret_cast<const int64_t *>(ws + o_knn_off);
         LaunchTimer lt(h, "finalize", 0, 0, 0, 0, (int64_t)ap.spilled.size(), 0);
         e = launch_finalize(h->stream, fa);
         if (e != hipSuccess) return hip_fail(h, e, "finalize kernel");
@@ -639,6 +646,7 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     if (k_neighbors > 0) {
         size_t lists = o.chunks > 0 ? (m + 16 * launches) * (size_t)o.chunks
                                     : launches * 16 * (16 * (size_t)o.n_cus + 1) + m + 16 * launches;
+        lists += std::min(sliced_rows_max, m) * (n / (size_t)kFinalizeTile + 1);     // the tiles of spilled rows
         add(lists * (size_t)k_neighbors * sizeof(KnnEntry)); add(m * 8); add(m * 4);
     }
     *bytes = total;

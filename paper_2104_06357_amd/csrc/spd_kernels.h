@@ -64,9 +64,11 @@ struct FinalizeArgs {
     OpParams q;
     float *out;                   // pairwise
     int32_t knn_k;
-    int64_t *out_idx;             // k-NN
-    float *out_dist;
+    KnnEntry *knn_part;           // k-NN: a spilled row's candidate lists, one per tile of kFinalizeTile columns,
+    const int64_t *knn_row_off;   //       at knn_row_off[row] + tile * k (merged with the others afterwards)
 };
+
+constexpr int kFinalizeTile = 8192;     // columns of B one workgroup of the k-NN finalize kernel walks
 
 hipError_t launch_pack_b(hipStream_t st, const int64_t *b_indptr, const int32_t *b_indices, const float *b_values,
                          const BDevice &b, uint2 *packed_out, double *norms_out, int metric, int transform,

@@ -143,17 +143,21 @@ __global__ void __launch_bounds__(256) spd_finalize_pairwise_kernel(const Finali
 }
 
 __global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArgs a) {
+    // grid (tiles of kFinalizeTile columns, spilled rows): the k best of the tile go to the
+    // row's candidate lists, which the merge kernel joins like those of the scan's chunks
     __shared__ KnnEntry s_area[4 * kKnnMaxK];
-    const SpilledRow sr = a.spilled[blockIdx.x];
+    const SpilledRow sr = a.spilled[blockIdx.y];
     const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
     const int kk = a.knn_k;
     double na0, na1;
     spilled_row_norms(a, sr, na0, na1);
     KnnList list;
     list.reset();
-    for (int64_t j0 = 0; j0 < a.n_b; j0 += 256) {
+    const int64_t j_begin = (int64_t)blockIdx.x * kFinalizeTile;
+    const int64_t j_end = min(j_begin + (int64_t)kFinalizeTile, a.n_b);
+    for (int64_t j0 = j_begin; j0 < j_end; j0 += 256) {
         int64_t j = j0 + threadIdx.x;
-        bool valid = j < a.n_b;
+        bool valid = j < j_end;
         float d = 0.f;
         if (valid) {
             d = finalize_one(a, sr, j, na0, na1);
@@ -175,17 +179,15 @@ __global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArg
             valid = valid && c.j != 0x7fffffff;
             merged.offer(c.d, c.j, valid, kk, __builtin_huge_valf());
         }
-        if (lane < kk) {
-            a.out_idx[(size_t)sr.row * kk + lane] = (int64_t)merged.j;
-            a.out_dist[(size_t)sr.row * kk + lane] = a.q.metric == MT_INNER ? -merged.d : merged.d;
-        }
+        if (lane < kk) a.knn_part[a.knn_row_off[sr.row] + (int64_t)blockIdx.x * kk + lane] = KnnEntry{merged.d, merged.j};
     }
 }
 
 hipError_t launch_finalize(hipStream_t st, const FinalizeArgs &args) {
     if (args.n_spilled <= 0) return hipSuccess;
     if (args.knn_k > 0) {
-        hipLaunchKernelGGL(spd_finalize_knn_kernel, dim3((unsigned)args.n_spilled), dim3(256), 0, st, args);
+        dim3 grid((unsigned)((args.n_b + kFinalizeTile - 1) / kFinalizeTile), (unsigned)args.n_spilled);
+        hipLaunchKernelGGL(spd_finalize_knn_kernel, grid, dim3(256), 0, st, args);
     } else {
         dim3 grid((unsigned)((args.n_b + 255) / 256), (unsigned)args.n_spilled);
         hipLaunchKernelGGL(spd_finalize_pairwise_kernel, grid, dim3(256), 0, st, args);
@@ -205,7 +207,7 @@ __global__ void __launch_bounds__(256) spd_knn_merge_kernel(const KnnEntry *__re
     const int64_t row = (int64_t)blockIdx.x * 4 + ((int)threadIdx.x >> 6);
     if (row >= n_rows) return;
     const int lists = row_lists[row];
-    if (lists <= 0) return;                                // a spilled row: written by the finalize kernel
+    if (lists <= 0) return;
     KnnList merged;
     merged.reset();
     const int total = lists * k;

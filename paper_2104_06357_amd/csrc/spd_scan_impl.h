@@ -195,32 +195,49 @@ template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const 
 // column -> slot of the staged value table
 // ------------------------------------------------------------------------------------
 // The hash table is an array of buckets of two {column, slot} entries, read with one
-// 16-byte LDS load.  An entry is claimed in the first free place of its home bucket, else
-// of the next bucket, and entries are never removed.  While the table is built the longest
-// such walk is recorded: a lookup reads exactly that many buckets from its home bucket on,
-// the same number in every lane, with no branch (a column that was never staged, and the
-// idle column, which is the empty key, come out as slot 0).
+// 16-byte LDS load.  A lookup reads a fixed number of buckets, the same in every lane, with no
+// branch (a column that was never staged, and the idle column, which is the empty key, come
+// out as slot 0).  Two ways of filling it:
+//  * sparse tables (a quarter full or less): an entry is claimed in the first free place of
+//    its home bucket, else of the next bucket; the longest such walk is recorded and is the
+//    number of buckets a lookup reads (one or two, rarely three);
+//  * denser tables: every column has two candidate buckets (two hash functions) and an
+//    insertion that finds both full moves an older entry to its other bucket (cuckoo
+//    hashing): a lookup reads exactly the two.  Half full, linear probing would walk 8 to 13
+//    buckets for its unluckiest entry, and every lookup would have to read as many.
 template <int KIND> struct ColumnMap {
     const uint16_t *slot16;   // KIND_SLOT: k+1 entries
     const uint4 *table;       // KIND_HASH: buckets {column, slot, column, slot}, empty = {kEmptyKey, 0}
     uint32_t mask, shift;     // over buckets
+    uint32_t mult1, mult2;    // odd multipliers of the two hash functions
+    bool two_choice;          // KIND_HASH: the second way
     int reach;                // KIND_HASH: buckets a lookup reads (at least 1)
-    __device__ __forceinline__ uint32_t home(uint32_t c) const { return (c * 0x9E3779B1u) >> shift; }
+    __device__ __forceinline__ uint32_t home(uint32_t c) const { return (c * mult1) >> shift; }
+    __device__ __forceinline__ uint32_t other(uint32_t c) const { return (c * mult2) >> shift; }
     __device__ __forceinline__ static uint32_t match(uint32_t c, uint4 e, uint32_t slot) {
         slot = (e.x == c) ? e.y : slot;
         return (e.z == c) ? e.w : slot;
     }
-    // Buckets after the home bucket.
-    __device__ __forceinline__ uint32_t beyond(uint32_t c, uint32_t h, uint32_t slot) const {
-        for (int i = 1; i < reach; ++i) slot = match(c, table[(h + (uint32_t)i) & mask], slot);
-        return slot;
+    // The i-th bucket (i >= 1) a lookup of column c reads after its home bucket h.
+    __device__ __forceinline__ uint32_t next_bucket(uint32_t c, uint32_t h, int i) const {
+        return two_choice ? other(c) : ((h + (uint32_t)i) & mask);
     }
     __device__ __forceinline__ uint32_t lookup(uint32_t c) const {
         if constexpr (KIND == KIND_STRIP) return c;
         else if constexpr (KIND == KIND_SLOT) return slot16[c];
-        else { uint32_t h = home(c); return beyond(c, h, match(c, table[h], 0u)); }
+        else {
+            const uint32_t h = home(c);
+            uint32_t slot = match(c, table[h], 0u);
+            for (int i = 1; i < reach; ++i) slot = match(c, table[next_bucket(c, h, i)], slot);
+            return slot;
+        }
     }
 };
+
+constexpr int kCuckooKicks = 96;          // moves after which an insertion gives up
+constexpr int kCuckooAttempts = 3;        // pairs of hash functions tried before linear probing takes over
+__device__ __constant__ const uint32_t kHashMult[kCuckooAttempts][2] = {
+    {0x9E3779B1u, 0x85EBCA77u}, {0xC2B2AE3Du, 0x27D4EB2Fu}, {0x165667B1u, 0xD3A2646Du}};
 
 template <int R> struct RowVals { float v[R]; };
 
@@ -317,6 +334,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     cmap.mask = L.cap ? L.cap / 2u - 1u : 0u;
     cmap.shift = L.cap ? 33u - (uint32_t)__builtin_ctz(L.cap) : 0u;
     cmap.reach = 1;
+    cmap.mult1 = 0x9E3779B1u;
+    cmap.mult2 = 0x85EBCA77u;
+    cmap.two_choice = false;
 
     // ---- stage ------------------------------------------------------------------------
     // 1. clear the value table and the column map
@@ -373,34 +393,83 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
     //    a column may both write: either slot id will do, the fill below reads the winner.
     const uint32_t total = s_prefix[R];
     if constexpr (KIND != KIND_STRIP) {
-        for (uint32_t e = tid; e < total; e += nthr) {
-            int r = 0;
+        // inserts every stored entry's column (the slot id is the entry's position + 1)
+        auto for_each_entry = [&](auto &&insert) {
+            for (uint32_t e = tid; e < total; e += nthr) {
+                int r = 0;
 #pragma unroll
-            for (int q = 1; q < R; ++q) r += (e >= s_prefix[q]) ? 1 : 0;
-            const int64_t at = s_rows[r].start + (e - s_prefix[r]);
-            const float t = transform_value(args.transform, args.a_values[at]);
-            if (t != 0.0f) {                              // a stored zero is absent
-                const uint32_t c = (uint32_t)args.a_indices[at];
-                if constexpr (KIND == KIND_SLOT) {
-                    if (slot16[c] == 0) slot16[c] = (uint16_t)(e + 1u);
-                } else {
+                for (int q = 1; q < R; ++q) r += (e >= s_prefix[q]) ? 1 : 0;
+                const int64_t at = s_rows[r].start + (e - s_prefix[r]);
+                const float t = transform_value(args.transform, args.a_values[at]);
+                if (t != 0.0f) insert((uint32_t)args.a_indices[at], e + 1u);     // a stored zero is absent
+            }
+        };
+        if constexpr (KIND == KIND_SLOT) {
+            for_each_entry([&](uint32_t c, uint32_t id) { if (slot16[c] == 0) slot16[c] = (uint16_t)id; });
+            __syncthreads();
+        } else {
+            unsigned long long *t64 = reinterpret_cast<unsigned long long *>(table);   // entry = column | slot << 32
+            const unsigned long long kEmpty64 = (unsigned long long)kEmptyKey;
+            bool built = false;
+            if (args.hscale == 1) {
+                // dense table: two candidate buckets per column
+                for (int attempt = 0; attempt < kCuckooAttempts && !built; ++attempt) {
+                    cmap.mult1 = kHashMult[attempt][0];
+                    cmap.mult2 = kHashMult[attempt][1];
+                    if (attempt > 0) {
+                        for (uint32_t i = tid; i < L.cap / 2u; i += nthr) table[i] = make_uint4(kEmptyKey, 0u, kEmptyKey, 0u);
+                        if (tid == 0) s_reach = 1;
+                        __syncthreads();
+                    }
+                    for_each_entry([&](uint32_t c, uint32_t id) {
+                        unsigned long long item = (unsigned long long)c | ((unsigned long long)id << 32);
+                        uint32_t bkt = cmap.home(c);
+                        for (int kick = 0; kick < kCuckooKicks; ++kick) {
+                            unsigned long long *pair = t64 + 2u * bkt;
+                            unsigned long long old = atomicCAS(&pair[0], kEmpty64, item);
+                            if (old == kEmpty64 || (uint32_t)old == (uint32_t)item) return;
+                            old = atomicCAS(&pair[1], kEmpty64, item);
+                            if (old == kEmpty64 || (uint32_t)old == (uint32_t)item) return;
+                            // both places taken: take one over and carry its entry to its other bucket
+                            item = atomicExch(&pair[(kick ^ (int)(c >> 7)) & 1], item);
+                            const uint32_t moved = (uint32_t)item;
+                            const uint32_t b1 = cmap.home(moved), b2 = cmap.other(moved);
+                            bkt = (b1 == bkt) ? b2 : b1;
+                        }
+                        s_reach = -1;                          // gave up: this pair of functions fails
+                    });
+                    __syncthreads();
+                    built = wave_uniform(s_reach) > 0;
+                    __syncthreads();
+                }
+                if (built) { cmap.two_choice = true; cmap.reach = 2; }
+            }
+            if (!built) {
+                cmap.mult1 = kHashMult[0][0];
+                cmap.two_choice = false;
+                if (args.hscale == 1) {
+                    for (uint32_t i = tid; i < L.cap / 2u; i += nthr) table[i] = make_uint4(kEmptyKey, 0u, kEmptyKey, 0u);
+                    if (tid == 0) s_reach = 1;
+                    __syncthreads();
+                }
+                for_each_entry([&](uint32_t c, uint32_t id) {
                     uint32_t h = cmap.home(c);
                     int walked = 1;
                     for (;; ++walked) {
                         uint32_t old = atomicCAS(&table[h].x, kEmptyKey, c);
-                        if (old == kEmptyKey) { table[h].y = e + 1u; break; }
+                        if (old == kEmptyKey) { table[h].y = id; break; }
                         if (old == c) break;
                         old = atomicCAS(&table[h].z, kEmptyKey, c);
-                        if (old == kEmptyKey) { table[h].w = e + 1u; break; }
+                        if (old == kEmptyKey) { table[h].w = id; break; }
                         if (old == c) break;
                         h = (h + 1u) & cmap.mask;
                     }
                     if (walked > 1) atomicMax(&s_reach, walked);
-                }
+                });
+                __syncthreads();
+                cmap.reach = wave_uniform(s_reach);
             }
         }
-        __syncthreads();
-        if constexpr (KIND == KIND_HASH) cmap.reach = wave_uniform(s_reach);
     }
     // 4. fill the value table
     for (uint32_t e = tid; e < total; e += nthr) {
@@ -566,7 +635,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                 for (int u = 0; u < U; ++u) slot[u] = ColumnMap<KIND>::match(cur[u].x, e[u], 0u);
                 for (int i = 1; i < cmap.reach; ++i) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) e[u] = table[(h[u] + (uint32_t)i) & cmap.mask];
+                    for (int u = 0; u < U; ++u) e[u] = table[cmap.next_bucket(cur[u].x, h[u], i)];
 #pragma unroll
                     for (int u = 0; u < U; ++u) slot[u] = ColumnMap<KIND>::match(cur[u].x, e[u], slot[u]);
                 }
