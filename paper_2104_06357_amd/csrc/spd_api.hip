@@ -21,7 +21,9 @@
 using namespace spd;
 
 // A helper thread that runs one job at a time beside the caller's thread (the plan of A is
-// made there while the caller plans B, uploads its plan and starts the repack).
+// made there while the caller plans B, uploads its plan and starts the repack).  A sleeping
+// thread can take longer to wake than the job takes: when the caller comes to wait and the
+// helper has not begun yet, the caller runs the job itself.
 class Helper {
 public:
     ~Helper() {
@@ -32,25 +34,35 @@ public:
     }
     void post(std::function<void()> job) {
         if (!th_.joinable()) th_ = std::thread([this] { loop(); });
-        { std::lock_guard<std::mutex> g(m_); job_ = std::move(job); pending_ = true; done_ = false; }
+        { std::lock_guard<std::mutex> g(m_); job_ = std::move(job); state_ = kPosted; }
         cv_.notify_all();
     }
     void wait() {
         std::unique_lock<std::mutex> g(m_);
-        cv_.wait(g, [this] { return done_; });
-    }
-private:
-    void loop() {
-        std::unique_lock<std::mutex> g(m_);
-        for (;;) {
-            cv_.wait(g, [this] { return pending_ || quit_; });
-            if (quit_) return;
+        if (state_ == kPosted) {                 // not begun: do it here
+            state_ = kRunning;
             std::function<void()> job = std::move(job_);
-            pending_ = false;
             g.unlock();
             job();
             g.lock();
-            done_ = true;
+            state_ = kIdle;
+            return;
+        }
+        cv_.wait(g, [this] { return state_ == kIdle; });
+    }
+private:
+    enum State { kIdle, kPosted, kRunning };
+    void loop() {
+        std::unique_lock<std::mutex> g(m_);
+        for (;;) {
+            cv_.wait(g, [this] { return state_ == kPosted || quit_; });
+            if (quit_) return;
+            state_ = kRunning;
+            std::function<void()> job = std::move(job_);
+            g.unlock();
+            job();
+            g.lock();
+            state_ = kIdle;
             cv_.notify_all();
         }
     }
@@ -58,7 +70,8 @@ private:
     std::mutex m_;
     std::condition_variable cv_;
     std::function<void()> job_;
-    bool pending_ = false, done_ = true, quit_ = false;
+    State state_ = kIdle;
+    bool quit_ = false;
 };
 
 struct spd_handle {

@@ -103,19 +103,26 @@ __device__ __forceinline__ uint64_t wave_merge_asc(uint64_t x, int lane) {
 }
 
 // Sorted list of the k best (distance, index) pairs of one query row, entry t in lane t.
-// (tau_d, tau_j) caches entry k-1, the bar a candidate has to beat.
+// Entry k-1 is the bar a candidate has to beat; it is read from its lane when needed (scalar
+// registers), so a list costs two vector registers.
 struct KnnList {
-    float d, tau_d;
-    int j, tau_j;
+    float d;
+    int j;
     __device__ __forceinline__ void reset() {
-        d = tau_d = __builtin_huge_valf();
-        j = tau_j = 0x7fffffff;
+        d = __builtin_huge_valf();
+        j = 0x7fffffff;
     }
-    __device__ __forceinline__ bool full() const { return tau_j != 0x7fffffff; }
+    __device__ __forceinline__ float bar_d(int k) const {
+        return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d), k - 1));
+    }
+    __device__ __forceinline__ int bar_j(int k) const { return __builtin_amdgcn_readlane(j, k - 1); }
+    __device__ __forceinline__ bool full(int k) const { return bar_j(k) != 0x7fffffff; }
     // Every lane may offer one candidate; the list stays sorted by (d, j).  `bound` is any
     // upper bound of the final k-th distance known from elsewhere (candidates above it are
     // dropped unseen).  Returns true if the list changed.
     __device__ __forceinline__ bool offer(float dv, int jv, bool valid, int k, float bound) {
+        float tau_d = bar_d(k);
+        int tau_j = bar_j(k);
         const bool pass = valid && dv <= bound && lex_less(dv, jv, tau_d, tau_j);
         uint64_t m = __ballot(pass);
         if (m == 0) return false;
@@ -130,8 +137,6 @@ struct KnnList {
             if (lane >= k) c = unused;
             d = float_from_order_key((uint32_t)(c >> 32));
             j = (int)(uint32_t)c;
-            tau_d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d), k - 1));
-            tau_j = __builtin_amdgcn_readlane(j, k - 1);
             return true;
         }
         bool changed = false;
@@ -146,8 +151,8 @@ struct KnnList {
             const int sj = wave_shr1(j);
             if (lane > pos) { d = sd; j = sj; }
             else if (lane == pos) { d = x; j = xj; }
-            tau_d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d), k - 1));
-            tau_j = __builtin_amdgcn_readlane(j, k - 1);
+            tau_d = bar_d(k);
+            tau_j = bar_j(k);
             changed = true;
         } while (m);
         return changed;
@@ -691,7 +696,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
 
         // The rows are finished eight at a time (all at once would keep the sums and distances of
         // up to 32 rows in registers together).
-        constexpr int RB = R < 8 ? R : 8;
+        constexpr int RB = R < 8 ? R : (KNN && R >= 16 ? 4 : 8);
 #pragma unroll
         for (int r0 = 0; r0 < R; r0 += RB) {
             double v0[RB], v1[RB], v2[RB];
@@ -750,7 +755,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(co
                     const float bound = float_from_order_key(s_tau[r]);
                     if (lists[r].offer(dist[i], row, leader, args.knn_k, bound)) {
                         lists_changed = true;
-                        if (lists[r].full() && lane == 0) atomicMin(&s_tau[r], float_order_key(lists[r].tau_d));
+                        if (lists[r].full(args.knn_k) && lane == 0)
+                            atomicMin(&s_tau[r], float_order_key(lists[r].bar_d(args.knn_k)));
                     }
                 }
             }
