@@ -21,6 +21,14 @@ int block_for(uint32_t stage_bytes, int64_t lds_total, int waves_per_cu) {
     return std::max(block, 256);
 }
 
+// Launches are kept apart by how many workgroups of their LDS size a compute unit holds (four
+// or more, two or three, one), so that groups needing little are not held to the occupancy of
+// the heaviest.
+int occupancy_bucket(uint32_t stage_bytes, int64_t lds_total) {
+    int64_t per_cu = lds_total / (int64_t)(stage_bytes + kStaticLds);
+    return per_cu >= 4 ? 0 : (per_cu >= 2 ? 1 : 2);
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------
@@ -304,10 +312,10 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         if (c.kind == KIND_HASH) {
             // a sparser table shortens the probe sequences: take the sparsest one that
             // leaves the launch as many workgroups per compute unit as it has now
-            const int now = block_for(need, opt.lds_budget, want_waves);
+            const int now = occupancy_bucket(need, opt.lds_budget);
             for (int hs = 3; hs >= 2; --hs) {
                 uint32_t wider = need_at(hs);
-                if ((int64_t)wider <= budget && block_for(wider, opt.lds_budget, want_waves) == now) { c.hscale = hs; need = wider; break; }
+                if ((int64_t)wider <= budget && occupancy_bucket(wider, opt.lds_budget) == now) { c.hscale = hs; need = wider; break; }
             }
         }
         c.block = std::min(block_for(need, opt.lds_budget, want_waves), scan_max_block(op, c.R, knn_k > 0));
@@ -370,7 +378,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
 
     // one launch per (R, workgroups per compute unit): groups that need little LDS are not
     // held to the occupancy of the heaviest ones
-    AClass *by_key[6][3];                     // R = 32, 16, 8, 4, 2, 1  x  block 256 / 512 / 1024
+    AClass *by_key[6][3];                     // R = 32, 16, 8, 4, 2, 1  x  workgroups of that LDS size per compute unit
     for (int q = 0; q < 6; ++q)
         for (int b = 0; b < 3; ++b) {
             by_key[q][b] = &out.pool[(size_t)(q * 3 + b)];
@@ -394,8 +402,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 int ci = 0;
                 while ((32 >> ci) != R) ++ci;
                 uint32_t need = lds_layout(kind, table_words(op, R), (uint32_t)sum, k, cheb, 1).total;
-                int blk = block_for(need, opt.lds_budget, want_waves);
-                AClass &c = *by_key[ci][blk == 256 ? 0 : (blk == 512 ? 1 : 2)];
+                AClass &c = *by_key[ci][occupancy_bucket(need, opt.lds_budget)];
                 for (int q = 0; q < R; ++q)
                     c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});
                 c.sumlen.push_back((int32_t)sum);
