@@ -71,6 +71,13 @@ SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
     return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_MINK) && R == 8)) ? 512 : 1024;
 }
 
+// Wavefronts per SIMD the compiler is asked to make room for (it bounds the registers per
+// lane: 8 means at most 64).  The light pairwise instances run two workgroups of 16
+// wavefronts per compute unit that way.
+SPD_HD constexpr int scan_min_waves(int op, int R, int kind, bool knn) {
+    return (!knn && R <= 8 && kind != 3 /* KIND_HASH */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM)) ? 8 : 1;
+}
+
 // Dynamic-LDS layout of one staged group.  The same function sizes the launch on the host
 // and carves the buffer in the kernel.  `R` here is table_words(op, rows).
 struct LdsLayout {

@@ -276,7 +276,8 @@ template <int R> __device__ __forceinline__ RowVals<R> load_vals(const float *va
 // the kernel
 // ------------------------------------------------------------------------------------
 template <int OP, int R, int KIND, bool KNN>
-__global__ void __launch_bounds__(scan_max_block(OP, R, KNN)) spd_scan_kernel(const ScanArgs args) {
+__global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
+    __attribute__((amdgpu_waves_per_eu(scan_min_waves(OP, R, KIND, KNN)))) spd_scan_kernel(const ScanArgs args) {
     using O = Op<OP>;
     using Acc = typename O::Acc;
     constexpr bool kCheb = (OP == OP_CHEB);
