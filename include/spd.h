@@ -23,6 +23,10 @@
  *    handle's stream and return without waiting for them.
  *  - Scratch memory comes from the handle's own grow-only allocation, or from the caller
  *    through spd_set_workspace().
+ *  - A handle serves one call at a time (calls on one handle from several threads must be
+ *    serialised by the caller; different handles are independent).  A handle owns one helper
+ *    thread, started by its first call, on which part of the planning runs, and up to three
+ *    internal streams of default priority beside the caller's stream.
  *  - Stored zeros are legal and count as absent.  Values must be finite; Hellinger, KL and
  *    Jensen-Shannon expect non-negative values (anything else is undefined, and reported by
  *    spd_csr_validate()).
