@@ -27,3 +27,10 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_runtest_logstart(nodeid, location):
+    """Names every test on the real stderr as it starts (output capture hides prints, and a
+    long GPU run that prints nothing for minutes looks hung to whoever is watching it)."""
+    sys.__stderr__.write("[test] %s\n" % nodeid)
+    sys.__stderr__.flush()

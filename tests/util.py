@@ -58,3 +58,10 @@ def assert_knn_matches(idx, dist, oracle_rows, k, metric, what=""):
             assert abs(a - b) <= 2.0 * max(REL_TOL * abs(b), ABS_TOL), \
                 "%s: row %d position %d: index %d (%.9g) instead of %d (%.9g)" % (
                     what, r, t, idx[r, t], a, order[t], b)
+
+
+def progress(message):
+    """A line on the real stderr, past pytest's capture: the steps of the long tests."""
+    import sys
+    sys.__stderr__.write("[step] %s\n" % message)
+    sys.__stderr__.flush()
