@@ -29,8 +29,15 @@ def pytest_collection_modifyitems(config, items):
             item.add_marker(skip)
 
 
+_T0 = None
+
+
 def pytest_runtest_logstart(nodeid, location):
-    """Names every test on the real stderr as it starts (output capture hides prints, and a
-    long GPU run that prints nothing for minutes looks hung to whoever is watching it)."""
-    sys.__stderr__.write("[test] %s\n" % nodeid)
-    sys.__stderr__.flush()
+    """Names every test on stderr as it starts, with the seconds since the first one (a long
+    GPU run that prints nothing for minutes looks hung to whoever is watching it)."""
+    import time
+    global _T0
+    if _T0 is None:
+        _T0 = time.time()
+    sys.stderr.write("[test +%4.0fs] %s\n" % (time.time() - _T0, nodeid))
+    sys.stderr.flush()

@@ -38,21 +38,21 @@ def _gather(out, rows, cols):
     return out.index_select(0, r).index_select(1, c).cpu().numpy()
 
 
-def _timed(label, fn):
+def _timed(capsys, label, fn):
     import torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     out = fn()
     torch.cuda.synchronize()
-    progress("%s: %.1f ms" % (label, 1e3 * (time.perf_counter() - t0)))
+    progress(capsys, "%s: %.1f ms" % (label, 1e3 * (time.perf_counter() - t0)))
     return out
 
 
-def test_config2_bag_of_words_tile(spd):
+def test_config2_bag_of_words_tile(spd, capsys):
     """1,024 queries (one output tile of 1.2 GB) against the 300,000-row index."""
     import torch
     Q, I = synth.workload(2)
-    progress("config2 generated")
+    progress(capsys, "config2 generated")
     rng = np.random.default_rng(2)
     tile_rows = _extremes_and_sample(Q, 1024, rng)
     tile = synth.take_rows(Q, tile_rows)
@@ -63,10 +63,10 @@ def test_config2_bag_of_words_tile(spd):
     ra = _extremes_and_sample(tile, 64, rng)
     rb = _extremes_and_sample(I, 2048, rng)
     for metric in ("cosine", "inner_product", "hellinger"):
-        _timed("config2 " + metric, lambda: h.pairwise(dQ, dI, metric, out=out))
+        _timed(capsys, "config2 " + metric, lambda: h.pairwise(dQ, dI, metric, out=out))
         want = oracle.pairwise(tile, I, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
         assert_distances_close(_gather(out, ra, rb), want, "config2 " + metric)
-        progress("config2 %s checked against the oracle" % metric)
+        progress(capsys, "config2 %s checked against the oracle" % metric)
     # rows are L2-normalised: cosine distance = 1 - inner product (a property at any size)
     cos = h.pairwise(dQ, dI, "cosine", out=out).index_select(0, torch.as_tensor(ra, device="cuda")).clone()
     ip = h.pairwise(dQ, dI, "inner_product", out=out).index_select(0, torch.as_tensor(ra, device="cuda"))
@@ -74,11 +74,11 @@ def test_config2_bag_of_words_tile(spd):
     h.close()
 
 
-def test_config3_count_matrix_tile(spd):
+def test_config3_count_matrix_tile(spd, capsys):
     """A 4,096-row query tile of the 65,536-row self-join, union-family metrics."""
     import torch
     M, _ = synth.workload(3)
-    progress("config3 generated")
+    progress(capsys, "config3 generated")
     deg = np.diff(M["indptr"])
     heavy = np.nonzero(deg > 10_240)[0]
     assert heavy.size >= 8
@@ -94,35 +94,35 @@ def test_config3_count_matrix_tile(spd):
     # index sample: extremes, the heavy rows, and the tile's own rows (the self-join diagonal)
     rb = _extremes_and_sample(M, 2048, rng, extra=list(heavy) + list(tile_rows[ra]))
     for metric in ("kl_divergence", "jensen_shannon", "canberra", "l1"):
-        _timed("config3 " + metric, lambda: h.pairwise(dQ, dM, metric, out=out))
+        _timed(capsys, "config3 " + metric, lambda: h.pairwise(dQ, dM, metric, out=out))
         want = oracle.pairwise(tile, M, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
         assert_distances_close(_gather(out, ra, rb), want, "config3 " + metric)
-        progress("config3 %s checked against the oracle" % metric)
+        progress(capsys, "config3 %s checked against the oracle" % metric)
     # the same rows through hash staging: the >10,240-entry rows are cut into slices
     h.set_option("force_kind", 3)
     plan = spd.host_plan_summary(tile["indptr"], M["indptr"], M["n_cols"], "l1", force_kind=3)
     assert plan["spilled_rows"] >= 8
-    _timed("config3 l1 (hash staging)", lambda: h.pairwise(dQ, dM, "l1", out=out))
+    _timed(capsys, "config3 l1 (hash staging)", lambda: h.pairwise(dQ, dM, "l1", out=out))
     want = oracle.pairwise(tile, M, "manhattan", rows_a=ra, rows_b=rb)
     assert_distances_close(_gather(out, ra, rb), want, "config3 l1 with slices")
     h.close()
 
 
-def test_config4_binary_knn(spd):
+def test_config4_binary_knn(spd, capsys):
     """4,096 binary queries against 500,000 index rows over 2^20 columns, fused top-32."""
     import torch
     Q, I = synth.workload(4)
-    progress("config4 generated")
+    progress(capsys, "config4 generated")
     dQ, dI = spd.DeviceCsr.from_host(Q), spd.DeviceCsr.from_host(I)
     h = spd.Handle()
     h.set_option("check_plan", 1)
     rng = np.random.default_rng(4)
     rq = _extremes_and_sample(Q, 24, rng)
     plan = spd.host_plan_summary(Q["indptr"], I["indptr"], Q["n_cols"], "jaccard", k_neighbors=32)
-    progress("config4 plan: spilled rows %d, slabs %d" % (plan["spilled_rows"], plan["slabs"]))
+    progress(capsys, "config4 plan: spilled rows %d, slabs %d" % (plan["spilled_rows"], plan["slabs"]))
     for metric in ("jaccard", "dice", "hamming"):
-        idx, dist = _timed("config4 knn " + metric, lambda: h.knn(dQ, dI, metric, 32))
+        idx, dist = _timed(capsys, "config4 knn " + metric, lambda: h.knn(dQ, dI, metric, 32))
         rows = oracle.pairwise(Q, I, ORACLE_NAME[metric], rows_a=rq)
         assert_knn_matches(idx.cpu().numpy()[rq], dist.cpu().numpy()[rq], rows, 32, metric, "config4 " + metric)
-        progress("config4 %s checked against the oracle" % metric)
+        progress(capsys, "config4 %s checked against the oracle" % metric)
     h.close()

@@ -60,8 +60,11 @@ def assert_knn_matches(idx, dist, oracle_rows, k, metric, what=""):
                     what, r, t, idx[r, t], a, order[t], b)
 
 
-def progress(message):
-    """A line on the real stderr, past pytest's capture: the steps of the long tests."""
+def progress(capsys, message):
+    """A line on stderr past pytest's capture (`capsys` is the test's fixture): the steps of the
+    long tests, so that they stay visibly alive."""
     import sys
-    sys.__stderr__.write("[step] %s\n" % message)
-    sys.__stderr__.flush()
+    import time
+    with capsys.disabled():
+        sys.stderr.write("[step %s] %s\n" % (time.strftime("%H:%M:%S"), message))
+        sys.stderr.flush()
