@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+ALU_LANE_OPS = 78.6e12 / 2.0      # fp64 vector peak in FMAs = lane-instructions per second (256 CUs, 2.4 GHz)
 COPY_BYTES = 256 << 20
 
 
@@ -122,6 +123,14 @@ def main():
         all_ms = float(np.mean([sum(r["ms"] for r in recs) for recs in per_step]))
         alg = algorithmic_bytes(rec["a_rows"], nnz_b, n)
         achieved = alg / (ms * 1e-3) / 1e9
+        # the same launch against the vector ALU: a visit (row of A x stored entry of B) cannot
+        # cost less than the product's own instructions (L1: median, conversion, fp64 add;
+        # dot: conversion, fp64 FMA), and the chip issues 78.6e12 / 2 fp64 lane-instructions/s
+        per_visit = 3 if name == "l1" else 2
+        visits = float(rec["a_rows"]) * nnz_b / (ms * 1e-3)
+        alu_peak = ALU_LANE_OPS / per_visit
+        alu = {"bound": "alu", "achieved": visits, "peak": alu_peak, "unit": "visits/s",
+               "frac": round(visits / alu_peak, 4), "vector_instructions_per_visit": per_visit}
         return {
             "bound": "hbm", "kernel": "spd_scan_kernel (%s, R=%d rows of A per workgroup, staging kind %d)"
                                       % (name, rec["rows_per_group"], rec["staging_kind"]),
@@ -132,6 +141,7 @@ def main():
             "lds_bytes": rec["lds_bytes"], "scan_launches_per_call": len(scans),
             "all_scan_launches_ms": round(scan_ms, 4), "all_kernels_ms": round(all_ms, 4),
             "serialised_call_wall_ms": round(1e3 * wall[name] / args.steps, 4),
+            "alu": alu,
             "note": "effective rate: the R rows staged together share every entry of B that is loaded and B "
                     "stays resident in L2, so the HBM stream is far below the algorithmic bytes (see traffic)",
         }
