@@ -18,7 +18,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 METRICS = (
     "inner_product", "cosine", "euclidean", "correlation", "jaccard", "dice", "hellinger",
     "manhattan", "chebyshev", "minkowski", "canberra", "hamming", "kl_divergence",
-    "jensen_shannon", "russell_rao",
+    "jensen_shannon", "russell_rao", "kl_divergence_strict", "jaccard_literal",
 )
 
 _lib = None

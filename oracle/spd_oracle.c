@@ -33,13 +33,13 @@
 enum {
     M_INNER = 0, M_COSINE, M_EUCLIDEAN, M_CORRELATION, M_JACCARD, M_DICE, M_HELLINGER,
     M_MANHATTAN, M_CHEBYSHEV, M_MINKOWSKI, M_CANBERRA, M_HAMMING, M_KL, M_JENSEN_SHANNON,
-    M_RUSSELL_RAO, M_COUNT
+    M_RUSSELL_RAO, M_KL_STRICT, M_JACCARD_LITERAL, M_COUNT
 };
 
 static const char *const k_names[M_COUNT] = {
     "inner_product", "cosine", "euclidean", "correlation", "jaccard", "dice", "hellinger",
     "manhattan", "chebyshev", "minkowski", "canberra", "hamming", "kl_divergence",
-    "jensen_shannon", "russell_rao"
+    "jensen_shannon", "russell_rao", "kl_divergence_strict", "jaccard_literal"
 };
 
 int oracle_metric_id(const char *name) {
@@ -191,6 +191,33 @@ static double eval_pair(int metric, double p, const double *x, const double *y,
             both += (double)(x[c] != 0.0 && y[c] != 0.0);
         }
         return ((double)k - both) / (double)k;
+    }
+    case M_KL_STRICT: {
+        /* The textbook KL divergence, sum x log(x/y) with 0 log 0 = 0: infinite as soon as
+         * x holds mass in a column where y holds none (the variant Section 2.2's product,
+         * which only sees columns present on both sides, leaves out). */
+        double s = 0.0;
+        for (int64_t t = 0; t < nc; ++t) {
+            int64_t c = COL(t);
+            if (x[c] > 0.0) {
+                if (!(y[c] > 0.0)) return INFINITY;
+                s += x[c] * log(x[c] / y[c]);
+            }
+        }
+        return s;
+    }
+    case M_JACCARD_LITERAL: {
+        /* Table 1, "Jaccard", expansion column taken literally: the dot product of the
+         * stored values over (|x|_0 + |y|_0 - dot), as a distance; 0 where that denominator
+         * vanishes (two empty rows).  Equal to the set reading on 0/1 data. */
+        double dot = 0.0, nx = 0.0, ny = 0.0;
+        for (int64_t t = 0; t < nc; ++t) {
+            int64_t c = COL(t);
+            dot += x[c] * y[c]; nx += (double)(x[c] != 0.0); ny += (double)(y[c] != 0.0);
+        }
+        double den = nx + ny - dot;
+        if (den == 0.0) return 0.0;
+        return 1.0 - dot / den;
     }
     default:
         return NAN;

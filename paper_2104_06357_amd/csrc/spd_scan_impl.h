@@ -442,7 +442,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                             const uint32_t b1 = cmap.home(moved), b2 = cmap.other(moved);
                             bkt = (b1 == bkt) ? b2 : b1;
                         }
-                        s_reach = -1;                          // gave up: this pair of functions fails
+                        atomicExch(&s_reach, -1);              // gave up: this pair of functions fails
                     });
                     __syncthreads();
                     built = wave_uniform(s_reach) > 0;

@@ -234,6 +234,51 @@ def test_kl_against_rel_entr():
     assert np.abs(d - dT.T).max() > 1e-3
 
 
+def test_strict_kl_is_the_textbook_divergence():
+    """The strict variant is scipy's rel_entr sum (infinite where x has mass and y has none);
+    where supp(x) lies inside supp(y) it is the paper-mode value, elsewhere +inf."""
+    rng = np.random.default_rng(23)
+    X = _random_sparse_dense(rng, 7, 19, 0.4, signed=False, zero_rows=True)
+    Y = _random_sparse_dense(rng, 6, 19, 0.7, signed=False, zero_rows=True)
+    Y[0] = X[1]                                   # same support: finite
+    Y[1] = X[2] + 0.25                            # full support: finite
+    Y = np.asarray(Y.astype(np.float32), dtype=np.float64)
+    got = _both(synth.from_dense(X), synth.from_dense(Y), "kl_divergence_strict")
+    want = _scipy_pairs(X, Y, lambda x, y: rel_entr(x, y).sum())
+    assert np.array_equal(np.isinf(got), np.isinf(want)) and np.isinf(got).any() and np.isfinite(got).any()
+    fin = np.isfinite(want)
+    np.testing.assert_allclose(got[fin], want[fin], rtol=1e-12, atol=1e-14)
+    paper = _both(synth.from_dense(X), synth.from_dense(Y), "kl_divergence")
+    inside = np.array([[not np.any((x > 0) & ~(y > 0)) for y in Y] for x in X])
+    assert np.array_equal(inside, fin)
+    np.testing.assert_allclose(got[inside], paper[inside], rtol=0, atol=0)
+    assert got[3].tolist() == [0.0] * 6           # the empty row is at divergence 0 from everything
+    same = _both(synth.from_dense(X), synth.from_dense(X), "kl_divergence_strict")
+    assert np.all(np.diag(same) == 0.0)
+
+
+def test_literal_jaccard_reading():
+    """Expansion column of Table 1 taken literally: 1 - <x,y>/(|x|_0 + |y|_0 - <x,y>).  On 0/1
+    data it is the set reading (scipy's boolean jaccard); on other values a hand-computed case."""
+    rng = np.random.default_rng(29)
+    Xb = (rng.random((8, 23)) < 0.3).astype(np.float64); Xb[4] = 0.0
+    Yb = (rng.random((5, 23)) < 0.4).astype(np.float64); Yb[0] = 0.0
+    lit = _both(synth.from_dense(Xb), synth.from_dense(Yb), "jaccard_literal")
+    sets = _both(synth.from_dense(Xb), synth.from_dense(Yb), "jaccard")
+    np.testing.assert_allclose(lit, sets, rtol=0, atol=1e-15)
+    for i, x in enumerate(Xb):
+        for j, y in enumerate(Yb):
+            if x.any() or y.any():
+                assert lit[i, j] == pytest.approx(ssd.jaccard(x.astype(bool), y.astype(bool)), abs=1e-15)
+            else:
+                assert lit[i, j] == 0.0
+    x = np.array([[0.5, 0.5, 0.0, 2.0]]); y = np.array([[0.5, 0.0, 3.0, 1.0]])
+    # <x,y> = 0.25 + 2 = 2.25; |x|_0 = 3, |y|_0 = 3: 1 - 2.25 / (6 - 2.25) = 0.4
+    assert _both(synth.from_dense(x), synth.from_dense(y), "jaccard_literal")[0, 0] == pytest.approx(0.4, abs=1e-15)
+    # not a metric on general values: d(x, x) = 1 - 5.25/(6 - 5.25) is negative here
+    assert _both(synth.from_dense(x), synth.from_dense(x), "jaccard_literal")[0, 0] == pytest.approx(1 - 4.5 / 1.5, abs=1e-14)
+
+
 # ---------------------------------------------------------------- closed forms and invariants
 def test_self_distance_symmetry_triangle():
     A, _ = synth.workload(0)
