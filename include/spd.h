@@ -67,6 +67,12 @@ typedef enum {
     SPD_KL_DIVERGENCE,      /* sum over columns present in both rows of x log(x/y)           */
     SPD_JENSEN_SHANNON,     /* sqrt(sum(x log(x/mu) + y log(y/mu))/2), mu=(x+y)/2           */
     SPD_RUSSELL_RAO,        /* (k - |sx & sy|)/k                                             */
+    /* variants */
+    SPD_L2_UNEXPANDED,      /* sqrt(sum (x-y)^2) through the union product (Section 2.1: the
+                               expanded form cancels for close rows; this one is Minkowski, p = 2) */
+    SPD_KL_STRICT,          /* sum x log(x/y), +infinity where x > 0 meets y = 0 (textbook KL)       */
+    SPD_JACCARD_LITERAL,    /* 1 - <x,y>/(|x|_0 + |y|_0 - <x,y>): Table 1's expansion column by the
+                               letter (the set reading on 0/1 data; 0 if the denominator is 0)      */
     SPD_METRIC_COUNT
 } spd_metric;
 

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(HERE, "libspd.so")
 METRICS = (
     "inner_product", "cosine", "l2_expanded", "correlation", "jaccard", "dice", "hellinger", "l1",
     "chebyshev", "minkowski", "canberra", "hamming", "kl_divergence", "jensen_shannon", "russell_rao",
+    "l2_unexpanded", "kl_divergence_strict", "jaccard_literal",
 )
 METRIC_ID = {name: i for i, name in enumerate(METRICS)}
 STATUS = ("SPD_OK", "SPD_ERR_NULL", "SPD_ERR_DIM_MISMATCH", "SPD_ERR_BAD_CSR", "SPD_ERR_BAD_METRIC",

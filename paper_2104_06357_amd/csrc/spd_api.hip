@@ -108,7 +108,8 @@ namespace {
 
 const char *const kMetricNames[SPD_METRIC_COUNT] = {
     "inner_product", "cosine", "l2_expanded", "correlation", "jaccard", "dice", "hellinger", "l1",
-    "chebyshev", "minkowski", "canberra", "hamming", "kl_divergence", "jensen_shannon", "russell_rao"};
+    "chebyshev", "minkowski", "canberra", "hamming", "kl_divergence", "jensen_shannon", "russell_rao",
+    "l2_unexpanded", "kl_divergence_strict", "jaccard_literal"};
 
 spd_status fail(spd_handle *h, spd_status st, const std::string &msg) {
     if (h) h->err = msg;
@@ -299,10 +300,11 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     const uint32_t padcol = a_kind == KIND_HASH ? kEmptyKey : (uint32_t)A->n_cols;
     OpParams q;
     q.p = p;
-    q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : 1.0f;
+    if (metric == SPD_L2_UNEXPANDED) q.p = 2.0f;
+    q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : (metric == SPD_L2_UNEXPANDED ? 0.5f : 1.0f);
     q.k = (double)A->n_cols;
     q.metric = (int)metric;
-    if (metric != SPD_MINKOWSKI) q.p = 1.0f;
+    if (metric != SPD_MINKOWSKI && metric != SPD_L2_UNEXPANDED) q.p = 1.0f;
 
     const int planes = metric_planes((int)metric);
     const size_t lanes = (size_t)bp.n_slabs * kWave;

@@ -34,7 +34,8 @@ enum NormKind { NORM_NONE = 0, NORM_SUMSQ, NORM_SUM_SUMSQ, NORM_SUM, NORM_SUM_AB
 // metric ids follow spd_metric in include/spd.h
 enum MetricId {
     MT_INNER = 0, MT_COSINE, MT_L2, MT_CORRELATION, MT_JACCARD, MT_DICE, MT_HELLINGER, MT_L1,
-    MT_CHEBYSHEV, MT_MINKOWSKI, MT_CANBERRA, MT_HAMMING, MT_KL, MT_JS, MT_RUSSELL_RAO, MT_COUNT
+    MT_CHEBYSHEV, MT_MINKOWSKI, MT_CANBERRA, MT_HAMMING, MT_KL, MT_JS, MT_RUSSELL_RAO,
+    MT_L2_UNEXPANDED, MT_KL_STRICT, MT_JACCARD_LITERAL, MT_COUNT
 };
 
 struct MetricInfo { int op, transform, norm; };
@@ -56,6 +57,9 @@ SPD_HD constexpr MetricInfo metric_info(int metric) {
     case MT_KL:          return {OP_KL, TR_ID, NORM_NONE};
     case MT_JS:          return {OP_JS, TR_ID, NORM_SUM};
     case MT_RUSSELL_RAO: return {OP_CNT, TR_NONZERO, NORM_NONE};
+    case MT_L2_UNEXPANDED:   return {OP_MINK, TR_ID, NORM_SUM_POW};      // Minkowski with p fixed at 2
+    case MT_KL_STRICT:       return {OP_KL, TR_ID, NORM_NNZ};            // the row's entries must all be met
+    case MT_JACCARD_LITERAL: return {OP_DOT, TR_ID, NORM_NNZ};
     default:             return {-1, 0, 0};
     }
 }
@@ -250,18 +254,19 @@ template <> struct Op<OP_CNT> {
 // KL: a log(a/b) = ln 2 * a log2(a/b) on shared columns, with a correctly rounded quotient so
 // that equal entries give exactly 0; the factor ln 2 is applied once, by finish().
 template <> struct Op<OP_KL> {
-    struct Acc { double v; };
+    struct Acc { double v; int hits; };      // hits: columns where both rows hold mass (the strict variant needs them)
     struct Bv { float b; };
-    SPD_HD static void init(Acc &x) { x.v = 0.0; }
+    SPD_HD static void init(Acc &x) { x.v = 0.0; x.hits = 0; }
     SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
         bool hit = (a > 0.0f) && (b.b > 0.0f);
         float t = a * fast_log2(hit ? a / b.b : 1.0f);
         x.v += hit ? (double)t : 0.0;
+        x.hits += hit ? 1 : 0;
     }
-    SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; x.hits += y.hits; }
     SPD_HD static double v0(const Acc &x) { return x.v; }
-    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v1(const Acc &x) { return (double)x.hits; }
     SPD_HD static double v2(const Acc &) { return 0.0; }
 };
 
@@ -337,7 +342,7 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
     } else if constexpr (MT == MT_L1 || MT == MT_CANBERRA) {
         double t = a0 + b0 + v;
         return (float)(t > 0.0 ? t : 0.0);
-    } else if constexpr (MT == MT_MINKOWSKI) {
+    } else if constexpr (MT == MT_MINKOWSKI || MT == MT_L2_UNEXPANDED) {
         // v: differences on shared columns, s: their share of the norms, w: how many;
         // a1 / b1 count the entries of the rows: equal supports leave no one-sided part
         double one_sided = (w == a1 && w == b1) ? 0.0 : (a0 + b0) - s;
@@ -350,6 +355,13 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
         return (float)((a0 + b0 + v) / q.k);
     } else if constexpr (MT == MT_KL) {
         return (float)(LN2 * v);
+    } else if constexpr (MT == MT_KL_STRICT) {
+        // s counts the columns where both rows hold mass, a0 the entries of x: an entry of x that
+        // met nothing in y makes the divergence infinite
+        return s == a0 ? (float)(LN2 * v) : __builtin_huge_valf();
+    } else if constexpr (MT == MT_JACCARD_LITERAL) {
+        double u = a0 + b0 - v;
+        return (float)((u == 0.0) ? 0.0 : 1.0 - v / u);
     } else if constexpr (MT == MT_JS) {
         double t = 0.5 * LN2 * (((a0 + b0) - s) + v);
         return sqrtf((float)(t > 0.0 ? t : 0.0));
@@ -376,6 +388,7 @@ template <int OP, typename F> SPD_HD void for_metric_of(int metric, F &&f) {
         SPD_CASE(MT_INNER) SPD_CASE(MT_COSINE) SPD_CASE(MT_L2) SPD_CASE(MT_CORRELATION) SPD_CASE(MT_JACCARD)
         SPD_CASE(MT_DICE) SPD_CASE(MT_HELLINGER) SPD_CASE(MT_L1) SPD_CASE(MT_CHEBYSHEV) SPD_CASE(MT_MINKOWSKI)
         SPD_CASE(MT_CANBERRA) SPD_CASE(MT_HAMMING) SPD_CASE(MT_KL) SPD_CASE(MT_JS) SPD_CASE(MT_RUSSELL_RAO)
+        SPD_CASE(MT_L2_UNEXPANDED) SPD_CASE(MT_KL_STRICT) SPD_CASE(MT_JACCARD_LITERAL)
     default: break;
     }
 #undef SPD_CASE
@@ -388,6 +401,7 @@ SPD_HD float finish(const OpParams &q, double v, double s, double w, double a0, 
         SPD_CASE(MT_INNER) SPD_CASE(MT_COSINE) SPD_CASE(MT_L2) SPD_CASE(MT_CORRELATION) SPD_CASE(MT_JACCARD)
         SPD_CASE(MT_DICE) SPD_CASE(MT_HELLINGER) SPD_CASE(MT_L1) SPD_CASE(MT_CHEBYSHEV) SPD_CASE(MT_MINKOWSKI)
         SPD_CASE(MT_CANBERRA) SPD_CASE(MT_HAMMING) SPD_CASE(MT_KL) SPD_CASE(MT_JS) SPD_CASE(MT_RUSSELL_RAO)
+        SPD_CASE(MT_L2_UNEXPANDED) SPD_CASE(MT_KL_STRICT) SPD_CASE(MT_JACCARD_LITERAL)
 #undef SPD_CASE
     default: return 0.0f;
     }

@@ -232,7 +232,7 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
     const bool cheb = metric == MT_CHEBYSHEV;
     const uint32_t k = (uint32_t)n_cols;
     max_r = std::min(opt.max_rows, 16);
-    if (metric == MT_JS || metric == MT_MINKOWSKI) max_r = std::min(max_r, 8);   // two fp64 sums per pair
+    if (metric == MT_JS || metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED) max_r = std::min(max_r, 8);   // two fp64 sums per pair
     if (max_r < 1) max_r = 1;
     while (max_r & (max_r - 1)) max_r &= max_r - 1;         // power of two
     min_r = 1;
@@ -431,7 +431,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
     for (const AClass &c : a.classes) {
         if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16 && c.R != 32) return "class R";
         if (op == OP_CNT ? (c.R < 4 || (knn_k > 0 && c.R > 16)) : c.R > 16) return "class R outside the product's range";
-        if ((metric == MT_JS || metric == MT_MINKOWSKI) && c.R > 8) return "two-sum product with R > 8";
+        if ((metric == MT_JS || metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED) && c.R > 8) return "two-sum product with R > 8";
         if (c.kind < KIND_STRIP || c.kind > KIND_HASH) return "class kind";
         if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";
         if ((int64_t)c.lds_bytes + kStaticLds > opt.lds_budget) return "class LDS over budget";

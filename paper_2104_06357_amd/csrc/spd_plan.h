@@ -62,7 +62,9 @@ inline int split_len_for(const PlanOptions &opt, int64_t nnz_b) {
 }
 
 // Sums a pair carries through the slices of a spilled row.
-SPD_HD constexpr int metric_planes(int metric) { return metric == MT_MINKOWSKI ? 3 : (metric == MT_JS ? 2 : 1); }
+SPD_HD constexpr int metric_planes(int metric) {
+    return (metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED) ? 3 : ((metric == MT_JS || metric == MT_KL_STRICT) ? 2 : 1);
+}
 
 // Largest workgroup a scan kernel instance may be launched with: the instances that carry
 // the most per-lane state get 256 registers per lane instead of 128.

@@ -187,10 +187,12 @@ SPD_ACC_SHFL1(OP_L1, v)
 SPD_ACC_SHFL1(OP_CANB, v)
 SPD_ACC_SHFL1(OP_HAMM, c)
 SPD_ACC_SHFL1(OP_CNT, c)
-SPD_ACC_SHFL1(OP_KL, v)
 SPD_ACC_SHFL1(OP_CHEB, m)
 template <> __device__ __forceinline__ Op<OP_MINK>::Acc acc_shfl_xor<OP_MINK>(const Op<OP_MINK>::Acc &a, int m) {
     Op<OP_MINK>::Acc r; r.d = __shfl_xor(a.d, m); r.s = __shfl_xor(a.s, m); r.hits = __shfl_xor(a.hits, m); return r;
+}
+template <> __device__ __forceinline__ Op<OP_KL>::Acc acc_shfl_xor<OP_KL>(const Op<OP_KL>::Acc &a, int m) {
+    Op<OP_KL>::Acc r; r.v = __shfl_xor(a.v, m); r.hits = __shfl_xor(a.hits, m); return r;
 }
 template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const Op<OP_JS>::Acc &a, int m) {
     Op<OP_JS>::Acc r; r.f = __shfl_xor(a.f, m); r.s = __shfl_xor(a.s, m); return r;

@@ -46,8 +46,8 @@ spd_status spd_host_pair_value(spd_metric metric, float p, int64_t n_cols, const
     if (a_len < 0 || b_len < 0 || n_cols < 0) return SPD_ERR_DIM_MISMATCH;
     const MetricInfo mi = metric_info((int)metric);
     OpParams q;
-    q.p = metric == SPD_MINKOWSKI ? p : 1.0f;
-    q.inv_p = metric == SPD_MINKOWSKI ? 1.0f / p : 1.0f;
+    q.p = metric == SPD_MINKOWSKI ? p : (metric == SPD_L2_UNEXPANDED ? 2.0f : 1.0f);
+    q.inv_p = 1.0f / q.p;
     q.k = (double)n_cols;
     q.metric = (int)metric;
     double ra0 = 0, ra1 = 0, rb0 = 0, rb1 = 0;

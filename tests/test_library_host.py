@@ -10,7 +10,7 @@ import pytest
 import oracle
 import paper_2104_06357_amd as spd
 from gen import synth
-from util import ALL_METRICS, ORACLE_NAME, assert_distances_close
+from util import ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, assert_distances_close
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -83,7 +83,7 @@ def test_single_sweep_arithmetic_matches_the_oracle(metric):
 @pytest.mark.parametrize("metric", ALL_METRICS)
 def test_single_sweep_arithmetic_identical_and_signed_rows(metric):
     rng = np.random.default_rng(5)
-    signed = metric not in ("hellinger", "kl_divergence", "jensen_shannon")
+    signed = metric not in NONNEGATIVE_ONLY
     k = 300
     rows = []
     for _ in range(6):

@@ -8,9 +8,10 @@ ORACLE_NAME = {
     "l1": "manhattan", "chebyshev": "chebyshev", "minkowski": "minkowski", "canberra": "canberra",
     "hamming": "hamming", "kl_divergence": "kl_divergence", "jensen_shannon": "jensen_shannon",
     "russell_rao": "russell_rao",
+    "l2_unexpanded": "euclidean", "kl_divergence_strict": "kl_divergence_strict", "jaccard_literal": "jaccard_literal",
 }
 ALL_METRICS = tuple(ORACLE_NAME)
-NONNEGATIVE_ONLY = ("hellinger", "kl_divergence", "jensen_shannon")
+NONNEGATIVE_ONLY = ("hellinger", "kl_divergence", "jensen_shannon", "kl_divergence_strict")
 
 REL_TOL = 1e-4      # max relative error of an fp32 distance
 ABS_TOL = 1e-5      # absolute error allowed near zero
@@ -25,7 +26,12 @@ def assert_distances_close(got, want, what=""):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
-    assert np.all(np.isfinite(got)), what + ": non-finite result"
+    # an infinite oracle value (the strict KL divergence) must be met by the same infinity
+    infinite = np.isinf(want)
+    assert np.array_equal(got[infinite], want[infinite]), what + ": infinite values differ"
+    assert np.all(np.isfinite(got[~infinite])), what + ": non-finite result"
+    got = np.where(infinite, 0.0, got)
+    want = np.where(infinite, 0.0, want)
     excess = np.abs(got - want) / tolerance(want)
     worst = np.unravel_index(np.argmax(excess), excess.shape) if excess.size else None
     assert excess.size == 0 or excess.max() <= 1.0, (
