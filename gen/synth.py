@@ -280,10 +280,36 @@ def binary_highdim(role: int, n_rows: int, n_cols: int = 1 << 20, d_max: int = 5
 
 
 # --------------------------------------------------------------------------------------
+# two more shapes, at the ends the five configs leave out (the shapes of two of the paper's
+# datasets, Section 4.1 / Table 2; the data itself is drawn here, not reconstructed)
+#   5: n-gram-like   - 663,000 x 858,000, almost every row under 10 entries, none above 51
+#   6: ratings-like  - 283,000 x 194,000, power-law degrees up to 24,000 (mean ~100)
+# --------------------------------------------------------------------------------------
+def ngram_like(n_rows: int = 663_000, n_cols: int = 858_000, config: int = 5):
+    rng = np.random.Generator(np.random.PCG64(seed_for(config, 0)))
+    deg = np.minimum(rng.geometric(0.45, size=n_rows), 51).astype(np.int64)      # P(deg >= 10) = 0.5 %
+    deg[rng.integers(0, n_rows, size=4)] = 51                                    # the longest rows are always there
+    law = ZipfColumns(n_cols, 1.05, perm_seed=seed_for(config, 7))
+    indptr, indices = rows_with_degrees(rng, deg, law)
+    v = 1.0 + rng.poisson(0.3, size=indices.size)                                # small counts
+    return _csr(n_rows, n_cols, indptr, indices, v.astype(np.float32))
+
+
+def ratings_like(n_rows: int = 283_000, n_cols: int = 194_000, d_max: int = 24_000, config: int = 6):
+    rng = np.random.Generator(np.random.PCG64(seed_for(config, 0)))
+    deg = np.minimum(_powerlaw_degrees(rng, n_rows, 1.45, d_max), n_cols)
+    deg[rng.integers(0, n_rows)] = min(d_max, n_cols)                           # the extreme row is always there
+    law = ZipfColumns(n_cols, 1.02, perm_seed=seed_for(config, 7))
+    indptr, indices = rows_with_degrees(rng, deg, law)
+    v = 0.5 * rng.integers(1, 11, size=indices.size)                             # 0.5 .. 5.0 in steps of 0.5
+    return _csr(n_rows, n_cols, indptr, indices, v.astype(np.float32))
+
+
+# --------------------------------------------------------------------------------------
 # named workloads
 # --------------------------------------------------------------------------------------
 def workload(config: int, scale: float = 1.0):
-    """(A, B) for BASELINE config 0..4.  ``scale`` < 1 shrinks row counts only (the
+    """(A, B) for BASELINE config 0..4, and the two extra shapes 5 and 6.  ``scale`` < 1 shrinks row counts only (the
     column count, degree law, column law and value law stay those of the full size)."""
     s = float(scale)
 
@@ -301,7 +327,13 @@ def workload(config: int, scale: float = 1.0):
         return b, b                                   # self-join; callers slice query tiles
     if config == 4:
         return binary_highdim(0, rows(4096)), binary_highdim(1, rows(500_000))
-    raise ValueError("config must be 0..4")
+    if config == 5:
+        b = ngram_like(rows(663_000))
+        return b, b                                   # self-join; callers slice query tiles
+    if config == 6:
+        b = ratings_like(rows(283_000))
+        return b, b
+    raise ValueError("config must be 0..6")
 
 
 def slice_rows(csr, r0: int, r1: int):

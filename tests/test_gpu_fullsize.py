@@ -1,4 +1,5 @@
-"""Parity at the full sizes of BASELINE configs 2-4 (needs an MI355X; run with -m gpu).
+"""Parity at the full sizes of BASELINE configs 2-4 and of two more shapes (the ultra-short rows
+of an n-gram matrix, the extreme skew of a ratings matrix); needs an MI355X, run with -m gpu.
 
 The library runs a whole query tile against the whole index, exactly as a user would call
 it; the oracle then recomputes a seeded sample of the outputs one by one (always including
@@ -126,3 +127,59 @@ def test_config4_binary_knn(spd, capsys):
         assert_knn_matches(idx.cpu().numpy()[rq], dist.cpu().numpy()[rq], rows, 32, metric, "config4 " + metric)
         progress(capsys, "config4 %s checked against the oracle" % metric)
     h.close()
+
+
+def _knn_tile_against_oracle(spd, capsys, label, M, tile_rows, metrics, k, n_checked):
+    """Self-join protocol: a tile of the matrix's own rows queries the whole matrix."""
+    tile = synth.take_rows(M, tile_rows)
+    dQ, dM = spd.DeviceCsr.from_host(tile), spd.DeviceCsr.from_host(M)
+    h = spd.Handle()
+    h.set_option("check_plan", 1)
+    rng = np.random.default_rng(len(tile_rows))
+    rq = _extremes_and_sample(tile, n_checked, rng)
+    for metric in metrics:
+        idx, dist = _timed(capsys, "%s knn %s" % (label, metric), lambda: h.knn(dQ, dM, metric, k))
+        idx, dist = idx.cpu().numpy(), dist.cpu().numpy()
+        rows = oracle.pairwise(tile, M, ORACLE_NAME[metric], rows_a=rq)
+        assert_knn_matches(idx[rq], dist[rq], rows, k, metric, "%s %s" % (label, metric))
+        progress(capsys, "%s %s checked against the oracle" % (label, metric))
+        # every query is in the index: it, or a row at the same distance, comes first
+        assert np.all(dist[:, 0] <= 1e-5), metric
+    h.close()
+    return tile, dQ, dM
+
+
+def test_shape5_ngram_like(spd, capsys):
+    """663,000 x 858,000 with 2.2 entries per row on average (99.5 % of the rows under 10, none
+    above 51): 4,096 of its rows against all of it, fused top-32, and a pairwise tile."""
+    import torch
+    M, _ = synth.workload(5)
+    progress(capsys, "shape 5 generated: %d entries" % int(M["indptr"][-1]))
+    rng = np.random.default_rng(5)
+    tile_rows = _extremes_and_sample(M, 4096, rng)
+    tile, dQ, dM = _knn_tile_against_oracle(spd, capsys, "shape5", M, tile_rows, ("cosine", "jaccard"), 32, 8)
+    h = spd.Handle()
+    small = synth.slice_rows(tile, 0, 256)
+    dS = spd.DeviceCsr.from_host(small)
+    out = torch.empty((256, M["n_rows"]), dtype=torch.float32, device="cuda")
+    ra = _extremes_and_sample(small, 16, rng)
+    rb = _extremes_and_sample(M, 4096, rng, extra=list(tile_rows[:256][ra]))
+    for metric in ("l1", "hamming"):
+        _timed(capsys, "shape5 pairwise " + metric, lambda: h.pairwise(dS, dM, metric, out=out))
+        want = oracle.pairwise(small, M, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
+        assert_distances_close(_gather(out, ra, rb), want, "shape5 " + metric)
+    h.close()
+
+
+def test_shape6_ratings_like(spd, capsys):
+    """283,000 x 194,000 with power-law degrees up to 24,000 (46 M entries): 1,024 of its rows,
+    the 24,000-entry one among them (cut into slices), against all of it, fused top-32."""
+    M, _ = synth.workload(6)
+    progress(capsys, "shape 6 generated: %d entries" % int(M["indptr"][-1]))
+    rng = np.random.default_rng(6)
+    tile_rows = _extremes_and_sample(M, 1024, rng)
+    plan = spd.host_plan_summary(synth.take_rows(M, tile_rows)["indptr"], M["indptr"], M["n_cols"], "cosine",
+                                 k_neighbors=32)
+    progress(capsys, "shape6 plan: spilled rows %d, slabs %d" % (plan["spilled_rows"], plan["slabs"]))
+    assert plan["spilled_rows"] >= 1
+    _knn_tile_against_oracle(spd, capsys, "shape6", M, tile_rows, ("cosine", "l1"), 32, 8)
