@@ -21,6 +21,9 @@ METRICS = (
     "jensen_shannon", "russell_rao", "kl_divergence_strict", "jaccard_literal",
 )
 
+PRODUCTS = ("times", "plus", "min", "max", "abs_diff", "sq_diff")
+SUMS = ("plus", "min", "max")
+
 _lib = None
 
 
@@ -48,6 +51,10 @@ def _load():
             ctypes.c_int64, ctypes.c_int64, P, P, P, ctypes.c_int64, P, P, P, ctypes.c_int,
             ctypes.c_double, P, ctypes.c_int64, P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, P]
         lib.oracle_pairwise.restype = ctypes.c_int
+        lib.oracle_semiring_pairwise.argtypes = [
+            ctypes.c_int64, ctypes.c_int64, P, P, P, ctypes.c_int64, P, P, P, ctypes.c_int, ctypes.c_int,
+            ctypes.c_int, P, ctypes.c_int64, P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, P]
+        lib.oracle_semiring_pairwise.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -92,6 +99,40 @@ def pairwise(A, B, metric: str, p: float = 2.0, rows_a=None, rows_b=None, mode: 
     if used < 0:
         raise RuntimeError("oracle failed (%d)" % used)
     return (out, used) if return_threads else out
+
+
+def semiring_pairwise(A, B, product: str, sum: str, over_union: bool, rows_a=None, rows_b=None,
+                      mode: str = "support", threads: int = 0):
+    """fp64 semiring products between rows (Section 2.2): the `sum` fold of `product` over the
+    columns stored in both rows (over_union False) or in either row, the missing side read as 0
+    (over_union True); the identity of `sum` where that set is empty."""
+    lib = _load()
+    if A["n_cols"] != B["n_cols"]:
+        raise ValueError("column counts differ")
+    aip, aix, av = _csr_arrays(A)
+    bip, bix, bv = _csr_arrays(B)
+    ra = None if rows_a is None else np.ascontiguousarray(rows_a, dtype=np.int64)
+    rb = None if rows_b is None else np.ascontiguousarray(rows_b, dtype=np.int64)
+    na = A["n_rows"] if ra is None else ra.size
+    nb = B["n_rows"] if rb is None else rb.size
+    out = np.empty((na, nb), dtype=np.float64)
+    used = lib.oracle_semiring_pairwise(
+        A["n_rows"], A["n_cols"], _ptr(aip), _ptr(aix), _ptr(av), B["n_rows"], _ptr(bip), _ptr(bix),
+        _ptr(bv), PRODUCTS.index(product), SUMS.index(sum), int(bool(over_union)), _ptr(ra), na, _ptr(rb), nb,
+        {"full": 0, "support": 1}[mode], int(threads), _ptr(out))
+    if used < 0:
+        raise RuntimeError("oracle failed (%d)" % used)
+    return out
+
+
+def semiring_knn(Q, Index, product: str, sum: str, over_union: bool, k: int, rows_q=None, threads: int = 0):
+    """The k index rows with the smallest semiring value for each query row, by (value, index)."""
+    d = semiring_pairwise(Q, Index, product, sum, over_union, rows_a=rows_q, threads=threads)
+    n = d.shape[1]
+    idx = np.empty((d.shape[0], k), dtype=np.int64)
+    for r in range(d.shape[0]):
+        idx[r] = np.lexsort((np.arange(n), d[r]))[:k]
+    return idx, np.take_along_axis(d, idx, axis=1)
 
 
 def knn(Q, Index, metric: str, k: int, p: float = 2.0, rows_q=None, threads: int = 0):

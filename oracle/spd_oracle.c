@@ -224,6 +224,47 @@ static double eval_pair(int metric, double p, const double *x, const double *y,
     }
 }
 
+/*
+ * A semiring product between two rows (Section 2.2; the tropical semiring of Eq. 1 is one
+ * instance): result = sum()-fold of product(x_c, y_c) over the columns c of the domain,
+ *   domain = columns stored (non-zero) in BOTH rows when the product annihilates on 0,
+ *   domain = columns stored in EITHER row, the missing side read as 0, for a
+ *            non-annihilating product (the NAMM of Section 2.2, Eq. 2);
+ * an empty domain gives the identity of sum(): 0 for +, +infinity for min, -infinity for max.
+ */
+enum { P_TIMES = 0, P_PLUS, P_MIN, P_MAX, P_ABS_DIFF, P_SQ_DIFF, P_COUNT };
+enum { S_PLUS = 0, S_MIN, S_MAX, S_COUNT };
+
+typedef struct { int product, sum, over_union; } semiring_t;
+
+static double semiring_product(int product, double a, double b) {
+    switch (product) {
+    case P_TIMES: return a * b;
+    case P_PLUS: return a + b;
+    case P_MIN: return a < b ? a : b;
+    case P_MAX: return a > b ? a : b;
+    case P_ABS_DIFF: return fabs(a - b);
+    case P_SQ_DIFF: return (a - b) * (a - b);
+    default: return NAN;
+    }
+}
+
+static double eval_semiring(const semiring_t *sr, const double *x, const double *y,
+                            const int32_t *cols, int64_t nc) {
+    double acc = sr->sum == S_PLUS ? 0.0 : (sr->sum == S_MIN ? INFINITY : -INFINITY);
+    for (int64_t t = 0; t < nc; ++t) {
+        int64_t c = COL(t);
+        int in_x = x[c] != 0.0, in_y = y[c] != 0.0;
+        int in_domain = sr->over_union ? (in_x || in_y) : (in_x && in_y);
+        if (!in_domain) continue;
+        double v = semiring_product(sr->product, x[c], y[c]);
+        if (sr->sum == S_PLUS) acc += v;
+        else if (sr->sum == S_MIN) { if (v < acc) acc = v; }
+        else { if (v > acc) acc = v; }
+    }
+    return acc;
+}
+
 typedef struct {
     int64_t n_rows, n_cols;
     const int64_t *indptr;
@@ -236,12 +277,11 @@ typedef struct {
  * sel_a / sel_b may be NULL (all rows in order).  mode: 0 full dense, 1 support restricted.
  * n_threads <= 0: all hardware threads.  Returns the number of threads used, <0 on error.
  */
-int oracle_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, const int32_t *a_indices,
-                    const float *a_values, int64_t b_rows, const int64_t *b_indptr,
-                    const int32_t *b_indices, const float *b_values, int metric, double p,
-                    const int64_t *sel_a, int64_t n_sel_a, const int64_t *sel_b, int64_t n_sel_b,
-                    int mode, int n_threads, double *out) {
-    if (metric < 0 || metric >= M_COUNT) return -1;
+static int run_pairs(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, const int32_t *a_indices,
+                     const float *a_values, int64_t b_rows, const int64_t *b_indptr,
+                     const int32_t *b_indices, const float *b_values, int metric, double p,
+                     const semiring_t *sr, const int64_t *sel_a, int64_t n_sel_a, const int64_t *sel_b,
+                     int64_t n_sel_b, int mode, int n_threads, double *out) {
     if (!sel_a) n_sel_a = a_rows;
     if (!sel_b) n_sel_b = b_rows;
     int used = 1;
@@ -275,7 +315,8 @@ int oracle_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, con
                     for (int64_t q = b0; q < b1; ++q) y[b_indices[q]] = (double)b_values[q];
                     double d;
                     if (mode == 0) {
-                        d = eval_pair(metric, p, x, y, NULL, n_cols, n_cols);
+                        d = sr ? eval_semiring(sr, x, y, NULL, n_cols)
+                               : eval_pair(metric, p, x, y, NULL, n_cols, n_cols);
                     } else {
                         int64_t cap = (a1 - a0) + (b1 - b0), nc = 0;
                         cols = (int32_t *)realloc(cols, (size_t)(cap > 0 ? cap : 1) * sizeof(int32_t));
@@ -287,7 +328,7 @@ int oracle_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, con
                             int32_t c = b_indices[q];
                             if (!seen[c]) { seen[c] = 1; cols[nc++] = c; }
                         }
-                        d = eval_pair(metric, p, x, y, cols, nc, n_cols);
+                        d = sr ? eval_semiring(sr, x, y, cols, nc) : eval_pair(metric, p, x, y, cols, nc, n_cols);
                         for (int64_t t = 0; t < nc; ++t) seen[cols[t]] = 0;
                     }
                     out[ia * n_sel_b + jb] = d;
@@ -299,6 +340,28 @@ int oracle_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, con
         free(x); free(y); free(seen); free(cols);
     }
     return failed ? -2 : used;
+}
+
+int oracle_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, const int32_t *a_indices,
+                    const float *a_values, int64_t b_rows, const int64_t *b_indptr,
+                    const int32_t *b_indices, const float *b_values, int metric, double p,
+                    const int64_t *sel_a, int64_t n_sel_a, const int64_t *sel_b, int64_t n_sel_b,
+                    int mode, int n_threads, double *out) {
+    if (metric < 0 || metric >= M_COUNT) return -1;
+    return run_pairs(a_rows, n_cols, a_indptr, a_indices, a_values, b_rows, b_indptr, b_indices, b_values,
+                     metric, p, NULL, sel_a, n_sel_a, sel_b, n_sel_b, mode, n_threads, out);
+}
+
+/* The same for a semiring: out[a * n_sel_b + b] = sum()-fold of product() over the domain. */
+int oracle_semiring_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, const int32_t *a_indices,
+                             const float *a_values, int64_t b_rows, const int64_t *b_indptr,
+                             const int32_t *b_indices, const float *b_values, int product, int sum,
+                             int over_union, const int64_t *sel_a, int64_t n_sel_a, const int64_t *sel_b,
+                             int64_t n_sel_b, int mode, int n_threads, double *out) {
+    if (product < 0 || product >= P_COUNT || sum < 0 || sum >= S_COUNT) return -1;
+    semiring_t sr = {product, sum, over_union != 0};
+    return run_pairs(a_rows, n_cols, a_indptr, a_indices, a_values, b_rows, b_indptr, b_indices, b_values,
+                     0, 0.0, &sr, sel_a, n_sel_a, sel_b, n_sel_b, mode, n_threads, out);
 }
 
 int oracle_max_threads(void) {
