@@ -120,6 +120,42 @@ spd_status spd_pairwise(spd_handle *handle, const spd_csr *A, const spd_csr *B, 
 spd_status spd_knn(spd_handle *handle, const spd_csr *Q, const spd_csr *Index, spd_metric metric,
                    float p, int k, int64_t *out_idx, float *out_dist);
 
+/* Semirings (Section 2.2).  A value between two rows is the sum() fold of product(x_c, y_c) over
+ * the columns c both rows store, when 0 annihilates the product (the dot-product semiring is
+ * {TIMES, PLUS}; the tropical semiring of Eq. 1 is {PLUS, MIN}); with `over_union` set, over the
+ * columns either row stores, the missing side read as 0: the non-annihilating multiplicative
+ * monoid of Section 2.2 ({ABS_DIFF, PLUS} is the Manhattan distance, {ABS_DIFF, MAX} Chebyshev's).
+ * A pair with no such column gets the identity of sum(): 0, +infinity (MIN) or -infinity (MAX).
+ * Every product offered is commutative, as Section 2.2 asks of the union form. */
+typedef enum {
+    SPD_PRODUCT_TIMES = 0,  /* x * y     */
+    SPD_PRODUCT_PLUS,       /* x + y     */
+    SPD_PRODUCT_MIN,        /* min(x, y) */
+    SPD_PRODUCT_MAX,        /* max(x, y) */
+    SPD_PRODUCT_ABS_DIFF,   /* |x - y|   */
+    SPD_PRODUCT_SQ_DIFF,    /* (x - y)^2 */
+    SPD_PRODUCT_COUNT
+} spd_product;
+
+typedef enum { SPD_SUM_PLUS = 0, SPD_SUM_MIN, SPD_SUM_MAX, SPD_SUM_COUNT } spd_sum;
+
+typedef struct {
+    spd_product product;
+    spd_sum sum;
+    int over_union;         /* 0: columns stored in both rows; 1: in either row */
+} spd_semiring;
+
+/* out[i * B.n_rows + j] = the semiring's value between A_i and B_j, fp32, row-major, m x n.
+ * An unknown product or sum returns SPD_ERR_BAD_METRIC.  Scratch: the bound spd_workspace_bytes()
+ * gives for SPD_MINKOWSKI covers every semiring. */
+spd_status spd_semiring_pairwise(spd_handle *handle, const spd_csr *A, const spd_csr *B,
+                                 const spd_semiring *semiring, float *out);
+
+/* For each query row the k index rows with the smallest semiring value, ordered by (value,
+ * index) ascending, selected inside the kernels like spd_knn's. */
+spd_status spd_semiring_knn(spd_handle *handle, const spd_csr *Q, const spd_csr *Index,
+                            const spd_semiring *semiring, int k, int64_t *out_idx, float *out_dist);
+
 /* Device pass over a matrix that checks what the other calls assume: row pointers start
  * at 0, never decrease and end at nnz; columns ascend strictly inside a row and lie in
  * [0, n_cols); values are finite (and, if `require_nonnegative`, not negative).

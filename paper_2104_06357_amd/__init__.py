@@ -2,5 +2,5 @@
 
 The package is a thin binding over ``libspd.so`` (built from ``csrc/`` by ``build.py``).
 """
-from .binding import (KNN_MAX_K, METRICS, DeviceCsr, Handle, SpdError, host_pair_value,  # noqa: F401
+from .binding import (KNN_MAX_K, METRICS, PRODUCTS, SUMS, DeviceCsr, Handle, SpdError, host_pair_value,  # noqa: F401
                       host_plan_summary, lib)

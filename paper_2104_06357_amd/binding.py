@@ -17,6 +17,8 @@ METRICS = (
     "l2_unexpanded", "kl_divergence_strict", "jaccard_literal",
 )
 METRIC_ID = {name: i for i, name in enumerate(METRICS)}
+PRODUCTS = ("times", "plus", "min", "max", "abs_diff", "sq_diff")       # spd_product
+SUMS = ("plus", "min", "max")                                            # spd_sum
 STATUS = ("SPD_OK", "SPD_ERR_NULL", "SPD_ERR_DIM_MISMATCH", "SPD_ERR_BAD_CSR", "SPD_ERR_BAD_METRIC",
           "SPD_ERR_BAD_P", "SPD_ERR_BAD_K", "SPD_ERR_WORKSPACE", "SPD_ERR_HIP", "SPD_ERR_UNSUPPORTED")
 KNN_MAX_K = 64
@@ -32,6 +34,10 @@ class SpdError(RuntimeError):
 class CsrStruct(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int64), ("n_cols", ctypes.c_int64), ("nnz", ctypes.c_int64),
                 ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("values", ctypes.c_void_p)]
+
+
+class SemiringStruct(ctypes.Structure):
+    _fields_ = [("product", ctypes.c_int), ("sum", ctypes.c_int), ("over_union", ctypes.c_int)]
 
 
 class KernelTime(ctypes.Structure):
@@ -59,6 +65,8 @@ def lib():
         L.spd_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
         L.spd_pairwise.argtypes = [vp, csr_p, csr_p, i32, f32, vp]
         L.spd_knn.argtypes = [vp, csr_p, csr_p, i32, f32, i32, vp, vp]
+        L.spd_semiring_pairwise.argtypes = [vp, csr_p, csr_p, ctypes.POINTER(SemiringStruct), vp]
+        L.spd_semiring_knn.argtypes = [vp, csr_p, csr_p, ctypes.POINTER(SemiringStruct), i32, vp, vp]
         L.spd_csr_validate.argtypes = [vp, csr_p, i32]
         L.spd_set_option.argtypes = [vp, ctypes.c_char_p, i64]
         L.spd_last_error.argtypes = [vp]
@@ -72,7 +80,7 @@ def lib():
         L.spd_host_plan_summary.argtypes = [vp, i64, vp, i64, i64, i32, i32, ctypes.POINTER(ctypes.c_char_p),
                                             ctypes.POINTER(i64), i32, ctypes.c_char_p, ctypes.c_size_t]
         for fn in ("spd_create", "spd_destroy", "spd_workspace_bytes", "spd_set_workspace", "spd_pairwise",
-                   "spd_knn", "spd_csr_validate", "spd_set_option", "spd_host_pair_value",
+                   "spd_knn", "spd_semiring_pairwise", "spd_semiring_knn", "spd_csr_validate", "spd_set_option", "spd_host_pair_value",
                    "spd_host_plan_summary"):
             getattr(L, fn).restype = ctypes.c_int
         _lib = L
@@ -194,6 +202,36 @@ class Handle:
         self._check(self._lib.spd_knn(self._h, ctypes.byref(sa), ctypes.byref(sb), metric_id(metric), float(p), int(k),
                                       out_idx.data_ptr() if out_idx.numel() else None,
                                       out_dist.data_ptr() if out_dist.numel() else None))
+        return out_idx, out_dist
+
+
+    @staticmethod
+    def _semiring(product, sum, over_union) -> SemiringStruct:
+        prod = PRODUCTS.index(product) if isinstance(product, str) else int(product)
+        sm = SUMS.index(sum) if isinstance(sum, str) else int(sum)
+        return SemiringStruct(prod, sm, int(bool(over_union)))
+
+    def semiring_pairwise(self, A: DeviceCsr, B: DeviceCsr, product, sum, over_union: bool, out=None):
+        """out[i, j] = the semiring's value between A_i and B_j as an fp32 torch tensor (m, n)."""
+        import torch
+        if out is None:
+            out = torch.empty((A.n_rows, B.n_rows), dtype=torch.float32, device=A.indptr.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        assert tuple(out.shape) == (A.n_rows, B.n_rows)
+        sa, sb, sr = A.struct(), B.struct(), self._semiring(product, sum, over_union)
+        self._check(self._lib.spd_semiring_pairwise(self._h, ctypes.byref(sa), ctypes.byref(sb), ctypes.byref(sr),
+                                                    out.data_ptr() if out.numel() else None))
+        return out
+
+    def semiring_knn(self, Q: DeviceCsr, Index: DeviceCsr, product, sum, over_union: bool, k: int):
+        """(idx int64 [m, k], value fp32 [m, k]) of the k smallest semiring values per query row."""
+        import torch
+        out_idx = torch.empty((Q.n_rows, k), dtype=torch.int64, device=Q.indptr.device)
+        out_dist = torch.empty((Q.n_rows, k), dtype=torch.float32, device=Q.indptr.device)
+        sa, sb, sr = Q.struct(), Index.struct(), self._semiring(product, sum, over_union)
+        self._check(self._lib.spd_semiring_knn(self._h, ctypes.byref(sa), ctypes.byref(sb), ctypes.byref(sr), int(k),
+                                               out_idx.data_ptr() if out_idx.numel() else None,
+                                               out_dist.data_ptr() if out_dist.numel() else None))
         return out_idx, out_dist
 
 

@@ -143,7 +143,8 @@ spd_status check_csr_args(spd_handle *h, const spd_csr *M, const char *name) {
 }
 
 spd_status check_call_args(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, int knn_k,
-                           bool is_knn, const void *o1, const void *o2) {
+                           bool is_knn, const void *o1, const void *o2, const spd_semiring *semiring = nullptr,
+                           bool is_semiring = false) {
     if (!h) return SPD_ERR_NULL;
     h->err.clear();
     spd_status st = check_csr_args(h, A, is_knn ? "Q" : "A");
@@ -151,9 +152,16 @@ spd_status check_call_args(spd_handle *h, const spd_csr *A, const spd_csr *B, sp
     st = check_csr_args(h, B, is_knn ? "Index" : "B");
     if (st != SPD_OK) return st;
     if (A->n_cols != B->n_cols) return fail(h, SPD_ERR_DIM_MISMATCH, "the two matrices differ in n_cols");
-    if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return fail(h, SPD_ERR_BAD_METRIC, "unknown metric");
-    if (metric == SPD_MINKOWSKI && !(p > 0.0f && std::isfinite(p)))
-        return fail(h, SPD_ERR_BAD_P, "Minkowski needs a finite p > 0");
+    if (is_semiring) {
+        if (!semiring) return fail(h, SPD_ERR_NULL, "semiring is NULL");
+        if ((int)semiring->product < 0 || (int)semiring->product >= SPD_PRODUCT_COUNT)
+            return fail(h, SPD_ERR_BAD_METRIC, "unknown product");
+        if ((int)semiring->sum < 0 || (int)semiring->sum >= SPD_SUM_COUNT) return fail(h, SPD_ERR_BAD_METRIC, "unknown sum");
+    } else {
+        if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return fail(h, SPD_ERR_BAD_METRIC, "unknown metric");
+        if (metric == SPD_MINKOWSKI && !(p > 0.0f && std::isfinite(p)))
+            return fail(h, SPD_ERR_BAD_P, "Minkowski needs a finite p > 0");
+    }
     if (is_knn) {
         if (knn_k < 1 || (int64_t)knn_k > B->n_rows || knn_k > SPD_KNN_MAX_K)
             return fail(h, SPD_ERR_BAD_K, "k must lie in [1, min(Index.n_rows, SPD_KNN_MAX_K)]");
@@ -231,8 +239,11 @@ struct Upload {
     void add(size_t off, const void *src, size_t bytes) { if (bytes) parts.push_back({off, {src, bytes}}); }
 };
 
-spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, int knn_k,
-               float *out, int64_t *out_idx, float *out_dist) {
+size_t workspace_bound(const spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, int k_neighbors);
+
+// `metric` is a spd_metric, or, with `semiring` set, the internal id its sum() runs as.
+spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, float p, const spd_semiring *semiring,
+               int knn_k, float *out, int64_t *out_idx, float *out_dist) {
     const int64_t m = A->n_rows, n = B->n_rows;
     static const bool host_times = std::getenv("SPD_HOST_TIMES") != nullptr;
     auto now = [] { return std::chrono::steady_clock::now(); };
@@ -270,7 +281,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
 
     // ---- B first: plan it, upload its plan and start the repack, so that the device is
     //      busy while the host plans A -----------------------------------------------------
-    const MetricInfo mi = metric_info((int)metric);
+    MetricInfo mi = metric_info(metric);
+    if (semiring && mi.norm == NORM_SEMI) mi.norm = NORM_SEMI + (int)semiring->product;
     APlan &ap = h->plan_of_a;
     BPlan &bp = h->plan_of_b;
     // the set metrics count shared columns in byte lanes, or (option) as a dot product of 0/1 values
@@ -282,7 +294,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         const int64_t *a_rows_ptr = a_ip;
         h->helper.post([&why_a, &ap, h, a_rows_ptr, m, A, metric, op, knn_k] {
             try {
-                why_a = plan_a(a_rows_ptr, m, A->n_cols, (int)metric, op, knn_k, h->opt, ap);
+                why_a = plan_a(a_rows_ptr, m, A->n_cols, metric, op, knn_k, h->opt, ap);
             } catch (const std::exception &ex) {
                 why_a = std::string("planning failed: ") + ex.what();
             }
@@ -294,7 +306,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     lap("plan b");
     int a_kind = 0, a_max_r = 1, a_min_r = 1;
     uint64_t a_dmax = 0;
-    why = plan_staging(A->n_cols, (int)metric, op, knn_k > 0, h->opt, a_kind, a_max_r, a_min_r, a_dmax);
+    why = plan_staging(A->n_cols, metric, op, knn_k > 0, h->opt, a_kind, a_max_r, a_min_r, a_dmax);
     if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "A: " + why);
     // every launch of a call stages the same way: one pad column serves them all
     const uint32_t padcol = a_kind == KIND_HASH ? kEmptyKey : (uint32_t)A->n_cols;
@@ -303,10 +315,15 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     if (metric == SPD_L2_UNEXPANDED) q.p = 2.0f;
     q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : (metric == SPD_L2_UNEXPANDED ? 0.5f : 1.0f);
     q.k = (double)A->n_cols;
-    q.metric = (int)metric;
+    q.metric = metric;
     if (metric != SPD_MINKOWSKI && metric != SPD_L2_UNEXPANDED) q.p = 1.0f;
+    if (semiring) {
+        q.product = (int)semiring->product;
+        q.over_union = semiring->over_union != 0;
+        q.sign = semiring->sum == SPD_SUM_MIN ? -1.0f : 1.0f;
+    }
 
-    const int planes = metric_planes((int)metric);
+    const int planes = metric_planes(metric);
     const size_t lanes = (size_t)bp.n_slabs * kWave;
     Carver cv;
     // (1) B's plan, contiguous so that one copy moves it, then what the repack produces
@@ -333,7 +350,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         // room for A's part as well, from the documented bound, so that the scratch does not
         // have to move once the repack has been started (checked again below)
         size_t guess = 0;
-        if (!h->ws_external && spd_workspace_bytes(h, A, B, metric, knn_k, &guess) != SPD_OK) guess = 0;
+        if (!h->ws_external) guess = workspace_bound(h, A, B, metric, knn_k);
         st = ensure_workspace(h, std::max(b_end, guess));
         if (st != SPD_OK) return st;
     }
@@ -374,7 +391,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
         LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, bp.n_slabs);
         hipError_t err = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd,
                                        reinterpret_cast<uint2 *>(ws + o_packed), reinterpret_cast<double *>(ws + o_norms),
-                                       (int)metric, mi.transform, mi.norm, q.p, q.k, padcol);
+                                       metric, mi.transform, mi.norm, q.p, q.k, padcol);
         if (err != hipSuccess) return hip_fail(h, err, "pack kernel");
         lt.done();
         return SPD_OK;
@@ -391,7 +408,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric met
     for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
     lap("chunks");
     if (h->check_plan) {
-        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, (int)metric, op, knn_k, h->opt);
+        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, metric, op, knn_k, h->opt);
         if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
     }
     for (const AClass &c : ap.classes)
@@ -628,6 +645,14 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     if (!h || !A || !B || !bytes) return SPD_ERR_NULL;
     if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return SPD_ERR_BAD_METRIC;
     if (A->n_rows < 0 || B->n_rows < 0 || A->nnz < 0 || B->nnz < 0 || A->n_cols != B->n_cols) return SPD_ERR_DIM_MISMATCH;
+    *bytes = workspace_bound(h, A, B, (int)metric, k_neighbors);
+    return SPD_OK;
+}
+
+}  // extern "C"
+
+namespace {
+size_t workspace_bound(const spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, int k_neighbors) {
     const PlanOptions &o = h->opt;
     const size_t m = (size_t)A->n_rows, n = (size_t)B->n_rows;
     const int split_len = split_len_for(o, B->nnz);
@@ -643,7 +668,7 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     // slice the budget admits; 512 entries is a floor for any budget the planner accepts
     size_t slices = 2 * (size_t)A->nnz / 512 + 2;
     slices = std::min(slices, (size_t)A->nnz / 64 + 2);
-    size_t planes = (size_t)metric_planes((int)metric);
+    size_t planes = (size_t)metric_planes(metric);
     size_t total = 0;
     auto add = [&](size_t b) { total += align256(b); };
     // padded slabs: at most 64 idle entries per step of the longest row of each window, one per
@@ -664,9 +689,11 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
         lists += std::min(sliced_rows_max, m) * (n / (size_t)kFinalizeTile + 1);     // the tiles of spilled rows
         add(lists * (size_t)k_neighbors * sizeof(KnnEntry)); add(m * 8); add(m * 4);
     }
-    *bytes = total;
-    return SPD_OK;
+    return total;
 }
+}  // namespace
+
+extern "C" {
 
 spd_status spd_set_workspace(spd_handle *h, void *device_ptr, size_t bytes) {
     if (!h) return SPD_ERR_NULL;
@@ -687,14 +714,29 @@ spd_status spd_set_workspace(spd_handle *h, void *device_ptr, size_t bytes) {
 spd_status spd_pairwise(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, float *out) {
     spd_status st = check_call_args(h, A, B, metric, p, 0, false, out, nullptr);
     if (st != SPD_OK) return st;
-    return run(h, A, B, metric, p, 0, out, nullptr, nullptr);
+    return run(h, A, B, (int)metric, p, nullptr, 0, out, nullptr, nullptr);
 }
 
 spd_status spd_knn(spd_handle *h, const spd_csr *Q, const spd_csr *Index, spd_metric metric, float p, int k,
                    int64_t *out_idx, float *out_dist) {
     spd_status st = check_call_args(h, Q, Index, metric, p, k, true, out_idx, out_dist);
     if (st != SPD_OK) return st;
-    return run(h, Q, Index, metric, p, k, nullptr, out_idx, out_dist);
+    return run(h, Q, Index, (int)metric, p, nullptr, k, nullptr, out_idx, out_dist);
+}
+
+spd_status spd_semiring_pairwise(spd_handle *h, const spd_csr *A, const spd_csr *B, const spd_semiring *semiring,
+                                 float *out) {
+    spd_status st = check_call_args(h, A, B, SPD_INNER_PRODUCT, 0.0f, 0, false, out, nullptr, semiring, true);
+    if (st != SPD_OK) return st;
+    return run(h, A, B, semiring->sum == SPD_SUM_PLUS ? MT_SEMI_SUM : MT_SEMI_EXT, 1.0f, semiring, 0, out, nullptr, nullptr);
+}
+
+spd_status spd_semiring_knn(spd_handle *h, const spd_csr *Q, const spd_csr *Index, const spd_semiring *semiring, int k,
+                            int64_t *out_idx, float *out_dist) {
+    spd_status st = check_call_args(h, Q, Index, SPD_INNER_PRODUCT, 0.0f, k, true, out_idx, out_dist, semiring, true);
+    if (st != SPD_OK) return st;
+    return run(h, Q, Index, semiring->sum == SPD_SUM_PLUS ? MT_SEMI_SUM : MT_SEMI_EXT, 1.0f, semiring, k, nullptr, out_idx,
+               out_dist);
 }
 
 spd_status spd_csr_validate(spd_handle *h, const spd_csr *M, int require_nonnegative) {

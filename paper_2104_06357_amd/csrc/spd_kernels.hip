@@ -113,11 +113,12 @@ hipError_t launch_pack_b(hipStream_t st, const int64_t *b_indptr, const int32_t 
 // ------------------------------------------------------------------------------------
 __device__ __forceinline__ float finalize_one(const FinalizeArgs &a, const SpilledRow &sr, int64_t j,
                                               double na0, double na1) {
-    double v0 = 0.0, v1 = 0.0, v2 = 0.0;
+    const bool by_max = sum_is_max(a.q.metric);
+    double v0 = by_max ? -__builtin_huge_val() : 0.0, v1 = 0.0, v2 = 0.0;
     for (int q = 0; q < sr.n_slots; ++q) {
         size_t slot = (size_t)(sr.first_slot + q);
         double t = a.partial[(slot * a.planes) * (size_t)a.n_b + (size_t)j];
-        if (a.q.metric == MT_CHEBYSHEV) v0 = fmax(v0, t); else v0 += t;
+        if (by_max) v0 = fmax(v0, t); else v0 += t;
         if (a.planes >= 2) v1 += a.partial[(slot * a.planes + 1) * (size_t)a.n_b + (size_t)j];
         if (a.planes == 3) v2 += a.partial[(slot * 3 + 2) * (size_t)a.n_b + (size_t)j];
     }

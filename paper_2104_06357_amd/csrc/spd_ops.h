@@ -13,6 +13,9 @@
 //     parts of Eq. 2 in one sweep over y instead of the two passes of Section 3.3.
 //   * Chebyshev (sum() = max) keeps max |x_c - y_c| over the entries of y; the part of x
 //     that y does not store is completed by the kernel from x's largest entries.
+//   * semirings built from a menu of product() and sum() (Section 2.2; Eq. 1 is (min, +)):
+//     sum() = + works like the union family with product(., 0) in the place of the row norm,
+//     sum() = min / max like Chebyshev, with x's entries ranked by product(x_c, 0).
 // Sums are carried in fp64 so the cancellations of the expanded forms (Section 2.1) stay
 // far below the fp32 result's resolution.
 #pragma once
@@ -27,15 +30,24 @@
 
 namespace spd {
 
-enum OpId { OP_DOT = 0, OP_L1, OP_MINK, OP_CANB, OP_HAMM, OP_KL, OP_JS, OP_CHEB, OP_CNT, OP_COUNT };
+enum OpId { OP_DOT = 0, OP_L1, OP_MINK, OP_CANB, OP_HAMM, OP_KL, OP_JS, OP_CHEB, OP_CNT, OP_SEMI_SUM, OP_SEMI_EXT, OP_COUNT };
 enum Transform { TR_ID = 0, TR_SQRT, TR_NONZERO };
-enum NormKind { NORM_NONE = 0, NORM_SUMSQ, NORM_SUM_SUMSQ, NORM_SUM, NORM_SUM_ABS, NORM_SUM_POW, NORM_NNZ };
+enum NormKind {
+    NORM_NONE = 0, NORM_SUMSQ, NORM_SUM_SUMSQ, NORM_SUM, NORM_SUM_ABS, NORM_SUM_POW, NORM_NNZ,
+    NORM_SEMI            // NORM_SEMI + product id: the sum of product(t, 0), and the number of entries
+};
+// products and sums a semiring may be built from; the ids follow spd_product / spd_sum in include/spd.h
+enum SemiProduct { SP_TIMES = 0, SP_PLUS, SP_MIN, SP_MAX, SP_ABS_DIFF, SP_SQ_DIFF, SP_COUNT };
+enum SemiSum { SS_PLUS = 0, SS_MIN, SS_MAX, SS_COUNT };
 
 // metric ids follow spd_metric in include/spd.h
 enum MetricId {
     MT_INNER = 0, MT_COSINE, MT_L2, MT_CORRELATION, MT_JACCARD, MT_DICE, MT_HELLINGER, MT_L1,
     MT_CHEBYSHEV, MT_MINKOWSKI, MT_CANBERRA, MT_HAMMING, MT_KL, MT_JS, MT_RUSSELL_RAO,
-    MT_L2_UNEXPANDED, MT_KL_STRICT, MT_JACCARD_LITERAL, MT_COUNT
+    MT_L2_UNEXPANDED, MT_KL_STRICT, MT_JACCARD_LITERAL, MT_COUNT,
+    // not in spd_metric: what the semiring entry points run as
+    MT_SEMI_SUM = MT_COUNT,   // sum() = +
+    MT_SEMI_EXT               // sum() = min or max
 };
 
 struct MetricInfo { int op, transform, norm; };
@@ -60,6 +72,8 @@ SPD_HD constexpr MetricInfo metric_info(int metric) {
     case MT_L2_UNEXPANDED:   return {OP_MINK, TR_ID, NORM_SUM_POW};      // Minkowski with p fixed at 2
     case MT_KL_STRICT:       return {OP_KL, TR_ID, NORM_NNZ};            // the row's entries must all be met
     case MT_JACCARD_LITERAL: return {OP_DOT, TR_ID, NORM_NNZ};
+    case MT_SEMI_SUM:        return {OP_SEMI_SUM, TR_ID, NORM_SEMI};     // the caller adds the product id
+    case MT_SEMI_EXT:        return {OP_SEMI_EXT, TR_ID, NORM_NONE};
     default:             return {-1, 0, 0};
     }
 }
@@ -69,6 +83,10 @@ struct OpParams {
     float inv_p;
     double k;       // number of columns
     int metric;
+    // semirings
+    int product = 0;      // SemiProduct
+    int over_union = 0;   // 1: product() over the union of the stored columns, the missing side read as 0
+    float sign = 1.0f;    // sum() = min is carried as the max of the negated products
 };
 
 // log2, exp2 and x/y as the kernels use them: the hardware's transcendental units on the device
@@ -117,6 +135,34 @@ SPD_HD float pow_abs(float v, float p) {
     return a == 0.0f ? 0.0f : fast_exp2(p * fast_log2(a));
 }
 
+// product() of a semiring, in the type it is accumulated in.
+template <int P, typename T> SPD_HD T semi_product(T a, T b) {
+    if constexpr (P == SP_TIMES) return a * b;
+    else if constexpr (P == SP_PLUS) return a + b;
+    else if constexpr (P == SP_MIN) return a < b ? a : b;
+    else if constexpr (P == SP_MAX) return a > b ? a : b;
+    else if constexpr (P == SP_ABS_DIFF) return a > b ? a - b : b - a;
+    else { T d = a - b; return d * d; }
+}
+template <int P> struct ProductTag { static constexpr int value = P; };
+// Calls f(ProductTag<p>) for the product id `product`.
+template <typename F> SPD_HD void for_product(int product, F &&f) {
+    switch (product) {
+    case SP_TIMES: f(ProductTag<SP_TIMES>{}); break;
+    case SP_PLUS: f(ProductTag<SP_PLUS>{}); break;
+    case SP_MIN: f(ProductTag<SP_MIN>{}); break;
+    case SP_MAX: f(ProductTag<SP_MAX>{}); break;
+    case SP_ABS_DIFF: f(ProductTag<SP_ABS_DIFF>{}); break;
+    case SP_SQ_DIFF: f(ProductTag<SP_SQ_DIFF>{}); break;
+    default: break;
+    }
+}
+template <typename T> SPD_HD T semi_product_of(int product, T a, T b) {
+    T out = (T)0;
+    for_product(product, [&](auto tag) { out = semi_product<decltype(tag)::value, T>(a, b); });
+    return out;
+}
+
 SPD_HD float transform_value(int tr, float v) {
     if (tr == TR_SQRT) return sqrtf(v);
     if (tr == TR_NONZERO) return v != 0.0f ? 1.0f : 0.0f;
@@ -133,7 +179,9 @@ SPD_HD void norm_accumulate(int norm, float t, float p, double &s0, double &s1) 
     case NORM_SUM_ABS:   s0 += fabs(d); break;
     case NORM_SUM_POW:   s0 += (double)pow_abs(t, p); s1 += (t != 0.0f) ? 1.0 : 0.0; break;
     case NORM_NNZ:       s0 += (t != 0.0f) ? 1.0 : 0.0; break;
-    default: break;
+    default:
+        if (norm >= NORM_SEMI && t != 0.0f) { s0 += semi_product_of<double>(norm - NORM_SEMI, d, 0.0); s1 += 1.0; }
+        break;
     }
 }
 
@@ -308,6 +356,71 @@ template <> struct Op<OP_CHEB> {
     SPD_HD static double v2(const Acc &) { return 0.0; }
 };
 
+// Semiring with sum() = + (Section 2.2).  Over the intersection the sum of product(a, b) is the
+// result.  Over the union (a non-annihilating product) the one-sided columns add product(a, 0)
+// and product(0, b): they come from the two rows' sums of product(., 0) minus `s`, the share of
+// those sums that falls on shared columns; `hits` counts the shared columns, so that two rows
+// with the same support leave exactly nothing (as for Minkowski).  Terms are formed in fp64:
+// products and sums of fp32 values are exact there.
+template <> struct Op<OP_SEMI_SUM> {
+    struct Acc { double d, s; int hits; };
+    struct Bv { float b; };
+    SPD_HD static void init(Acc &x) { x.d = 0.0; x.s = 0.0; x.hits = 0; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    template <int P> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &) {
+        const bool hit = (a != 0.0f) && (b.b != 0.0f);
+        const double da = (double)a, db = (double)b.b;
+        x.d += hit ? semi_product<P, double>(da, db) : 0.0;
+        x.s += hit ? semi_product<P, double>(da, 0.0) + semi_product<P, double>(0.0, db) : 0.0;
+        x.hits += hit ? 1 : 0;
+    }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
+        for_product(q.product, [&](auto tag) { visit_as<decltype(tag)::value>(x, a, b, q); });
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.d += y.d; x.s += y.s; x.hits += y.hits; }
+    SPD_HD static double v0(const Acc &x) { return x.d; }
+    SPD_HD static double v1(const Acc &x) { return x.s; }
+    SPD_HD static double v2(const Acc &x) { return (double)x.hits; }
+};
+
+// Semiring with sum() = max, or min as the max of the negated products (`sign`).  A column
+// takes part when both rows store it, or, over the union, when either does (a then may be 0);
+// what only x stores is completed by the kernel like Chebyshev's.  The product is formed in
+// fp32: rounding is monotone, so the maximum of the rounded terms is the rounded maximum.
+template <> struct Op<OP_SEMI_EXT> {
+    struct Acc { float m; };
+    struct Bv { float b; };
+    SPD_HD static void init(Acc &x) { x.m = -__builtin_huge_valf(); }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    template <int P> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &q) {
+        const bool in_a = a != 0.0f, in_b = b.b != 0.0f;
+        const bool take = q.over_union ? (in_a || in_b) : (in_a && in_b);
+        const float v = q.sign * semi_product<P, float>(a, b.b);
+        x.m = take ? fmaxf(x.m, v) : x.m;
+    }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
+        for_product(q.product, [&](auto tag) { visit_as<decltype(tag)::value>(x, a, b, q); });
+    }
+    SPD_HD static void combine(Acc &x, const Acc &y) { x.m = fmaxf(x.m, y.m); }
+    SPD_HD static double v0(const Acc &x) { return (double)x.m; }
+    SPD_HD static double v1(const Acc &) { return 0.0; }
+    SPD_HD static double v2(const Acc &) { return 0.0; }
+};
+
+// What a staged row's entry a would contribute in a column the other row does not store, as the
+// key the rows' largest such contributions are ranked by (Chebyshev: |a|).
+template <int OP> SPD_HD float one_sided_key(float a, const OpParams &q) {
+    if constexpr (OP == OP_SEMI_EXT) return q.sign * semi_product_of<float>(q.product, a, 0.0f);
+    else return fabsf(a);
+}
+
+// One visit, with the product of a semiring known at compile time (P is ignored otherwise).
+template <int OP, int P> SPD_HD void visit_with(typename Op<OP>::Acc &x, float a, const typename Op<OP>::Bv &b,
+                                                const OpParams &q) {
+    if constexpr (OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) Op<OP>::template visit_as<P>(x, a, b, q);
+    else Op<OP>::visit(x, a, b, q);
+}
+
 // Expansion function (Table 1, "Expansion" column, and the closing steps of the union
 // family).  v, s, w: the accumulated sums; a0,a1 / b0,b1: derived norms of the two rows.
 // The metric is a template argument so that a kernel can pick the formula once per slab
@@ -367,6 +480,13 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
         return sqrtf((float)(t > 0.0 ? t : 0.0));
     } else if constexpr (MT == MT_RUSSELL_RAO) {
         return (float)((q.k - v) / q.k);
+    } else if constexpr (MT == MT_SEMI_SUM) {
+        // v: products on shared columns, s: what those columns hold of the two rows' sums of
+        // product(., 0), w: how many they are; a1 / b1 count the entries of the rows
+        if (!q.over_union) return (float)v;
+        return (float)(v + ((w == a1 && w == b1) ? 0.0 : (a0 + b0) - s));
+    } else if constexpr (MT == MT_SEMI_EXT) {
+        return (float)((double)q.sign * v);
     } else {
         return 0.0f;
     }
@@ -389,6 +509,7 @@ template <int OP, typename F> SPD_HD void for_metric_of(int metric, F &&f) {
         SPD_CASE(MT_DICE) SPD_CASE(MT_HELLINGER) SPD_CASE(MT_L1) SPD_CASE(MT_CHEBYSHEV) SPD_CASE(MT_MINKOWSKI)
         SPD_CASE(MT_CANBERRA) SPD_CASE(MT_HAMMING) SPD_CASE(MT_KL) SPD_CASE(MT_JS) SPD_CASE(MT_RUSSELL_RAO)
         SPD_CASE(MT_L2_UNEXPANDED) SPD_CASE(MT_KL_STRICT) SPD_CASE(MT_JACCARD_LITERAL)
+        SPD_CASE(MT_SEMI_SUM) SPD_CASE(MT_SEMI_EXT)
     default: break;
     }
 #undef SPD_CASE
@@ -402,6 +523,7 @@ SPD_HD float finish(const OpParams &q, double v, double s, double w, double a0, 
         SPD_CASE(MT_DICE) SPD_CASE(MT_HELLINGER) SPD_CASE(MT_L1) SPD_CASE(MT_CHEBYSHEV) SPD_CASE(MT_MINKOWSKI)
         SPD_CASE(MT_CANBERRA) SPD_CASE(MT_HAMMING) SPD_CASE(MT_KL) SPD_CASE(MT_JS) SPD_CASE(MT_RUSSELL_RAO)
         SPD_CASE(MT_L2_UNEXPANDED) SPD_CASE(MT_KL_STRICT) SPD_CASE(MT_JACCARD_LITERAL)
+        SPD_CASE(MT_SEMI_SUM) SPD_CASE(MT_SEMI_EXT)
 #undef SPD_CASE
     default: return 0.0f;
     }

@@ -229,10 +229,10 @@ bool staging_fits(int kind, int R, uint64_t sumlen, uint32_t k, bool cheb, int64
 
 std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const PlanOptions &opt, int &kind, int &max_r,
                          int &min_r, uint64_t &dmax) {
-    const bool cheb = metric == MT_CHEBYSHEV;
+    const bool cheb = sum_is_max(metric);
     const uint32_t k = (uint32_t)n_cols;
     max_r = std::min(opt.max_rows, 16);
-    if (metric == MT_JS || metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED) max_r = std::min(max_r, 8);   // two fp64 sums per pair
+    if (wide_sums(metric)) max_r = std::min(max_r, 8);   // two fp64 sums per pair
     if (max_r < 1) max_r = 1;
     while (max_r & (max_r - 1)) max_r &= max_r - 1;         // power of two
     min_r = 1;
@@ -287,7 +287,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     if (n_rows && indptr[0] != 0) return "indptr[0] != 0";
     for (int64_t i = 0; i < n_rows; ++i)
         if (indptr[i + 1] < indptr[i]) return fmt("row pointers decrease at row", i);
-    const bool cheb = metric == MT_CHEBYSHEV;
+    const bool cheb = sum_is_max(metric);
     const uint32_t k = (uint32_t)n_cols;
     int kind = 0, max_r = 1, min_r = 1;
     uint64_t dmax = 0;
@@ -423,7 +423,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
 // ------------------------------------------------------------------------------------
 std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, const int64_t *b_indptr,
                        int64_t n_cols, int metric, int op, int knn_k, const PlanOptions &opt) {
-    const bool cheb = metric == MT_CHEBYSHEV;
+    const bool cheb = sum_is_max(metric);
     const int64_t a_nnz = a.n_rows ? a_indptr[a.n_rows] : 0;
     std::vector<int64_t> covered((size_t)a.n_rows, 0);
     std::vector<int64_t> slot_lo((size_t)a.n_partial_slots, -1), slot_hi((size_t)a.n_partial_slots, -1);
@@ -431,7 +431,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
     for (const AClass &c : a.classes) {
         if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16 && c.R != 32) return "class R";
         if (op == OP_CNT ? (c.R < 4 || (knn_k > 0 && c.R > 16)) : c.R > 16) return "class R outside the product's range";
-        if ((metric == MT_JS || metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED) && c.R > 8) return "two-sum product with R > 8";
+        if (wide_sums(metric) && c.R > 8) return "two-sum product with R > 8";
         if (c.kind < KIND_STRIP || c.kind > KIND_HASH) return "class kind";
         if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";
         if ((int64_t)c.lds_bytes + kStaticLds > opt.lds_budget) return "class LDS over budget";

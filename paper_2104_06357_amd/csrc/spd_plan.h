@@ -35,7 +35,7 @@ constexpr int kScanUnroll = 4;              // a slab is scanned in blocks of th
 constexpr int kMaxR = 32;                   // 32 only for the set metrics (one byte per staged row)
 constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
 constexpr int kKnnMaxK = 64;                // fused k-NN: one list entry per lane
-constexpr int kTopRanks = 32;               // Chebyshev: largest entries tracked per staged row
+constexpr int kTopRanks = 32;               // sum() = max: largest one-sided contributions tracked per staged row
 constexpr uint32_t kStaticLds = 4096;       // upper bound of the kernels' static __shared__ use
 
 struct PlanOptions {
@@ -63,14 +63,23 @@ inline int split_len_for(const PlanOptions &opt, int64_t nnz_b) {
 
 // Sums a pair carries through the slices of a spilled row.
 SPD_HD constexpr int metric_planes(int metric) {
-    return (metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED) ? 3 : ((metric == MT_JS || metric == MT_KL_STRICT) ? 2 : 1);
+    return (metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED || metric == MT_SEMI_SUM)
+               ? 3 : ((metric == MT_JS || metric == MT_KL_STRICT) ? 2 : 1);
+}
+
+// Metrics whose sum() is a maximum: a staged row's largest one-sided contributions are ranked
+// beside the value table, and the slices of a spilled row are joined by max.
+SPD_HD constexpr bool sum_is_max(int metric) { return metric == MT_CHEBYSHEV || metric == MT_SEMI_EXT; }
+// Products that carry two fp64 sums (or more) per pair: at most 8 rows are staged together.
+SPD_HD constexpr bool wide_sums(int metric) {
+    return metric == MT_JS || metric == MT_MINKOWSKI || metric == MT_L2_UNEXPANDED || metric == MT_SEMI_SUM || metric == MT_SEMI_EXT;
 }
 
 // Largest workgroup a scan kernel instance may be launched with: the instances that carry
 // the most per-lane state get 256 registers per lane instead of 128.
 SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
     if (op == OP_CNT) return (knn && R >= 16) ? 512 : 1024;
-    return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_MINK) && R == 8)) ? 512 : 1024;
+    return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_MINK || op == OP_SEMI_SUM || op == OP_SEMI_EXT) && R == 8)) ? 512 : 1024;
 }
 
 // Wavefronts per SIMD the compiler is asked to make room for (it bounds the registers per

@@ -13,6 +13,10 @@ hipError_t launch_scan_hamm(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_kl(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_js(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_cheb(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_semi_sum(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_semi_sum_knn(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_semi_ext(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_semi_ext_knn(hipStream_t, int, int, uint32_t, const ScanArgs &);
 
 hipError_t launch_scan(hipStream_t st, int op, int R, int block, uint32_t lds_bytes, const ScanArgs &args) {
     switch (op) {
@@ -29,6 +33,12 @@ hipError_t launch_scan(hipStream_t st, int op, int R, int block, uint32_t lds_by
     case OP_KL: return launch_scan_kl(st, R, block, lds_bytes, args);
     case OP_JS: return launch_scan_js(st, R, block, lds_bytes, args);
     case OP_CHEB: return launch_scan_cheb(st, R, block, lds_bytes, args);
+    case OP_SEMI_SUM:
+        return args.knn_k > 0 ? launch_scan_semi_sum_knn(st, R, block, lds_bytes, args)
+                              : launch_scan_semi_sum(st, R, block, lds_bytes, args);
+    case OP_SEMI_EXT:
+        return args.knn_k > 0 ? launch_scan_semi_ext_knn(st, R, block, lds_bytes, args)
+                              : launch_scan_semi_ext(st, R, block, lds_bytes, args);
     default: return hipErrorInvalidValue;
     }
 }

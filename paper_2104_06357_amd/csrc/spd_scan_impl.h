@@ -188,8 +188,12 @@ SPD_ACC_SHFL1(OP_CANB, v)
 SPD_ACC_SHFL1(OP_HAMM, c)
 SPD_ACC_SHFL1(OP_CNT, c)
 SPD_ACC_SHFL1(OP_CHEB, m)
+SPD_ACC_SHFL1(OP_SEMI_EXT, m)
 template <> __device__ __forceinline__ Op<OP_MINK>::Acc acc_shfl_xor<OP_MINK>(const Op<OP_MINK>::Acc &a, int m) {
     Op<OP_MINK>::Acc r; r.d = __shfl_xor(a.d, m); r.s = __shfl_xor(a.s, m); r.hits = __shfl_xor(a.hits, m); return r;
+}
+template <> __device__ __forceinline__ Op<OP_SEMI_SUM>::Acc acc_shfl_xor<OP_SEMI_SUM>(const Op<OP_SEMI_SUM>::Acc &a, int m) {
+    Op<OP_SEMI_SUM>::Acc r; r.d = __shfl_xor(a.d, m); r.s = __shfl_xor(a.s, m); r.hits = __shfl_xor(a.hits, m); return r;
 }
 template <> __device__ __forceinline__ Op<OP_KL>::Acc acc_shfl_xor<OP_KL>(const Op<OP_KL>::Acc &a, int m) {
     Op<OP_KL>::Acc r; r.v = __shfl_xor(a.v, m); r.hits = __shfl_xor(a.hits, m); return r;
@@ -282,7 +286,10 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     __attribute__((amdgpu_waves_per_eu(scan_min_waves(OP, R, KIND, KNN)))) spd_scan_kernel(const ScanArgs args) {
     using O = Op<OP>;
     using Acc = typename O::Acc;
-    constexpr bool kCheb = (OP == OP_CHEB);
+    // sum() = max: a column that only the staged row stores still counts, and is completed from
+    // the row's ranked entries (Chebyshev, and the semirings whose sum() is min or max)
+    constexpr bool kCheb = (OP == OP_CHEB || OP == OP_SEMI_EXT);
+    constexpr bool kSemi = (OP == OP_SEMI_SUM || OP == OP_SEMI_EXT);   // product() picked at run time
     constexpr bool kCnt = (OP == OP_CNT);          // set metrics: one byte of the table per staged row
     constexpr int W = table_words(OP, R);          // 4-byte words per slot of the value table
     static_assert(!kCnt || (R % 4 == 0), "byte counters come four to the word");
@@ -508,31 +515,35 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     __syncthreads();
 
     if constexpr (kCheb) {
-        // The kTopRanks largest |values| of each staged row, in order, and their ranks
-        // beside the value table: what a row of B leaves unvisited is completed from them.
+        // The kTopRanks largest one-sided contributions (Chebyshev: |values|) of each staged
+        // row, in order, and their ranks beside the value table: what a row of B leaves
+        // unvisited is completed from them.  A product over the intersection has none.
+        constexpr uint32_t kNone = 0xFFFFFFFFu;             // no column: columns stay below 2^31
+        const bool one_sided = (OP == OP_CHEB) || args.q.over_union != 0;
         for (int r = wave; r < R; r += nw) {
             const int64_t start = s_rows[r].start;
-            const int len = s_rows[r].len;
+            const int len = one_sided ? s_rows[r].len : 0;
             float prev_v = __builtin_huge_valf();
             uint32_t prev_c = 0u;
             bool first = true;
             int found = 0;
             for (int round = 0; round < kTopRanks; ++round) {
-                float best_v = -1.0f;
-                uint32_t best_c = 0xFFFFFFFFu;
+                float best_v = 0.0f;
+                uint32_t best_c = kNone;
                 for (int qi = lane; qi < len; qi += 64) {
-                    float v = fabsf(args.a_values[start + qi]);
+                    const float a = args.a_values[start + qi];
+                    const float v = one_sided_key<OP>(a, args.q);
                     uint32_t c = (uint32_t)args.a_indices[start + qi];
                     bool after_prev = first || v < prev_v || (v == prev_v && c > prev_c);
-                    bool better = v > best_v || (v == best_v && c < best_c);
-                    if (v > 0.0f && after_prev && better) { best_v = v; best_c = c; }
+                    bool better = best_c == kNone || v > best_v || (v == best_v && c < best_c);
+                    if (a != 0.0f && after_prev && better) { best_v = v; best_c = c; }
                 }
                 for (int m = 32; m >= 1; m >>= 1) {
                     float ov = __shfl_xor(best_v, m);
                     uint32_t oc = (uint32_t)__shfl_xor((int)best_c, m);
-                    if (ov > best_v || (ov == best_v && oc < best_c)) { best_v = ov; best_c = oc; }
+                    if (oc != kNone && (best_c == kNone || ov > best_v || (ov == best_v && oc < best_c))) { best_v = ov; best_c = oc; }
                 }
-                if (best_v <= 0.0f) break;
+                if (best_c == kNone) break;
                 if (lane == 0) {
                     s_top[r * kTopRanks + round] = best_v;
                     rank8[(size_t)cmap.lookup(best_c) * R + r] = (unsigned char)round;
@@ -602,18 +613,25 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             } else {
                 const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
                 const RowVals<R> a = load_vals<R>(vals, slot, L.nslots);
-                if constexpr (kCheb) {
-                    const unsigned char *rk = rank8 + (size_t)slot * R;
+                // (a semiring's product is a run-time choice: it is switched on once per step, not
+                // once per visit)
+                auto visit_rows = [&](auto product_tag) {
+                    constexpr int P = decltype(product_tag)::value;
+                    if constexpr (kCheb) {
+                        const unsigned char *rk = rank8 + (size_t)slot * R;
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        if (entry.x - s_clo[r] <= s_cspan[r]) O::visit(acc[r], a.v[r], bv, args.q);
-                        uint32_t q = rk[r];
-                        hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
+                        for (int r = 0; r < R; ++r) {
+                            if (entry.x - s_clo[r] <= s_cspan[r]) visit_with<OP, P>(acc[r], a.v[r], bv, args.q);
+                            uint32_t q = rk[r];
+                            hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < R; ++r) visit_with<OP, P>(acc[r], a.v[r], bv, args.q);
                     }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < R; ++r) O::visit(acc[r], a.v[r], bv, args.q);
-                }
+                };
+                if constexpr (kSemi) for_product(args.q.product, visit_rows);
+                else visit_rows(ProductTag<0>{});
             }
         };
         // Byte counters hold up to 255: they are folded into the pairs' 32-bit counts before a
@@ -714,7 +732,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                         const int topn = s_topn[r];
                         uint32_t tracked = topn >= 32 ? 0xFFFFFFFFu : ((1u << topn) - 1u);
                         uint32_t unhit = ~hit[r] & tracked;
-                        float extra = 0.0f;
+                        float extra = -__builtin_huge_valf();
                         if (unhit) {
                             extra = s_top[r * kTopRanks + __builtin_ctz(unhit)];
                         } else if (topn == kTopRanks) {
@@ -725,7 +743,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                             for (int64_t ai = a0; ai < a1; ++ai) {
                                 int32_t c = args.a_indices[ai];
                                 while (bj < be && args.b_indices[bj] < c) ++bj;
-                                if (bj >= be || args.b_indices[bj] != c) extra = fmaxf(extra, fabsf(args.a_values[ai]));
+                                const float av = args.a_values[ai];
+                                if ((bj >= be || args.b_indices[bj] != c) && av != 0.0f)
+                                    extra = fmaxf(extra, one_sided_key<OP>(av, args.q));
                             }
                         }
                         v0[i] = fmax(v0[i], (double)extra);
@@ -905,7 +925,7 @@ static hipError_t launch_scan_op(hipStream_t st, int R, int block, uint32_t lds_
         case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
         case 8: return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
         case 16:
-            if constexpr (OP == OP_JS || OP == OP_MINK) return hipErrorInvalidValue;
+            if constexpr (OP == OP_JS || OP == OP_MINK || OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) return hipErrorInvalidValue;
             else return launch_scan_r<OP, 16, WHICH>(st, block, lds_bytes, args);
         default: return hipErrorInvalidValue;
         }

@@ -61,7 +61,7 @@ def assert_knn_matches(idx, dist, oracle_rows, k, metric, what=""):
         diff = np.nonzero(idx[r] != order)[0]
         for t in diff:
             a, b = oracle_rows[r, idx[r, t]], oracle_rows[r, order[t]]
-            assert abs(a - b) <= 2.0 * max(REL_TOL * abs(b), ABS_TOL), \
+            assert a == b or abs(a - b) <= 2.0 * max(REL_TOL * abs(b), ABS_TOL), \
                 "%s: row %d position %d: index %d (%.9g) instead of %d (%.9g)" % (
                     what, r, t, idx[r, t], a, order[t], b)
 
