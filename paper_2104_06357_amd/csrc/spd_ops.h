@@ -136,31 +136,60 @@ SPD_HD float pow_abs(float v, float p) {
 }
 
 // product() of a semiring, in the type it is accumulated in.
+SPD_HD float abs_of(float v) { return __builtin_fabsf(v); }
+SPD_HD double abs_of(double v) { return __builtin_fabs(v); }
+SPD_HD float min_of(float a, float b) { return __builtin_fminf(a, b); }
+SPD_HD double min_of(double a, double b) { return __builtin_fmin(a, b); }
+SPD_HD float max_of(float a, float b) { return __builtin_fmaxf(a, b); }
+SPD_HD double max_of(double a, double b) { return __builtin_fmax(a, b); }
 template <int P, typename T> SPD_HD T semi_product(T a, T b) {
     if constexpr (P == SP_TIMES) return a * b;
     else if constexpr (P == SP_PLUS) return a + b;
-    else if constexpr (P == SP_MIN) return a < b ? a : b;
-    else if constexpr (P == SP_MAX) return a > b ? a : b;
-    else if constexpr (P == SP_ABS_DIFF) return a > b ? a - b : b - a;
+    else if constexpr (P == SP_MIN) return min_of(a, b);
+    else if constexpr (P == SP_MAX) return max_of(a, b);
+    else if constexpr (P == SP_ABS_DIFF) return abs_of(a - b);
     else { T d = a - b; return d * d; }
 }
-template <int P> struct ProductTag { static constexpr int value = P; };
-// Calls f(ProductTag<p>) for the product id `product`.
-template <typename F> SPD_HD void for_product(int product, F &&f) {
+// A product and where it is applied (UNION: over the columns either row stores), as a type.
+template <int P, bool UNION = false> struct ProductTag {
+    static constexpr int value = P;
+    static constexpr bool over_union = UNION;
+};
+// Calls f(ProductTag<p, u>) for the product id `product` and the domain `over_union`.
+template <typename F> SPD_HD void for_product(int product, bool over_union, F &&f) {
+#define SPD_CASE(P) case P: if (over_union) f(ProductTag<P, true>{}); else f(ProductTag<P, false>{}); break;
     switch (product) {
-    case SP_TIMES: f(ProductTag<SP_TIMES>{}); break;
-    case SP_PLUS: f(ProductTag<SP_PLUS>{}); break;
-    case SP_MIN: f(ProductTag<SP_MIN>{}); break;
-    case SP_MAX: f(ProductTag<SP_MAX>{}); break;
-    case SP_ABS_DIFF: f(ProductTag<SP_ABS_DIFF>{}); break;
-    case SP_SQ_DIFF: f(ProductTag<SP_SQ_DIFF>{}); break;
+        SPD_CASE(SP_TIMES) SPD_CASE(SP_PLUS) SPD_CASE(SP_MIN) SPD_CASE(SP_MAX) SPD_CASE(SP_ABS_DIFF) SPD_CASE(SP_SQ_DIFF)
     default: break;
     }
+#undef SPD_CASE
 }
 template <typename T> SPD_HD T semi_product_of(int product, T a, T b) {
     T out = (T)0;
-    for_product(product, [&](auto tag) { out = semi_product<decltype(tag)::value, T>(a, b); });
+    for_product(product, false, [&](auto tag) { out = semi_product<decltype(tag)::value, T>(a, b); });
     return out;
+}
+
+// |v|^p with the degree known at compile time: DEG 1..4 are plain products, 0 is any other p.
+// pow_abs(v, p) == pow_abs_as<degree_class(p)>(v, p) bit for bit.
+template <int DEG> SPD_HD float pow_abs_as(float v, float p) {
+    float a = fabsf(v);
+    if constexpr (DEG == 1) return a;
+    else if constexpr (DEG == 2) return a * a;
+    else if constexpr (DEG == 3) return a * a * a;
+    else if constexpr (DEG == 4) { float q = a * a; return q * q; }
+    else return a == 0.0f ? 0.0f : fast_exp2(p * fast_log2(a));
+}
+SPD_HD int degree_class(float p) { return p == 1.0f ? 1 : (p == 2.0f ? 2 : (p == 3.0f ? 3 : (p == 4.0f ? 4 : 0))); }
+// Calls f(ProductTag<d>) for the class d of the Minkowski degree p.
+template <typename F> SPD_HD void for_degree(float p, F &&f) {
+    switch (degree_class(p)) {
+    case 1: f(ProductTag<1>{}); break;
+    case 2: f(ProductTag<2>{}); break;
+    case 3: f(ProductTag<3>{}); break;
+    case 4: f(ProductTag<4>{}); break;
+    default: f(ProductTag<0>{}); break;
+    }
 }
 
 SPD_HD float transform_value(int tr, float v) {
@@ -239,11 +268,14 @@ template <> struct Op<OP_MINK> {
     struct Bv { float b; double pwb; };
     SPD_HD static void init(Acc &x) { x.d = 0.0; x.s = 0.0; x.hits = 0; }
     SPD_HD static Bv prep(float b, const OpParams &q) { return {b, (double)pow_abs(b, q.p)}; }
-    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
+    template <int DEG> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &q) {
         bool hit = (a != 0.0f) && (b.b != 0.0f);
-        x.d += hit ? (double)pow_abs(a - b.b, q.p) : 0.0;
-        x.s += hit ? (double)pow_abs(a, q.p) + b.pwb : 0.0;
+        x.d += hit ? (double)pow_abs_as<DEG>(a - b.b, q.p) : 0.0;
+        x.s += hit ? (double)pow_abs_as<DEG>(a, q.p) + b.pwb : 0.0;
         x.hits += hit ? 1 : 0;
+    }
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
+        for_degree(q.p, [&](auto tag) { visit_as<decltype(tag)::value>(x, a, b, q); });
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.d += y.d; x.s += y.s; x.hits += y.hits; }
     SPD_HD static double v0(const Acc &x) { return x.d; }
@@ -367,15 +399,20 @@ template <> struct Op<OP_SEMI_SUM> {
     struct Bv { float b; };
     SPD_HD static void init(Acc &x) { x.d = 0.0; x.s = 0.0; x.hits = 0; }
     SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
-    template <int P> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &) {
-        const bool hit = (a != 0.0f) && (b.b != 0.0f);
-        const double da = (double)a, db = (double)b.b;
-        x.d += hit ? semi_product<P, double>(da, db) : 0.0;
-        x.s += hit ? semi_product<P, double>(da, 0.0) + semi_product<P, double>(0.0, db) : 0.0;
-        x.hits += hit ? 1 : 0;
+    template <int P, bool UNION> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &) {
+        // every product offered gives 0 at (0, 0): a column that one side does not store is
+        // silenced by clearing the other side's value, not by selecting among the fp64 results
+        const double da = (double)((b.b != 0.0f) ? a : 0.0f), db = (double)((a != 0.0f) ? b.b : 0.0f);
+        x.d += semi_product<P, double>(da, db);
+        if constexpr (UNION) {
+            x.s += semi_product<P, double>(da, 0.0) + semi_product<P, double>(0.0, db);
+            x.hits += ((a != 0.0f) && (b.b != 0.0f)) ? 1 : 0;
+        }
     }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
-        for_product(q.product, [&](auto tag) { visit_as<decltype(tag)::value>(x, a, b, q); });
+        for_product(q.product, q.over_union != 0, [&](auto tag) {
+            visit_as<decltype(tag)::value, decltype(tag)::over_union>(x, a, b, q);
+        });
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.d += y.d; x.s += y.s; x.hits += y.hits; }
     SPD_HD static double v0(const Acc &x) { return x.d; }
@@ -392,14 +429,16 @@ template <> struct Op<OP_SEMI_EXT> {
     struct Bv { float b; };
     SPD_HD static void init(Acc &x) { x.m = -__builtin_huge_valf(); }
     SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
-    template <int P> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &q) {
+    template <int P, bool UNION> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &q) {
         const bool in_a = a != 0.0f, in_b = b.b != 0.0f;
-        const bool take = q.over_union ? (in_a || in_b) : (in_a && in_b);
+        const bool take = UNION ? (in_a || in_b) : (in_a && in_b);
         const float v = q.sign * semi_product<P, float>(a, b.b);
-        x.m = take ? fmaxf(x.m, v) : x.m;
+        x.m = fmaxf(x.m, take ? v : -__builtin_huge_valf());
     }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
-        for_product(q.product, [&](auto tag) { visit_as<decltype(tag)::value>(x, a, b, q); });
+        for_product(q.product, q.over_union != 0, [&](auto tag) {
+            visit_as<decltype(tag)::value, decltype(tag)::over_union>(x, a, b, q);
+        });
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.m = fmaxf(x.m, y.m); }
     SPD_HD static double v0(const Acc &x) { return (double)x.m; }
@@ -414,10 +453,12 @@ template <int OP> SPD_HD float one_sided_key(float a, const OpParams &q) {
     else return fabsf(a);
 }
 
-// One visit, with the product of a semiring known at compile time (P is ignored otherwise).
-template <int OP, int P> SPD_HD void visit_with(typename Op<OP>::Acc &x, float a, const typename Op<OP>::Bv &b,
-                                                const OpParams &q) {
-    if constexpr (OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) Op<OP>::template visit_as<P>(x, a, b, q);
+// One visit, with the product and the domain of a semiring known at compile time (they are
+// ignored otherwise).
+template <int OP, int P, bool UNION>
+SPD_HD void visit_with(typename Op<OP>::Acc &x, float a, const typename Op<OP>::Bv &b, const OpParams &q) {
+    if constexpr (OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) Op<OP>::template visit_as<P, UNION>(x, a, b, q);
+    else if constexpr (OP == OP_MINK) Op<OP>::template visit_as<P>(x, a, b, q);     // P: the class of the degree
     else Op<OP>::visit(x, a, b, q);
 }
 

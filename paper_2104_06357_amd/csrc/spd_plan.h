@@ -86,7 +86,10 @@ SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
 // lane: 8 means at most 64).  The light pairwise instances run two workgroups of 16
 // wavefronts per compute unit that way.
 SPD_HD constexpr int scan_min_waves(int op, int R, int kind, bool knn) {
-    return (!knn && R <= 8 && kind != 3 /* KIND_HASH */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM)) ? 8 : 1;
+    if (!knn && R <= 8 && kind != 3 /* KIND_HASH */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM)) return 8;
+    // 128 registers: two workgroups of 8 wavefronts per compute unit
+    if (!knn && R == 8 && (op == OP_SEMI_SUM || op == OP_SEMI_EXT)) return 4;
+    return 1;
 }
 
 // Dynamic-LDS layout of one staged group.  The same function sizes the launch on the host

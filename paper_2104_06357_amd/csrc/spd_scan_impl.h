@@ -559,11 +559,16 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     // what the epilogue of every slab needs of the staged rows, once, in scalar registers
     int row_out[R];
     double row_na0[R], row_na1[R];
+    uint32_t row_clo[kCheb ? R : 1], row_cspan[kCheb ? R : 1];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         row_out[r] = wave_uniform(s_rows[r].out);
         row_na0[r] = wave_uniform_f64(s_na[r][0]);
         row_na1[r] = wave_uniform_f64(s_na[r][1]);
+        if constexpr (kCheb) {
+            row_clo[r] = (uint32_t)wave_uniform((int)s_clo[r]);
+            row_cspan[r] = (uint32_t)wave_uniform((int)s_cspan[r]);
+        }
     }
 
     // ---- scan: every wavefront takes slabs of the chunk until none is left -----------
@@ -613,24 +618,28 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             } else {
                 const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
                 const RowVals<R> a = load_vals<R>(vals, slot, L.nslots);
-                // (a semiring's product is a run-time choice: it is switched on once per step, not
-                // once per visit)
+                // (a semiring's product and Minkowski's degree are run-time choices: they are
+                // switched on once per step, not once per visit)
                 auto visit_rows = [&](auto product_tag) {
                     constexpr int P = decltype(product_tag)::value;
-                    if constexpr (kCheb) {
+                    constexpr bool kUnion = decltype(product_tag)::over_union;
+                    // (over the intersection a slice meets only its own columns and nothing is
+                    // one-sided: no range to check, no ranks to mark)
+                    if constexpr (kCheb && (kUnion || !kSemi)) {
                         const unsigned char *rk = rank8 + (size_t)slot * R;
 #pragma unroll
                         for (int r = 0; r < R; ++r) {
-                            if (entry.x - s_clo[r] <= s_cspan[r]) visit_with<OP, P>(acc[r], a.v[r], bv, args.q);
+                            if (entry.x - row_clo[r] <= row_cspan[r]) visit_with<OP, P, kUnion>(acc[r], a.v[r], bv, args.q);
                             uint32_t q = rk[r];
                             hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
                         }
                     } else {
 #pragma unroll
-                        for (int r = 0; r < R; ++r) visit_with<OP, P>(acc[r], a.v[r], bv, args.q);
+                        for (int r = 0; r < R; ++r) visit_with<OP, P, kUnion>(acc[r], a.v[r], bv, args.q);
                     }
                 };
-                if constexpr (kSemi) for_product(args.q.product, visit_rows);
+                if constexpr (kSemi) for_product(args.q.product, args.q.over_union != 0, visit_rows);
+                else if constexpr (OP == OP_MINK) for_degree(args.q.p, visit_rows);
                 else visit_rows(ProductTag<0>{});
             }
         };
@@ -715,9 +724,10 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         double nb0 = 0.0, nb1 = 0.0;
         if (leader) { nb0 = args.b.norms[(size_t)row * 2]; nb1 = args.b.norms[(size_t)row * 2 + 1]; }
 
-        // The rows are finished eight at a time (all at once would keep the sums and distances of
-        // up to 32 rows in registers together).
-        constexpr int RB = R < 8 ? R : (KNN && R >= 16 ? 4 : 8);
+        // The rows are finished eight at a time, or four (all at once would keep the sums and
+        // distances of up to 32 rows in registers together).
+        constexpr bool kThreeSums = (OP == OP_MINK || OP == OP_SEMI_SUM);
+        constexpr int RB = R < 8 ? R : ((KNN && R >= 16) || kThreeSums ? 4 : 8);
 #pragma unroll
         for (int r0 = 0; r0 < R; r0 += RB) {
             double v0[RB], v1[RB], v2[RB];
