@@ -36,7 +36,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--only", choices=("l1", "cosine", "knn"), default=None)
+    ap.add_argument("--only", choices=("l1", "cosine", "knn", "tropical", "l1_semiring"), default=None,
+                    help="time one call instead of the step; the last two are semiring calls, "
+                         "(min,+) over the intersection and (+,|x-y|) over the union, which are not part of the step")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true",
@@ -73,6 +75,8 @@ def main():
         "l1": lambda: h.pairwise(dA, dB, "l1", out=out),
         "cosine": lambda: h.pairwise(dA, dB, "cosine", out=out),
         "knn": lambda: h.knn(dA, dB, "cosine", 32, out_idx=idx, out_dist=dist),
+        "tropical": lambda: h.semiring_pairwise(dA, dB, "plus", "min", False, out=out),
+        "l1_semiring": lambda: h.semiring_pairwise(dA, dB, "abs_diff", "plus", True, out=out),
     }
     names = [args.only] if args.only else ["l1", "cosine", "knn"]
 
@@ -126,7 +130,9 @@ def main():
         # the same launch against the vector ALU: a visit (row of A x stored entry of B) cannot
         # cost less than the product's own instructions (L1: median, conversion, fp64 add;
         # dot: conversion, fp64 FMA), and the chip issues 78.6e12 / 2 fp64 lane-instructions/s
-        per_visit = 3 if name == "l1" else 2
+        # (semirings: compare, sign-flipped sum, select, max; the union sum: two masked conversions,
+        # three fp64 terms and their adds, the count)
+        per_visit = {"l1": 3, "tropical": 4, "l1_semiring": 9}.get(name, 2)
         visits = float(rec["a_rows"]) * nnz_b / (ms * 1e-3)
         alu_peak = ALU_LANE_OPS / per_visit
         alu = {"bound": "alu", "achieved": visits, "peak": alu_peak, "unit": "visits/s",

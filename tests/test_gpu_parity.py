@@ -67,6 +67,22 @@ def test_config0_every_staging_path(handle, config0, metric, kind, max_rows):
     assert_distances_close(got, want, "%s kind=%d R=%d" % (metric, kind, max_rows))
 
 
+@pytest.mark.parametrize("p", [0.5, 1.0, 1.5, 2.0, 2.5, 3.0, 4.0, 7.0])
+def test_minkowski_degrees(handle, spd, config0, p):
+    """Every class of degree the kernel specialises (1 runs as the Manhattan distance, 2 to 4 as
+    plain products, the rest through exp2/log2), on config 0 and on signed rows with slices."""
+    A, B, dA, dB = config0
+    print("minkowski p", p, flush=True)
+    assert_distances_close(_run_pairwise(handle, dA, dB, "minkowski", p),
+                           oracle.pairwise(A, B, "minkowski", p), "minkowski p=%g" % p)
+    A, B = _wide_pair(True)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    for name, value in (("split_len", 4), ("window", 64), ("force_kind", 3), ("lds_budget", 8192)):
+        handle.set_option(name, value)
+    assert_distances_close(_run_pairwise(handle, dA, dB, "minkowski", p),
+                           oracle.pairwise(A, B, "minkowski", p, mode="full"), "minkowski p=%g, slices" % p)
+
+
 def _wide_pair(signed):
     """Two small matrices over 400 columns whose rows have 0..400 entries."""
     rng = np.random.default_rng(77)
