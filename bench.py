@@ -31,6 +31,49 @@ def algorithmic_bytes(a_rows, nnz_b, n_b):
     return a_rows * (8.0 * nnz_b + 4.0 * n_b)
 
 
+def selfjoin(args):
+    """k-NN of a matrix against itself, batch by batch: every call is a whole spd_knn (planning
+    and repacking of the index included), the query rows a slice of the index's own arrays."""
+    import torch
+
+    import paper_2104_06357_amd as spd
+    from gen import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs an MI355X: no GPU is visible")
+    torch.cuda.set_device(0)
+    _, B = synth.workload(args.selfjoin)
+    n, k = B["n_rows"], 32
+    dB = spd.DeviceCsr.from_host(B)
+    h = spd.Handle()
+    idx = torch.empty((args.batch, k), dtype=torch.int64, device="cuda")
+    dist = torch.empty((args.batch, k), dtype=torch.float32, device="cuda")
+    starts = list(range(0, n, args.batch))
+    if args.max_batches > 0:
+        starts = starts[:args.max_batches]
+    tiles = []
+    for r0 in starts:                       # the slices are made before the clock starts
+        r1 = min(n, r0 + args.batch)
+        lo, hi = int(B["indptr"][r0]), int(B["indptr"][r1])
+        tiles.append(spd.DeviceCsr(r1 - r0, B["n_cols"], (dB.indptr[r0:r1 + 1] - lo).contiguous(),
+                                   dB.indices[lo:hi], dB.values[lo:hi]))
+    h.knn(tiles[0], dB, args.metric, k, out_idx=idx[:tiles[0].n_rows], out_dist=dist[:tiles[0].n_rows])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for q in tiles:
+        h.knn(q, dB, args.metric, k, out_idx=idx[:q.n_rows], out_dist=dist[:q.n_rows])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    rows = sum(q.n_rows for q in tiles)
+    print(json.dumps({
+        "metric": "self-join brute-force k-NN, row-pairs/s", "value": rows * float(n) / elapsed, "unit": "row-pairs/s",
+        "n_gpus": 1, "dtype": "f32", "data": "synthetic", "k": k, "distance": args.metric,
+        "config": {"workload": "shape %d self-join" % args.selfjoin, "rows": n, "n_cols": B["n_cols"],
+                   "nnz": int(B["indptr"][-1]), "batch": args.batch},
+        "query_rows_timed": rows, "calls": len(tiles), "seconds": elapsed, "ms_per_call": 1e3 * elapsed / len(tiles),
+        "seconds_for_all_rows": elapsed * n / rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,9 +86,18 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true",
                     help="keep every launch on one stream in the timed region too (for kernel traces)")
+    ap.add_argument("--selfjoin", type=int, choices=(2, 3, 4, 5, 6), default=None,
+                    help="instead of the step: brute-force k-NN (k = 32) of every row of a dataset-shaped "
+                         "synthetic matrix against the whole matrix, in batches of query rows (the protocol of "
+                         "the paper's Table 3); prints a JSON line of its own")
+    ap.add_argument("--metric", default="cosine", help="--selfjoin: the distance")
+    ap.add_argument("--batch", type=int, default=4096, help="--selfjoin: query rows per call")
+    ap.add_argument("--max-batches", type=int, default=0, help="--selfjoin: stop after this many calls (0: all rows)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (use --gpus 1)")
+    if args.selfjoin is not None:
+        return selfjoin(args)
 
     import numpy as np
     import torch
@@ -165,9 +217,9 @@ def main():
     }
     keys = {"l1": "roofline", "cosine": "roofline_cosine", "knn": "roofline_knn_cosine"}
     for name in names:
-        line[keys[name]] = roofline(name)
+        line[keys.get(name, "roofline_" + name)] = roofline(name)
     if "roofline" not in line:
-        line["roofline"] = line[keys[names[0]]]
+        line["roofline"] = line[keys.get(names[0], "roofline_" + names[0])]
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
