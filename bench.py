@@ -60,8 +60,13 @@ def selfjoin(args):
     h.knn(tiles[0], dB, args.metric, k, out_idx=idx[:tiles[0].n_rows], out_dist=dist[:tiles[0].n_rows])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for q in tiles:
-        h.knn(q, dB, args.metric, k, out_idx=idx[:q.n_rows], out_dist=dist[:q.n_rows])
+    if args.index:
+        ix = h.index_create(dB, args.metric)
+        for q in tiles:
+            ix.knn(q, k, out_idx=idx[:q.n_rows], out_dist=dist[:q.n_rows])
+    else:
+        for q in tiles:
+            h.knn(q, dB, args.metric, k, out_idx=idx[:q.n_rows], out_dist=dist[:q.n_rows])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     rows = sum(q.n_rows for q in tiles)
@@ -69,7 +74,8 @@ def selfjoin(args):
         "metric": "self-join brute-force k-NN, row-pairs/s", "value": rows * float(n) / elapsed, "unit": "row-pairs/s",
         "n_gpus": 1, "dtype": "f32", "data": "synthetic", "k": k, "distance": args.metric,
         "config": {"workload": "shape %d self-join" % args.selfjoin, "rows": n, "n_cols": B["n_cols"],
-                   "nnz": int(B["indptr"][-1]), "batch": args.batch},
+                   "nnz": int(B["indptr"][-1]), "batch": args.batch,
+                   "calls": "spd_index_create + spd_index_knn" if args.index else "spd_knn"},
         "query_rows_timed": rows, "calls": len(tiles), "seconds": elapsed, "ms_per_call": 1e3 * elapsed / len(tiles),
         "seconds_for_all_rows": elapsed * n / rows}))
 
@@ -93,6 +99,8 @@ def main():
     ap.add_argument("--metric", default="cosine", help="--selfjoin: the distance")
     ap.add_argument("--batch", type=int, default=4096, help="--selfjoin: query rows per call")
     ap.add_argument("--max-batches", type=int, default=0, help="--selfjoin: stop after this many calls (0: all rows)")
+    ap.add_argument("--index", action="store_true",
+                    help="--selfjoin: prepare the matrix once with spd_index_create (timed too) and query that")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (use --gpus 1)")

@@ -42,6 +42,7 @@ extern "C" {
 #endif
 
 typedef struct spd_handle spd_handle;
+typedef struct spd_index spd_index;
 
 typedef struct {
     int64_t n_rows, n_cols, nnz;
@@ -119,6 +120,24 @@ spd_status spd_pairwise(spd_handle *handle, const spd_csr *A, const spd_csr *B, 
  * ordered by (distance, index) ascending: equal distances go to the lower index. */
 spd_status spd_knn(spd_handle *handle, const spd_csr *Q, const spd_csr *Index, spd_metric metric,
                    float p, int k, int64_t *out_idx, float *out_dist);
+
+/* An index: the second operand of a distance, prepared once for many calls (Section 4.2's
+ * protocol fits the whole dataset, then queries it batch by batch).  spd_index_create does what
+ * every spd_pairwise / spd_knn call does for B - reads its row pointers back, bins its rows by
+ * degree, repacks it and sums its row norms for `metric` (`p`: SPD_MINKOWSKI only) - into device
+ * memory the index owns (about 8 bytes per stored entry and 40 per row); spd_index_pairwise /
+ * spd_index_knn then return exactly what spd_pairwise / spd_knn return for the same operands.
+ * The index keeps the pointers of `Index`, not a copy: the three arrays must stay valid and
+ * unchanged until spd_index_destroy.  The work is enqueued on the creating handle's stream; use
+ * the index with that handle (or, after synchronising its stream, with another handle on the same
+ * device).  The planner options "split_len" and "window" are read at creation.
+ * spd_index_destroy waits for the handle's stream before it frees the memory. */
+spd_status spd_index_create(spd_handle *handle, const spd_csr *Index, spd_metric metric, float p,
+                            spd_index **index);
+spd_status spd_index_destroy(spd_handle *handle, spd_index *index);
+spd_status spd_index_pairwise(spd_handle *handle, const spd_csr *A, const spd_index *index, float *out);
+spd_status spd_index_knn(spd_handle *handle, const spd_csr *Q, const spd_index *index, int k,
+                         int64_t *out_idx, float *out_dist);
 
 /* Semirings (Section 2.2).  A value between two rows is the sum() fold of product(x_c, y_c) over
  * the columns c both rows store, when 0 annihilates the product (the dot-product semiring is

@@ -67,6 +67,10 @@ def lib():
         L.spd_knn.argtypes = [vp, csr_p, csr_p, i32, f32, i32, vp, vp]
         L.spd_semiring_pairwise.argtypes = [vp, csr_p, csr_p, ctypes.POINTER(SemiringStruct), vp]
         L.spd_semiring_knn.argtypes = [vp, csr_p, csr_p, ctypes.POINTER(SemiringStruct), i32, vp, vp]
+        L.spd_index_create.argtypes = [vp, csr_p, i32, f32, ctypes.POINTER(vp)]
+        L.spd_index_destroy.argtypes = [vp, vp]
+        L.spd_index_pairwise.argtypes = [vp, csr_p, vp, vp]
+        L.spd_index_knn.argtypes = [vp, csr_p, vp, i32, vp, vp]
         L.spd_csr_validate.argtypes = [vp, csr_p, i32]
         L.spd_set_option.argtypes = [vp, ctypes.c_char_p, i64]
         L.spd_last_error.argtypes = [vp]
@@ -80,7 +84,8 @@ def lib():
         L.spd_host_plan_summary.argtypes = [vp, i64, vp, i64, i64, i32, i32, ctypes.POINTER(ctypes.c_char_p),
                                             ctypes.POINTER(i64), i32, ctypes.c_char_p, ctypes.c_size_t]
         for fn in ("spd_create", "spd_destroy", "spd_workspace_bytes", "spd_set_workspace", "spd_pairwise",
-                   "spd_knn", "spd_semiring_pairwise", "spd_semiring_knn", "spd_csr_validate", "spd_set_option", "spd_host_pair_value",
+                   "spd_knn", "spd_semiring_pairwise", "spd_semiring_knn", "spd_index_create", "spd_index_destroy",
+                   "spd_index_pairwise", "spd_index_knn", "spd_csr_validate", "spd_set_option", "spd_host_pair_value",
                    "spd_host_plan_summary"):
             getattr(L, fn).restype = ctypes.c_int
         _lib = L
@@ -205,6 +210,13 @@ class Handle:
         return out_idx, out_dist
 
 
+    def index_create(self, Index: DeviceCsr, metric, p: float = 2.0) -> "Index":
+        """Prepares `Index` as the second operand of `metric` (spd_index_create)."""
+        ptr = ctypes.c_void_p()
+        s = Index.struct()
+        self._check(self._lib.spd_index_create(self._h, ctypes.byref(s), metric_id(metric), float(p), ctypes.byref(ptr)))
+        return Index_(self, ptr, Index)
+
     @staticmethod
     def _semiring(product, sum, over_union) -> SemiringStruct:
         prod = PRODUCTS.index(product) if isinstance(product, str) else int(product)
@@ -232,6 +244,48 @@ class Handle:
         self._check(self._lib.spd_semiring_knn(self._h, ctypes.byref(sa), ctypes.byref(sb), ctypes.byref(sr), int(k),
                                                out_idx.data_ptr() if out_idx.numel() else None,
                                                out_dist.data_ptr() if out_dist.numel() else None))
+        return out_idx, out_dist
+
+
+class Index_:
+    """spd_index: owned by the handle that made it; keeps the matrix's tensors alive."""
+
+    def __init__(self, handle: Handle, ptr, matrix: DeviceCsr):
+        self._handle, self._ptr, self.matrix = handle, ptr, matrix
+
+    def close(self):
+        if self._ptr and self._handle._h:
+            self._handle._lib.spd_index_destroy(self._handle._h, self._ptr)
+        self._ptr = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def pairwise(self, A: DeviceCsr, out=None):
+        import torch
+        h = self._handle
+        if out is None:
+            out = torch.empty((A.n_rows, self.matrix.n_rows), dtype=torch.float32, device=A.indptr.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        assert tuple(out.shape) == (A.n_rows, self.matrix.n_rows)
+        sa = A.struct()
+        h._check(h._lib.spd_index_pairwise(h._h, ctypes.byref(sa), self._ptr, out.data_ptr() if out.numel() else None))
+        return out
+
+    def knn(self, Q: DeviceCsr, k: int, out_idx=None, out_dist=None):
+        import torch
+        h = self._handle
+        if out_idx is None:
+            out_idx = torch.empty((Q.n_rows, k), dtype=torch.int64, device=Q.indptr.device)
+        if out_dist is None:
+            out_dist = torch.empty((Q.n_rows, k), dtype=torch.float32, device=Q.indptr.device)
+        sa = Q.struct()
+        h._check(h._lib.spd_index_knn(h._h, ctypes.byref(sa), self._ptr, int(k),
+                                      out_idx.data_ptr() if out_idx.numel() else None,
+                                      out_dist.data_ptr() if out_dist.numel() else None))
         return out_idx, out_dist
 
 

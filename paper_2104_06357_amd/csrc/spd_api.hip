@@ -104,6 +104,19 @@ struct spd_handle {
     std::vector<int32_t> knn_row_lists;
 };
 
+// B of a distance, planned and repacked once (spd_index_create): the plan on the host, and on
+// the device the plan's arrays, the packed slabs and the row norms in one allocation.
+struct spd_index {
+    spd_csr matrix;              // the caller's arrays (they must stay valid and unchanged)
+    int metric = 0;
+    float p = 1.0f;
+    int device = 0;
+    BPlan plan;
+    void *dev = nullptr;
+    size_t dev_bytes = 0;
+    BDevice bd;
+};
+
 namespace {
 
 const char *const kMetricNames[SPD_METRIC_COUNT] = {
@@ -241,12 +254,93 @@ struct Upload {
 
 size_t workspace_bound(const spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, int k_neighbors);
 
-// `metric` is a spd_metric, or, with `semiring` set, the internal id its sum() runs as.
+// Where B's plan, its packed slabs and its norms sit in a device buffer: the plan's arrays first,
+// contiguous, so that one copy moves them.
+struct BLayout {
+    size_t slab_base, slab_steps, slab_split, seg_start, seg_len, seg_row, seg_glog, plan_end, packed, norms, end;
+};
+
+BLayout layout_b(const BPlan &bp, int64_t n, Carver &cv) {
+    const size_t lanes = (size_t)bp.n_slabs * kWave;
+    BLayout L;
+    L.slab_base = cv.take(bp.slab_base.size() * 8);
+    L.slab_steps = cv.take(bp.slab_steps.size() * 4);
+    L.slab_split = cv.take(bp.slab_split.size());
+    L.seg_start = cv.take(lanes * 8);
+    L.seg_len = cv.take(lanes * 4);
+    L.seg_row = cv.take(lanes * 4);
+    L.seg_glog = cv.take(lanes);
+    L.plan_end = cv.off;
+    L.packed = cv.take((size_t)bp.slab_base[(size_t)bp.n_slabs] * 8);
+    L.norms = cv.take((size_t)n * 16);
+    L.end = cv.off;
+    return L;
+}
+
+// Copies B's plan through the pinned buffer at `pin` into the device buffer `dev` (laid out by
+// `L`) and starts the repack there.  Everything is enqueued on the handle's stream.
+spd_status stage_b_into(spd_handle *h, const spd_csr *B, const BPlan &bp, const BLayout &L, unsigned char *dev,
+                        unsigned char *pin, int metric, const MetricInfo &mi, const OpParams &q, uint32_t padcol,
+                        BDevice &bd) {
+    const size_t lanes = (size_t)bp.n_slabs * kWave;
+    auto put = [&](size_t off, const void *src, size_t bytes) { if (bytes) std::memcpy(pin + off, src, bytes); };
+    put(L.slab_base, bp.slab_base.data(), bp.slab_base.size() * 8);
+    put(L.slab_steps, bp.slab_steps.data(), bp.slab_steps.size() * 4);
+    put(L.slab_split, bp.slab_split.data(), bp.slab_split.size());
+    put(L.seg_start, bp.seg_start.data(), lanes * 8);
+    put(L.seg_len, bp.seg_len.data(), lanes * 4);
+    put(L.seg_row, bp.seg_row.data(), lanes * 4);
+    put(L.seg_glog, bp.seg_glog.data(), lanes);
+    if (L.plan_end) {
+        hipError_t err = hipMemcpyAsync(dev, pin, L.plan_end, hipMemcpyHostToDevice, h->stream);
+        if (err != hipSuccess) return hip_fail(h, err, "upload of B's plan");
+    }
+    bd.packed = reinterpret_cast<const uint2 *>(dev + L.packed);
+    bd.slab_base = reinterpret_cast<const int64_t *>(dev + L.slab_base);
+    bd.slab_steps = reinterpret_cast<const int32_t *>(dev + L.slab_steps);
+    bd.slab_split = dev + L.slab_split;
+    bd.seg_start = reinterpret_cast<const int64_t *>(dev + L.seg_start);
+    bd.seg_len = reinterpret_cast<const int32_t *>(dev + L.seg_len);
+    bd.seg_row = reinterpret_cast<const int32_t *>(dev + L.seg_row);
+    bd.seg_glog = dev + L.seg_glog;
+    bd.norms = reinterpret_cast<const double *>(dev + L.norms);
+    bd.n_slabs = bp.n_slabs;
+    bd.n_rows = B->n_rows;
+    LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, bp.n_slabs);
+    hipError_t err = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd, reinterpret_cast<uint2 *>(dev + L.packed),
+                                   reinterpret_cast<double *>(dev + L.norms), metric, mi.transform, mi.norm, q.p, q.k, padcol);
+    if (err != hipSuccess) return hip_fail(h, err, "pack kernel");
+    lt.done();
+    return SPD_OK;
+}
+
+// The parameters of a metric's product as the kernels read them.
+OpParams op_params(int metric, float p, int64_t n_cols, const spd_semiring *semiring) {
+    OpParams q;
+    q.p = p;
+    if (metric == SPD_L2_UNEXPANDED) q.p = 2.0f;
+    q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : (metric == SPD_L2_UNEXPANDED ? 0.5f : 1.0f);
+    q.k = (double)n_cols;
+    q.metric = metric;
+    if (metric != SPD_MINKOWSKI && metric != SPD_L2_UNEXPANDED) q.p = 1.0f;
+    if (semiring) {
+        q.product = (int)semiring->product;
+        q.over_union = semiring->over_union != 0;
+        q.sign = semiring->sum == SPD_SUM_MIN ? -1.0f : 1.0f;
+    }
+    return q;
+}
+
+// The metric a call runs as (Minkowski of degree 1 is the Manhattan distance, whose product is
+// a third of the work).
+int effective_metric(int metric, float p) { return (metric == SPD_MINKOWSKI && p == 1.0f) ? (int)SPD_L1 : metric; }
+
+// `metric` is a spd_metric, or, with `semiring` set, the internal id its sum() runs as.  With
+// `index` set, B is that index's matrix and its plan, packed slabs and norms are taken from it.
 spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, float p, const spd_semiring *semiring,
-               int knn_k, float *out, int64_t *out_idx, float *out_dist) {
+               int knn_k, float *out, int64_t *out_idx, float *out_dist, const spd_index *index = nullptr) {
     const int64_t m = A->n_rows, n = B->n_rows;
-    // Minkowski of degree 1 is the Manhattan distance, whose product is a third of the work
-    if (metric == SPD_MINKOWSKI && p == 1.0f) metric = SPD_L1;
+    metric = effective_metric(metric, p);
     static const bool host_times = std::getenv("SPD_HOST_TIMES") != nullptr;
     auto now = [] { return std::chrono::steady_clock::now(); };
     auto t_begin = now();
@@ -263,30 +357,31 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     if (e != hipSuccess) return hip_fail(h, e, "hipSetDevice");
 
     // ---- row pointers to the host ---------------------------------------------------
-    const bool same = A->indptr == B->indptr && m == n;
-    size_t ip_bytes = (size_t)(m + 1) * 8 + (same ? 0 : (size_t)(n + 1) * 8);
+    const bool same = !index && A->indptr == B->indptr && m == n;
+    const bool copy_b = !index && !same;
+    size_t ip_bytes = (size_t)(m + 1) * 8 + (copy_b ? (size_t)(n + 1) * 8 : 0);
     // (sized for the two plan uploads as well, which follow the row pointers in the buffer)
-    spd_status st = ensure_pinned(h, ip_bytes + 32 * ((size_t)n + 4096) + 48 * ((size_t)m + 4096));
+    spd_status st = ensure_pinned(h, ip_bytes + (index ? 0 : 32 * ((size_t)n + 4096)) + 48 * ((size_t)m + 4096));
     if (st != SPD_OK) return st;
     int64_t *a_ip = reinterpret_cast<int64_t *>(h->pinned);
     int64_t *b_ip = same ? a_ip : a_ip + (m + 1);
     e = hipMemcpyAsync(a_ip, A->indptr, (size_t)(m + 1) * 8, hipMemcpyDeviceToHost, h->stream);
     if (e != hipSuccess) return hip_fail(h, e, "copy of A.indptr");
-    if (!same) {
+    if (copy_b) {
         e = hipMemcpyAsync(b_ip, B->indptr, (size_t)(n + 1) * 8, hipMemcpyDeviceToHost, h->stream);
         if (e != hipSuccess) return hip_fail(h, e, "copy of B.indptr");
     }
     e = hipStreamSynchronize(h->stream);
     if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
-    if (a_ip[m] != A->nnz || b_ip[n] != B->nnz) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
+    if (a_ip[m] != A->nnz || (!index && b_ip[n] != B->nnz)) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
     lap("indptr d2h");
 
     // ---- B first: plan it, upload its plan and start the repack, so that the device is
-    //      busy while the host plans A -----------------------------------------------------
+    //      busy while the host plans A (an index brings all of that with it) ---------------
     MetricInfo mi = metric_info(metric);
     if (semiring && mi.norm == NORM_SEMI) mi.norm = NORM_SEMI + (int)semiring->product;
     APlan &ap = h->plan_of_a;
-    BPlan &bp = h->plan_of_b;
+    const BPlan &bp = index ? index->plan : h->plan_of_b;
     // the set metrics count shared columns in byte lanes, or (option) as a dot product of 0/1 values
     int op = mi.op;
     if (op == OP_CNT && h->no_byte_counters) op = OP_DOT;
@@ -303,52 +398,28 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         });
     }
     struct WaitForHelper { Helper &w; ~WaitForHelper() { w.wait(); } } wait_for_helper{h->helper};
-    std::string why = plan_b(b_ip, n, h->opt, bp);
-    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
-    lap("plan b");
+    std::string why;
+    if (!index) {
+        why = plan_b(b_ip, n, h->opt, h->plan_of_b);
+        if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
+        lap("plan b");
+    }
     int a_kind = 0, a_max_r = 1, a_min_r = 1;
     uint64_t a_dmax = 0;
     why = plan_staging(A->n_cols, metric, op, knn_k > 0, h->opt, a_kind, a_max_r, a_min_r, a_dmax);
     if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "A: " + why);
-    // every launch of a call stages the same way: one pad column serves them all
-    const uint32_t padcol = a_kind == KIND_HASH ? kEmptyKey : (uint32_t)A->n_cols;
-    OpParams q;
-    q.p = p;
-    if (metric == SPD_L2_UNEXPANDED) q.p = 2.0f;
-    q.inv_p = (metric == SPD_MINKOWSKI) ? 1.0f / p : (metric == SPD_L2_UNEXPANDED ? 0.5f : 1.0f);
-    q.k = (double)A->n_cols;
-    q.metric = metric;
-    if (metric != SPD_MINKOWSKI && metric != SPD_L2_UNEXPANDED) q.p = 1.0f;
-    if (semiring) {
-        q.product = (int)semiring->product;
-        q.over_union = semiring->over_union != 0;
-        q.sign = semiring->sum == SPD_SUM_MIN ? -1.0f : 1.0f;
-    }
+    // The column an idle lane looks up: no row stores it, so every kind of map sends it to the
+    // table's zero row.
+    const uint32_t padcol = (uint32_t)A->n_cols;
+    const OpParams q = op_params(metric, p, A->n_cols, semiring);
 
     const int planes = metric_planes(metric);
-    const size_t lanes = (size_t)bp.n_slabs * kWave;
     Carver cv;
-    // (1) B's plan, contiguous so that one copy moves it, then what the repack produces
-    Upload up_b;
-    const size_t o_slab_base = cv.take(bp.slab_base.size() * 8);
-    const size_t o_slab_steps = cv.take(bp.slab_steps.size() * 4);
-    const size_t o_slab_split = cv.take(bp.slab_split.size());
-    const size_t o_seg_start = cv.take(lanes * 8);
-    const size_t o_seg_len = cv.take(lanes * 4);
-    const size_t o_seg_row = cv.take(lanes * 4);
-    const size_t o_seg_glog = cv.take(lanes);
-    up_b.add(o_slab_base, bp.slab_base.data(), bp.slab_base.size() * 8);
-    up_b.add(o_slab_steps, bp.slab_steps.data(), bp.slab_steps.size() * 4);
-    up_b.add(o_slab_split, bp.slab_split.data(), bp.slab_split.size());
-    up_b.add(o_seg_start, bp.seg_start.data(), lanes * 8);
-    up_b.add(o_seg_len, bp.seg_len.data(), lanes * 4);
-    up_b.add(o_seg_row, bp.seg_row.data(), lanes * 4);
-    up_b.add(o_seg_glog, bp.seg_glog.data(), lanes);
-    const size_t b_plan_end = cv.off;
-    const size_t o_packed = cv.take((size_t)bp.slab_base[(size_t)bp.n_slabs] * 8);
-    const size_t o_norms = cv.take((size_t)n * 16);
+    // (1) B's plan, then what the repack produces (none of it with an index)
+    BLayout bl{};
+    if (!index) bl = layout_b(bp, n, cv);
     const size_t b_end = cv.off;
-    {
+    if (!index) {
         // room for A's part as well, from the documented bound, so that the scratch does not
         // have to move once the repack has been started (checked again below)
         size_t guess = 0;
@@ -358,7 +429,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     }
     // pinned staging: [row pointers | B's plan | A's plan]
     const size_t pin_b = align256(ip_bytes);
-    const size_t pin_a = pin_b + align256(b_plan_end);
+    const size_t pin_a = pin_b + align256(bl.plan_end);
     if (h->pinned_bytes < pin_a + (size_t)m * (sizeof(ARow) + 16) + (64 << 10)) {
         // growing the pinned buffer moves it: let the helper finish reading, keep the row pointers
         h->helper.wait();
@@ -372,35 +443,16 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     }
     BDevice bd;
     auto stage_b = [&]() -> spd_status {
-        unsigned char *ws = reinterpret_cast<unsigned char *>(h->ws);
-        unsigned char *pin = reinterpret_cast<unsigned char *>(h->pinned) + pin_b;
-        for (auto &pt : up_b.parts) std::memcpy(pin + pt.first, pt.second.first, pt.second.second);
-        if (b_plan_end) {
-            hipError_t err = hipMemcpyAsync(ws, pin, b_plan_end, hipMemcpyHostToDevice, h->stream);
-            if (err != hipSuccess) return hip_fail(h, err, "upload of B's plan");
-        }
-        bd.packed = reinterpret_cast<const uint2 *>(ws + o_packed);
-        bd.slab_base = reinterpret_cast<const int64_t *>(ws + o_slab_base);
-        bd.slab_steps = reinterpret_cast<const int32_t *>(ws + o_slab_steps);
-        bd.slab_split = ws + o_slab_split;
-        bd.seg_start = reinterpret_cast<const int64_t *>(ws + o_seg_start);
-        bd.seg_len = reinterpret_cast<const int32_t *>(ws + o_seg_len);
-        bd.seg_row = reinterpret_cast<const int32_t *>(ws + o_seg_row);
-        bd.seg_glog = ws + o_seg_glog;
-        bd.norms = reinterpret_cast<const double *>(ws + o_norms);
-        bd.n_slabs = bp.n_slabs;
-        bd.n_rows = n;
-        LaunchTimer lt(h, "pack_b", 0, 0, 0, 0, 0, bp.n_slabs);
-        hipError_t err = launch_pack_b(h->stream, B->indptr, B->indices, B->values, bd,
-                                       reinterpret_cast<uint2 *>(ws + o_packed), reinterpret_cast<double *>(ws + o_norms),
-                                       metric, mi.transform, mi.norm, q.p, q.k, padcol);
-        if (err != hipSuccess) return hip_fail(h, err, "pack kernel");
-        lt.done();
-        return SPD_OK;
+        return stage_b_into(h, B, bp, bl, reinterpret_cast<unsigned char *>(h->ws),
+                            reinterpret_cast<unsigned char *>(h->pinned) + pin_b, metric, mi, q, padcol, bd);
     };
-    st = stage_b();
-    if (st != SPD_OK) return st;
-    lap("stage b");
+    if (index) {
+        bd = index->bd;
+    } else {
+        st = stage_b();
+        if (st != SPD_OK) return st;
+        lap("stage b");
+    }
 
     // ---- A, while the repack runs -------------------------------------------------------
     h->helper.wait();
@@ -410,7 +462,17 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
     lap("chunks");
     if (h->check_plan) {
-        why = plan_check(ap, bp, a_ip, b_ip, A->n_cols, metric, op, knn_k, h->opt);
+        std::vector<int64_t> index_rows;
+        const int64_t *b_rows_ptr = b_ip;
+        if (index) {
+            // the index keeps no host copy of the row pointers: rebuild them from its segments
+            index_rows.assign((size_t)n + 1, 0);
+            for (size_t l = 0; l < index->plan.seg_row.size(); ++l)
+                if (index->plan.seg_row[l] >= 0) index_rows[(size_t)index->plan.seg_row[l] + 1] += index->plan.seg_len[l];
+            for (int64_t j = 0; j < n; ++j) index_rows[(size_t)j + 1] += index_rows[(size_t)j];
+            b_rows_ptr = index_rows.data();
+        }
+        why = plan_check(ap, bp, a_ip, b_rows_ptr, A->n_cols, metric, op, knn_k, h->opt);
         if (!why.empty()) return fail(h, SPD_ERR_UNSUPPORTED, "internal plan check failed: " + why);
     }
     for (const AClass &c : ap.classes)
@@ -466,18 +528,20 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     const size_t o_partial_norms = cv.take((size_t)ap.n_partial_slots * 16);
     const size_t o_knn_part = cv.take((size_t)knn_entries * sizeof(KnnEntry));
     if (cv.off > h->ws_bytes || pin_a + (a_plan_end - a_plan_begin) > h->pinned_bytes) {
-        // the bound was too small after all: growing waits for the repack, discards it and
-        // runs it again in the new buffers
+        // the bound was too small after all (or, with an index, this is where the scratch is
+        // sized): growing waits for the repack, discards it and runs it again in the new buffers
         st = ensure_workspace(h, cv.off);
         if (st != SPD_OK) return st;
         st = ensure_pinned(h, pin_a + (a_plan_end - a_plan_begin));
         if (st != SPD_OK) return st;
-        if (h->profile && !h->timed.empty()) {
-            h->event_pool.push_back(h->timed.back().start); h->event_pool.push_back(h->timed.back().stop);
-            h->timed.pop_back();
+        if (!index) {
+            if (h->profile && !h->timed.empty()) {
+                h->event_pool.push_back(h->timed.back().start); h->event_pool.push_back(h->timed.back().stop);
+                h->timed.pop_back();
+            }
+            st = stage_b();
+            if (st != SPD_OK) return st;
         }
-        st = stage_b();
-        if (st != SPD_OK) return st;
     }
     unsigned char *ws = reinterpret_cast<unsigned char *>(h->ws);
     if (a_plan_end > a_plan_begin) {
@@ -739,6 +803,93 @@ spd_status spd_semiring_knn(spd_handle *h, const spd_csr *Q, const spd_csr *Inde
     if (st != SPD_OK) return st;
     return run(h, Q, Index, semiring->sum == SPD_SUM_PLUS ? MT_SEMI_SUM : MT_SEMI_EXT, 1.0f, semiring, k, nullptr, out_idx,
                out_dist);
+}
+
+spd_status spd_index_create(spd_handle *h, const spd_csr *Index, spd_metric metric, float p, spd_index **out) {
+    if (!h) return SPD_ERR_NULL;
+    h->err.clear();
+    if (!out) return fail(h, SPD_ERR_NULL, "index is NULL");
+    *out = nullptr;
+    spd_status st = check_csr_args(h, Index, "Index");
+    if (st != SPD_OK) return st;
+    if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return fail(h, SPD_ERR_BAD_METRIC, "unknown metric");
+    if (metric == SPD_MINKOWSKI && !(p > 0.0f && std::isfinite(p))) return fail(h, SPD_ERR_BAD_P, "Minkowski needs a finite p > 0");
+    for (auto &t : h->timed) { h->event_pool.push_back(t.start); h->event_pool.push_back(t.stop); }
+    h->timed.clear();
+    hipError_t e = hipSetDevice(h->device);
+    if (e != hipSuccess) return hip_fail(h, e, "hipSetDevice");
+    const int64_t n = Index->n_rows;
+    spd_index *ix = new (std::nothrow) spd_index();
+    if (!ix) return fail(h, SPD_ERR_WORKSPACE, "out of host memory");
+    struct Guard { spd_index *p; ~Guard() { if (p) { if (p->dev) (void)hipFree(p->dev); delete p; } } } guard{ix};
+    ix->matrix = *Index;
+    ix->metric = (int)metric;
+    ix->p = p;
+    ix->device = h->device;
+    st = ensure_pinned(h, (size_t)(n + 1) * 8 + 32 * ((size_t)n + 4096));
+    if (st != SPD_OK) return st;
+    int64_t *b_ip = reinterpret_cast<int64_t *>(h->pinned);
+    e = hipMemcpyAsync(b_ip, Index->indptr, (size_t)(n + 1) * 8, hipMemcpyDeviceToHost, h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "copy of Index.indptr");
+    e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+    if (b_ip[n] != Index->nnz) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
+    std::string why;
+    try {
+        why = plan_b(b_ip, n, h->opt, ix->plan);
+    } catch (const std::exception &ex) {
+        why = std::string("planning failed: ") + ex.what();
+    }
+    if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "Index: " + why);
+    Carver cv;
+    const BLayout bl = layout_b(ix->plan, n, cv);
+    ix->dev_bytes = std::max<size_t>(cv.off, 256);
+    e = hipMalloc(&ix->dev, ix->dev_bytes);
+    if (e != hipSuccess) { ix->dev = nullptr; return fail(h, SPD_ERR_WORKSPACE, std::string("hipMalloc of the index failed: ") + hipGetErrorString(e)); }
+    // (the row pointers have served: the plan's arrays may overwrite them in the pinned buffer)
+    st = ensure_pinned(h, bl.plan_end + 256);
+    if (st != SPD_OK) return st;
+    const int run_as = effective_metric((int)metric, p);
+    const MetricInfo mi = metric_info(run_as);
+    const OpParams q = op_params(run_as, p, Index->n_cols, nullptr);
+    if (n > 0) {
+        st = stage_b_into(h, Index, ix->plan, bl, reinterpret_cast<unsigned char *>(ix->dev),
+                          reinterpret_cast<unsigned char *>(h->pinned), run_as, mi, q, (uint32_t)Index->n_cols, ix->bd);
+        if (st != SPD_OK) return st;
+    }
+    guard.p = nullptr;
+    *out = ix;
+    return SPD_OK;
+}
+
+spd_status spd_index_destroy(spd_handle *h, spd_index *index) {
+    if (!h) return SPD_ERR_NULL;
+    h->err.clear();
+    if (!index) return SPD_OK;
+    hipError_t e = hipStreamSynchronize(h->stream);      // calls that read the index may still be running
+    (void)e;
+    if (index->dev) (void)hipFree(index->dev);
+    delete index;
+    return SPD_OK;
+}
+
+spd_status spd_index_pairwise(spd_handle *h, const spd_csr *A, const spd_index *index, float *out) {
+    if (!h) return SPD_ERR_NULL;
+    if (!index) { h->err = "index is NULL"; return SPD_ERR_NULL; }
+    spd_status st = check_call_args(h, A, &index->matrix, (spd_metric)index->metric, index->p, 0, false, out, nullptr);
+    if (st != SPD_OK) return st;
+    if (index->device != h->device) return fail(h, SPD_ERR_UNSUPPORTED, "the index lives on another device");
+    return run(h, A, &index->matrix, index->metric, index->p, nullptr, 0, out, nullptr, nullptr, index);
+}
+
+spd_status spd_index_knn(spd_handle *h, const spd_csr *Q, const spd_index *index, int k, int64_t *out_idx,
+                         float *out_dist) {
+    if (!h) return SPD_ERR_NULL;
+    if (!index) { h->err = "index is NULL"; return SPD_ERR_NULL; }
+    spd_status st = check_call_args(h, Q, &index->matrix, (spd_metric)index->metric, index->p, k, true, out_idx, out_dist);
+    if (st != SPD_OK) return st;
+    if (index->device != h->device) return fail(h, SPD_ERR_UNSUPPORTED, "the index lives on another device");
+    return run(h, Q, &index->matrix, index->metric, index->p, nullptr, k, nullptr, out_idx, out_dist, index);
 }
 
 spd_status spd_csr_validate(spd_handle *h, const spd_csr *M, int require_nonnegative) {
