@@ -220,7 +220,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[1] skewed medium: A,B 10000x20000 CSR, Zipf degrees, |N(0,1)| values; "
                                "step = " + " + ".join({"l1": "pairwise L1", "cosine": "pairwise cosine",
-                                                       "knn": "k-NN cosine k=32"}[x] for x in names),
+                                                       "knn": "k-NN cosine k=32",
+                                                       "tropical": "semiring {plus, min} over the intersection",
+                                                       "l1_semiring": "semiring {abs_diff, plus} over the union"}[x]
+                                                      for x in names),
                    "a_rows": m, "b_rows": n, "n_cols": A["n_cols"], "nnz_a": int(A["indptr"][-1]), "nnz_b": nnz_b},
     }
     keys = {"l1": "roofline", "cosine": "roofline_cosine", "knn": "roofline_knn_cosine"}
