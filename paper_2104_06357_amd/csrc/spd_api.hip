@@ -384,7 +384,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     const BPlan &bp = index ? index->plan : h->plan_of_b;
     // the set metrics count shared columns in byte lanes, or (option) as a dot product of 0/1 values
     int op = mi.op;
-    if (op == OP_CNT && h->no_byte_counters) op = OP_DOT;
+    if (op == OP_CNT && (h->no_byte_counters || h->opt.force_kind == KIND_BLOOM)) op = OP_DOT;
     // A is planned on the helper thread meanwhile; every way out of this function waits for it
     std::string why_a;
     {
@@ -477,7 +477,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     }
     for (const AClass &c : ap.classes)
         if ((int64_t)c.n_groups * c.n_chunks >= ((int64_t)1 << 31) || (int64_t)c.lds_bytes + kStaticLds > h->opt.lds_budget ||
-            c.kind != a_kind)
+            (c.kind != a_kind && c.kind != KIND_BLOOM))
             return fail(h, SPD_ERR_UNSUPPORTED, "internal: launch outside the device limits");
     lap("plan check");
 
@@ -927,7 +927,7 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
         if (value < 8192 || value > 160 * 1024) return fail(h, SPD_ERR_UNSUPPORTED, "lds_budget must lie in [8192, 163840]");
         o.lds_budget = value;
     } else if (s == "force_kind") {
-        if (value < 0 || value > 3) return fail(h, SPD_ERR_UNSUPPORTED, "force_kind must be 0..3");
+        if (value < 0 || value > 4) return fail(h, SPD_ERR_UNSUPPORTED, "force_kind must be 0..4");
         o.force_kind = (int)value;
     } else if (s == "max_rows") {
         if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
@@ -950,6 +950,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
         if (value != 0 && value != 8 && value != 16 && value != 32)
             return fail(h, SPD_ERR_UNSUPPORTED, "waves_per_cu must be 0 (automatic), 8, 16 or 32");
         o.waves_per_cu = (int)value;
+    } else if (s == "bloom_long_rows") {
+        if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "bloom_long_rows must be 0 or 1");
+        o.bloom_long_rows = (int)value;
     } else if (s == "side_streams") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must be 0 or 1");
         h->multi_stream = value != 0;

@@ -218,6 +218,7 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
 namespace {
 
 bool staging_fits(int kind, int R, uint64_t sumlen, uint32_t k, bool cheb, int64_t budget) {
+    if (kind == KIND_BLOOM) return (int64_t)lds_layout(kind, R, (uint32_t)std::min<uint64_t>(sumlen, 1u << 30), k, cheb, 1).total <= budget;
     if (kind != KIND_STRIP && sumlen > 65534u) return false;      // 16-bit slot ids
     uint64_t nslots = (kind == KIND_STRIP) ? (uint64_t)k + 1u : sumlen + 1u;
     if (nslots * (uint64_t)R * 5u > (uint64_t)budget) return false;   // also keeps the 32-bit layout math safe
@@ -251,8 +252,14 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
         else if ((int64_t)(k + 1) * 2 <= budget / 3) kind = KIND_SLOT;
         else kind = KIND_HASH;
     }
-    if (kind < KIND_STRIP || kind > KIND_HASH) return "bad staging kind";
+    if (kind < KIND_STRIP || kind > KIND_BLOOM) return "bad staging kind";
     dmax = 0;
+    if (kind == KIND_BLOOM) {
+        if (!bloom_serves(op)) return "Bloom staging does not serve this product";
+        if ((int64_t)kBloomMaxBits / 8 > budget) return "lds_budget too small for a Bloom filter";
+        max_r = min_r = 1;
+        return std::string();
+    }
     if (kind == KIND_STRIP) {
         if (!staging_fits(KIND_STRIP, words(min_r), 0, k, cheb, budget)) return "dense strip does not fit the LDS budget";
         while (max_r > min_r && !staging_fits(KIND_STRIP, words(max_r), 0, k, cheb, budget)) max_r /= 2;
@@ -274,7 +281,7 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
 std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int op, int knn_k,
                    const PlanOptions &opt, APlan &out) {
     // take the buffers of the previous plan back before anything else
-    constexpr size_t kPool = 6 * 3 + 1;       // 6 group sizes x 3 occupancies, and the dense strip's one class
+    constexpr size_t kPool = 6 * 3 + 2;       // 6 group sizes x 3 occupancies, the dense strip's one class, the Bloom class
     if (out.pool.size() != kPool) out.pool.assign(kPool, AClass());
     for (AClass &c : out.classes) { const int slot = c.pool_slot; out.pool[(size_t)slot] = std::move(c); }
     out.classes.clear();
@@ -328,8 +335,8 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
 
     if (kind == KIND_STRIP) {
         int R = max_r;
-        AClass &c = out.pool[kPool - 1];
-        c.pool_slot = (int)kPool - 1;
+        AClass &c = out.pool[kPool - 2];
+        c.pool_slot = (int)kPool - 2;
         c.R = R; c.kind = KIND_STRIP;
         c.n_groups = (int)((n_rows + R - 1) / R);
         c.rows.assign((size_t)c.n_groups * R, ARow{0, 0, -1, kRowFirst | kRowLast, 0});
@@ -344,13 +351,24 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         return std::string();
     }
 
+    // rows behind a Bloom filter: one per workgroup, whole, whatever their length
+    AClass &bloom = out.pool[kPool - 1];
+    bloom.pool_slot = (int)kPool - 1;
+    bloom.R = 1; bloom.kind = KIND_BLOOM;
+    const bool bloom_all = kind == KIND_BLOOM;
+    const bool bloom_long = !bloom_all && opt.bloom_long_rows && bloom_serves(op) &&
+                            (int64_t)kBloomMaxBits / 8 <= budget;
     std::vector<ARow> &items = out.items;
     items.clear();
     items.reserve((size_t)n_rows);
     for (int64_t i = 0; i < n_rows; ++i) {
         int64_t len = indptr[i + 1] - indptr[i];
         if (len > (int64_t)k) return fmt("row longer than the column count", i);
-        if ((uint64_t)len <= dmax) {
+        if (bloom_all || (bloom_long && (uint64_t)len > dmax)) {
+            bloom.rows.push_back(ARow{indptr[i], (int32_t)len, (int32_t)i, kRowFirst | kRowLast, 0});
+            bloom.sumlen.push_back((int32_t)len);
+            ++bloom.n_groups;
+        } else if ((uint64_t)len <= dmax) {
             items.push_back(ARow{indptr[i], (int32_t)len, (int32_t)i, kRowFirst | kRowLast, 0});
         } else {
             int64_t parts = (len + (int64_t)dmax - 1) / (int64_t)dmax;
@@ -415,6 +433,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     for (int q = 0; q < 6; ++q)
         for (int b = 0; b < 3; ++b)
             if (by_key[q][b]->n_groups) { finish_class(*by_key[q][b]); out.classes.push_back(std::move(*by_key[q][b])); }
+    if (bloom.n_groups) { finish_class(bloom); out.classes.push_back(std::move(bloom)); }
     return std::string();
 }
 
@@ -432,7 +451,8 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
         if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16 && c.R != 32) return "class R";
         if (op == OP_CNT ? (c.R < 4 || (knn_k > 0 && c.R > 16)) : c.R > 16) return "class R outside the product's range";
         if (wide_sums(metric) && c.R > 8) return "two-sum product with R > 8";
-        if (c.kind < KIND_STRIP || c.kind > KIND_HASH) return "class kind";
+        if (c.kind < KIND_STRIP || c.kind > KIND_BLOOM) return "class kind";
+        if (c.kind == KIND_BLOOM && (c.R != 1 || !bloom_serves(op))) return "Bloom class outside its range";
         if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";
         if ((int64_t)c.lds_bytes + kStaticLds > opt.lds_budget) return "class LDS over budget";
         if ((size_t)c.n_groups * c.R != c.rows.size() || (size_t)c.n_groups != c.sumlen.size()) return "class sizes";
@@ -466,6 +486,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
             if (c.kind == KIND_HASH && (L.cap < 2u * (uint32_t)sum || L.cap < 16u)) return "hash table too full";
             if (L.total > c.lds_bytes) return "group LDS over the launch size";
             if (c.kind != KIND_STRIP && L.nslots > 65535u) return "slot ids over 16 bits";
+            if (c.kind == KIND_BLOOM && (L.cap < kBloomMinBits || L.cap > kBloomMaxBits || (L.cap & (L.cap - 1)))) return "Bloom filter size";
         }
     }
     for (const SpilledRow &s : a.spilled) {

@@ -11,7 +11,10 @@
 //     hash table of the union of their columns) in front of a table of R values per
 //     column, so a column of B is looked up once for the R rows;
 //   * rows that do not fit alone are cut into contiguous slices whose partial results are
-//     summed afterwards (the partitions of Section 3.3.3, by column range);
+//     summed afterwards (the partitions of Section 3.3.3, by column range); or (option) they
+//     stay in global memory behind a Bloom filter of their columns in LDS, and a column
+//     that passes the filter is looked up by binary search (the alternative Section 3.3.2
+//     closes with);
 //   * B is repacked once per call into "slabs" of 64 rows of similar degree, one row per
 //     lane, stored so that the t-th entries of the 64 rows are contiguous (shorter rows
 //     padded with a column that stages nothing).  Each lane
@@ -28,7 +31,7 @@
 
 namespace spd {
 
-enum StageKind { KIND_AUTO = 0, KIND_STRIP = 1, KIND_SLOT = 2, KIND_HASH = 3 };
+enum StageKind { KIND_AUTO = 0, KIND_STRIP = 1, KIND_SLOT = 2, KIND_HASH = 3, KIND_BLOOM = 4 };
 
 constexpr int kWave = 64;
 constexpr int kScanUnroll = 4;              // a slab is scanned in blocks of this many steps
@@ -47,7 +50,16 @@ struct PlanOptions {
     int chunks = 0;
     int n_cus = 256;
     int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32, or 16 for k-NN)
+    int bloom_long_rows = 0;                // 1: a row too long for the LDS gets a Bloom filter instead of slices
 };
+
+// Bloom staging: filter bits per stored entry (two hash functions: ~1.4 % false positives), and
+// the bounds of a filter's size.
+constexpr uint32_t kBloomBitsPerEntry = 16;
+constexpr uint32_t kBloomMinBits = 1024, kBloomMaxBits = 1u << 19;
+// The products a Bloom-staged row serves: one row per workgroup, values fetched from global
+// memory (not the byte-counted set metrics, not the ranked completion of sum() = max).
+SPD_HD constexpr bool bloom_serves(int op) { return op != OP_CNT && op != OP_CHEB && op != OP_SEMI_EXT; }
 
 // 4-byte words a slot of the staged value table holds for R rows: one fp32 per row, or one
 // byte per row for the set metrics.
@@ -110,6 +122,18 @@ SPD_HD uint32_t pow2_at_least(uint32_t v) {
 SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool cheb, int hscale) {
     LdsLayout L;
     L.cap = 0;
+    if (kind == KIND_BLOOM) {
+        // only the filter: `cap` bits at off_map; the values stay in global memory
+        uint32_t want = sumlen > kBloomMaxBits / kBloomBitsPerEntry ? kBloomMaxBits : sumlen * kBloomBitsPerEntry;
+        uint32_t bits = kBloomMinBits;
+        while (bits < want && bits < kBloomMaxBits) bits <<= 1;
+        L.cap = bits;
+        L.nslots = 0;
+        L.off_vals = 0; L.off_map = 0;
+        L.off_rank = bits / 8u;
+        L.total = bits / 8u;
+        return L;
+    }
     L.nslots = (kind == KIND_STRIP) ? k + 1u : sumlen + 1u;
     uint32_t off = 0;
     L.off_vals = off;

@@ -216,7 +216,15 @@ template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const 
 //    insertion that finds both full moves an older entry to its other bucket (cuckoo
 //    hashing): a lookup reads exactly the two.  Half full, linear probing would walk 8 to 13
 //    buckets for its unluckiest entry, and every lookup would have to read as many.
+//
+// KIND_BLOOM keeps no table at all: the row's columns set two bits each of a Bloom filter in
+// LDS, and a column that finds both of its bits set is searched for in the row itself (global
+// memory, ascending columns: a binary search of a fixed number of steps).  The "slot" is the
+// entry's position in the row plus one, 0 for a column the row does not store.
 template <int KIND> struct ColumnMap {
+    const uint32_t *bits;     // KIND_BLOOM: the filter, `mask` + 1 bits
+    const int32_t *row_cols;  // KIND_BLOOM: the staged row's columns (global memory)
+    int row_len, search_steps;
     const uint16_t *slot16;   // KIND_SLOT: k+1 entries
     const uint4 *table;       // KIND_HASH: buckets {column, slot, column, slot}, empty = {kEmptyKey, 0}
     uint32_t mask, shift;     // over buckets
@@ -233,10 +241,29 @@ template <int KIND> struct ColumnMap {
     __device__ __forceinline__ uint32_t next_bucket(uint32_t c, uint32_t h, int i) const {
         return two_choice ? other(c) : ((h + (uint32_t)i) & mask);
     }
+    // the two filter bits of column c
+    __device__ __forceinline__ uint32_t bit1(uint32_t c) const { return ((c * mult1) >> shift) & mask; }
+    __device__ __forceinline__ uint32_t bit2(uint32_t c) const { return ((c * mult2) >> shift) & mask; }
     __device__ __forceinline__ uint32_t lookup(uint32_t c) const {
         if constexpr (KIND == KIND_STRIP) return c;
         else if constexpr (KIND == KIND_SLOT) return slot16[c];
-        else {
+        else if constexpr (KIND == KIND_BLOOM) {
+            const uint32_t b1 = bit1(c), b2 = bit2(c);
+            const bool maybe = ((bits[b1 >> 5] >> (b1 & 31u)) & (bits[b2 >> 5] >> (b2 & 31u)) & 1u) != 0u;
+            uint32_t pos = 0u;
+            if (maybe) {
+                // first entry not below c: every probe stays inside [0, row_len)
+                int lo = 0, hi = row_len;
+                for (int it = 0; it < search_steps; ++it) {
+                    if (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if ((uint32_t)row_cols[mid] < c) lo = mid + 1; else hi = mid;
+                    }
+                }
+                if (lo < row_len && (uint32_t)row_cols[lo] == c) pos = (uint32_t)lo + 1u;
+            }
+            return pos;
+        } else {
             const uint32_t h = home(c);
             uint32_t slot = match(c, table[h], 0u);
             for (int i = 1; i < reach; ++i) slot = match(c, table[next_bucket(c, h, i)], slot);
@@ -293,6 +320,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     constexpr bool kCnt = (OP == OP_CNT);          // set metrics: one byte of the table per staged row
     constexpr int W = table_words(OP, R);          // 4-byte words per slot of the value table
     static_assert(!kCnt || (R % 4 == 0), "byte counters come four to the word");
+    static_assert(KIND != KIND_BLOOM || (R == 1 && bloom_serves(OP)), "a Bloom-staged row is alone in its workgroup");
     constexpr int U = kScanUnroll;
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ ARow s_rows[R];
@@ -352,6 +380,14 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     cmap.mult1 = 0x9E3779B1u;
     cmap.mult2 = 0x85EBCA77u;
     cmap.two_choice = false;
+    cmap.bits = reinterpret_cast<const uint32_t *>(dyn + L.off_map);
+    cmap.row_cols = args.a_indices;
+    cmap.row_len = 0;
+    cmap.search_steps = 0;
+    if constexpr (KIND == KIND_BLOOM) {
+        cmap.mask = L.cap - 1u;
+        cmap.shift = 32u - (uint32_t)__builtin_ctz(L.cap);        // the high bits of the product
+    }
 
     // ---- stage ------------------------------------------------------------------------
     // 1. clear the value table and the column map
@@ -365,6 +401,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             for (uint32_t i = tid; i < nw32; i += nthr) m32[i] = 0u;
         } else if constexpr (KIND == KIND_HASH) {
             for (uint32_t i = tid; i < L.cap / 2u; i += nthr) table[i] = make_uint4(kEmptyKey, 0u, kEmptyKey, 0u);
+        } else if constexpr (KIND == KIND_BLOOM) {
+            uint32_t *bits = reinterpret_cast<uint32_t *>(dyn + L.off_map);
+            for (uint32_t i = tid; i < L.cap / 32u; i += nthr) bits[i] = 0u;
         }
         if constexpr (kCheb) {
             uint32_t nr4 = (L.nslots * R + 3u) / 4u;
@@ -421,6 +460,17 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         };
         if constexpr (KIND == KIND_SLOT) {
             for_each_entry([&](uint32_t c, uint32_t id) { if (slot16[c] == 0) slot16[c] = (uint16_t)id; });
+            __syncthreads();
+        } else if constexpr (KIND == KIND_BLOOM) {
+            uint32_t *bits = reinterpret_cast<uint32_t *>(dyn + L.off_map);
+            for_each_entry([&](uint32_t c, uint32_t) {
+                const uint32_t b1 = cmap.bit1(c), b2 = cmap.bit2(c);
+                atomicOr(&bits[b1 >> 5], 1u << (b1 & 31u));
+                atomicOr(&bits[b2 >> 5], 1u << (b2 & 31u));
+            });
+            cmap.row_cols = args.a_indices + s_rows[0].start;
+            cmap.row_len = s_rows[0].len;
+            cmap.search_steps = 32 - __builtin_clz((uint32_t)cmap.row_len | 1u);   // halvings that empty [0, len)
             __syncthreads();
         } else {
             unsigned long long *t64 = reinterpret_cast<unsigned long long *>(table);   // entry = column | slot << 32
@@ -486,8 +536,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             }
         }
     }
-    // 4. fill the value table
-    for (uint32_t e = tid; e < total; e += nthr) {
+    // 4. fill the value table (a Bloom-staged row keeps its values where they are)
+    for (uint32_t e = tid; e < (KIND == KIND_BLOOM ? 0u : total); e += nthr) {
         int r = 0;
 #pragma unroll
         for (int q = 1; q < R; ++q) r += (e >= s_prefix[q]) ? 1 : 0;
@@ -578,6 +628,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         for (int r = 0; r < R; ++r) lists[r].reset();
     }
     const int64_t n_b = args.b.n_rows;
+    const float *bloom_values = args.a_values + (KIND == KIND_BLOOM ? s_rows[0].start : 0);
 
     for (;;) {
         int s = 0;
@@ -617,7 +668,13 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                 for (int w = 0; w < W; ++w) counts[w] += __float_as_uint(a.v[w]);
             } else {
                 const typename O::Bv bv = O::prep(__uint_as_float(entry.y), args.q);
-                const RowVals<R> a = load_vals<R>(vals, slot, L.nslots);
+                RowVals<R> a;
+                if constexpr (KIND == KIND_BLOOM) {
+                    // slot = position in the row + 1 (0: not stored)
+                    a.v[0] = slot ? transform_value(args.transform, bloom_values[slot - 1u]) : 0.0f;
+                } else {
+                    a = load_vals<R>(vals, slot, L.nslots);
+                }
                 // (a semiring's product and Minkowski's degree are run-time choices: they are
                 // switched on once per step, not once per visit)
                 auto visit_rows = [&](auto product_tag) {
@@ -900,6 +957,9 @@ static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, c
             case KIND_STRIP: return launch_scan_rkk<OP, R, KIND_STRIP, true>(st, block, lds_bytes, args);
             case KIND_SLOT: return launch_scan_rkk<OP, R, KIND_SLOT, true>(st, block, lds_bytes, args);
             case KIND_HASH: return launch_scan_rkk<OP, R, KIND_HASH, true>(st, block, lds_bytes, args);
+            case KIND_BLOOM:
+                if constexpr (R == 1 && bloom_serves(OP)) return launch_scan_rkk<OP, R, KIND_BLOOM, true>(st, block, lds_bytes, args);
+                else return hipErrorInvalidValue;
             default: return hipErrorInvalidValue;
             }
         }
@@ -909,6 +969,9 @@ static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, c
         case KIND_STRIP: return launch_scan_rkk<OP, R, KIND_STRIP, false>(st, block, lds_bytes, args);
         case KIND_SLOT: return launch_scan_rkk<OP, R, KIND_SLOT, false>(st, block, lds_bytes, args);
         case KIND_HASH: return launch_scan_rkk<OP, R, KIND_HASH, false>(st, block, lds_bytes, args);
+        case KIND_BLOOM:
+            if constexpr (R == 1 && bloom_serves(OP)) return launch_scan_rkk<OP, R, KIND_BLOOM, false>(st, block, lds_bytes, args);
+            else return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
         }
     }

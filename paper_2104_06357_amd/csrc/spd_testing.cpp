@@ -96,12 +96,14 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
         else if (s == "window") opt.window = (int)v;
         else if (s == "chunks") opt.chunks = (int)v;
         else if (s == "n_cus") opt.n_cus = (int)v;
+        else if (s == "bloom_long_rows") opt.bloom_long_rows = (int)v;
         else return SPD_ERR_UNSUPPORTED;
     }
     APlan ap;
     BPlan bp;
     std::string why = plan_b(b_indptr, b_rows, opt, bp);
     int op = metric_info((int)metric).op;
+    if (op == OP_CNT && opt.force_kind == KIND_BLOOM) op = OP_DOT;      // as the library does
     if (why.empty()) why = plan_a(a_indptr, a_rows, n_cols, (int)metric, op, k_neighbors, opt, ap);
     if (why.empty()) {
         for (AClass &c : ap.classes) plan_chunks(bp, c, opt);
