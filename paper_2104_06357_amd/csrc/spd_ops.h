@@ -114,6 +114,47 @@ SPD_HD float fast_div(float x, float y) {
 #endif
 }
 
+// x / d in fp32 through a reciprocal: quotient estimate, exact residual (one FMA), correction
+// (one FMA).  With the reciprocal good to an ulp this is the correctly rounded quotient (in
+// particular exactly 1 for x == d, exactly 1/2 for d == 2x), at 5 instructions per quotient
+// where the IEEE sequence with its range scaling takes 11.  The divisor is prepared once and
+// serves many numerators; one whose magnitude lies outside [2^-100, 2^100] is brought into
+// range by a power of two that the numerator then shares (a quotient beyond the fp32 range
+// is undefined, where IEEE division gives 0 or infinity).  The host takes the plain quotient.
+struct Divisor { float d, y, s; };        // scaled divisor, its reciprocal, the scale
+SPD_HD Divisor divisor_of(float d) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const float m = fabsf(d);
+    const float s = m < 0x1p-100f ? 0x1p64f : (m > 0x1p100f ? 0x1p-64f : 1.0f);
+    const float ds = d * s;
+    return {ds, __builtin_amdgcn_rcpf(ds), s};
+#else
+    return {d, 0.0f, 1.0f};
+#endif
+}
+SPD_HD float divide(float x, const Divisor &v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const float xs = x * v.s;
+    const float q = xs * v.y;
+    const float r = __builtin_fmaf(-q, v.d, xs);
+    return __builtin_fmaf(r, v.y, q);
+#else
+    return x / v.d;
+#endif
+}
+
+// The same for one quotient whose divisor is known to lie in [2^-100, 2^100].
+SPD_HD float divide_in_range(float x, float d) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const float y = __builtin_amdgcn_rcpf(d);
+    const float q = x * y;
+    const float r = __builtin_fmaf(-q, d, x);
+    return __builtin_fmaf(r, y, q);
+#else
+    return x / d;
+#endif
+}
+
 // Median of (a, b, 0): the one of a and b nearer to zero when they have the same sign, else 0.
 SPD_HD float median_with_zero(float a, float b) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -335,13 +376,14 @@ template <> struct Op<OP_CNT> {
 // that equal entries give exactly 0; the factor ln 2 is applied once, by finish().
 template <> struct Op<OP_KL> {
     struct Acc { double v; int hits; };      // hits: columns where both rows hold mass (the strict variant needs them)
-    struct Bv { float b; };
+    struct Bv { float b; Divisor by_b; };
     SPD_HD static void init(Acc &x) { x.v = 0.0; x.hits = 0; }
-    SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
+    SPD_HD static Bv prep(float b, const OpParams &) { return {b, divisor_of(b > 0.0f ? b : 1.0f)}; }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
         bool hit = (a > 0.0f) && (b.b > 0.0f);
-        float t = a * fast_log2(hit ? a / b.b : 1.0f);
-        x.v += hit ? (double)t : 0.0;
+        // elsewhere the quotient is 1, its logarithm 0 and the term a * 0: nothing to select away
+        float t = a * fast_log2(hit ? divide(a, b.by_b) : 1.0f);
+        x.v += (double)t;
         x.hits += hit ? 1 : 0;
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; x.hits += y.hits; }
@@ -364,10 +406,12 @@ template <> struct Op<OP_JS> {
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
         bool hit = (a > 0.0f) && (b.b > 0.0f);
         float aa = hit ? a : 1.0f, bb = hit ? b.b : 1.0f;
-        float sum = aa + bb;
-        float u = aa / sum;                              // correctly rounded: 1/2 for aa == bb
+        // (a sum outside [2^-100, 2^100] is clamped: below it, the two entries' term is far below the
+        // result's resolution whatever u is taken; above it lie sums of values beyond 6e29)
+        float sum = fminf(fmaxf(aa + bb, 0x1p-100f), 0x1p100f);
+        float u = divide_in_range(aa, sum);              // correctly rounded: 1/2 for aa == bb
         float t = aa * fast_log2(2.0f * u) + bb * fast_log2(2.0f * (1.0f - u));
-        x.f += hit ? (double)t : 0.0;
+        x.f += (double)t;                                // elsewhere aa == bb == 1: u = 1/2, both logarithms 0
         x.s += hit ? (double)a + b.db : 0.0;
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.f += y.f; x.s += y.s; }
