@@ -29,7 +29,8 @@
  *    internal streams of default priority beside the caller's stream.
  *  - Stored zeros are legal and count as absent.  Values must be finite; Hellinger, KL and
  *    Jensen-Shannon expect non-negative values (anything else is undefined, and reported by
- *    spd_csr_validate()).
+ *    spd_csr_validate()); for KL and Jensen-Shannon the quotient of two entries of one column
+ *    must lie within the fp32 range.
  */
 #ifndef SPD_H
 #define SPD_H
