@@ -385,6 +385,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     // the set metrics count shared columns in byte lanes, or (option) as a dot product of 0/1 values
     int op = mi.op;
     if (op == OP_CNT && (h->no_byte_counters || h->opt.force_kind == KIND_BLOOM)) op = OP_DOT;
+    // Minkowski: the small integer degrees share one set of kernels, every other degree has its own
+    if (op == OP_MINK && degree_class(metric == SPD_L2_UNEXPANDED ? 2.0f : p) == 0) op = OP_MINK_ANY;
     // A is planned on the helper thread meanwhile; every way out of this function waits for it
     std::string why_a;
     {

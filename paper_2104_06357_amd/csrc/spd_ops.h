@@ -30,7 +30,11 @@
 
 namespace spd {
 
-enum OpId { OP_DOT = 0, OP_L1, OP_MINK, OP_CANB, OP_HAMM, OP_KL, OP_JS, OP_CHEB, OP_CNT, OP_SEMI_SUM, OP_SEMI_EXT, OP_COUNT };
+enum OpId {
+    OP_DOT = 0, OP_L1, OP_MINK, OP_CANB, OP_HAMM, OP_KL, OP_JS, OP_CHEB, OP_CNT, OP_SEMI_SUM, OP_SEMI_EXT,
+    OP_MINK_ANY,      // Minkowski of a degree other than 1..4 (powers through exp2 / log2: kernels of their own)
+    OP_COUNT
+};
 enum Transform { TR_ID = 0, TR_SQRT, TR_NONZERO };
 enum NormKind {
     NORM_NONE = 0, NORM_SUMSQ, NORM_SUM_SUMSQ, NORM_SUM, NORM_SUM_ABS, NORM_SUM_POW, NORM_NNZ,
@@ -311,8 +315,16 @@ template <> struct Op<OP_MINK> {
     SPD_HD static Bv prep(float b, const OpParams &q) { return {b, (double)pow_abs(b, q.p)}; }
     template <int DEG> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &q) {
         bool hit = (a != 0.0f) && (b.b != 0.0f);
-        x.d += hit ? (double)pow_abs_as<DEG>(a - b.b, q.p) : 0.0;
-        x.s += hit ? (double)pow_abs_as<DEG>(a, q.p) + b.pwb : 0.0;
+        if constexpr (DEG != 0) {
+            // a power is 0 at 0: a column one side does not store is silenced by clearing the other
+            // side's value (the power of b is cheap enough to form again, bit for bit the norm's)
+            const float am = (b.b != 0.0f) ? a : 0.0f, bm = (a != 0.0f) ? b.b : 0.0f;
+            x.d += (double)pow_abs_as<DEG>(am - bm, q.p);
+            x.s += (double)pow_abs_as<DEG>(am, q.p) + (double)pow_abs_as<DEG>(bm, q.p);
+        } else {
+            x.d += hit ? (double)pow_abs_as<DEG>(a - b.b, q.p) : 0.0;
+            x.s += hit ? (double)pow_abs_as<DEG>(a, q.p) + b.pwb : 0.0;
+        }
         x.hits += hit ? 1 : 0;
     }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
@@ -322,6 +334,12 @@ template <> struct Op<OP_MINK> {
     SPD_HD static double v0(const Acc &x) { return x.d; }
     SPD_HD static double v1(const Acc &x) { return x.s; }
     SPD_HD static double v2(const Acc &x) { return (double)x.hits; }
+};
+
+// The same sums for any other degree: the powers go through exp2 / log2, which takes so many
+// more registers that these kernels are kept apart from the ones of the small integer degrees.
+template <> struct Op<OP_MINK_ANY> : Op<OP_MINK> {
+    SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) { Op<OP_MINK>::visit_as<0>(x, a, b, q); }
 };
 
 template <> struct Op<OP_CANB> {
@@ -502,7 +520,7 @@ template <int OP> SPD_HD float one_sided_key(float a, const OpParams &q) {
 template <int OP, int P, bool UNION>
 SPD_HD void visit_with(typename Op<OP>::Acc &x, float a, const typename Op<OP>::Bv &b, const OpParams &q) {
     if constexpr (OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) Op<OP>::template visit_as<P, UNION>(x, a, b, q);
-    else if constexpr (OP == OP_MINK) Op<OP>::template visit_as<P>(x, a, b, q);     // P: the class of the degree
+    else if constexpr (OP == OP_MINK) Op<OP>::template visit_as<(P == 0 ? 2 : P)>(x, a, b, q);   // P: the class of the degree, 1..4
     else Op<OP>::visit(x, a, b, q);
 }
 
@@ -582,7 +600,8 @@ template <int MT> struct MetricTag { static constexpr int value = MT; };
 // The product that computes a metric, and OP_DOT for the set metrics too (a dot product of
 // 0/1 values counts the shared columns: the route the option "byte_counters" 0 selects).
 SPD_HD constexpr bool op_serves(int op, int metric) {
-    return metric_info(metric).op == op || (op == OP_DOT && metric_info(metric).op == OP_CNT);
+    return metric_info(metric).op == op || (op == OP_DOT && metric_info(metric).op == OP_CNT) ||
+           (op == OP_MINK_ANY && metric == MT_MINKOWSKI);
 }
 
 // Calls f(MetricTag<m>) for the metric `metric`, which must be one that product OP serves

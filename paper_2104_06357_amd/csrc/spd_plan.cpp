@@ -234,6 +234,9 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
     const uint32_t k = (uint32_t)n_cols;
     max_r = std::min(opt.max_rows, 16);
     if (wide_sums(metric)) max_r = std::min(max_r, 8);   // two fp64 sums per pair
+    // Minkowski: three sums per pair and the powers beside them: 4 rows keep the kernel within 128
+    // registers, so that a compute unit holds two workgroups of 8 wavefronts
+    if (op == OP_MINK || op == OP_MINK_ANY) max_r = std::min(max_r, 4);
     if (max_r < 1) max_r = 1;
     while (max_r & (max_r - 1)) max_r &= max_r - 1;         // power of two
     min_r = 1;
@@ -451,6 +454,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
         if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16 && c.R != 32) return "class R";
         if (op == OP_CNT ? (c.R < 4 || (knn_k > 0 && c.R > 16)) : c.R > 16) return "class R outside the product's range";
         if (wide_sums(metric) && c.R > 8) return "two-sum product with R > 8";
+        if ((op == OP_MINK || op == OP_MINK_ANY) && c.R > 4) return "Minkowski with R > 4";
         if (c.kind < KIND_STRIP || c.kind > KIND_BLOOM) return "class kind";
         if (c.kind == KIND_BLOOM && (c.R != 1 || !bloom_serves(op))) return "Bloom class outside its range";
         if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";

@@ -91,7 +91,8 @@ SPD_HD constexpr bool wide_sums(int metric) {
 // the most per-lane state get 256 registers per lane instead of 128.
 SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
     if (op == OP_CNT) return (knn && R >= 16) ? 512 : 1024;
-    return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_MINK || op == OP_SEMI_SUM || op == OP_SEMI_EXT) && R == 8)) ? 512 : 1024;
+    if (op == OP_MINK || op == OP_MINK_ANY) return 512;
+    return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_SEMI_SUM || op == OP_SEMI_EXT) && R == 8)) ? 512 : 1024;
 }
 
 // Wavefronts per SIMD the compiler is asked to make room for (it bounds the registers per

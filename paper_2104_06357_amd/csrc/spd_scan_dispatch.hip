@@ -8,6 +8,7 @@ hipError_t launch_scan_cnt(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_cnt_knn(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_l1(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_mink(hipStream_t, int, int, uint32_t, const ScanArgs &);
+hipError_t launch_scan_mink_any(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_canb(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_hamm(hipStream_t, int, int, uint32_t, const ScanArgs &);
 hipError_t launch_scan_kl(hipStream_t, int, int, uint32_t, const ScanArgs &);
@@ -27,7 +28,9 @@ hipError_t launch_scan(hipStream_t st, int op, int R, int block, uint32_t lds_by
         return args.knn_k > 0 ? launch_scan_cnt_knn(st, R, block, lds_bytes, args)
                               : launch_scan_cnt(st, R, block, lds_bytes, args);
     case OP_L1: return launch_scan_l1(st, R, block, lds_bytes, args);
-    case OP_MINK: return launch_scan_mink(st, R, block, lds_bytes, args);
+    case OP_MINK:       // (its kernels hold the degrees 1 to 4 only)
+        return degree_class(args.q.p) == 0 ? hipErrorInvalidValue : launch_scan_mink(st, R, block, lds_bytes, args);
+    case OP_MINK_ANY: return launch_scan_mink_any(st, R, block, lds_bytes, args);
     case OP_CANB: return launch_scan_canb(st, R, block, lds_bytes, args);
     case OP_HAMM: return launch_scan_hamm(st, R, block, lds_bytes, args);
     case OP_KL: return launch_scan_kl(st, R, block, lds_bytes, args);

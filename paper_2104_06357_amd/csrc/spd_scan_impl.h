@@ -195,6 +195,9 @@ template <> __device__ __forceinline__ Op<OP_MINK>::Acc acc_shfl_xor<OP_MINK>(co
 template <> __device__ __forceinline__ Op<OP_SEMI_SUM>::Acc acc_shfl_xor<OP_SEMI_SUM>(const Op<OP_SEMI_SUM>::Acc &a, int m) {
     Op<OP_SEMI_SUM>::Acc r; r.d = __shfl_xor(a.d, m); r.s = __shfl_xor(a.s, m); r.hits = __shfl_xor(a.hits, m); return r;
 }
+template <> __device__ __forceinline__ Op<OP_MINK_ANY>::Acc acc_shfl_xor<OP_MINK_ANY>(const Op<OP_MINK_ANY>::Acc &a, int m) {
+    return acc_shfl_xor<OP_MINK>(a, m);
+}
 template <> __device__ __forceinline__ Op<OP_KL>::Acc acc_shfl_xor<OP_KL>(const Op<OP_KL>::Acc &a, int m) {
     Op<OP_KL>::Acc r; r.v = __shfl_xor(a.v, m); r.hits = __shfl_xor(a.hits, m); return r;
 }
@@ -783,7 +786,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
 
         // The rows are finished eight at a time, or four (all at once would keep the sums and
         // distances of up to 32 rows in registers together).
-        constexpr bool kThreeSums = (OP == OP_MINK || OP == OP_SEMI_SUM);
+        constexpr bool kThreeSums = (OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_SEMI_SUM);
         constexpr int RB = R < 8 ? R : ((KNN && R >= 16) || kThreeSums ? 4 : 8);
 #pragma unroll
         for (int r0 = 0; r0 < R; r0 += RB) {
@@ -996,9 +999,11 @@ static hipError_t launch_scan_op(hipStream_t st, int R, int block, uint32_t lds_
         case 1: return launch_scan_r<OP, 1, WHICH>(st, block, lds_bytes, args);
         case 2: return launch_scan_r<OP, 2, WHICH>(st, block, lds_bytes, args);
         case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
-        case 8: return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
+        case 8:
+            if constexpr (OP == OP_MINK || OP == OP_MINK_ANY) return hipErrorInvalidValue;
+            else return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
         case 16:
-            if constexpr (OP == OP_JS || OP == OP_MINK || OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) return hipErrorInvalidValue;
+            if constexpr (OP == OP_JS || OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) return hipErrorInvalidValue;
             else return launch_scan_r<OP, 16, WHICH>(st, block, lds_bytes, args);
         default: return hipErrorInvalidValue;
         }

@@ -104,6 +104,7 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
     std::string why = plan_b(b_indptr, b_rows, opt, bp);
     int op = metric_info((int)metric).op;
     if (op == OP_CNT && opt.force_kind == KIND_BLOOM) op = OP_DOT;      // as the library does
+    // (the planner hook has no degree: it plans Minkowski for the small integer degrees)
     if (why.empty()) why = plan_a(a_indptr, a_rows, n_cols, (int)metric, op, k_neighbors, opt, ap);
     if (why.empty()) {
         for (AClass &c : ap.classes) plan_chunks(bp, c, opt);
