@@ -349,8 +349,10 @@ template <> struct Op<OP_CANB> {
     SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &) {
         bool hit = (a != 0.0f) && (b.b != 0.0f);
-        float ratio = fast_div(fabsf(a - b.b), hit ? fabsf(a) + fabsf(b.b) : 1.0f);
-        x.v += hit ? (double)ratio - 2.0 : 0.0;                   // each one-sided column counts 1
+        // each one-sided column counts 1: a shared one replaces two of them by its ratio; elsewhere
+        // the ratio (0/0 where both are absent) is replaced by the 2 that cancels
+        float ratio = hit ? fast_div(fabsf(a - b.b), fabsf(a) + fabsf(b.b)) : 2.0f;
+        x.v += (double)ratio - 2.0;
     }
     SPD_HD static void combine(Acc &x, const Acc &y) { x.v += y.v; }
     SPD_HD static double v0(const Acc &x) { return x.v; }
