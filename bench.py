@@ -174,7 +174,6 @@ def main():
             torch.cuda.synchronize()
             wall[name] += time.perf_counter() - t1
     h.set_option("profile", 0)
-    h.set_option("side_streams", 0 if args.serial else 1)
 
     def roofline(name):
         per_step = records[name]

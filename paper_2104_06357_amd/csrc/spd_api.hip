@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <condition_variable>
 #include <functional>
 #include <mutex>
@@ -34,13 +35,14 @@ public:
     }
     void post(std::function<void()> job) {
         if (!th_.joinable()) th_ = std::thread([this] { loop(); });
-        { std::lock_guard<std::mutex> g(m_); job_ = std::move(job); state_ = kPosted; }
+        { std::lock_guard<std::mutex> g(m_); job_ = std::move(job); state_ = kPosted; posted_.store(true, std::memory_order_release); }
         cv_.notify_all();
     }
     void wait() {
         std::unique_lock<std::mutex> g(m_);
         if (state_ == kPosted) {                 // not begun: do it here
             state_ = kRunning;
+            posted_.store(false, std::memory_order_relaxed);
             std::function<void()> job = std::move(job_);
             g.unlock();
             job();
@@ -55,7 +57,20 @@ private:
     void loop() {
         std::unique_lock<std::mutex> g(m_);
         for (;;) {
+            // calls tend to come back to back: look out for the next job for a little while
+            // before going to sleep (waking a sleeping thread takes as long as a small plan)
+            if (state_ != kPosted && !quit_) {
+                g.unlock();
+                const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(kSpinMicros);
+                while (!posted_.load(std::memory_order_acquire) && std::chrono::steady_clock::now() < until) {
+#if defined(__x86_64__)
+                    __builtin_ia32_pause();
+#endif
+                }
+                g.lock();
+            }
             cv_.wait(g, [this] { return state_ == kPosted || quit_; });
+            posted_.store(false, std::memory_order_relaxed);
             if (quit_) return;
             state_ = kRunning;
             std::function<void()> job = std::move(job_);
@@ -72,6 +87,8 @@ private:
     std::function<void()> job_;
     State state_ = kIdle;
     bool quit_ = false;
+    std::atomic<bool> posted_{false};           // what the helper polls while it spins
+    static constexpr int kSpinMicros = 300;
 };
 
 struct spd_handle {
@@ -90,7 +107,7 @@ struct spd_handle {
     bool profile = false;
     bool check_plan = false;
     bool no_byte_counters = false;   // option "byte_counters" 0: set metrics through the dot product
-    bool multi_stream = true;    // option "side_streams": small launches run beside the large one
+    int side_streams = 2;        // option "side_streams": how many internal streams the small launches may use beside the large one
     static constexpr int kSideStreams = 3;
     hipStream_t side[kSideStreams] = {nullptr, nullptr, nullptr};
     hipEvent_t fork_event = nullptr, join_event[kSideStreams] = {nullptr, nullptr, nullptr};     // full consistency check of every plan before launching
@@ -566,8 +583,16 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
             int64_t work = (int64_t)ap.classes[ci].n_groups * ap.classes[ci].R;
             if (work > best) { best = work; main_class = ci; }
         }
-        if (h->multi_stream && ap.classes.size() > 1) {
-            for (int q = 0; q < spd_handle::kSideStreams; ++q) {
+        // A launch goes beside the large one only if it is small against it: two large launches
+        // side by side push each other's share of B out of the L2 caches.
+        auto small = [&](size_t ci) {
+            return ci != main_class && (int64_t)ap.classes[ci].n_groups * ap.classes[ci].R * 4 <= best;
+        };
+        int n_small = 0;
+        for (size_t ci = 0; ci < ap.classes.size(); ++ci) n_small += small(ci) ? 1 : 0;
+        if (h->side_streams > 0 && n_small > 0) {
+            const int want = std::min<int>(h->side_streams, n_small);
+            for (int q = 0; q < want; ++q) {
                 if (!h->side[q] && hipStreamCreateWithFlags(&h->side[q], hipStreamNonBlocking) != hipSuccess) { h->side[q] = nullptr; break; }
                 if (!h->join_event[q] && hipEventCreateWithFlags(&h->join_event[q], hipEventDisableTiming) != hipSuccess) break;
                 side_used = q + 1;
@@ -583,12 +608,14 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
             }
             int next = 0;
             for (size_t ci = 0; ci < ap.classes.size(); ++ci)
-                if (ci != main_class) { lane_of[ci] = next; next = (next + 1) % side_used; }
+                if (small(ci)) { lane_of[ci] = next; next = (next + 1) % side_used; }
         }
     }
+    // the large launch goes first: every microsecond the host spends on the others would
+    // otherwise delay it
     std::vector<size_t> launch_order;
-    for (size_t ci = 0; ci < ap.classes.size(); ++ci) if (ci != main_class) launch_order.push_back(ci);
     if (!ap.classes.empty()) launch_order.push_back(main_class);
+    for (size_t ci = 0; ci < ap.classes.size(); ++ci) if (ci != main_class) launch_order.push_back(ci);
     for (size_t ci : launch_order) {
         hipStream_t st_launch = lane_of[ci] >= 0 ? h->side[lane_of[ci]] : h->stream;
         const AClass &c = ap.classes[ci];
@@ -956,8 +983,8 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "bloom_long_rows must be 0 or 1");
         o.bloom_long_rows = (int)value;
     } else if (s == "side_streams") {
-        if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must be 0 or 1");
-        h->multi_stream = value != 0;
+        if (value < 0 || value > spd_handle::kSideStreams) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must lie in [0, 3]");
+        h->side_streams = (int)value;
     } else if (s == "check_plan") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "check_plan must be 0 or 1");
         h->check_plan = value != 0;

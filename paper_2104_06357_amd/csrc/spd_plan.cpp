@@ -295,8 +295,11 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     if (n_rows < 0 || n_cols < 0) return "negative size";
     if (n_rows >= (int64_t)1 << 31 || n_cols >= ((int64_t)1 << 31) - 1) return "more than 2^31-2 rows or columns";
     if (n_rows && indptr[0] != 0) return "indptr[0] != 0";
-    for (int64_t i = 0; i < n_rows; ++i)
+    int64_t longest = 0;
+    for (int64_t i = 0; i < n_rows; ++i) {
         if (indptr[i + 1] < indptr[i]) return fmt("row pointers decrease at row", i);
+        longest = std::max(longest, indptr[i + 1] - indptr[i]);
+    }
     const bool cheb = sum_is_max(metric);
     const uint32_t k = (uint32_t)n_cols;
     int kind = 0, max_r = 1, min_r = 1;
@@ -361,39 +364,45 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     const bool bloom_all = kind == KIND_BLOOM;
     const bool bloom_long = !bloom_all && opt.bloom_long_rows && bloom_serves(op) &&
                             (int64_t)kBloomMaxBits / 8 <= budget;
+    // Rows (and slices of rows) sorted by length, longest first, stable: a counting sort whose
+    // histogram is filled while the items are made.
     std::vector<ARow> &items = out.items;
-    items.clear();
-    items.reserve((size_t)n_rows);
+    std::vector<uint32_t> &start = out.sort_start;
+    const size_t len_cap = (size_t)std::min<uint64_t>(std::min<uint64_t>(dmax, (uint64_t)longest), 65534u) + 2;   // lengths 0..dmax
+    start.assign(len_cap + 1, 0);
+    items.resize((size_t)n_rows);
+    size_t n_items = 0;
     for (int64_t i = 0; i < n_rows; ++i) {
-        int64_t len = indptr[i + 1] - indptr[i];
+        const int64_t len = indptr[i + 1] - indptr[i];
         if (len > (int64_t)k) return fmt("row longer than the column count", i);
-        if (bloom_all || (bloom_long && (uint64_t)len > dmax)) {
+        if ((uint64_t)len <= dmax && !bloom_all) {
+            items[n_items++] = ARow{indptr[i], (int32_t)len, (int32_t)i, kRowFirst | kRowLast, 0};
+            ++start[(size_t)len];
+        } else if (bloom_all || bloom_long) {
             bloom.rows.push_back(ARow{indptr[i], (int32_t)len, (int32_t)i, kRowFirst | kRowLast, 0});
             bloom.sumlen.push_back((int32_t)len);
             ++bloom.n_groups;
-        } else if ((uint64_t)len <= dmax) {
-            items.push_back(ARow{indptr[i], (int32_t)len, (int32_t)i, kRowFirst | kRowLast, 0});
         } else {
             int64_t parts = (len + (int64_t)dmax - 1) / (int64_t)dmax;
             if (out.n_partial_slots + parts > (1 << 24)) return "too many row slices";
             out.spilled.push_back(SpilledRow{(int32_t)i, out.n_partial_slots, (int32_t)parts});
+            if (items.size() < n_items + (size_t)parts + (size_t)(n_rows - i)) items.resize(n_items + (size_t)parts + (size_t)(n_rows - i));
             for (int64_t q = 0; q < parts; ++q) {
                 int64_t lo = len * q / parts, hi = len * (q + 1) / parts;
                 uint32_t fl = (q == 0 ? kRowFirst : 0u) | (q == parts - 1 ? kRowLast : 0u);
-                items.push_back(ARow{indptr[i] + lo, (int32_t)(hi - lo), -2 - (out.n_partial_slots++), fl, 0});
+                items[n_items++] = ARow{indptr[i] + lo, (int32_t)(hi - lo), -2 - (out.n_partial_slots++), fl, 0};
+                ++start[(size_t)(hi - lo)];
             }
         }
     }
-    {   // counting sort by length, longest first, stable
-        int32_t max_len = 0;
-        for (const ARow &r : items) max_len = std::max(max_len, r.len);
-        std::vector<uint32_t> &start = out.sort_start;
-        start.assign((size_t)max_len + 2, 0);
-        for (const ARow &r : items) ++start[(size_t)(max_len - r.len) + 1];
-        for (size_t q = 1; q < start.size(); ++q) start[q] += start[q - 1];
+    items.resize(n_items);
+    {
+        // start[l] = number of items longer than l
+        uint32_t longer = 0;
+        for (size_t l = len_cap; l-- > 0;) { const uint32_t here = start[l]; start[l] = longer; longer += here; }
         std::vector<ARow> &sorted = out.sorted;
-        sorted.resize(items.size());
-        for (const ARow &r : items) sorted[start[(size_t)(max_len - r.len)]++] = r;
+        sorted.resize(n_items);
+        for (const ARow &r : items) sorted[start[(size_t)r.len]++] = r;
         items.swap(sorted);
     }
 
@@ -407,6 +416,21 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
             by_key[q][b]->R = 32 >> q;
             by_key[q][b]->kind = kind;
         }
+    // the largest sum of lengths a group of R rows may stage (staging_fits is monotone in it)
+    uint64_t room[6];
+    for (int q = 0; q < 6; ++q) {
+        const int R = 32 >> q;
+        room[q] = 0;
+        if (R > max_r || R < min_r || !fits(kind, R, 0)) continue;
+        uint64_t lo = 0, hi = 65534;
+        while (lo < hi) {
+            const uint64_t mid = (lo + hi + 1) / 2;
+            if (fits(kind, R, mid)) lo = mid; else hi = mid - 1;
+        }
+        room[q] = lo;
+    }
+    auto room_of = [&](int R) { int q = 0; while ((32 >> q) != R) ++q; return room[q]; };
+    auto fits_group = [&](int R, uint64_t sum) { return sum <= room_of(R) && (sum == 0 ? fits(kind, R, 0) : true); };
     size_t t = 0;
     while (t < items.size()) {
         size_t remaining = items.size() - t;
@@ -416,10 +440,10 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
             size_t n = std::min<size_t>((size_t)R, remaining);
             uint64_t sum = 0;
             for (size_t q = 0; q < n; ++q) sum += (uint64_t)items[t + q].len;
-            if (fits(kind, R, sum) || R == min_r) {
+            if (fits_group(R, sum) || R == min_r) {
                 // the smallest group may have to leave places empty (longest items come first)
-                while (n > 1 && !fits(kind, R, sum)) sum -= (uint64_t)items[t + --n].len;
-                if (!fits(kind, R, sum)) return "internal: slice does not fit";
+                while (n > 1 && !fits_group(R, sum)) sum -= (uint64_t)items[t + --n].len;
+                if (!fits_group(R, sum)) return "internal: slice does not fit";
                 int ci = 0;
                 while ((32 >> ci) != R) ++ci;
                 uint32_t need = lds_layout(kind, table_words(op, R), (uint32_t)sum, k, cheb, 1).total;

@@ -7,6 +7,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <atomic>
+
 #include "spd_kernels.h"
 
 namespace spd {
@@ -940,9 +943,24 @@ template <int OP, int R, int KIND, bool KNN>
 static hipError_t launch_scan_rkk(hipStream_t st, int block, uint32_t lds_bytes, const ScanArgs &args) {
     if (block > scan_max_block(OP, R, KNN) || block < kWave || (block & (kWave - 1))) return hipErrorInvalidValue;
     auto kern = spd_scan_kernel<OP, R, KIND, KNN>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    // the instance's LDS limit is raised once per device (to the most a launch may ask for), not
+    // at every launch
+    constexpr int kMaxDevices = 64;
+    static std::atomic<uint32_t> allowed[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices || allowed[dev].load(std::memory_order_acquire) < lds_bytes) {
+        const uint32_t want = std::max<uint32_t>(lds_bytes, 160u * 1024u - kStaticLds);
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)want);
+        if (e != hipSuccess) {
+            // a device with less LDS: ask for what this launch needs
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+        } else if (dev >= 0 && dev < kMaxDevices) {
+            allowed[dev].store(want, std::memory_order_release);
+        }
+    }
     dim3 grid((unsigned)((size_t)args.n_groups * (size_t)args.n_chunks));
     hipLaunchKernelGGL(kern, grid, dim3((unsigned)block), lds_bytes, st, args);
     return hipGetLastError();
