@@ -183,3 +183,27 @@ def test_shape6_ratings_like(spd, capsys):
     progress(capsys, "shape6 plan: spilled rows %d, slabs %d" % (plan["spilled_rows"], plan["slabs"]))
     assert plan["spilled_rows"] >= 1
     _knn_tile_against_oracle(spd, capsys, "shape6", M, tile_rows, ("cosine", "l1"), 32, 8)
+
+
+def test_output_of_more_than_2_to_32_distances(spd, capsys):
+    """70,000 x 70,000 rows of the config-1 kind: 4.9e9 distances (19.6 GB), so every product
+    of a row number and a row length in the kernels' addressing has to be formed in 64 bits."""
+    import torch
+    A, B = synth.workload(1, scale=7.0)
+    assert A["n_rows"] == 70_000 and B["n_rows"] == 70_000
+    progress(capsys, "70,000-row pair generated")
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    h = spd.Handle()
+    out = torch.empty((A["n_rows"], B["n_rows"]), dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(7)
+    ra = _extremes_and_sample(A, 48, rng, extra=(0, A["n_rows"] - 1, 61_357, 65_536))
+    rb = _extremes_and_sample(B, 1024, rng, extra=(0, B["n_rows"] - 1, 61_356, 65_535))
+    for metric in ("cosine", "l1"):
+        out.fill_(float("nan"))
+        _timed(capsys, "70,000 x 70,000 %s" % metric, lambda: h.pairwise(dA, dB, metric, out=out))
+        want = oracle.pairwise(A, B, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
+        assert_distances_close(_gather(out, ra, rb), want, metric)
+        # nothing was left unwritten, nothing was written past the end
+        assert not bool(torch.isnan(out[-1]).any()) and not bool(torch.isnan(out[::4099, ::13]).any())
+    h.close()
+    del out
