@@ -197,6 +197,9 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 or 512 when B has 2^22 stored entries or more)
  *   "window"      B rows per degree-sorting window
  *   "chunks"      number of B chunks (0 = automatic)
+ *   "sort_slack"  1 (default): inside a window B's rows are sorted by their length in blocks of four
+ *                 entries, and by row number among equals (neighbouring rows then share slabs and
+ *                 their results share cache lines); 0: by their exact length
  *   "byte_counters" 1 (default): Jaccard, Dice and Russell-Rao count shared columns in byte lanes,
  *                 four staged rows to the 32-bit word; 0: through the dot product of 0/1 values
  *   "waves_per_cu" wavefronts a launch aims to keep on a compute unit: 8, 16 or 32

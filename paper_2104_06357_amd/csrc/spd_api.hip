@@ -979,6 +979,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
         if (value != 0 && value != 8 && value != 16 && value != 32)
             return fail(h, SPD_ERR_UNSUPPORTED, "waves_per_cu must be 0 (automatic), 8, 16 or 32");
         o.waves_per_cu = (int)value;
+    } else if (s == "sort_slack") {
+        if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "sort_slack must be 0 or 1");
+        o.sort_slack = (int)value;
     } else if (s == "bloom_long_rows") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "bloom_long_rows must be 0 or 1");
         o.bloom_long_rows = (int)value;

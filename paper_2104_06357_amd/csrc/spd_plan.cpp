@@ -47,6 +47,14 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     for (int64_t j = 0; j < n_rows; ++j)
         if (indptr[j + 1] < indptr[j]) return fmt("row pointers decrease at row", j);
 
+    // Rows of a window are sorted by their length in whole blocks of kScanUnroll steps (a
+    // slab's steps are a multiple of that anyway, so the coarser key costs nothing), longest first,
+    // and by row number among equals: the rows of a slab then lie closer together in B, and
+    // the 64 results of a slab's store touch fewer cache lines (a matrix whose rows hold one to
+    // four entries is written in row order).  Option sort_slack 0 sorts by the exact length.
+    const int64_t quantum = opt.sort_slack > 0 ? kScanUnroll : 1;
+    auto class_of = [quantum](int64_t len) -> int64_t { return quantum == 1 ? len : (len + 3) >> 2; };
+    static_assert(kScanUnroll == 4, "the shift above divides by kScanUnroll");
     using Long = BPlan::LongRow;
     std::vector<Long> &longs = out.longs;
     std::vector<int32_t> &order = out.order;            // short rows, window by window, longest first
@@ -66,7 +74,7 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
                 while (glog < 6 && (seg_target << glog) < len) ++glog;
                 longs.push_back({(int32_t)j, len, glog});
             } else {
-                ++bucket_count[(size_t)len];
+                ++bucket_count[(size_t)class_of(len)];
             }
         }
         // counting sort, longest first, stable in j
@@ -76,7 +84,7 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
         order.resize(base + (size_t)acc);
         for (int64_t j = w0; j < w1; ++j) {
             int64_t len = indptr[j + 1] - indptr[j];
-            if (len < T) order[base + (size_t)pos[(size_t)len]++] = (int32_t)j;
+            if (len < T) order[base + (size_t)pos[(size_t)class_of(len)]++] = (int32_t)j;
         }
         window_end.push_back((int32_t)order.size());
     }
