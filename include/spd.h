@@ -25,8 +25,9 @@
  *    through spd_set_workspace().
  *  - A handle serves one call at a time (calls on one handle from several threads must be
  *    serialised by the caller; different handles are independent).  A handle owns one helper
- *    thread, started by its first call, on which part of the planning runs, and up to three
- *    internal streams of default priority beside the caller's stream.
+ *    thread, started by its first call, on which part of the planning runs (after a call it
+ *    polls for the next one for 300 microseconds before it sleeps), and up to three internal
+ *    streams of default priority beside the caller's stream.
  *  - Stored zeros are legal and count as absent.  Values must be finite; Hellinger, KL and
  *    Jensen-Shannon expect non-negative values (anything else is undefined, and reported by
  *    spd_csr_validate()); for KL and Jensen-Shannon the quotient of two entries of one column
