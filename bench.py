@@ -44,7 +44,7 @@ def selfjoin(args):
     torch.cuda.set_device(0)
     _, B = synth.workload(args.selfjoin)
     n, k = B["n_rows"], 32
-    dB = spd.DeviceCsr.from_host(B)
+    dB = spd.DeviceCsr.from_host(B, keep_host_indptr=not args.device_row_pointers)
     h = spd.Handle()
     idx = torch.empty((args.batch, k), dtype=torch.int64, device="cuda")
     dist = torch.empty((args.batch, k), dtype=torch.float32, device="cuda")
@@ -56,7 +56,8 @@ def selfjoin(args):
         r1 = min(n, r0 + args.batch)
         lo, hi = int(B["indptr"][r0]), int(B["indptr"][r1])
         tiles.append(spd.DeviceCsr(r1 - r0, B["n_cols"], (dB.indptr[r0:r1 + 1] - lo).contiguous(),
-                                   dB.indices[lo:hi], dB.values[lo:hi]))
+                                   dB.indices[lo:hi], dB.values[lo:hi],
+                                   host_indptr=None if args.device_row_pointers else B["indptr"][r0:r1 + 1] - lo))
     h.knn(tiles[0], dB, args.metric, k, out_idx=idx[:tiles[0].n_rows], out_dist=dist[:tiles[0].n_rows])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -90,6 +91,9 @@ def main():
                          "(min,+) over the intersection and (+,|x-y|) over the union, which are not part of the step")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--device-row-pointers", action="store_true",
+                    help="give the library no host copy of the row pointers: every call then reads them "
+                         "back and waits for the stream, so calls no longer overlap")
     ap.add_argument("--serial", action="store_true",
                     help="keep every launch on one stream in the timed region too (for kernel traces)")
     ap.add_argument("--selfjoin", type=int, choices=(2, 3, 4, 5, 6), default=None,
@@ -119,7 +123,8 @@ def main():
     A, B = synth.workload(1)
     m, n = A["n_rows"], B["n_rows"]
     nnz_b = int(B["indptr"][-1])
-    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    keep = not args.device_row_pointers
+    dA, dB = spd.DeviceCsr.from_host(A, keep_host_indptr=keep), spd.DeviceCsr.from_host(B, keep_host_indptr=keep)
     h = spd.Handle()
     if args.serial:
         h.set_option("side_streams", 0)
@@ -223,7 +228,9 @@ def main():
                                                        "tropical": "semiring {plus, min} over the intersection",
                                                        "l1_semiring": "semiring {abs_diff, plus} over the union"}[x]
                                                       for x in names),
-                   "a_rows": m, "b_rows": n, "n_cols": A["n_cols"], "nnz_a": int(A["indptr"][-1]), "nnz_b": nnz_b},
+                   "a_rows": m, "b_rows": n, "n_cols": A["n_cols"], "nnz_a": int(A["indptr"][-1]), "nnz_b": nnz_b,
+                   "row_pointers": "device arrays only: read back by every call" if args.device_row_pointers
+                                   else "device arrays, with the host copies the generator holds passed beside them"},
     }
     keys = {"l1": "roofline", "cosine": "roofline_cosine", "knn": "roofline_knn_cosine"}
     for name in names:

@@ -18,9 +18,13 @@
  *    overwritten.  A and B may be the same matrix.
  *  - All functions return a status; nothing is thrown across the boundary.
  *    spd_last_error() gives a text for the last failure on the handle.
- *  - spd_pairwise / spd_knn first read the two row-pointer arrays back to the host
- *    (one stream synchronisation) to bin rows by degree, then enqueue all kernels on the
- *    handle's stream and return without waiting for them.
+ *  - spd_pairwise / spd_knn bin the rows by degree on the host.  They take the row pointers from
+ *    `host_indptr` where the caller has a host copy, and else read the device arrays back (one
+ *    stream synchronisation); then they enqueue all kernels on the handle's stream and return
+ *    without waiting for them.  With host copies of both operands a call does not wait for the
+ *    stream at all, so the planning of one call runs while the kernels of the one before it do.
+ *    A host copy that differs from the device array gives wrong results (its last entry is
+ *    checked against nnz, and no access leaves the arrays).
  *  - Scratch memory comes from the handle's own grow-only allocation, or from the caller
  *    through spd_set_workspace().
  *  - A handle serves one call at a time (calls on one handle from several threads must be
@@ -51,6 +55,8 @@ typedef struct {
     const int64_t *indptr;  /* device, n_rows+1, indptr[0]==0, non-decreasing, last==nnz */
     const int32_t *indices; /* device, nnz, strictly ascending inside a row, 0<=c<n_cols  */
     const float *values;    /* device, nnz, finite                                        */
+    const int64_t *host_indptr; /* HOST, optional (NULL if there is none): a copy of indptr in
+                                   host memory, n_rows+1, valid and unchanged during the call  */
 } spd_csr;
 
 /* Table 1 of the paper.  The comment gives the value returned for rows x, y of length k. */

@@ -33,7 +33,8 @@ class SpdError(RuntimeError):
 
 class CsrStruct(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int64), ("n_cols", ctypes.c_int64), ("nnz", ctypes.c_int64),
-                ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("values", ctypes.c_void_p)]
+                ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("values", ctypes.c_void_p),
+                ("host_indptr", ctypes.c_void_p)]
 
 
 class SemiringStruct(ctypes.Structure):
@@ -101,28 +102,37 @@ def metric_id(metric) -> int:
 
 
 class DeviceCsr:
-    """A CSR matrix whose three arrays are torch tensors on the GPU."""
+    """A CSR matrix whose three arrays are torch tensors on the GPU; `host_indptr`, if given, is
+    a host copy of the row pointers (a contiguous int64 numpy array) that spares the library
+    reading them back."""
 
-    def __init__(self, n_rows, n_cols, indptr, indices, values):
+    def __init__(self, n_rows, n_cols, indptr, indices, values, host_indptr=None):
         import torch
         assert indptr.dtype == torch.int64 and indices.dtype == torch.int32 and values.dtype == torch.float32
         assert indptr.is_cuda and indices.is_cuda and values.is_cuda
         self.n_rows, self.n_cols = int(n_rows), int(n_cols)
         self.indptr, self.indices, self.values = indptr.contiguous(), indices.contiguous(), values.contiguous()
         self.nnz = int(self.indices.numel())
+        self.host_indptr = None
+        if host_indptr is not None:
+            import numpy as np
+            self.host_indptr = np.ascontiguousarray(host_indptr, dtype=np.int64)
+            assert self.host_indptr.shape == (self.n_rows + 1,)
 
     @classmethod
-    def from_host(cls, csr: dict, device="cuda:0"):
+    def from_host(cls, csr: dict, device="cuda:0", keep_host_indptr=True):
         import torch
         return cls(csr["n_rows"], csr["n_cols"],
                    torch.from_numpy(csr["indptr"]).to(device),
                    torch.from_numpy(csr["indices"]).to(device),
-                   torch.from_numpy(csr["values"]).to(device))
+                   torch.from_numpy(csr["values"]).to(device),
+                   host_indptr=csr["indptr"] if keep_host_indptr else None)
 
     def struct(self) -> CsrStruct:
         return CsrStruct(self.n_rows, self.n_cols, self.nnz, self.indptr.data_ptr(),
                          self.indices.data_ptr() if self.nnz else None,
-                         self.values.data_ptr() if self.nnz else None)
+                         self.values.data_ptr() if self.nnz else None,
+                         self.host_indptr.ctypes.data if self.host_indptr is not None else None)
 
 
 class Handle:

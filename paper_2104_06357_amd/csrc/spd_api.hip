@@ -96,6 +96,13 @@ struct spd_handle {
     int device = 0;
     PlanOptions opt;
     std::string err;
+    // Pinned staging memory: three buffers taken in turn, so that a call may fill one while the
+    // copies of the calls before it are still waiting in the stream.  `pinned` is the one the
+    // current call holds.
+    struct PinnedSlot { void *ptr = nullptr; size_t bytes = 0; hipEvent_t done = nullptr; bool pending = false; };
+    static constexpr int kPinnedSlots = 3;
+    PinnedSlot pinned_slots[kPinnedSlots];
+    int pinned_next = 0, pinned_held = -1;
     void *pinned = nullptr;
     size_t pinned_bytes = 0;
     void *ws = nullptr;          // device scratch in use
@@ -201,6 +208,35 @@ spd_status check_call_args(spd_handle *h, const spd_csr *A, const spd_csr *B, sp
     }
     return SPD_OK;
 }
+
+// Holds one of the handle's pinned buffers for the length of a call: waits until the copies the
+// buffer's last call enqueued have run, and on the way out marks the point in the stream after
+// which it may be written again.
+struct PinnedLease {
+    spd_handle *h;
+    explicit PinnedLease(spd_handle *hh) : h(hh) {
+        const int i = h->pinned_next;
+        h->pinned_next = (i + 1) % spd_handle::kPinnedSlots;
+        spd_handle::PinnedSlot &s = h->pinned_slots[i];
+        if (s.pending) { (void)hipEventSynchronize(s.done); s.pending = false; }
+        h->pinned = s.ptr;
+        h->pinned_bytes = s.bytes;
+        h->pinned_held = i;
+    }
+    ~PinnedLease() {
+        spd_handle::PinnedSlot &s = h->pinned_slots[h->pinned_held];
+        s.ptr = h->pinned;
+        s.bytes = h->pinned_bytes;
+        if (!s.done && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) != hipSuccess) s.done = nullptr;
+        if (s.done && hipEventRecord(s.done, h->stream) == hipSuccess) s.pending = true;
+        else (void)hipStreamSynchronize(h->stream);       // no event: fall back to waiting here
+        h->pinned = nullptr;
+        h->pinned_bytes = 0;
+        h->pinned_held = -1;
+    }
+    PinnedLease(const PinnedLease &) = delete;
+    PinnedLease &operator=(const PinnedLease &) = delete;
+};
 
 spd_status ensure_pinned(spd_handle *h, size_t bytes) {
     if (bytes <= h->pinned_bytes) return SPD_OK;
@@ -373,23 +409,38 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     hipError_t e = hipSetDevice(h->device);
     if (e != hipSuccess) return hip_fail(h, e, "hipSetDevice");
 
-    // ---- row pointers to the host ---------------------------------------------------
+    // ---- row pointers on the host: the caller's copies, or read back (the call's only
+    //      synchronisation) ----------------------------------------------------------------
+    PinnedLease lease(h);
     const bool same = !index && A->indptr == B->indptr && m == n;
-    const bool copy_b = !index && !same;
-    size_t ip_bytes = (size_t)(m + 1) * 8 + (copy_b ? (size_t)(n + 1) * 8 : 0);
+    const int64_t *a_host = A->host_indptr ? A->host_indptr : (same ? B->host_indptr : nullptr);
+    const int64_t *b_host = index ? nullptr : (B->host_indptr ? B->host_indptr : (same ? A->host_indptr : nullptr));
+    const bool copy_a = !a_host;
+    const bool copy_b = !index && !same && !b_host;
+    const size_t ip_bytes = (copy_a ? (size_t)(m + 1) * 8 : 0) + (copy_b ? (size_t)(n + 1) * 8 : 0);
     // (sized for the two plan uploads as well, which follow the row pointers in the buffer)
     spd_status st = ensure_pinned(h, ip_bytes + (index ? 0 : 32 * ((size_t)n + 4096)) + 48 * ((size_t)m + 4096));
     if (st != SPD_OK) return st;
-    int64_t *a_ip = reinterpret_cast<int64_t *>(h->pinned);
-    int64_t *b_ip = same ? a_ip : a_ip + (m + 1);
-    e = hipMemcpyAsync(a_ip, A->indptr, (size_t)(m + 1) * 8, hipMemcpyDeviceToHost, h->stream);
-    if (e != hipSuccess) return hip_fail(h, e, "copy of A.indptr");
+    // where the two arrays are read from: the caller's memory, or the start of the pinned buffer
+    auto locate = [&](const int64_t *&a_at, const int64_t *&b_at) {
+        int64_t *pin = reinterpret_cast<int64_t *>(h->pinned);
+        a_at = a_host ? a_host : pin;
+        b_at = b_host ? b_host : (same ? a_at : pin + (copy_a ? m + 1 : 0));
+    };
+    const int64_t *a_ip = nullptr, *b_ip = nullptr;
+    locate(a_ip, b_ip);
+    if (copy_a) {
+        e = hipMemcpyAsync(const_cast<int64_t *>(a_ip), A->indptr, (size_t)(m + 1) * 8, hipMemcpyDeviceToHost, h->stream);
+        if (e != hipSuccess) return hip_fail(h, e, "copy of A.indptr");
+    }
     if (copy_b) {
-        e = hipMemcpyAsync(b_ip, B->indptr, (size_t)(n + 1) * 8, hipMemcpyDeviceToHost, h->stream);
+        e = hipMemcpyAsync(const_cast<int64_t *>(b_ip), B->indptr, (size_t)(n + 1) * 8, hipMemcpyDeviceToHost, h->stream);
         if (e != hipSuccess) return hip_fail(h, e, "copy of B.indptr");
     }
-    e = hipStreamSynchronize(h->stream);
-    if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+    if (copy_a || copy_b) {
+        e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+    }
     if (a_ip[m] != A->nnz || (!index && b_ip[n] != B->nnz)) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
     lap("indptr d2h");
 
@@ -457,8 +508,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         st = ensure_pinned(h, pin_a + (size_t)m * (sizeof(ARow) + 16) + (64 << 10));
         if (st != SPD_OK) return st;
         std::memcpy(h->pinned, keep.data(), ip_bytes);
-        a_ip = reinterpret_cast<int64_t *>(h->pinned);
-        b_ip = same ? a_ip : a_ip + (m + 1);
+        locate(a_ip, b_ip);
     }
     BDevice bd;
     auto stage_b = [&]() -> spd_status {
@@ -721,7 +771,10 @@ spd_status spd_destroy(spd_handle *h) {
     if (!h) return SPD_ERR_NULL;
     hipError_t e = hipStreamSynchronize(h->stream);
     (void)e;
-    if (h->pinned) (void)hipHostFree(h->pinned);
+    for (spd_handle::PinnedSlot &ps : h->pinned_slots) {
+        if (ps.ptr) (void)hipHostFree(ps.ptr);
+        if (ps.done) (void)hipEventDestroy(ps.done);
+    }
     if (h->own_ws) (void)hipFree(h->own_ws);
     if (h->flag) (void)hipFree(h->flag);
     for (auto &t : h->timed) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
@@ -855,13 +908,18 @@ spd_status spd_index_create(spd_handle *h, const spd_csr *Index, spd_metric metr
     ix->metric = (int)metric;
     ix->p = p;
     ix->device = h->device;
+    PinnedLease lease(h);
     st = ensure_pinned(h, (size_t)(n + 1) * 8 + 32 * ((size_t)n + 4096));
     if (st != SPD_OK) return st;
-    int64_t *b_ip = reinterpret_cast<int64_t *>(h->pinned);
-    e = hipMemcpyAsync(b_ip, Index->indptr, (size_t)(n + 1) * 8, hipMemcpyDeviceToHost, h->stream);
-    if (e != hipSuccess) return hip_fail(h, e, "copy of Index.indptr");
-    e = hipStreamSynchronize(h->stream);
-    if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+    const int64_t *b_ip = Index->host_indptr;
+    if (!b_ip) {
+        int64_t *pin = reinterpret_cast<int64_t *>(h->pinned);
+        e = hipMemcpyAsync(pin, Index->indptr, (size_t)(n + 1) * 8, hipMemcpyDeviceToHost, h->stream);
+        if (e != hipSuccess) return hip_fail(h, e, "copy of Index.indptr");
+        e = hipStreamSynchronize(h->stream);
+        if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+        b_ip = pin;
+    }
     if (b_ip[n] != Index->nnz) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
     std::string why;
     try {

@@ -216,6 +216,63 @@ def test_results_are_bitwise_reproducible(handle, config0):
         assert np.array_equal(a, b), metric
 
 
+def test_row_pointers_from_the_host_or_read_back(handle, spd, config0):
+    """The same results, bit for bit, whether the library reads the row pointers back or takes
+    the caller's host copies (of either operand, of both, of one matrix on both sides)."""
+    A, B, _, _ = config0
+    variants = {}
+    for ka in (True, False):
+        for kb in (True, False):
+            dA = spd.DeviceCsr.from_host(A, keep_host_indptr=ka)
+            dB = spd.DeviceCsr.from_host(B, keep_host_indptr=kb)
+            variants[(ka, kb)] = (_run_pairwise(handle, dA, dB, "l1"), handle.knn(dA, dB, "cosine", 5))
+    ref = variants[(False, False)]
+    for key, (d, (idx, dist)) in variants.items():
+        assert np.array_equal(d, ref[0]), key
+        assert np.array_equal(idx.cpu().numpy(), ref[1][0].cpu().numpy()), key
+    assert_distances_close(ref[0], oracle.pairwise(A, B, "manhattan"), "l1")
+    for keep in (True, False):
+        dM = spd.DeviceCsr.from_host(A, keep_host_indptr=keep)
+        assert_distances_close(_run_pairwise(handle, dM, dM, "l1"), oracle.pairwise(A, A, "manhattan"), "self-join")
+    # a host copy whose end does not match nnz is refused
+    bad = spd.DeviceCsr.from_host(A)
+    bad.host_indptr = bad.host_indptr.copy()
+    bad.host_indptr[-1] += 1
+    with pytest.raises(spd.SpdError) as e:
+        handle.pairwise(bad, bad, "l1")
+    assert e.value.status_name == "SPD_ERR_BAD_CSR"
+
+
+def test_calls_in_flight_behind_one_another(spd):
+    """With host copies of the row pointers a call returns without waiting for the stream: twelve
+    calls with different operands, metrics and sizes are enqueued back to back (more than the
+    handle has staging buffers) before any result is looked at."""
+    import torch
+    h = spd.Handle()
+    c0a, c0b = synth.workload(0)
+    wa, wb = _wide_pair(False)
+    edge = _edge_matrices(False)
+    c1a, c1b = synth.workload(1, scale=0.05)
+    mats = [c0a, c0b, wa, wb, edge, c1a, c1b]
+    dev = [spd.DeviceCsr.from_host(m) for m in mats]
+    pairs = [(0, 1), (2, 3), (4, 4), (5, 6), (1, 0), (3, 2), (6, 5), (0, 0), (5, 5), (2, 2), (1, 1), (6, 6)]
+    jobs = []
+    for t, (i, j) in enumerate(pairs):
+        metric = ("l1", "cosine", "jensen_shannon", "jaccard")[t % 4]
+        if t % 3 == 2:
+            jobs.append((i, j, metric, "knn", h.knn(dev[i], dev[j], metric, 3)))
+        else:
+            jobs.append((i, j, metric, "pairwise", h.pairwise(dev[i], dev[j], metric)))
+    torch.cuda.synchronize()
+    for i, j, metric, kind, got in jobs:
+        want = oracle.pairwise(mats[i], mats[j], ORACLE_NAME[metric])
+        if kind == "knn":
+            assert_knn_matches(got[0].cpu().numpy(), got[1].cpu().numpy(), want, 3, metric, "queued %s" % metric)
+        else:
+            assert_distances_close(got.cpu().numpy(), want, "queued %s" % metric)
+    h.close()
+
+
 # ------------------------------------------------------------------ config 1: sampled pairs
 def _sample_rows(csr, n, rng):
     deg = np.diff(csr["indptr"])
