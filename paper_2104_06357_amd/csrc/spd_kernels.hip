@@ -16,18 +16,21 @@ namespace spd {
 // ------------------------------------------------------------------------------------
 constexpr int kPackTile = 16;       // steps of a slab that pass through LDS together
 
-__global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restrict__ b_indptr,
+// kPackWaves: wavefronts of a workgroup, which take the slab's tiles in turn (8 for a B of few
+// slabs, where the longest slab sets the time; 4 otherwise, so that more slabs run at once).
+template <int kPackWaves>
+__global__ void __launch_bounds__(kPackWaves * kWave) spd_pack_b_kernel(const int64_t *__restrict__ b_indptr,
                                                          const int32_t *__restrict__ b_indices,
                                                          const float *__restrict__ b_values, BDevice b,
                                                          uint2 *__restrict__ packed, double *__restrict__ norms,
                                                          int metric, int transform, int norm, float p, double k,
                                                          uint32_t padcol) {
-    // One workgroup per slab, its four wavefronts taking the slab's tiles of 16 steps in turn.
+    // One workgroup per slab, its wavefronts taking the slab's tiles of 16 steps in turn.
     // The CSR rows are read along the rows (16 consecutive entries of a row per quarter
     // wavefront: a cache line) into an LDS tile and written out along the steps (the 64 lanes'
     // entries of one step are 512 contiguous bytes): both sides coalesced.
-    __shared__ uint2 s_tile[4][kPackTile][kWave];
-    __shared__ double s_sums[4][kWave][2];
+    __shared__ uint2 s_tile[kPackWaves][kPackTile][kWave];
+    __shared__ double s_sums[kPackWaves][kWave][2];
     const int lane = (int)threadIdx.x & 63, wave = (int)threadIdx.x >> 6;
     const int s = (int)blockIdx.x;
     const size_t at = (size_t)s * kWave + lane;
@@ -40,7 +43,7 @@ __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restri
     uint2 (*tile)[kWave] = s_tile[wave];
     const int quarter = lane / kPackTile, within = lane % kPackTile;
     double s0 = 0.0, s1 = 0.0;
-    for (int t0 = wave * kPackTile; t0 < steps; t0 += 4 * kPackTile) {
+    for (int t0 = wave * kPackTile; t0 < steps; t0 += kPackWaves * kPackTile) {
         // fixed trip counts, so that all of a tile's loads are in flight together
         uint2 got[kPackTile];
 #pragma unroll
@@ -79,8 +82,9 @@ __global__ void __launch_bounds__(256) spd_pack_b_kernel(const int64_t *__restri
     s_sums[wave][lane][1] = s1;
     __syncthreads();
     if (wave != 0) return;
-    s0 = (s_sums[0][lane][0] + s_sums[1][lane][0]) + (s_sums[2][lane][0] + s_sums[3][lane][0]);
-    s1 = (s_sums[0][lane][1] + s_sums[1][lane][1]) + (s_sums[2][lane][1] + s_sums[3][lane][1]);
+    s0 = 0.0; s1 = 0.0;
+#pragma unroll
+    for (int w = 0; w < kPackWaves; ++w) { s0 += s_sums[w][lane][0]; s1 += s_sums[w][lane][1]; }
     if (b.slab_split[s]) {
 #pragma unroll
         for (int step = 0; step < 6; ++step) {
@@ -101,8 +105,12 @@ hipError_t launch_pack_b(hipStream_t st, const int64_t *b_indptr, const int32_t 
                          int norm, float p, double k, uint32_t padcol) {
     if (b.n_slabs <= 0) return hipSuccess;
     dim3 grid((unsigned)b.n_slabs);
-    hipLaunchKernelGGL(spd_pack_b_kernel, grid, dim3(256), 0, st, b_indptr, b_indices, b_values, b, packed_out,
-                       norms_out, metric, transform, norm, p, k, padcol);
+    if (b.n_slabs <= 1024)
+        hipLaunchKernelGGL(spd_pack_b_kernel<8>, grid, dim3(8 * kWave), 0, st, b_indptr, b_indices, b_values, b, packed_out,
+                           norms_out, metric, transform, norm, p, k, padcol);
+    else
+        hipLaunchKernelGGL(spd_pack_b_kernel<4>, grid, dim3(4 * kWave), 0, st, b_indptr, b_indices, b_values, b, packed_out,
+                           norms_out, metric, transform, norm, p, k, padcol);
     return hipGetLastError();
 }
 
