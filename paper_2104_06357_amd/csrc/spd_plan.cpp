@@ -465,6 +465,21 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
             }
         }
     }
+    // A launch of a few groups costs as much time as one of a few hundred: a small class joins
+    // the class of the same R that needs more LDS, if there is one
+    constexpr int kFewGroups = 32;
+    for (int q = 0; q < 6; ++q)
+        for (int b = 0; b < 2; ++b) {
+            AClass &from = *by_key[q][b];
+            if (from.n_groups == 0 || from.n_groups >= kFewGroups) continue;
+            AClass *to = nullptr;
+            for (int b2 = b + 1; b2 < 3 && !to; ++b2) if (by_key[q][b2]->n_groups) to = by_key[q][b2];
+            if (!to) continue;
+            to->rows.insert(to->rows.end(), from.rows.begin(), from.rows.end());
+            to->sumlen.insert(to->sumlen.end(), from.sumlen.begin(), from.sumlen.end());
+            to->n_groups += from.n_groups;
+            from.rows.clear(); from.sumlen.clear(); from.n_groups = 0;
+        }
     for (int q = 0; q < 6; ++q)
         for (int b = 0; b < 3; ++b)
             if (by_key[q][b]->n_groups) { finish_class(*by_key[q][b]); out.classes.push_back(std::move(*by_key[q][b])); }
