@@ -326,6 +326,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     constexpr bool kCnt = (OP == OP_CNT);          // set metrics: one byte of the table per staged row
     constexpr int W = table_words(OP, R);          // 4-byte words per slot of the value table
     static_assert(!kCnt || (R % 4 == 0), "byte counters come four to the word");
+    static_assert(kTopRanks == 32, "a pair's visited ranks are the bits of one 32-bit word");
     static_assert(KIND != KIND_BLOOM || (R == 1 && bloom_serves(OP)), "a Bloom-staged row is alone in its workgroup");
     constexpr int U = kScanUnroll;
     extern __shared__ __align__(16) unsigned char dyn[];
@@ -693,8 +694,10 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
 #pragma unroll
                         for (int r = 0; r < R; ++r) {
                             if (entry.x - row_clo[r] <= row_cspan[r]) visit_with<OP, P, kUnion>(acc[r], a.v[r], bv, args.q);
-                            uint32_t q = rk[r];
-                            hit[r] |= (q < (uint32_t)kTopRanks) ? (1u << q) : 0u;
+                            // a ranked entry's byte is its rank (below 32), any other byte is 255: a
+                            // 64-bit one shifted by the byte's low six bits lands beyond bit 31 for those
+                            const uint32_t q = rk[r];
+                            hit[r] |= (uint32_t)(1ull << (q & 63u));
                         }
                     } else {
 #pragma unroll
