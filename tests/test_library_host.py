@@ -165,3 +165,29 @@ def test_planner_on_the_large_shapes(config, scale):
         assert s["spilled_rows"] == 0
         h = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], metric, force_kind=3)
         assert h["spilled_rows"] >= 1 and h["partial_slots"] >= 2
+
+
+def test_planner_sort_key_small_classes_and_bloom_rows():
+    A, B = synth.workload(1)
+    # sorting B's rows by whole blocks of four steps costs no step, and keeps equal rows in row order
+    exact = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine", sort_slack=0)
+    blocks = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine", sort_slack=1)
+    assert blocks["total_slab_steps"] == exact["total_slab_steps"] and blocks["slabs"] == exact["slabs"]
+    # a class of a few groups joins the class of the same R that needs more LDS: four launches, not five
+    assert sorted((c["R"], c["groups"]) for c in blocks["classes"]) == [(2, 28), (4, 24), (8, 29), (8, 1202)]
+    assert sum(c["R"] * c["groups"] for c in blocks["classes"]) >= A["n_rows"]
+    # Bloom staging: every row alone, or only the rows that would have been cut into slices
+    s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "l1", force_kind=4)
+    assert [(c["kind"], c["R"], c["groups"]) for c in s["classes"]] == [(4, 1, A["n_rows"])]
+    assert all(c["lds_bytes"] <= 65536 for c in s["classes"])
+    with pytest.raises(spd.SpdError):
+        spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "chebyshev", force_kind=4)
+    tight = dict(force_kind=3, lds_budget=8192 + 65536)
+    long_rows = int((np.diff(A["indptr"]) > 2048).sum())
+    sliced = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "l1", **tight)
+    assert sliced["spilled_rows"] == long_rows == 0 or sliced["spilled_rows"] == long_rows
+    ip = np.array([0, 5, 3005, 3010, 9010], dtype=np.int64)                  # rows of 5, 3000, 5, 6000 entries
+    sliced = spd.host_plan_summary(ip, ip, 10000, "l1", **tight)
+    filtered = spd.host_plan_summary(ip, ip, 10000, "l1", bloom_long_rows=1, **tight)
+    assert sliced["spilled_rows"] == 2 and filtered["spilled_rows"] == 0
+    assert sorted(c["kind"] for c in filtered["classes"]) == [3, 4]
