@@ -114,7 +114,7 @@ struct spd_handle {
     bool profile = false;
     bool check_plan = false;
     bool no_byte_counters = false;   // option "byte_counters" 0: set metrics through the dot product
-    int side_streams = 2;        // option "side_streams": how many internal streams the small launches may use beside the large one
+    int side_streams = 3;        // option "side_streams": how many internal streams the small launches may use beside the large one
     static constexpr int kSideStreams = 3;
     hipStream_t side[kSideStreams] = {nullptr, nullptr, nullptr};
     hipEvent_t fork_event = nullptr, join_event[kSideStreams] = {nullptr, nullptr, nullptr};     // full consistency check of every plan before launching

@@ -2,6 +2,7 @@
 #include "spd_plan.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <numeric>
 
 namespace spd {
@@ -192,7 +193,7 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
     if (nc <= 0) {
         // Model of the launch time in slab steps: workgroups run in rounds over the chip's
         // slots; each stages its rows, then its wavefronts share the chunk's slabs, the
-        // last one finishing up to half a slab after the others.
+        // last one finishing up to a quarter of a slab after the others.
         const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(opt.lds_budget / ((int64_t)c.lds_bytes + kStaticLds),
                                                                       (int64_t)32 / waves));
         const int64_t slots = (int64_t)opt.n_cus * per_cu;
@@ -205,7 +206,8 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
         for (int cand = 1; cand <= max_nc; cand = cand < 8 ? cand + 1 : cand + 8) {
             int64_t wgs = (int64_t)c.n_groups * cand;
             double rounds = (double)((wgs + slots - 1) / slots);
-            double per_wg = stage + (double)total / cand / waves + 0.5 * (double)longest;
+            // (a wavefront works its slab alone: no chunk is done before its longest slab is)
+            double per_wg = stage + std::max((double)total / cand / waves, (double)longest) + 0.25 * (double)longest;
             double t = rounds * per_wg;
             if (best < 0.0 || t < best * 0.98) { best = t; nc = cand; }
         }
