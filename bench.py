@@ -241,8 +241,9 @@ def main():
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
             measured = json.load(f)
-        for key in ("roofline", "roofline_cosine"):
-            if key in line and key in measured:
+        for name in names:
+            key = keys.get(name, "roofline_" + name)
+            if key in measured:
                 line[key]["traffic"] = measured[key]
 
     if not args.no_cpu_baseline:
@@ -252,10 +253,19 @@ def main():
         for metric in ("manhattan", "cosine", "euclidean", "chebyshev", "minkowski"):
             _, used = oracle.pairwise(A, B, metric, 3.0, return_threads=True)
         cpu_s = time.perf_counter() - t1
+        # the same five metrics on one thread, over the first 200 rows of A
+        one_rows = np.arange(min(200, m))
+        t1 = time.perf_counter()
+        for metric in ("manhattan", "cosine", "euclidean", "chebyshev", "minkowski"):
+            oracle.pairwise(A, B, metric, 3.0, rows_a=one_rows, threads=1)
+        one_s = time.perf_counter() - t1
         line["cpu_baseline"] = {
             "value": 5.0 * m * n / cpu_s, "unit": "row-pairs/s", "cores": int(used), "kind": "oracle",
             "sample": "all 10000 x 10000 row pairs of configs[1] for its five metrics (L1, cosine, L2, Chebyshev, "
-                      "Minkowski p=3), support-restricted fp64 oracle, %.1f s of wall time" % cpu_s}
+                      "Minkowski p=3), support-restricted fp64 oracle, %.1f s of wall time" % cpu_s,
+            "one_thread": {"value": 5.0 * one_rows.size * n / one_s, "unit": "row-pairs/s", "cores": 1,
+                           "sample": "the first %d rows of A against all of B, the same five metrics, %.1f s"
+                                     % (one_rows.size, one_s)}}
     print(json.dumps(line))
 
 
