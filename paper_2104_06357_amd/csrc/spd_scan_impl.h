@@ -794,6 +794,11 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         // distances of up to 32 rows in registers together).
         constexpr bool kThreeSums = (OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_SEMI_SUM);
         constexpr int RB = R < 8 ? R : ((KNN && R >= 16) || kThreeSums ? 4 : 8);
+        // k-NN: the workgroup's bounds of all R rows are read and decoded once per slab, row r's in
+        // lane r (a wavefront publishes its own list's k-th distance there as soon as it has one,
+        // so the shared bound is never looser than the list's own)
+        float tau_of_lane = 0.0f;
+        if constexpr (KNN) tau_of_lane = float_from_order_key(s_tau[lane < R ? lane : 0]);
 #pragma unroll
         for (int r0 = 0; r0 < R; r0 += RB) {
             double v0[RB], v1[RB], v2[RB];
@@ -851,7 +856,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                 for (int i = 0; i < RB; ++i) {
                     const int r = r0 + i;
                     if (row_out[r] < 0) continue;
-                    const float bound = float_from_order_key(s_tau[r]);
+                    const float bound = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tau_of_lane), r));
+                    if (__ballot(leader && dist[i] <= bound) == 0) continue;      // the usual case once the lists are warm
                     if (lists[r].offer(dist[i], row, leader, args.knn_k, bound)) {
                         lists_changed = true;
                         if (lists[r].full(args.knn_k) && lane == 0)
