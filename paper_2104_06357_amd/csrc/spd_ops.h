@@ -547,10 +547,20 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
         // counts below 2^24 are exact in fp32, and a correctly rounded fp32 quotient is well inside
         // the tolerance and the same for equal ratios (pairs that tie exactly stay tied): the
         // 64-bit division is kept for rows beyond that
+        // (with fewer than 2^23 columns every count and the union's size are exact in fp32, and
+        // the question is settled once per launch, not once per pair)
+        if (q.k < 8388608.0) {
+            const float vf = (float)v, uf = ((float)a0 + (float)b0) - vf;
+            return uf == 0.0f ? 0.0f : 1.0f - vf / uf;
+        }
         double u = a0 + b0 - v;
         if (u < 16777216.0) { float uf = (float)u; return uf == 0.0f ? 0.0f : 1.0f - (float)v / uf; }
         return (float)(1.0 - v / u);
     } else if constexpr (MT == MT_DICE) {
+        if (q.k < 4194304.0) {
+            const float tf = (float)a0 + (float)b0;
+            return tf == 0.0f ? 0.0f : 1.0f - (2.0f * (float)v) / tf;
+        }
         double t = a0 + b0;
         if (t < 8388608.0) { float tf = (float)t; return tf == 0.0f ? 0.0f : 1.0f - (2.0f * (float)v) / tf; }
         return (float)(1.0 - 2.0 * v / t);
