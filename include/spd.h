@@ -213,7 +213,9 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 (0 = automatic: 32, or 16 for the fused k-NN kernels)
  *   "side_streams" how many internal streams (0 to 3; default 3) the launches that are small against
  *                 the call's largest one may use beside it, forked and joined with events so that
- *                 the handle's stream still orders the whole call (0: everything on the handle's stream)
+ *                 the handle's stream still orders the whole call (0: everything on the handle's stream);
+ *                 they are used when the largest launch is short or the small ones hold a tenth of
+ *                 the call's sweeps over B, and not otherwise
  *   "check_plan"  1: verify every index the kernels will form from the plan before launching
  *   "profile"     1: bracket every kernel launch with HIP events (see spd_profile_read)
  * Unknown names or values out of range return SPD_ERR_UNSUPPORTED. */

@@ -638,9 +638,20 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         auto small = [&](size_t ci) {
             return ci != main_class && (int64_t)ap.classes[ci].n_groups * ap.classes[ci].R * 4 <= best;
         };
+        // ... and only if the small launches are worth hiding.  Beside a long launch over a large B,
+        // a few workgroups that sweep B in an order of their own cost more (config 3: 6 % of the
+        // call, the pairwise calls of config 2: 13 %) than the time they would take in line.  They
+        // are worth it when the large launch is short (by the planner's estimate: under some 2 ms),
+        // so that what a launch costs beside its sweep counts, or when they hold a tenth or more of
+        // the call's sweeps over B (a group's sweep weighed by its rows plus the column lookup).
+        auto sweeps = [&](size_t ci) { return (double)ap.classes[ci].n_groups * (3.0 + ap.classes[ci].R); };
         int n_small = 0;
-        for (size_t ci = 0; ci < ap.classes.size(); ++ci) n_small += small(ci) ? 1 : 0;
-        if (h->side_streams > 0 && n_small > 0) {
+        double small_sweeps = 0.0;
+        for (size_t ci = 0; ci < ap.classes.size(); ++ci)
+            if (small(ci)) { ++n_small; small_sweeps += sweeps(ci); }
+        const bool worth = !ap.classes.empty() &&
+                           (ap.classes[main_class].cost < 8000.0 || small_sweeps * 10.0 >= sweeps(main_class));
+        if (h->side_streams > 0 && n_small > 0 && worth) {
             const int want = std::min<int>(h->side_streams, n_small);
             for (int q = 0; q < want; ++q) {
                 if (!h->side[q] && hipStreamCreateWithFlags(&h->side[q], hipStreamNonBlocking) != hipSuccess) { h->side[q] = nullptr; break; }

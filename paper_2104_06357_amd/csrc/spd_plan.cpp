@@ -190,29 +190,33 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
     for (int32_t s : b.slab_steps) { total += std::max(1, s); longest = std::max<int64_t>(longest, s); }
     const int waves = std::max(1, c.block / kWave);
     int nc = opt.chunks;
+    // Model of the launch time in slab steps: workgroups run in rounds over the chip's
+    // slots; each stages its rows, then its wavefronts share the chunk's slabs, the
+    // last one finishing up to a quarter of a slab after the others.
+    const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(opt.lds_budget / ((int64_t)c.lds_bytes + kStaticLds),
+                                                                  (int64_t)32 / waves));
+    const int64_t slots = (int64_t)opt.n_cus * per_cu;
+    const double stage = 24.0;
+    auto model = [&](int cand) {
+        const int64_t wgs = (int64_t)c.n_groups * cand;
+        const double rounds = (double)((wgs + slots - 1) / slots);
+        // (a wavefront works its slab alone: no chunk is done before its longest slab is)
+        const double per_wg = stage + std::max((double)total / cand / waves, (double)longest) + 0.25 * (double)longest;
+        return rounds * per_wg;
+    };
     if (nc <= 0) {
-        // Model of the launch time in slab steps: workgroups run in rounds over the chip's
-        // slots; each stages its rows, then its wavefronts share the chunk's slabs, the
-        // last one finishing up to a quarter of a slab after the others.
-        const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(opt.lds_budget / ((int64_t)c.lds_bytes + kStaticLds),
-                                                                      (int64_t)32 / waves));
-        const int64_t slots = (int64_t)opt.n_cus * per_cu;
-        const double stage = 24.0;
         // more workgroups than four per slot buy nothing
         const int64_t useful = 4 * slots / std::max(1, c.n_groups) + 1;
         const int max_nc = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(4096, useful), b.n_slabs / waves));
         double best = -1.0;
         nc = 1;
         for (int cand = 1; cand <= max_nc; cand = cand < 8 ? cand + 1 : cand + 8) {
-            int64_t wgs = (int64_t)c.n_groups * cand;
-            double rounds = (double)((wgs + slots - 1) / slots);
-            // (a wavefront works its slab alone: no chunk is done before its longest slab is)
-            double per_wg = stage + std::max((double)total / cand / waves, (double)longest) + 0.25 * (double)longest;
-            double t = rounds * per_wg;
+            const double t = model(cand);
             if (best < 0.0 || t < best * 0.98) { best = t; nc = cand; }
         }
     }
     c.n_chunks = nc;
+    c.cost = model(nc);
     c.chunk_begin.assign((size_t)nc + 1, b.n_slabs);
     c.chunk_begin[0] = 0;
     int64_t run = 0;

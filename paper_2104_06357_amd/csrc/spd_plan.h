@@ -177,6 +177,7 @@ struct AClass {
     std::vector<int32_t> sumlen;    // n_groups
     int n_chunks = 0;               // how this launch cuts B's slabs (plan_chunks)
     std::vector<int32_t> chunk_begin;   // n_chunks + 1 slab indices
+    double cost = 0.0;              // plan_chunks' estimate of the launch's time, in slab steps of one wavefront
     int pool_slot = 0;              // where the planner keeps this class's buffers between calls
 };
 

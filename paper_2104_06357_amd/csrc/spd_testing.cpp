@@ -122,11 +122,11 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
         const AClass &c = ap.classes[i];
         int64_t max_sum = 0;
         for (int32_t s : c.sumlen) max_sum = std::max<int64_t>(max_sum, s);
-        char buf[256];
+        char buf[320];
         std::snprintf(buf, sizeof buf,
                       "%s{\"R\": %d, \"kind\": %d, \"block\": %d, \"lds_bytes\": %u, \"groups\": %d, \"max_sumlen\": %lld, "
-                      "\"chunks\": %d}",
-                      i ? ", " : "", c.R, c.kind, c.block, c.lds_bytes, c.n_groups, (long long)max_sum, c.n_chunks);
+                      "\"chunks\": %d, \"cost\": %.1f}",
+                      i ? ", " : "", c.R, c.kind, c.block, c.lds_bytes, c.n_groups, (long long)max_sum, c.n_chunks, c.cost);
         js += buf;
     }
     int64_t split_rows = 0, max_steps = 0, total_steps = 0;

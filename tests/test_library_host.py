@@ -176,6 +176,10 @@ def test_planner_sort_key_small_classes_and_bloom_rows():
     # a class of a few groups joins the class of the same R that needs more LDS: four launches, not five
     assert sorted((c["R"], c["groups"]) for c in blocks["classes"]) == [(2, 28), (4, 24), (8, 29), (8, 1202)]
     assert sum(c["R"] * c["groups"] for c in blocks["classes"]) >= A["n_rows"]
+    # the cost model's estimates: the large launch far above the small ones, a few groups of long rows get 2 chunks
+    by_groups = sorted(blocks["classes"], key=lambda c: c["groups"])
+    assert by_groups[-1]["cost"] > 3 * max(c["cost"] for c in by_groups[:-1]) > 0
+    assert all(c["chunks"] <= 2 for c in by_groups[:-1])
     # Bloom staging: every row alone, or only the rows that would have been cut into slices
     s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "l1", force_kind=4)
     assert [(c["kind"], c["R"], c["groups"]) for c in s["classes"]] == [(4, 1, A["n_rows"])]
