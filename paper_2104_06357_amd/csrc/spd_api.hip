@@ -836,15 +836,17 @@ size_t workspace_bound(const spd_handle *h, const spd_csr *A, const spd_csr *B, 
                     64 * (size_t)std::max(2, split_len) * (n / window + 8) + 64 * (size_t)kScanUnroll * slabs;
     add(padded * 8); add(n * 16); add((slabs + 1) * 8); add(slabs * 4); add(slabs);
     add(lanes * 8); add(lanes * 4); add(lanes * 4); add(lanes); add(chunk_words * 4); total += launches * 256;
-    add((m + slices + 16 * 6) * sizeof(ARow)); add((m + slices + 6) * 4); total += 12 * 256;
+    // (a group may leave a quarter of its places empty: up to a third more places than rows)
+    const size_t places = m + slices + (m + slices) / 3 + 32 * 6;
+    add(places * sizeof(ARow)); add((m + slices + 6) * 4); total += 12 * 256;
     add(slices * sizeof(SpilledRow));
     // partial results exist only for sliced rows; a row needs slicing only above ~9,000 entries
     size_t sliced_rows_max = (size_t)A->nnz / 4096 + 1;
     size_t partial_slots = std::min(slices, 2 * sliced_rows_max + (size_t)A->nnz / 4096);
     add(partial_slots * planes * n * 8); add(partial_slots * 16);
     if (k_neighbors > 0) {
-        size_t lists = o.chunks > 0 ? (m + 16 * launches) * (size_t)o.chunks
-                                    : launches * 16 * (16 * (size_t)o.n_cus + 1) + m + 16 * launches;
+        size_t lists = o.chunks > 0 ? (m + m / 3 + 16 * launches) * (size_t)o.chunks
+                                    : launches * 16 * (16 * (size_t)o.n_cus + 1) + m + m / 3 + 16 * launches;
         lists += std::min(sliced_rows_max, m) * (n / (size_t)kFinalizeTile + 1);     // the tiles of spilled rows
         add(lists * (size_t)k_neighbors * sizeof(KnnEntry)); add(m * 8); add(m * 4);
     }
@@ -1051,6 +1053,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "sort_slack") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "sort_slack must be 0 or 1");
         o.sort_slack = (int)value;
+    } else if (s == "partial_groups") {
+        if (value < 0 || value > 2) return fail(h, SPD_ERR_UNSUPPORTED, "partial_groups must be 0, 1 or 2");
+        o.partial_groups = (int)value;
     } else if (s == "bloom_long_rows") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "bloom_long_rows must be 0 or 1");
         o.bloom_long_rows = (int)value;

@@ -449,12 +449,37 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     while (t < items.size()) {
         size_t remaining = items.size() - t;
         int R = max_r;
-        while (R > min_r && (size_t)(R / 2) >= remaining) R /= 2;
+        // (the last few items take a smaller group only where that opens no launch of its own)
+        auto in_use = [&](int r) {
+            int q = 0;
+            while ((32 >> q) != r) ++q;
+            return by_key[q][0]->n_groups + by_key[q][1]->n_groups + by_key[q][2]->n_groups > 0;
+        };
+        while (R > min_r && remaining < (size_t)R) {
+            const bool half_holds_them = (size_t)(R / 2) >= remaining;
+            if (half_holds_them ? (in_use(R / 2) || !in_use(R)) : (!in_use(R) && in_use(R / 2))) R /= 2;
+            else break;
+        }
         for (;; R /= 2) {
             size_t n = std::min<size_t>((size_t)R, remaining);
             uint64_t sum = 0;
             for (size_t q = 0; q < n; ++q) sum += (uint64_t)items[t + q].len;
-            if (fits_group(R, sum) || R == min_r) {
+            bool take = fits_group(R, sum) || R == min_r;
+            const bool cheap_visit = op == OP_DOT || op == OP_L1 || op == OP_HAMM;   // two or three instructions
+            if (!take && opt.partial_groups && n == (size_t)R && R >= 4 &&
+                (op == OP_CNT || (cheap_visit && R <= opt.partial_groups * 4))) {
+                // Three rows out of four per sweep of B still beat two: where R rows are too much
+                // for the LDS but three quarters of them are not, the group keeps its size and
+                // leaves places empty.  It pays while the idle places' arithmetic is small against
+                // what a step costs anyway (the lookup, the loads): for the products of two or
+                // three instructions at R = 4, and at any R for the set metrics, whose visits are
+                // a byte add.
+                const size_t n3 = (size_t)(R - R / 4);
+                uint64_t s3 = 0;
+                for (size_t q = 0; q < n3; ++q) s3 += (uint64_t)items[t + q].len;
+                if (fits_group(R, s3)) { n = n3; sum = s3; take = true; }
+            }
+            if (take) {
                 // the smallest group may have to leave places empty (longest items come first)
                 while (n > 1 && !fits_group(R, sum)) sum -= (uint64_t)items[t + --n].len;
                 if (!fits_group(R, sum)) return "internal: slice does not fit";

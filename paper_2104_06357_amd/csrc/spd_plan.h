@@ -52,6 +52,7 @@ struct PlanOptions {
     int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32, or 16 for k-NN)
     int bloom_long_rows = 0;                // 1: a row too long for the LDS gets a Bloom filter instead of slices
     int sort_slack = 1;                     // 1: B's rows are sorted by length in whole blocks of steps, 0: by exact length
+    int partial_groups = 1;                 // 1: a group of R rows may leave a quarter of its places empty rather than fall to R/2
 };
 
 // Bloom staging: filter bits per stored entry (two hash functions: ~1.4 % false positives), and

@@ -87,6 +87,8 @@ def _case(seed):
         options["side_streams"] = int(rng.choice([0, 1, 3]))
     if rng.random() < 0.2:
         options["sort_slack"] = 0
+    if rng.random() < 0.3:
+        options["partial_groups"] = int(rng.choice([0, 2]))
     knn_k = int(rng.choice([1, 3, 17, 64]))
     p = float(rng.choice([0.5, 1.0, 2.0, 3.0, 3.5]))
     via_index = (not semiring) and rng.random() < 0.3
