@@ -209,9 +209,9 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 their results share cache lines); 0: by their exact length
  *   "partial_groups" 1 (default): where 4 rows of A are too much for the LDS but 3 are not, they
  *                 are staged as a group of 4 with a place left empty instead of two groups of 2
- *                 (products of two or three instructions per visit; for the set metrics at any
- *                 group size, three quarters filled); 2: also 6 rows in a group of 8; 0: a group
- *                 is full or halved
+ *                 (not for Chebyshev and the semirings with sum() = min or max; for the set
+ *                 metrics at any group size, three quarters filled); 2: also 6 rows in a group
+ *                 of 8 for the dot product, L1 and Hamming; 0: a group is full or halved
  *   "byte_counters" 1 (default): Jaccard, Dice and Russell-Rao count shared columns in byte lanes,
  *                 four staged rows to the 32-bit word; 0: through the dot product of 0/1 values
  *   "waves_per_cu" wavefronts a launch aims to keep on a compute unit: 8, 16 or 32

@@ -466,14 +466,14 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
             for (size_t q = 0; q < n; ++q) sum += (uint64_t)items[t + q].len;
             bool take = fits_group(R, sum) || R == min_r;
             const bool cheap_visit = op == OP_DOT || op == OP_L1 || op == OP_HAMM;   // two or three instructions
-            if (!take && opt.partial_groups && n == (size_t)R && R >= 4 &&
-                (op == OP_CNT || (cheap_visit && R <= opt.partial_groups * 4))) {
+            if (!take && opt.partial_groups && n == (size_t)R &&
+                (op == OP_CNT || (R == 4 && !cheb) || (R == 8 && cheap_visit && opt.partial_groups == 2))) {
                 // Three rows out of four per sweep of B still beat two: where R rows are too much
                 // for the LDS but three quarters of them are not, the group keeps its size and
                 // leaves places empty.  It pays while the idle places' arithmetic is small against
-                // what a step costs anyway (the lookup, the loads): for the products of two or
-                // three instructions at R = 4, and at any R for the set metrics, whose visits are
-                // a byte add.
+                // what a step costs anyway (the lookup, the loads): in groups of four (measured for
+                // every product; not where sum() = max, whose idle place still ranks its column),
+                // and at any size for the set metrics, whose visits are a byte add.
                 const size_t n3 = (size_t)(R - R / 4);
                 uint64_t s3 = 0;
                 for (size_t q = 0; q < n3; ++q) s3 += (uint64_t)items[t + q].len;

@@ -178,10 +178,13 @@ def test_planner_sort_key_small_classes_and_bloom_rows():
     assert sorted((c["R"], c["groups"]) for c in blocks["classes"]) == [(4, 43), (8, 29), (8, 1202)]
     halved = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine", partial_groups=0)
     assert sorted((c["R"], c["groups"]) for c in halved["classes"]) == [(2, 28), (4, 24), (8, 29), (8, 1202)]
-    # the expensive products keep full groups: idle places would cost more than the sweeps saved
+    # Chebyshev keeps full groups: an idle place there still ranks its column
+    ch = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "chebyshev")
+    ch0 = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "chebyshev", partial_groups=0)
+    assert [(c["R"], c["groups"]) for c in ch["classes"]] == [(c["R"], c["groups"]) for c in ch0["classes"]]
     js = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "jensen_shannon")
     js0 = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "jensen_shannon", partial_groups=0)
-    assert [(c["R"], c["groups"]) for c in js["classes"]] == [(c["R"], c["groups"]) for c in js0["classes"]]
+    assert sum(c["groups"] for c in js["classes"]) < sum(c["groups"] for c in js0["classes"])
     assert sum(c["R"] * c["groups"] for c in blocks["classes"]) >= A["n_rows"]
     # the cost model's estimates: the large launch far above the small ones, a few groups of long rows get 2 chunks
     by_groups = sorted(blocks["classes"], key=lambda c: c["groups"])
