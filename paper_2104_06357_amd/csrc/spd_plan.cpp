@@ -2,7 +2,6 @@
 #include "spd_plan.h"
 
 #include <algorithm>
-#include <cstdlib>
 #include <numeric>
 
 namespace spd {
