@@ -189,8 +189,8 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
     for (int32_t s : b.slab_steps) { total += std::max(1, s); longest = std::max<int64_t>(longest, s); }
     const int waves = std::max(1, c.block / kWave);
     int nc = opt.chunks;
-    // Model of the launch time in slab steps: workgroups run in rounds over the chip's
-    // slots; each stages its rows, then its wavefronts share the chunk's slabs, the
+    // Model of the launch time in slab steps: workgroups pass over the chip's slots in
+    // rounds; each stages its rows, then its wavefronts share the chunk's slabs, the
     // last one finishing up to a quarter of a slab after the others.
     const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(opt.lds_budget / ((int64_t)c.lds_bytes + kStaticLds),
                                                                   (int64_t)32 / waves));
@@ -198,7 +198,9 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
     const double stage = 24.0;
     auto model = [&](int cand) {
         const int64_t wgs = (int64_t)c.n_groups * cand;
-        const double rounds = (double)((wgs + slots - 1) / slots);
+        // (workgroups do not run in lockstep: beyond one round the chip's slots are refilled as
+        // they come free, and what is left of whole rounds is half a round on average)
+        const double rounds = wgs <= slots ? 1.0 : (double)wgs / (double)slots + 0.5;
         // (a wavefront works its slab alone: no chunk is done before its longest slab is)
         const double per_wg = stage + std::max((double)total / cand / waves, (double)longest) + 0.25 * (double)longest;
         return rounds * per_wg;
