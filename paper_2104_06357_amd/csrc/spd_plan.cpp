@@ -196,11 +196,15 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
                                                                   (int64_t)32 / waves));
     const int64_t slots = (int64_t)opt.n_cus * per_cu;
     const double stage = 24.0;
+    const bool light = per_cu >= 4;
     auto model = [&](int cand) {
         const int64_t wgs = (int64_t)c.n_groups * cand;
         // (workgroups do not run in lockstep: beyond one round the chip's slots are refilled as
-        // they come free, and what is left of whole rounds is half a round on average)
-        const double rounds = wgs <= slots ? 1.0 : (double)wgs / (double)slots + 0.5;
+        // they come free, and what is left of whole rounds is half a round on average.  Light
+        // workgroups, four or more to a compute unit, differ enough in length that the half
+        // round shows in a single round too: measured, their launches want more and smaller
+        // chunks than one round's worth, the heavy ones do not.)
+        const double rounds = (light || wgs > slots) ? (double)wgs / (double)slots + 0.5 : 1.0;
         // (a wavefront works its slab alone: no chunk is done before its longest slab is)
         const double per_wg = stage + std::max((double)total / cand / waves, (double)longest) + 0.25 * (double)longest;
         return rounds * per_wg;
@@ -211,7 +215,7 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
         const int max_nc = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(4096, useful), b.n_slabs / waves));
         double best = -1.0;
         nc = 1;
-        for (int cand = 1; cand <= max_nc; cand = cand < 8 ? cand + 1 : cand + 8) {
+        for (int cand = 1; cand <= max_nc; cand = cand < 8 ? cand + 1 : (light ? (cand < 16 ? cand + 2 : (cand < 32 ? cand + 4 : cand + 8)) : cand + 8)) {
             const double t = model(cand);
             if (best < 0.0 || t < best * 0.98) { best = t; nc = cand; }
         }
