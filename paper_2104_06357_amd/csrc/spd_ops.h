@@ -93,9 +93,9 @@ struct OpParams {
     float sign = 1.0f;    // sum() = min is carried as the max of the negated products
 };
 
-// log2, exp2 and x/y as the kernels use them: the hardware's transcendental units on the device
+// log2, exp2 and 1/x as the kernels use them: the hardware's transcendental units on the device
 // (v_log_f32, v_exp_f32, v_rcp_f32: about 1 ulp, far inside the 1e-4 tolerance), libm on the
-// host (test hooks only).
+// host (test hooks only).  Everything built on them below is the same code on both sides.
 SPD_HD float fast_log2(float x) {
 #if defined(__HIP_DEVICE_COMPILE__)
     return __builtin_amdgcn_logf(x);
@@ -110,13 +110,14 @@ SPD_HD float fast_exp2(float x) {
     return exp2f(x);
 #endif
 }
-SPD_HD float fast_div(float x, float y) {
+SPD_HD float fast_rcp(float x) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    return x * __builtin_amdgcn_rcpf(y);
+    return __builtin_amdgcn_rcpf(x);
 #else
-    return x / y;
+    return 1.0f / x;
 #endif
 }
+SPD_HD float fast_div(float x, float y) { return x * fast_rcp(y); }
 
 // x / d in fp32 through a reciprocal: quotient estimate, exact residual (one FMA), correction
 // (one FMA).  With the reciprocal good to an ulp this is the correctly rounded quotient (in
@@ -124,38 +125,35 @@ SPD_HD float fast_div(float x, float y) {
 // where the IEEE sequence with its range scaling takes 11.  The divisor is prepared once and
 // serves many numerators; one whose magnitude lies outside [2^-100, 2^100] is brought into
 // range by a power of two that the numerator then shares (a quotient beyond the fp32 range
-// is undefined, where IEEE division gives 0 or infinity).  The host takes the plain quotient.
+// is undefined, where IEEE division gives 0 or infinity).
 struct Divisor { float d, y, s; };        // scaled divisor, its reciprocal, the scale
 SPD_HD Divisor divisor_of(float d) {
-#if defined(__HIP_DEVICE_COMPILE__)
     const float m = fabsf(d);
     const float s = m < 0x1p-100f ? 0x1p64f : (m > 0x1p100f ? 0x1p-64f : 1.0f);
     const float ds = d * s;
-    return {ds, __builtin_amdgcn_rcpf(ds), s};
-#else
-    return {d, 0.0f, 1.0f};
-#endif
+    return {ds, fast_rcp(ds), s};
 }
 SPD_HD float divide(float x, const Divisor &v) {
-#if defined(__HIP_DEVICE_COMPILE__)
     const float xs = x * v.s;
     const float q = xs * v.y;
     const float r = __builtin_fmaf(-q, v.d, xs);
     return __builtin_fmaf(r, v.y, q);
-#else
-    return x / v.d;
-#endif
 }
 
 // The same for one quotient whose divisor is known to lie in [2^-100, 2^100].
 SPD_HD float divide_in_range(float x, float d) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    const float y = __builtin_amdgcn_rcpf(d);
+    const float y = fast_rcp(d);
     const float q = x * y;
     const float r = __builtin_fmaf(-q, d, x);
     return __builtin_fmaf(r, y, q);
+}
+
+// Median of three: v clamped to [lo, hi] when lo <= hi.
+SPD_HD float median3(float v, float lo, float hi) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_fmed3f(v, lo, hi);
 #else
-    return x / d;
+    return fmaxf(fminf(v, hi), fminf(fmaxf(v, hi), lo));
 #endif
 }
 
@@ -428,8 +426,11 @@ template <> struct Op<OP_JS> {
         float aa = hit ? a : 1.0f, bb = hit ? b.b : 1.0f;
         // (a sum outside [2^-100, 2^100] is clamped: below it, the two entries' term is far below the
         // result's resolution whatever u is taken; above it lie sums of values beyond 6e29)
-        float sum = fminf(fmaxf(aa + bb, 0x1p-100f), 0x1p100f);
-        float u = divide_in_range(aa, sum);              // correctly rounded: 1/2 for aa == bb
+        float sum = median3(aa + bb, 0x1p-100f, 0x1p100f);
+        // correctly rounded: 1/2 for aa == bb.  Kept inside [2^-126, 1 - 2^-24]: a quotient that
+        // rounds to 1 (aa beyond 2^25 bb) would leave log2(0) on the other side, one that
+        // underflows log2(0) on this one; what the clamp changes is below 1e-6 of the larger entry
+        float u = median3(divide_in_range(aa, sum), 0x1p-126f, 0x1.fffffep-1f);
         float t = aa * fast_log2(2.0f * u) + bb * fast_log2(2.0f * (1.0f - u));
         x.f += (double)t;                                // elsewhere aa == bb == 1: u = 1/2, both logarithms 0
         x.s += hit ? (double)a + b.db : 0.0;

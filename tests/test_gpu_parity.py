@@ -5,7 +5,8 @@ import pytest
 
 import oracle
 from gen import synth
-from util import ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, assert_distances_close, assert_knn_matches
+from util import (ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, assert_distances_close, assert_knn_matches,
+                  quotient_cases)
 
 pytestmark = pytest.mark.gpu
 
@@ -449,3 +450,28 @@ def test_csr_validate(handle, spd, config0):
     with pytest.raises(spd.SpdError):
         handle.csr_validate(bad)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("kind", [1, 3])
+@pytest.mark.parametrize("metric", ["jensen_shannon", "kl_divergence", "kl_divergence_strict", "canberra"])
+def test_device_quotients_on_crafted_pairs(handle, spd, metric, kind):
+    """The kernels' quotients (reciprocal, estimate, residual, correction) and logarithms on the
+    pairs that stress them: equal entries, one entry twice the other, ratios of 1e8 and 1e12
+    either way, entries near both ends of the fp32 range.  Every row of the first set meets
+    every row of the second."""
+    cases = quotient_cases()
+    A = synth.from_dense(np.stack([a for a, _ in cases]))
+    B = synth.from_dense(np.stack([b for _, b in cases]))
+    print("device quotients", metric, kind, flush=True)
+    handle.set_option("force_kind", kind)
+    got = _run_pairwise(handle, spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B), metric)
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], mode="full")
+    if metric == "kl_divergence":
+        # (the library documents a quotient of two entries beyond the fp32 range as undefined)
+        ratio = np.array([[a[3] / b[3] for _, b in cases] for a, _ in cases])
+        ok = (ratio > 1e-36) & (ratio < 1e36)
+        got, want = np.where(ok, got, 0.0), np.where(ok, want, 0.0)
+    assert_distances_close(got, want, metric)
+    # the same rows against themselves: equal entries everywhere give exactly 0
+    self_d = _run_pairwise(handle, spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(A), metric)
+    assert np.all(np.diag(self_d) == 0.0)

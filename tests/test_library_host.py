@@ -10,7 +10,7 @@ import pytest
 import oracle
 import paper_2104_06357_amd as spd
 from gen import synth
-from util import ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, assert_distances_close
+from util import ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, assert_distances_close, quotient_cases
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -205,3 +205,18 @@ def test_planner_sort_key_small_classes_and_bloom_rows():
     filtered = spd.host_plan_summary(ip, ip, 10000, "l1", bloom_long_rows=1, **tight)
     assert sliced["spilled_rows"] == 2 and filtered["spilled_rows"] == 0
     assert sorted(c["kind"] for c in filtered["classes"]) == [3, 4]
+
+
+@pytest.mark.parametrize("metric", ["jensen_shannon", "kl_divergence", "kl_divergence_strict"])
+def test_quotients_inside_the_logarithms_on_the_host(metric):
+    """A quotient that rounds to 1, or underflows, must not leave log(0) behind: a column whose
+    two entries differ by a factor of 1e8 adds what the formula says, not minus infinity."""
+    for a, b in quotient_cases():
+        A, B = synth.from_dense(a[None, :]), synth.from_dense(b[None, :])
+        want = oracle.pairwise(A, B, ORACLE_NAME[metric], mode="full")
+        got = spd.host_pair_value(metric, 2.0, 16, A["indices"], A["values"], B["indices"], B["values"])
+        assert_distances_close(np.array([[got]]), want, "%s on %s" % (metric, (a[3], b[3])))
+    # the case the advisor gave: a = {1, 0.5}, b = {1e-8, 0.5}
+    A = synth.from_dense(np.array([[1.0, 0.5]])); B = synth.from_dense(np.array([[1e-8, 0.5]]))
+    got = spd.host_pair_value("jensen_shannon", 2.0, 2, A["indices"], A["values"], B["indices"], B["values"])
+    assert abs(got - 0.5887) < 1e-4

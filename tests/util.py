@@ -74,3 +74,19 @@ def progress(capsys, message):
     with capsys.disabled():
         sys.stderr.write("[step %s] %s\n" % (time.strftime("%H:%M:%S"), message))
         sys.stderr.flush()
+
+
+def quotient_cases():
+    """Row pairs (over 16 columns) that stress the quotients inside the logarithms of KL and
+    Jensen-Shannon: equal entries, one entry twice the other, ratios of 1e8 and 1e12 either
+    way, entries near the ends of the fp32 range, and a plain pair beside each so that the
+    result is not dominated by the extreme column alone."""
+    cases = []
+    for x, y in ((1.0, 1.0), (0.25, 0.5), (0.5, 0.25), (1.0, 1e-8), (1e-8, 1.0), (1.0, 1e-12), (1e-12, 1.0),
+                 (3e-31, 2e-31), (2e29, 5e28), (7e-31, 7e-31), (1e-37, 1.0), (1.0, 1e-37), (1.5e-38, 1.5e-38)):
+        a = np.zeros(16); b = np.zeros(16)
+        a[3], b[3] = x, y
+        a[5], b[5] = 0.5, 0.5
+        a[9], b[11] = 0.125, 0.375            # one-sided columns
+        cases.append((a, b))
+    return cases
