@@ -122,6 +122,26 @@ spd_status spd_set_workspace(spd_handle *handle, void *device_ptr, size_t bytes)
 spd_status spd_pairwise(spd_handle *handle, const spd_csr *A, const spd_csr *B, spd_metric metric,
                         float p, float *out);
 
+/* spd_pairwise for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and same result as spd_pairwise,
+ * but the call allocates nothing (no hipMalloc, hipHostMalloc, hipFree, stream or event creation):
+ * its scratch is a static array of SPD_STATIC_SCRATCH_BYTES bytes that every GPU the library runs
+ * on holds from the library's first use there until the process ends, and its plans pass through
+ * the SPD_STATIC_STAGING_BYTES bytes of pinned memory every handle holds from spd_create.
+ *  - Both operands must bring `host_indptr` (nothing is copied back, the stream is not waited for).
+ *  - Operands whose packed copy of B, plans and partial sums exceed the array, or whose plans
+ *    exceed the staging memory, are rejected with SPD_ERR_WORKSPACE before anything is enqueued
+ *    (B up to some 3.5 million stored entries fits; spd_last_error gives the bytes needed).
+ *  - Everything runs on the handle's stream (no internal side streams), launch timing is off.
+ *  - All calls on one GPU, from any handle, share that GPU's array and leave their data in it:
+ *    no kernel reads scratch it has not written in the same call, so nothing needs clearing, but
+ *    two calls that overlap in time on one GPU (two handles, two streams) race.  Calls on one
+ *    stream, or ordered by events, are safe. */
+#define SPD_STATIC_SCRATCH_BYTES (32u << 20)
+#define SPD_STATIC_STAGING_BYTES (4u << 20)
+spd_status spd_pairwise_static(spd_handle *handle, const spd_csr *A, const spd_csr *B, spd_metric metric,
+                               float p, float *out);
+
 /* For each query row the k index rows at the smallest distance (largest value for
  * SPD_INNER_PRODUCT), selected inside the distance kernels without materialising the
  * m x n matrix (Section 4.2).  out_idx[i*k + t] (int64) and out_dist[i*k + t] (fp32) are

@@ -65,6 +65,7 @@ def lib():
         L.spd_workspace_bytes.argtypes = [vp, csr_p, csr_p, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.spd_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
         L.spd_pairwise.argtypes = [vp, csr_p, csr_p, i32, f32, vp]
+        L.spd_pairwise_static.argtypes = [vp, csr_p, csr_p, i32, f32, vp]
         L.spd_knn.argtypes = [vp, csr_p, csr_p, i32, f32, i32, vp, vp]
         L.spd_semiring_pairwise.argtypes = [vp, csr_p, csr_p, ctypes.POINTER(SemiringStruct), vp]
         L.spd_semiring_knn.argtypes = [vp, csr_p, csr_p, ctypes.POINTER(SemiringStruct), i32, vp, vp]
@@ -85,6 +86,7 @@ def lib():
         L.spd_host_plan_summary.argtypes = [vp, i64, vp, i64, i64, i32, i32, ctypes.POINTER(ctypes.c_char_p),
                                             ctypes.POINTER(i64), i32, ctypes.c_char_p, ctypes.c_size_t]
         for fn in ("spd_create", "spd_destroy", "spd_workspace_bytes", "spd_set_workspace", "spd_pairwise",
+                   "spd_pairwise_static",
                    "spd_knn", "spd_semiring_pairwise", "spd_semiring_knn", "spd_index_create", "spd_index_destroy",
                    "spd_index_pairwise", "spd_index_knn", "spd_csr_validate", "spd_set_option", "spd_host_pair_value",
                    "spd_host_plan_summary"):
@@ -204,6 +206,17 @@ class Handle:
         sa, sb = A.struct(), B.struct()
         self._check(self._lib.spd_pairwise(self._h, ctypes.byref(sa), ctypes.byref(sb), metric_id(metric),
                                            float(p), out.data_ptr() if out.numel() else None))
+        return out
+
+    def pairwise_static(self, A: DeviceCsr, B: DeviceCsr, metric, out, p: float = 2.0):
+        """spd_pairwise_static: the same distances into `out` (which the caller allocates), with the
+        library's static scratch array; the call allocates nothing."""
+        import torch
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+        assert tuple(out.shape) == (A.n_rows, B.n_rows)
+        sa, sb = A.struct(), B.struct()
+        self._check(self._lib.spd_pairwise_static(self._h, ctypes.byref(sa), ctypes.byref(sb), metric_id(metric),
+                                                  float(p), out.data_ptr() if out.numel() else None))
         return out
 
     def knn(self, Q: DeviceCsr, Index: DeviceCsr, metric, k: int, p: float = 2.0, out_idx=None, out_dist=None):

@@ -21,6 +21,19 @@
 
 using namespace spd;
 
+// Scratch of the entry point that allocates nothing (spd_pairwise_static): one array per GPU, held
+// from the moment the library's code is loaded on that GPU until the process ends.  In host code
+// the array's name is only a stand-in for the symbol; the address a kernel can use is asked for
+// once per device (spd_create, with that device current) and kept in g_static_scratch.
+constexpr size_t kStaticScratchBytes = (size_t)SPD_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kStaticScratchDevices = 64;
+static void *g_static_scratch[kStaticScratchDevices];
+static std::mutex g_static_scratch_mutex;
+// Pinned staging memory every handle holds from its creation, so that a call may not have to
+// allocate any: three buffers of this size.
+constexpr size_t kInitialPinnedBytes = (size_t)SPD_STATIC_STAGING_BYTES;
+
 // A helper thread that runs one job at a time beside the caller's thread (the plan of A is
 // made there while the caller plans B, uploads its plan and starts the repack).  A sleeping
 // thread can take longer to wake than the job takes: when the caller comes to wait and the
@@ -111,6 +124,8 @@ struct spd_handle {
     void *own_ws = nullptr;      // the handle's own allocation
     size_t own_ws_bytes = 0;
     int32_t *flag = nullptr;     // device word for spd_csr_validate
+    void *static_ws = nullptr;   // this device's copy of `scratch`
+    bool no_alloc = false;       // inside spd_pairwise_static: nothing may be allocated
     bool profile = false;
     bool check_plan = false;
     bool no_byte_counters = false;   // option "byte_counters" 0: set metrics through the dot product
@@ -240,6 +255,10 @@ struct PinnedLease {
 
 spd_status ensure_pinned(spd_handle *h, size_t bytes) {
     if (bytes <= h->pinned_bytes) return SPD_OK;
+    if (h->no_alloc)
+        return fail(h, SPD_ERR_WORKSPACE, "operands too large for the entry point that allocates nothing: the plan needs " +
+                                              std::to_string(bytes) + " bytes of staging memory, a handle holds " +
+                                              std::to_string(h->pinned_bytes));
     if (h->pinned) { hipError_t e = hipStreamSynchronize(h->stream); (void)e; (void)hipHostFree(h->pinned); h->pinned = nullptr; h->pinned_bytes = 0; }
     size_t want = align256(bytes + bytes / 4);
     hipError_t e = hipHostMalloc(&h->pinned, want, hipHostMallocDefault);
@@ -251,7 +270,11 @@ spd_status ensure_pinned(spd_handle *h, size_t bytes) {
 spd_status ensure_workspace(spd_handle *h, size_t bytes) {
     if (h->ws_external) {
         if (bytes > h->ws_bytes)
-            return fail(h, SPD_ERR_WORKSPACE, "caller workspace too small: need " + std::to_string(bytes) + " bytes");
+            return fail(h, SPD_ERR_WORKSPACE,
+                        h->no_alloc ? "operands too large for the entry point that allocates nothing: they need " +
+                                          std::to_string(bytes) + " bytes of scratch, the static array holds " +
+                                          std::to_string(h->ws_bytes)
+                                    : "caller workspace too small: need " + std::to_string(bytes) + " bytes");
         return SPD_OK;
     }
     if (bytes > h->own_ws_bytes) {
@@ -774,6 +797,23 @@ spd_status spd_create(spd_handle **handle, void *hip_stream) {
         h->opt.n_cus = cus;
     e = hipMalloc(reinterpret_cast<void **>(&h->flag), 256);
     if (e != hipSuccess) { delete h; return SPD_ERR_HIP; }
+    // this device's copy of the static scratch array: its address is asked for once per device
+    if (dev >= 0 && dev < kStaticScratchDevices) {
+        std::lock_guard<std::mutex> g(g_static_scratch_mutex);
+        if (!g_static_scratch[dev]) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) { (void)hipFree(h->flag); delete h; return SPD_ERR_HIP; }
+            g_static_scratch[dev] = ptr;
+        }
+        h->static_ws = g_static_scratch[dev];
+    }
+    // staging memory and the events that guard it, so that a call of modest size allocates nothing
+    for (spd_handle::PinnedSlot &ps : h->pinned_slots) {
+        if (hipHostMalloc(&ps.ptr, kInitialPinnedBytes, hipHostMallocDefault) != hipSuccess) { ps.ptr = nullptr; break; }
+        ps.bytes = kInitialPinnedBytes;
+        if (hipEventCreateWithFlags(&ps.done, hipEventDisableTiming) != hipSuccess) ps.done = nullptr;
+    }
     *handle = h;
     return SPD_OK;
 }
@@ -875,6 +915,32 @@ spd_status spd_set_workspace(spd_handle *h, void *device_ptr, size_t bytes) {
 spd_status spd_pairwise(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, float *out) {
     spd_status st = check_call_args(h, A, B, metric, p, 0, false, out, nullptr);
     if (st != SPD_OK) return st;
+    return run(h, A, B, (int)metric, p, nullptr, 0, out, nullptr, nullptr);
+}
+
+spd_status spd_pairwise_static(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p,
+                               float *out) {
+    spd_status st = check_call_args(h, A, B, metric, p, 0, false, out, nullptr);
+    if (st != SPD_OK) return st;
+    if (!A->host_indptr || !B->host_indptr)
+        return fail(h, SPD_ERR_NULL, "spd_pairwise_static needs host_indptr of both operands (it neither copies the row "
+                                     "pointers back nor waits for the stream)");
+    if (!h->static_ws) return fail(h, SPD_ERR_HIP, "no static scratch on this device");
+    for (const spd_handle::PinnedSlot &ps : h->pinned_slots)
+        if (!ps.ptr || !ps.done) return fail(h, SPD_ERR_WORKSPACE, "the handle holds no staging memory");
+    // the call runs as spd_pairwise does, with the static array as its scratch, on the handle's
+    // stream alone and without launch timers (internal streams and events would have to be created)
+    struct Saved {
+        spd_handle *h; void *ws; size_t ws_bytes; bool ws_external; int side_streams; bool profile;
+        ~Saved() { h->ws = ws; h->ws_bytes = ws_bytes; h->ws_external = ws_external; h->side_streams = side_streams;
+                   h->profile = profile; h->no_alloc = false; }
+    } saved{h, h->ws, h->ws_bytes, h->ws_external, h->side_streams, h->profile};
+    h->ws = h->static_ws;
+    h->ws_bytes = kStaticScratchBytes;
+    h->ws_external = true;
+    h->side_streams = 0;
+    h->profile = false;
+    h->no_alloc = true;
     return run(h, A, B, (int)metric, p, nullptr, 0, out, nullptr, nullptr);
 }
 
