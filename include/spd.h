@@ -241,6 +241,12 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 the handle's stream still orders the whole call (0: everything on the handle's stream);
  *                 they are used when the largest launch is short or the small ones hold a tenth of
  *                 the call's sweeps over B, and not otherwise
+ *   "swap_operands" spd_pairwise may stage B and stream A instead of the other way round (every distance
+ *                 but the two KL divergences is symmetric in its rows): B's rows are then staged in
+ *                 groups of consecutive rows, so that a lane's results are neighbours in the output
+ *                 and are stored as whole 32-byte sectors.  1 (default): where it pays (A of 2^18 or
+ *                 more stored entries and 1,024 or more rows, B's rows under 96 entries on average);
+ *                 0: never; 2: wherever the distance allows it
  *   "check_plan"  1: verify every index the kernels will form from the plan before launching
  *   "profile"     1: bracket every kernel launch with HIP events (see spd_profile_read)
  * Unknown names or values out of range return SPD_ERR_UNSUPPORTED. */

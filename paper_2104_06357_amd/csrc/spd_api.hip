@@ -129,6 +129,7 @@ struct spd_handle {
     bool profile = false;
     bool check_plan = false;
     bool no_byte_counters = false;   // option "byte_counters" 0: set metrics through the dot product
+    int swap_operands = 1;       // option "swap_operands": 0 never, 1 where it pays, 2 wherever the distance allows it
     int side_streams = 3;        // option "side_streams": how many internal streams the small launches may use beside the large one
     static constexpr int kSideStreams = 3;
     hipStream_t side[kSideStreams] = {nullptr, nullptr, nullptr};
@@ -413,10 +414,27 @@ int effective_metric(int metric, float p) { return (metric == SPD_MINKOWSKI && p
 
 // `metric` is a spd_metric, or, with `semiring` set, the internal id its sum() runs as.  With
 // `index` set, B is that index's matrix and its plan, packed slabs and norms are taken from it.
+// Whether a pairwise call stages B and streams A instead of the other way round.  A lane holds
+// the results of one streamed row against the R staged rows; with A staged these are R different
+// rows of the output and the 64 lanes of a store fall on 64 different cache lines (the streamed
+// rows of a slab are the ones of similar length inside a window, not neighbours), which costs
+// three times the output in write traffic.  With B staged in groups of consecutive rows a lane's
+// R results are neighbours in its own output row: whole 32-byte sectors.  The roles can be
+// exchanged for every distance that is symmetric in its two rows, and pay where the scan of a pair
+// is short against its store (short rows of B) and A is large enough to be worth sweeping.
+bool operands_may_swap(int metric) { return metric != SPD_KL_DIVERGENCE && metric != SPD_KL_STRICT; }
+bool operands_swap_pays(const spd_csr *A, const spd_csr *B) {
+    return A->nnz >= ((int64_t)1 << 18) && A->n_rows >= 1024 && B->nnz <= 96 * B->n_rows;
+}
+
 spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, float p, const spd_semiring *semiring,
                int knn_k, float *out, int64_t *out_idx, float *out_dist, const spd_index *index = nullptr) {
-    const int64_t m = A->n_rows, n = B->n_rows;
     metric = effective_metric(metric, p);
+    const bool swapped = knn_k == 0 && !index && operands_may_swap(metric) &&
+                         (h->swap_operands == 2 || (h->swap_operands == 1 && operands_swap_pays(A, B)));
+    if (swapped) std::swap(A, B);           // from here on A is the staged operand, B the streamed one
+    const int64_t m = A->n_rows, n = B->n_rows;
+    const int64_t out_stride_staged = swapped ? 1 : n, out_stride_streamed = swapped ? m : 1;
     static const bool host_times = std::getenv("SPD_HOST_TIMES") != nullptr;
     auto now = [] { return std::chrono::steady_clock::now(); };
     auto t_begin = now();
@@ -482,9 +500,11 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     std::string why_a;
     {
         const int64_t *a_rows_ptr = a_ip;
-        h->helper.post([&why_a, &ap, h, a_rows_ptr, m, A, metric, op, knn_k] {
+        PlanOptions opt_a = h->opt;
+        opt_a.consecutive_groups = swapped ? 1 : 0;
+        h->helper.post([&why_a, &ap, opt_a, a_rows_ptr, m, A, metric, op, knn_k] {
             try {
-                why_a = plan_a(a_rows_ptr, m, A->n_cols, metric, op, knn_k, h->opt, ap);
+                why_a = plan_a(a_rows_ptr, m, A->n_cols, metric, op, knn_k, opt_a, ap);
             } catch (const std::exception &ex) {
                 why_a = std::string("planning failed: ") + ex.what();
             }
@@ -722,6 +742,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         sa.k = (uint32_t)A->n_cols;
         sa.padcol = padcol;
         sa.out = out;
+        sa.out_stride_staged = out_stride_staged;
+        sa.out_stride_streamed = out_stride_streamed;
         sa.partial = reinterpret_cast<double *>(ws + o_partial);
         sa.partial_norms = reinterpret_cast<double *>(ws + o_partial_norms);
         sa.planes = planes;
@@ -733,15 +755,23 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         LaunchTimer lt(h, "scan", c.R, c.kind, c.block, c.lds_bytes, live_rows, (int64_t)c.n_groups * c.n_chunks,
                        st_launch);
         e = launch_scan(st_launch, op, c.R, c.block, c.lds_bytes, sa);
-        if (e != hipSuccess) return hip_fail(h, e, "scan kernel");
+        if (e != hipSuccess) {
+            // what already runs on the side streams still has to be ordered before the caller's next work
+            for (int q = 0; q < side_used; ++q)
+                if (hipEventRecord(h->join_event[q], h->side[q]) == hipSuccess) (void)hipStreamWaitEvent(h->stream, h->join_event[q], 0);
+            return hip_fail(h, e, "scan kernel");
+        }
         lt.done();
     }
 
-    for (int q = 0; q < side_used; ++q) {
-        e = hipEventRecord(h->join_event[q], h->side[q]);
-        if (e != hipSuccess) return hip_fail(h, e, "hipEventRecord");
-        e = hipStreamWaitEvent(h->stream, h->join_event[q], 0);
-        if (e != hipSuccess) return hip_fail(h, e, "hipStreamWaitEvent");
+    {
+        hipError_t first_error = hipSuccess;
+        for (int q = 0; q < side_used; ++q) {
+            e = hipEventRecord(h->join_event[q], h->side[q]);
+            if (e == hipSuccess) e = hipStreamWaitEvent(h->stream, h->join_event[q], 0);
+            if (e != hipSuccess && first_error == hipSuccess) first_error = e;      // the other streams are still joined
+        }
+        if (first_error != hipSuccess) return hip_fail(h, first_error, "joining the side streams");
     }
 
     if (!ap.spilled.empty()) {
@@ -755,6 +785,8 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         fa.n_b = n;
         fa.q = q;
         fa.out = out;
+        fa.out_stride_staged = out_stride_staged;
+        fa.out_stride_streamed = out_stride_streamed;
         fa.knn_k = knn_k;
         fa.knn_part = reinterpret_cast<KnnEntry *>(ws + o_knn_part);
         fa.knn_row_off = reinterpret_cast<const int64_t *>(ws + o_knn_off);
@@ -845,6 +877,9 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return SPD_ERR_BAD_METRIC;
     if (A->n_rows < 0 || B->n_rows < 0 || A->nnz < 0 || B->nnz < 0 || A->n_cols != B->n_cols) return SPD_ERR_DIM_MISMATCH;
     *bytes = workspace_bound(h, A, B, (int)metric, k_neighbors);
+    // (a pairwise call may exchange the roles of its operands)
+    if (k_neighbors == 0 && h->swap_operands != 0 && operands_may_swap((int)metric))
+        *bytes = std::max(*bytes, workspace_bound(h, B, A, (int)metric, 0));
     return SPD_OK;
 }
 
@@ -1128,6 +1163,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "side_streams") {
         if (value < 0 || value > spd_handle::kSideStreams) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must lie in [0, 3]");
         h->side_streams = (int)value;
+    } else if (s == "swap_operands") {
+        if (value < 0 || value > 2) return fail(h, SPD_ERR_UNSUPPORTED, "swap_operands must be 0, 1 or 2");
+        h->swap_operands = (int)value;
     } else if (s == "check_plan") {
         if (value != 0 && value != 1) return fail(h, SPD_ERR_UNSUPPORTED, "check_plan must be 0 or 1");
         h->check_plan = value != 0;

@@ -44,7 +44,9 @@ struct ScanArgs {
     uint32_t k;                   // columns
     uint32_t padcol;              // column an idle lane looks up (maps to the zero row)
     // results
-    float *out;                   // pairwise: m x n
+    float *out;                   // pairwise: the result of (staged row i, streamed row j) goes to
+    int64_t out_stride_staged;    //   out[i * out_stride_staged + j * out_stride_streamed]: (n, 1) when A is
+    int64_t out_stride_streamed;  //   staged and B streamed, (1, n) when the library has exchanged their roles
     double *partial;              // slices of spilled rows: [slot][plane][n]
     double *partial_norms;        // [slot][2] raw sums
     int32_t planes;               // 1, or 2 for Jensen-Shannon
@@ -62,7 +64,8 @@ struct FinalizeArgs {
     int32_t planes;
     int64_t n_b;
     OpParams q;
-    float *out;                   // pairwise
+    float *out;                   // pairwise: as in ScanArgs
+    int64_t out_stride_staged, out_stride_streamed;
     int32_t knn_k;
     KnnEntry *knn_part;           // k-NN: a spilled row's candidate lists, one per tile of kFinalizeTile columns,
     const int64_t *knn_row_off;   //       at knn_row_off[row] + tile * k (merged with the others afterwards)

@@ -144,11 +144,12 @@ __device__ __forceinline__ void spilled_row_norms(const FinalizeArgs &a, const S
 }
 
 __global__ void __launch_bounds__(256) spd_finalize_pairwise_kernel(const FinalizeArgs a) {
-    const SpilledRow sr = a.spilled[blockIdx.y];
+    const SpilledRow sr = a.spilled[blockIdx.y];      // (the launcher passes `spilled` advanced to its tile of rows)
     double na0, na1;
     spilled_row_norms(a, sr, na0, na1);
     int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (j < a.n_b) a.out[(size_t)sr.row * (size_t)a.n_b + (size_t)j] = finalize_one(a, sr, j, na0, na1);
+    if (j < a.n_b)
+        a.out[(size_t)sr.row * (size_t)a.out_stride_staged + (size_t)j * (size_t)a.out_stride_streamed] = finalize_one(a, sr, j, na0, na1);
 }
 
 __global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArgs a) {
@@ -194,14 +195,23 @@ __global__ void __launch_bounds__(256) spd_finalize_knn_kernel(const FinalizeArg
 
 hipError_t launch_finalize(hipStream_t st, const FinalizeArgs &args) {
     if (args.n_spilled <= 0) return hipSuccess;
-    if (args.knn_k > 0) {
-        dim3 grid((unsigned)((args.n_b + kFinalizeTile - 1) / kFinalizeTile), (unsigned)args.n_spilled);
-        hipLaunchKernelGGL(spd_finalize_knn_kernel, grid, dim3(256), 0, st, args);
-    } else {
-        dim3 grid((unsigned)((args.n_b + 255) / 256), (unsigned)args.n_spilled);
-        hipLaunchKernelGGL(spd_finalize_pairwise_kernel, grid, dim3(256), 0, st, args);
+    // the second grid dimension holds at most 65,535 workgroups: the spilled rows go in tiles of that many
+    constexpr int32_t kMaxGridY = 65535;
+    for (int32_t first = 0; first < args.n_spilled; first += kMaxGridY) {
+        FinalizeArgs part = args;
+        part.spilled = args.spilled + first;
+        part.n_spilled = std::min(kMaxGridY, args.n_spilled - first);
+        if (args.knn_k > 0) {
+            dim3 grid((unsigned)((args.n_b + kFinalizeTile - 1) / kFinalizeTile), (unsigned)part.n_spilled);
+            hipLaunchKernelGGL(spd_finalize_knn_kernel, grid, dim3(256), 0, st, part);
+        } else {
+            dim3 grid((unsigned)((args.n_b + 255) / 256), (unsigned)part.n_spilled);
+            hipLaunchKernelGGL(spd_finalize_pairwise_kernel, grid, dim3(256), 0, st, part);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 // ------------------------------------------------------------------------------------

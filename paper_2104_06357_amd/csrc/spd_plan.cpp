@@ -2,6 +2,7 @@
 #include "spd_plan.h"
 
 #include <algorithm>
+#include <functional>
 #include <numeric>
 
 namespace spd {
@@ -450,7 +451,57 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     }
     auto room_of = [&](int R) { int q = 0; while ((32 >> q) != R) ++q; return room[q]; };
     auto fits_group = [&](int R, uint64_t sum) { return sum <= room_of(R) && (sum == 0 ? fits(kind, R, 0) : true); };
+    auto emit_group = [&](int R, const ARow *rows, size_t n, uint64_t sum) {
+        int ci = 0;
+        while ((32 >> ci) != R) ++ci;
+        uint32_t need = lds_layout(kind, table_words(op, R), (uint32_t)sum, k, cheb, 1).total;
+        AClass &c = *by_key[ci][occupancy_bucket(need, opt.lds_budget)];
+        for (int q = 0; q < R; ++q)
+            c.rows.push_back((size_t)q < n ? rows[q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});
+        c.sumlen.push_back((int32_t)sum);
+        ++c.n_groups;
+    };
     size_t t = 0;
+    if (opt.consecutive_groups) {
+        // Whole rows in row order, in aligned blocks of R0; the slices of the rows that do not fit
+        // alone (sorted to the front of `items`, their outputs are partial slots) are grouped among
+        // themselves below.  A block that is too much for the table is cut in halves, each half
+        // keeping its place in the row order; a row that was taken out as slices leaves an empty
+        // place behind.
+        int R0 = op == OP_CNT ? max_r : std::min(max_r, 8);
+        while (R0 > min_r && room_of(R0) == 0 && !fits(kind, R0, 0)) R0 /= 2;
+        std::vector<ARow> whole((size_t)n_rows, ARow{0, 0, -1, kRowFirst | kRowLast, 0});
+        std::vector<ARow> &sl = out.sorted;          // the slices, still sorted by length
+        sl.clear();
+        for (const ARow &r : items) {
+            if (r.out >= 0) whole[(size_t)r.out] = r;
+            else sl.push_back(r);
+        }
+        std::function<void(int64_t, int)> place = [&](int64_t first, int R) {
+            const int64_t last = std::min<int64_t>(first + R, n_rows);
+            if (first >= last) return;
+            uint64_t sum = 0;
+            int live = 0;
+            for (int64_t i = first; i < last; ++i)
+                if (whole[(size_t)i].out >= 0) { sum += (uint64_t)whole[(size_t)i].len; ++live; }
+            if (live == 0) return;
+            if (fits_group(R, sum) || R == min_r) {
+                if (!fits_group(R, sum)) {
+                    // the smallest group size and still too much (rows that fit alone, R = min_r > 1):
+                    // one row per group, the other places empty
+                    for (int64_t i = first; i < last; ++i)
+                        if (whole[(size_t)i].out >= 0) emit_group(R, &whole[(size_t)i], 1, (uint64_t)whole[(size_t)i].len);
+                    return;
+                }
+                emit_group(R, &whole[(size_t)first], (size_t)(last - first), sum);
+                return;
+            }
+            place(first, R / 2);
+            place(first + R / 2, R / 2);
+        };
+        for (int64_t first = 0; first < n_rows; first += R0) place(first, R0);
+        items.swap(sl);                              // what is left for the sorted grouping: the slices
+    }
     while (t < items.size()) {
         size_t remaining = items.size() - t;
         int R = max_r;
@@ -488,14 +539,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
                 // the smallest group may have to leave places empty (longest items come first)
                 while (n > 1 && !fits_group(R, sum)) sum -= (uint64_t)items[t + --n].len;
                 if (!fits_group(R, sum)) return "internal: slice does not fit";
-                int ci = 0;
-                while ((32 >> ci) != R) ++ci;
-                uint32_t need = lds_layout(kind, table_words(op, R), (uint32_t)sum, k, cheb, 1).total;
-                AClass &c = *by_key[ci][occupancy_bucket(need, opt.lds_budget)];
-                for (int q = 0; q < R; ++q)
-                    c.rows.push_back((size_t)q < n ? items[t + (size_t)q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});
-                c.sumlen.push_back((int32_t)sum);
-                ++c.n_groups;
+                emit_group(R, &items[t], n, sum);
                 t += n;
                 break;
             }

@@ -53,6 +53,7 @@ struct PlanOptions {
     int bloom_long_rows = 0;                // 1: a row too long for the LDS gets a Bloom filter instead of slices
     int sort_slack = 1;                     // 1: B's rows are sorted by length in whole blocks of steps, 0: by exact length
     int partial_groups = 1;                 // 1: a group of R rows may leave a quarter of its places empty rather than fall to R/2
+    int consecutive_groups = 0;             // 1: a group holds consecutive rows, in row order (see plan_a)
 };
 
 // Bloom staging: filter bits per stored entry (two hash functions: ~1.4 % false positives), and
@@ -220,6 +221,11 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
 
 // Both return an empty string on success, else the reason.
 std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt, BPlan &out);
+// With opt.consecutive_groups the staged rows are not sorted by length: rows 8q .. 8q+7 (32q .. 32q+31
+// for the set metrics) form a group, halved where the eight do not fit together, so that the R
+// results a lane holds for one streamed row are neighbours in a matrix whose fast dimension is
+// the staged operand's row number (the library stages B and streams A that way when the output's
+// stores would otherwise be scattered: a lane then writes whole 32-byte sectors).
 std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int metric, int op, int knn_k,
                    const PlanOptions &opt, APlan &out);
 // Cuts B's slabs into chunks for one launch: enough workgroups to fill the chip, yet chunks

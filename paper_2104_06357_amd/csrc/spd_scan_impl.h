@@ -285,6 +285,9 @@ __device__ __constant__ const uint32_t kHashMult[kCuckooAttempts][2] = {
 
 template <int R> struct RowVals { float v[R]; };
 
+// Four floats stored with one instruction at an address that is only known to be 4-byte aligned.
+struct __attribute__((packed, aligned(4))) Float4Unaligned { float x, y, z, w; };
+
 // The value table is kept in planes of four staged rows: plane q holds, for every slot, the
 // values of rows 4q .. 4q+3 in 16 bytes.  A wavefront's 16-byte reads at random slots then
 // fall on all LDS banks alike (rows of 32 or 64 bytes would start on every other or every
@@ -628,6 +631,26 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         }
     }
 
+    // The rows are finished eight at a time, or four (all at once would keep the sums and
+    // distances of up to 32 rows in registers together).
+    constexpr bool kThreeSums = (OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_SEMI_SUM);
+    constexpr int RB = R < 8 ? R : ((KNN && R >= 16) || kThreeSums ? 4 : 8);
+    // Pairwise, with the staged operand along the output's rows (stride 1): a block of staged rows
+    // that are consecutive rows of that operand is stored by each lane as 16-byte pieces of its
+    // own output row.  Bit b: block b qualifies.
+    uint32_t out_vector_blocks = 0u;
+    if constexpr (!KNN && RB % 4 == 0) {
+        if (args.out_stride_staged == 1) {
+#pragma unroll
+            for (int r0 = 0; r0 < R; r0 += RB) {
+                bool ok = row_out[r0] >= 0;
+#pragma unroll
+                for (int i = 1; i < RB; ++i) ok = ok && row_out[r0 + i] == row_out[r0] + i;
+                out_vector_blocks |= ok ? (1u << (r0 / RB)) : 0u;
+            }
+        }
+    }
+
     // ---- scan: every wavefront takes slabs of the chunk until none is left -----------
     KnnList lists[KNN ? R : 1];
     if constexpr (KNN) {
@@ -790,10 +813,6 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         double nb0 = 0.0, nb1 = 0.0;
         if (leader) { nb0 = args.b.norms[(size_t)row * 2]; nb1 = args.b.norms[(size_t)row * 2 + 1]; }
 
-        // The rows are finished eight at a time, or four (all at once would keep the sums and
-        // distances of up to 32 rows in registers together).
-        constexpr bool kThreeSums = (OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_SEMI_SUM);
-        constexpr int RB = R < 8 ? R : ((KNN && R >= 16) || kThreeSums ? 4 : 8);
         // k-NN: the workgroup's bounds of all R rows are read and decoded once per slab, row r's in
         // lane r (a wavefront publishes its own list's k-th distance there as soon as it has one,
         // so the shared bound is never looser than the list's own)
@@ -845,10 +864,24 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             });
             if constexpr (!KNN) {
                 if (leader) {
+                    bool stored = false;
+                    if constexpr (RB % 4 == 0) {
+                        // the staged rows of this block are neighbours in the lane's output row: 16-byte stores
+                        if ((out_vector_blocks >> (r0 / RB)) & 1u) {
+                            float *dst = args.out + ((size_t)row * (size_t)args.out_stride_streamed + (size_t)row_out[r0]);
 #pragma unroll
-                    for (int i = 0; i < RB; ++i) {
-                        const int out = row_out[r0 + i];
-                        if (out >= 0) args.out[(size_t)out * (size_t)n_b + (size_t)row] = dist[i];
+                            for (int i = 0; i < RB; i += 4)
+                                *reinterpret_cast<Float4Unaligned *>(dst + i) = Float4Unaligned{dist[i], dist[i + 1], dist[i + 2], dist[i + 3]};
+                            stored = true;
+                        }
+                    }
+                    if (!stored) {
+#pragma unroll
+                        for (int i = 0; i < RB; ++i) {
+                            const int out = row_out[r0 + i];
+                            if (out >= 0)
+                                args.out[(size_t)out * (size_t)args.out_stride_staged + (size_t)row * (size_t)args.out_stride_streamed] = dist[i];
+                        }
                     }
                 }
             } else {

@@ -99,6 +99,7 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
         else if (s == "bloom_long_rows") opt.bloom_long_rows = (int)v;
         else if (s == "sort_slack") opt.sort_slack = (int)v;
         else if (s == "partial_groups") opt.partial_groups = (int)v;
+        else if (s == "consecutive_groups") opt.consecutive_groups = (int)v;
         else return SPD_ERR_UNSUPPORTED;
     }
     APlan ap;

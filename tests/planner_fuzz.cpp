@@ -59,6 +59,7 @@ int main(int argc, char **argv) {
         if (rng() % 4 == 0) { names.push_back("bloom_long_rows"); values.push_back((int64_t)(rng() % 2)); }
         if (rng() % 4 == 0) { names.push_back("sort_slack"); values.push_back((int64_t)(rng() % 2)); }
         if (rng() % 3 == 0) { names.push_back("partial_groups"); values.push_back((int64_t)(rng() % 3)); }
+        if (rng() % 3 == 0) { names.push_back("consecutive_groups"); values.push_back((int64_t)(rng() % 2)); }
         spd_status st = spd_host_plan_summary(a.data(), a_rows, b.data(), b_rows, n_cols, metric, k, names.data(),
                                               values.data(), (int)names.size(), json.data(), json.size());
         if (st == SPD_OK) {

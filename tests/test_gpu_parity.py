@@ -475,3 +475,67 @@ def test_device_quotients_on_crafted_pairs(handle, spd, metric, kind):
     # the same rows against themselves: equal entries everywhere give exactly 0
     self_d = _run_pairwise(handle, spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(A), metric)
     assert np.all(np.diag(self_d) == 0.0)
+
+
+# ------------------------------------------------------------------ operands with their roles exchanged
+SWAPPABLE = tuple(m for m in ALL_METRICS if not m.startswith("kl_divergence"))
+
+
+@pytest.mark.parametrize("metric", SWAPPABLE)
+def test_operands_swapped_config0_and_edge_rows(handle, spd, config0, metric):
+    """spd_pairwise with B staged (groups of consecutive rows) and A streamed, which the library
+    does by itself only for large operands with short rows: forced here, on config 0 through every
+    staging kind and group size, and on the matrix of edge rows against itself and single rows."""
+    A, B, dA, dB = config0
+    print("swapped config0", metric, flush=True)
+    p = _p_of(metric)
+    handle.set_option("swap_operands", 2)
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], p)
+    for kind, max_rows in ((1, 8), (2, 8), (3, 8), (2, 1), (3, 4), (2, 16)):
+        handle.set_option("force_kind", kind)
+        handle.set_option("max_rows", max_rows)
+        assert_distances_close(_run_pairwise(handle, dA, dB, metric, p), want, "%s kind=%d R=%d" % (metric, kind, max_rows))
+    handle.set_option("force_kind", 0)
+    handle.set_option("max_rows", 8)
+    M = _edge_matrices(metric not in NONNEGATIVE_ONLY)
+    dM = spd.DeviceCsr.from_host(M)
+    want = oracle.pairwise(M, M, ORACLE_NAME[metric], p, mode="full")
+    assert_distances_close(_run_pairwise(handle, dM, dM, metric, p), want, metric + " edge rows")
+    d1 = spd.DeviceCsr.from_host(synth.slice_rows(M, 6, 7))
+    assert_distances_close(_run_pairwise(handle, d1, dM, metric, p), want[6:7], metric + " m=1")
+    assert_distances_close(_run_pairwise(handle, dM, d1, metric, p), want[:, 6:7], metric + " n=1")
+
+
+@pytest.mark.parametrize("metric", SWAPPABLE)
+def test_operands_swapped_split_rows_and_sliced_rows(handle, spd, metric):
+    """The same with the streamed rows (now A's) cut over lanes and the staged rows (now B's) cut
+    into slices: a sliced row leaves an empty place in its group of consecutive rows."""
+    A, B = _wide_pair(metric not in NONNEGATIVE_ONLY)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    print("swapped split+slices", metric, flush=True)
+    plan = spd.host_plan_summary(B["indptr"], A["indptr"], 400, metric, split_len=4, window=64, force_kind=3,
+                                 lds_budget=8192, chunks=3, consecutive_groups=1)
+    assert plan["spilled_rows"] > 0 and plan["split_rows"] > 0
+    for name, value in (("split_len", 4), ("window", 64), ("force_kind", 3), ("lds_budget", 8192), ("chunks", 3),
+                        ("swap_operands", 2)):
+        handle.set_option(name, value)
+    got = _run_pairwise(handle, dA, dB, metric, _p_of(metric))
+    want = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric), mode="full")
+    assert_distances_close(got, want, metric)
+
+
+def test_config1_both_orientations(handle, config1):
+    """Config 1 is large enough, and its rows short enough, for the library to exchange the
+    operands' roles by itself: the same sampled pairs with the exchange switched off, left to
+    the library, and forced."""
+    A, B, dA, dB = config1
+    rng = np.random.default_rng(3)
+    ra, rb = _sample_rows(A, 64, rng), _sample_rows(B, 2048, rng)
+    for metric in ("cosine", "l1", "jaccard", "jensen_shannon"):
+        want = oracle.pairwise(A, B, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
+        for mode in (0, 1, 2):
+            print("config1 orientation", metric, mode, flush=True)
+            handle.set_option("swap_operands", mode)
+            got = _run_pairwise(handle, dA, dB, metric)
+            assert_distances_close(got[np.ix_(ra, rb)], want, "%s swap_operands=%d" % (metric, mode))
+            assert np.all(np.isfinite(got))

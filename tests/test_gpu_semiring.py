@@ -206,3 +206,19 @@ def test_error_statuses(handle, spd, config0):
     with pytest.raises(spd.SpdError) as e:
         handle.semiring_knn(dA, dB, "plus", "min", False, 65)
     assert e.value.status_name == "SPD_ERR_BAD_K"
+
+
+@pytest.mark.parametrize("sr", SEMIRINGS, ids=_name)
+def test_operands_swapped(handle, spd, signed0, sr):
+    """Every product offered is commutative, so spd_semiring_pairwise may stage B and stream A
+    like spd_pairwise: forced here, on the signed config 0 and on rows cut into slices."""
+    A, B, dA, dB = signed0
+    print("semiring swapped", _name(sr), flush=True)
+    handle.set_option("swap_operands", 2)
+    assert_distances_close(_run(handle, dA, dB, sr), oracle.semiring_pairwise(A, B, *sr), "swapped " + _name(sr))
+    A, B = _wide_pair(True)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    for name, value in (("split_len", 4), ("window", 64), ("force_kind", 3), ("lds_budget", 8192), ("chunks", 3)):
+        handle.set_option(name, value)
+    want = oracle.semiring_pairwise(A, B, *sr, mode="full")
+    assert_distances_close(_run(handle, dA, dB, sr), want, "swapped slices " + _name(sr))
