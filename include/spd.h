@@ -214,7 +214,8 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *   "force_kind"  0 auto, 1 dense strip, 2 column-slot strip, 3 hash, 4 Bloom filter (every row of A
  *                 alone in a workgroup, its columns in a Bloom filter in LDS, its values looked up in
  *                 global memory by binary search: Section 3.3.2's alternative; not for Chebyshev or the
- *                 semirings whose sum() is min or max)
+ *                 semirings whose sum() is min or max), 5 bitmap of the staged columns with running
+ *                 counts (a column's slot is the number of staged columns below it)
  *   "bloom_long_rows" 1: a row of A too long to be staged whole gets a Bloom filter instead of being
  *                 cut into slices (default 0: measured slower than slices on every shape tried)
  *   "max_rows"    largest number of A rows staged together (1, 2, 4, 8 or 16; the set metrics,
@@ -257,7 +258,7 @@ spd_status spd_set_option(spd_handle *handle, const char *name, int64_t value);
 typedef struct {
     char name[24];        /* "pack_b", "scan", "finalize", "knn_merge"                   */
     int32_t rows_per_group; /* scan: R, the rows of A staged together; else 0            */
-    int32_t staging_kind; /* scan: 1 dense strip, 2 column-slot strip, 3 hash, 4 Bloom; else 0 */
+    int32_t staging_kind; /* scan: 1 dense strip, 2 column-slot strip, 3 hash, 4 Bloom, 5 bitmap; else 0 */
     int32_t block;        /* scan: threads per workgroup; else 0                          */
     int32_t lds_bytes;    /* scan: dynamic LDS per workgroup; else 0                      */
     int64_t a_rows;       /* scan: rows (or slices of rows) of A the launch covers        */

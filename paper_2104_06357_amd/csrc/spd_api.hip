@@ -1128,7 +1128,7 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
         if (value < 8192 || value > 160 * 1024) return fail(h, SPD_ERR_UNSUPPORTED, "lds_budget must lie in [8192, 163840]");
         o.lds_budget = value;
     } else if (s == "force_kind") {
-        if (value < 0 || value > 4) return fail(h, SPD_ERR_UNSUPPORTED, "force_kind must be 0..4");
+        if (value < 0 || value > 5) return fail(h, SPD_ERR_UNSUPPORTED, "force_kind must be 0..5");
         o.force_kind = (int)value;
     } else if (s == "max_rows") {
         if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16)

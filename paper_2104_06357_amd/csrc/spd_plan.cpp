@@ -273,9 +273,10 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
     if (kind == KIND_AUTO) {
         if (staging_fits(KIND_STRIP, words(std::min(4 * min_r, max_r)), 0, k, cheb, budget)) kind = KIND_STRIP;
         else if ((int64_t)(k + 1) * 2 <= budget / 3) kind = KIND_SLOT;
+        else if ((int64_t)bitmap_words(k) * 8 <= budget / 3) kind = KIND_BITMAP;
         else kind = KIND_HASH;
     }
-    if (kind < KIND_STRIP || kind > KIND_BLOOM) return "bad staging kind";
+    if (kind < KIND_STRIP || kind > KIND_BITMAP) return "bad staging kind";
     dmax = 0;
     if (kind == KIND_BLOOM) {
         if (!bloom_serves(op)) return "Bloom staging does not serve this product";
@@ -582,7 +583,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
         if (op == OP_CNT ? (c.R < 4 || (knn_k > 0 && c.R > 16)) : c.R > 16) return "class R outside the product's range";
         if (wide_sums(metric) && c.R > 8) return "two-sum product with R > 8";
         if ((op == OP_MINK || op == OP_MINK_ANY) && c.R > 4) return "Minkowski with R > 4";
-        if (c.kind < KIND_STRIP || c.kind > KIND_BLOOM) return "class kind";
+        if (c.kind < KIND_STRIP || c.kind > KIND_BITMAP) return "class kind";
         if (c.kind == KIND_BLOOM && (c.R != 1 || !bloom_serves(op))) return "Bloom class outside its range";
         if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";
         if ((int64_t)c.lds_bytes + kStaticLds > opt.lds_budget) return "class LDS over budget";

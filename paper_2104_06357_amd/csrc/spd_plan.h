@@ -7,9 +7,9 @@
 // (Section 3.3).  On an MI355X the 160 KB of LDS per compute unit are spent differently:
 //   * R rows of A (up to 16) are staged together, so that every entry of B that a lane
 //     loads is applied to R rows;
-//   * the staged rows share ONE column map (direct strip, 16-bit column-slot strip, or a
-//     hash table of the union of their columns) in front of a table of R values per
-//     column, so a column of B is looked up once for the R rows;
+//   * the staged rows share ONE column map (direct strip, 16-bit column-slot strip, a bitmap of
+//     the columns with running counts, or a hash table of the union of their columns) in front
+//     of a table of R values per column, so a column of B is looked up once for the R rows;
 //   * rows that do not fit alone are cut into contiguous slices whose partial results are
 //     summed afterwards (the partitions of Section 3.3.3, by column range); or (option) they
 //     stay in global memory behind a Bloom filter of their columns in LDS, and a column
@@ -31,7 +31,7 @@
 
 namespace spd {
 
-enum StageKind { KIND_AUTO = 0, KIND_STRIP = 1, KIND_SLOT = 2, KIND_HASH = 3, KIND_BLOOM = 4 };
+enum StageKind { KIND_AUTO = 0, KIND_STRIP = 1, KIND_SLOT = 2, KIND_HASH = 3, KIND_BLOOM = 4, KIND_BITMAP = 5 };
 
 constexpr int kWave = 64;
 constexpr int kScanUnroll = 4;              // a slab is scanned in blocks of this many steps
@@ -102,7 +102,7 @@ SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
 // lane: 8 means at most 64).  The light pairwise instances run two workgroups of 16
 // wavefronts per compute unit that way.
 SPD_HD constexpr int scan_min_waves(int op, int R, int kind, bool knn) {
-    if (!knn && R <= 8 && kind != 3 /* KIND_HASH */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM || op == OP_CANB)) return 8;
+    if (!knn && R <= 8 && kind != 3 /* KIND_HASH */ && kind != 5 /* KIND_BITMAP */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM || op == OP_CANB)) return 8;
     // 128 registers: two workgroups of 8 wavefronts per compute unit
     if (!knn && R == 8 && (op == OP_SEMI_SUM || op == OP_SEMI_EXT)) return 4;
     // (the k-NN instances of these sit a register or two above 128 otherwise)
@@ -117,6 +117,10 @@ struct LdsLayout {
     uint32_t cap;        // hash capacity in entries (power of two, two entries per bucket), 0 otherwise
     uint32_t off_vals, off_map, off_rank, total;
 };
+
+// Bitmap staging: one 8-byte word per 32 columns {the columns' bits, the number of staged columns
+// below the word plus one}; the word of the column one past the last (the idle column) exists too.
+SPD_HD constexpr uint32_t bitmap_words(uint32_t k) { return (k >> 5) + 1u; }
 
 SPD_HD uint32_t pow2_at_least(uint32_t v) {
     uint32_t c = 16;
@@ -147,6 +151,8 @@ SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool c
     L.off_map = off;
     if (kind == KIND_SLOT) {
         off += ((k + 1u) * 2u + 15u) & ~15u;
+    } else if (kind == KIND_BITMAP) {
+        off += (bitmap_words(k) * 8u + 15u) & ~15u;
     } else if (kind == KIND_HASH) {
         L.cap = pow2_at_least(sumlen << hscale);
         off += L.cap * 8u;

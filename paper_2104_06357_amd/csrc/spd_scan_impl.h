@@ -223,6 +223,11 @@ template <> __device__ __forceinline__ Op<OP_JS>::Acc acc_shfl_xor<OP_JS>(const 
 //    hashing): a lookup reads exactly the two.  Half full, linear probing would walk 8 to 13
 //    buckets for its unluckiest entry, and every lookup would have to read as many.
 //
+// KIND_BITMAP replaces the table by one bit per column of the matrix and, per word of 32 bits,
+// the number of staged columns before it: one 8-byte read at a place the column number gives
+// directly, no multiplication, no comparison of keys (it fits while the column count stays
+// under some 200,000).
+//
 // KIND_BLOOM keeps no table at all: the row's columns set two bits each of a Bloom filter in
 // LDS, and a column that finds both of its bits set is searched for in the row itself (global
 // memory, ascending columns: a binary search of a fixed number of steps).  The "slot" is the
@@ -232,6 +237,7 @@ template <int KIND> struct ColumnMap {
     const int32_t *row_cols;  // KIND_BLOOM: the staged row's columns (global memory)
     int row_len, search_steps;
     const uint16_t *slot16;   // KIND_SLOT: k+1 entries
+    const uint2 *words;       // KIND_BITMAP: per 32 columns {their bits, staged columns below the word + 1}
     const uint4 *table;       // KIND_HASH: buckets {column, slot, column, slot}, empty = {kEmptyKey, 0}
     uint32_t mask, shift;     // over buckets
     uint32_t mult1, mult2;    // odd multipliers of the two hash functions
@@ -253,6 +259,15 @@ template <int KIND> struct ColumnMap {
     __device__ __forceinline__ uint32_t lookup(uint32_t c) const {
         if constexpr (KIND == KIND_STRIP) return c;
         else if constexpr (KIND == KIND_SLOT) return slot16[c];
+        else if constexpr (KIND == KIND_BITMAP) {
+            // the slot of a staged column is its rank among the staged columns (plus one): the
+            // count the word carries plus the bits below the column's own; 0 if its bit is clear
+            // (the bit-field extract takes its offset and its width from the low five bits of
+            // the operand: the column number serves as it is)
+            const uint2 e = words[c >> 5];
+            const uint32_t rank = (uint32_t)__builtin_popcount(__builtin_amdgcn_ubfe(e.x, 0u, c)) + e.y;
+            return __builtin_amdgcn_ubfe(e.x, c, 1u) ? rank : 0u;
+        }
         else if constexpr (KIND == KIND_BLOOM) {
             const uint32_t b1 = bit1(c), b2 = bit2(c);
             const bool maybe = ((bits[b1 >> 5] >> (b1 & 31u)) & (bits[b2 >> 5] >> (b2 & 31u)) & 1u) != 0u;
@@ -338,6 +353,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     __shared__ double s_na[R][2];
     __shared__ int s_ctr;
     __shared__ int s_reach;                      // hash staging: buckets the longest insertion walked
+    __shared__ uint32_t s_scan[KIND == KIND_BITMAP ? 16 : 1];   // bitmap staging: the wavefronts' totals of the scan
     __shared__ uint32_t s_tau[KNN ? R : 1];      // k-NN: an upper bound of the workgroup's k-th distance, per row
     __shared__ uint32_t s_share[KNN ? R * 16 : 1];   // k-NN: each wavefront's ceil(k / wavefronts)-th distance, per row
     __shared__ float s_top[kCheb ? R * kTopRanks : 1];
@@ -383,6 +399,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     unsigned char *rank8 = dyn + L.off_rank;
     ColumnMap<KIND> cmap;
     cmap.slot16 = slot16;
+    cmap.words = reinterpret_cast<const uint2 *>(dyn + L.off_map);
     cmap.table = table;
     cmap.mask = L.cap ? L.cap / 2u - 1u : 0u;
     cmap.shift = L.cap ? 33u - (uint32_t)__builtin_ctz(L.cap) : 0u;
@@ -409,6 +426,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             uint32_t nw32 = (args.k + 2u) / 2u;
             uint32_t *m32 = reinterpret_cast<uint32_t *>(slot16);
             for (uint32_t i = tid; i < nw32; i += nthr) m32[i] = 0u;
+        } else if constexpr (KIND == KIND_BITMAP) {
+            uint2 *w2 = reinterpret_cast<uint2 *>(dyn + L.off_map);
+            for (uint32_t i = tid; i < bitmap_words(args.k); i += nthr) w2[i] = make_uint2(0u, 0u);
         } else if constexpr (KIND == KIND_HASH) {
             for (uint32_t i = tid; i < L.cap / 2u; i += nthr) table[i] = make_uint4(kEmptyKey, 0u, kEmptyKey, 0u);
         } else if constexpr (KIND == KIND_BLOOM) {
@@ -470,6 +490,36 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         };
         if constexpr (KIND == KIND_SLOT) {
             for_each_entry([&](uint32_t c, uint32_t id) { if (slot16[c] == 0) slot16[c] = (uint16_t)id; });
+            __syncthreads();
+        } else if constexpr (KIND == KIND_BITMAP) {
+            // every stored column sets its bit; then the words' running counts: each thread sums
+            // the bits of its run of consecutive words, the runs' sums are scanned over the
+            // workgroup (inside the wavefronts, then over the wavefronts' totals), and each
+            // thread walks its run again
+            uint2 *w2 = reinterpret_cast<uint2 *>(dyn + L.off_map);
+            for_each_entry([&](uint32_t c, uint32_t) { atomicOr(&w2[c >> 5].x, 1u << (c & 31u)); });
+            __syncthreads();
+            const uint32_t nwords = bitmap_words(args.k);
+            const uint32_t per = (nwords + (uint32_t)nthr - 1u) / (uint32_t)nthr;
+            const uint32_t w_begin = min((uint32_t)tid * per, nwords), w_end = min(w_begin + per, nwords);
+            uint32_t mine = 0u;
+            for (uint32_t w = w_begin; w < w_end; ++w) mine += (uint32_t)__builtin_popcount(w2[w].x);
+            uint32_t incl = mine;                        // inclusive scan over the wavefront's lanes
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const uint32_t up = (uint32_t)__shfl_up((int)incl, d);
+                if (lane >= d) incl += up;
+            }
+            if (lane == kWave - 1) s_scan[wave] = incl;
+            __syncthreads();
+            uint32_t before = 1u;                        // slot ids start at 1
+            for (int w = 0; w < wave; ++w) before += s_scan[w];
+            before += incl - mine;
+            for (uint32_t w = w_begin; w < w_end; ++w) {
+                const uint32_t bits = w2[w].x;
+                w2[w].y = before;
+                before += (uint32_t)__builtin_popcount(bits);
+            }
             __syncthreads();
         } else if constexpr (KIND == KIND_BLOOM) {
             uint32_t *bits = reinterpret_cast<uint32_t *>(dyn + L.off_map);
@@ -1020,6 +1070,7 @@ static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, c
             case KIND_STRIP: return launch_scan_rkk<OP, R, KIND_STRIP, true>(st, block, lds_bytes, args);
             case KIND_SLOT: return launch_scan_rkk<OP, R, KIND_SLOT, true>(st, block, lds_bytes, args);
             case KIND_HASH: return launch_scan_rkk<OP, R, KIND_HASH, true>(st, block, lds_bytes, args);
+            case KIND_BITMAP: return launch_scan_rkk<OP, R, KIND_BITMAP, true>(st, block, lds_bytes, args);
             case KIND_BLOOM:
                 if constexpr (R == 1 && bloom_serves(OP)) return launch_scan_rkk<OP, R, KIND_BLOOM, true>(st, block, lds_bytes, args);
                 else return hipErrorInvalidValue;
@@ -1032,6 +1083,7 @@ static hipError_t launch_scan_r(hipStream_t st, int block, uint32_t lds_bytes, c
         case KIND_STRIP: return launch_scan_rkk<OP, R, KIND_STRIP, false>(st, block, lds_bytes, args);
         case KIND_SLOT: return launch_scan_rkk<OP, R, KIND_SLOT, false>(st, block, lds_bytes, args);
         case KIND_HASH: return launch_scan_rkk<OP, R, KIND_HASH, false>(st, block, lds_bytes, args);
+        case KIND_BITMAP: return launch_scan_rkk<OP, R, KIND_BITMAP, false>(st, block, lds_bytes, args);
         case KIND_BLOOM:
             if constexpr (R == 1 && bloom_serves(OP)) return launch_scan_rkk<OP, R, KIND_BLOOM, false>(st, block, lds_bytes, args);
             else return hipErrorInvalidValue;

@@ -52,12 +52,12 @@ def test_config0_every_pair(handle, config0, metric):
     assert_distances_close(got, want, metric)
 
 
-@pytest.mark.parametrize("kind", [1, 2, 3])
+@pytest.mark.parametrize("kind", [1, 2, 3, 5])
 @pytest.mark.parametrize("max_rows", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("metric", ["cosine", "l1", "chebyshev", "jensen_shannon", "minkowski", "hamming",
                                     "jaccard", "russell_rao"])
 def test_config0_every_staging_path(handle, config0, metric, kind, max_rows):
-    """Dense strip, column-slot strip and hash staging, with 1..16 rows of A per workgroup
+    """Dense strip, column-slot strip, hash and bitmap staging, with 1..16 rows of A per workgroup
     (4..32 for the set metrics, which stage a byte per row)."""
     A, B, dA, dB = config0
     print("config0 staging", metric, kind, max_rows, flush=True)
@@ -147,7 +147,7 @@ def test_set_metrics_both_routes_and_long_slabs(handle, spd, metric, byte_counte
     plan = spd.host_plan_summary(A["indptr"], B["indptr"], 1000, metric, split_len=1 << 20)
     assert plan["split_rows"] == 0 and plan["max_slab_steps"] >= 900
     want = oracle.pairwise(A, B, ORACLE_NAME[metric], mode="full")
-    for kind in (2, 3):
+    for kind in (2, 3, 5):
         handle.set_option("force_kind", kind)
         assert_distances_close(_run_pairwise(handle, dA, dB, metric), want, "%s kind %d" % (metric, kind))
         idx, dist = handle.knn(dA, dB, metric, 8)
@@ -301,7 +301,7 @@ def test_config1_sampled_pairs(handle, config1, metric):
     assert_distances_close(got[np.ix_(ra, rb)], want, metric)
 
 
-@pytest.mark.parametrize("kind", [1, 3])
+@pytest.mark.parametrize("kind", [1, 3, 5])
 def test_config1_other_staging_kinds(handle, config1, kind):
     A, B, dA, dB = config1
     print("config1 kind", kind, flush=True)
@@ -491,7 +491,7 @@ def test_operands_swapped_config0_and_edge_rows(handle, spd, config0, metric):
     p = _p_of(metric)
     handle.set_option("swap_operands", 2)
     want = oracle.pairwise(A, B, ORACLE_NAME[metric], p)
-    for kind, max_rows in ((1, 8), (2, 8), (3, 8), (2, 1), (3, 4), (2, 16)):
+    for kind, max_rows in ((1, 8), (2, 8), (3, 8), (5, 8), (2, 1), (3, 4), (5, 2), (2, 16)):
         handle.set_option("force_kind", kind)
         handle.set_option("max_rows", max_rows)
         assert_distances_close(_run_pairwise(handle, dA, dB, metric, p), want, "%s kind=%d R=%d" % (metric, kind, max_rows))

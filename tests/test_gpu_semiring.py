@@ -69,7 +69,7 @@ def test_config0_every_pair(handle, config0, signed0, sr):
         assert_distances_close(got, want, "%s %s" % (tag, _name(sr)))
 
 
-@pytest.mark.parametrize("kind", [1, 2, 3])
+@pytest.mark.parametrize("kind", [1, 2, 3, 5])
 @pytest.mark.parametrize("max_rows", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("sr", SELECTED, ids=_name)
 def test_every_staging_path(handle, signed0, sr, kind, max_rows):
@@ -132,7 +132,7 @@ def test_rows_with_more_entries_than_are_ranked(handle, spd):
     dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
     for sr in (("abs_diff", "max", True), ("plus", "min", True), ("sq_diff", "max", True), ("min", "min", True),
                ("max", "max", True), ("times", "min", True)):
-        for kind in (1, 2, 3):
+        for kind in (1, 2, 3, 5):
             handle.set_option("force_kind", kind)
             want = oracle.semiring_pairwise(A, B, *sr, mode="full")
             assert_distances_close(_run(handle, dA, dB, sr), want, "%s kind %d" % (_name(sr), kind))

@@ -108,7 +108,7 @@ def test_planner_paths_and_thresholds():
     auto = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine")
     assert all(c["kind"] == 2 for c in auto["classes"])                      # 20,000 columns: slot strip
     assert auto["packed_entries"] == B["indptr"][-1] and auto["spilled_rows"] == 0
-    for kind in (1, 3):
+    for kind in (1, 3, 5):
         s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], "cosine", force_kind=kind)
         assert all(c["kind"] == kind for c in s["classes"])
     small, _ = synth.workload(0)
@@ -158,7 +158,7 @@ def test_planner_on_the_large_shapes(config, scale):
     metric = {2: "cosine", 3: "jensen_shannon", 4: "jaccard"}[config]
     s = spd.host_plan_summary(A["indptr"], B["indptr"], A["n_cols"], metric, k_neighbors=32 if config == 4 else 0)
     assert s["packed_entries"] == B["indptr"][-1]
-    expected_kind = {2: 3, 3: 2, 4: 3}[config]                               # hash / slot strip / hash
+    expected_kind = {2: 5, 3: 2, 4: 3}[config]                               # bitmap / slot strip / hash
     assert all(c["kind"] == expected_kind for c in s["classes"]), s
     if config == 3:
         # the 16-bit column-slot strip leaves room for a whole 12,000-entry row; a hash table does not
