@@ -235,8 +235,7 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 of 8 for the dot product, L1 and Hamming; 0: a group is full or halved
  *   "byte_counters" 1 (default): Jaccard, Dice and Russell-Rao count shared columns in byte lanes,
  *                 four staged rows to the 32-bit word; 0: through the dot product of 0/1 values
- *   "waves_per_cu" wavefronts a launch aims to keep on a compute unit: 8, 16 or 32
- *                 (0 = automatic: 32, or 16 for the fused k-NN kernels)
+ *   "waves_per_cu" wavefronts a launch aims to keep on a compute unit: 8, 16 or 32 (0 = automatic: 32)
  *   "side_streams" how many internal streams (0 to 3; default 3) the launches that are small against
  *                 the call's largest one may use beside it, forked and joined with events so that
  *                 the handle's stream still orders the whole call (0: everything on the handle's stream);

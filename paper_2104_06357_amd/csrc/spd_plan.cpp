@@ -237,12 +237,14 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt) {
 
 namespace {
 
-bool staging_fits(int kind, int R, uint64_t sumlen, uint32_t k, bool cheb, int64_t budget) {
-    if (kind == KIND_BLOOM) return (int64_t)lds_layout(kind, R, (uint32_t)std::min<uint64_t>(sumlen, 1u << 30), k, cheb, 1).total <= budget;
+// `R`: words per slot of the value table; `knn_rows`: staged rows that keep a k-NN list.
+bool staging_fits(int kind, int R, uint64_t sumlen, uint32_t k, bool cheb, int64_t budget, uint32_t knn_rows) {
+    if (kind == KIND_BLOOM)
+        return (int64_t)lds_layout(kind, R, (uint32_t)std::min<uint64_t>(sumlen, 1u << 30), k, cheb, 1, knn_rows).total <= budget;
     if (kind != KIND_STRIP && sumlen > 65534u) return false;      // 16-bit slot ids
     uint64_t nslots = (kind == KIND_STRIP) ? (uint64_t)k + 1u : sumlen + 1u;
     if (nslots * (uint64_t)R * 5u > (uint64_t)budget) return false;   // also keeps the 32-bit layout math safe
-    LdsLayout L = lds_layout(kind, R, (uint32_t)sumlen, k, cheb, 1);
+    LdsLayout L = lds_layout(kind, R, (uint32_t)sumlen, k, cheb, 1, knn_rows);
     return (int64_t)L.total <= budget;
 }
 
@@ -267,11 +269,12 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
         max_r = std::min(4 * max_r, knn ? (opt.max_rows > 8 ? 16 : 8) : 32);
     }
     auto words = [&](int R) { return table_words(op, R); };
+    auto lists = [&](int R) { return knn ? (uint32_t)R : 0u; };
     if (opt.lds_budget <= (int64_t)kStaticLds + 256) return "lds_budget too small";
     const int64_t budget = opt.lds_budget - kStaticLds;
     kind = opt.force_kind;
     if (kind == KIND_AUTO) {
-        if (staging_fits(KIND_STRIP, words(std::min(4 * min_r, max_r)), 0, k, cheb, budget)) kind = KIND_STRIP;
+        if (staging_fits(KIND_STRIP, words(std::min(4 * min_r, max_r)), 0, k, cheb, budget, lists(std::min(4 * min_r, max_r)))) kind = KIND_STRIP;
         else if ((int64_t)(k + 1) * 2 <= budget / 3) kind = KIND_SLOT;
         else if ((int64_t)bitmap_words(k) * 8 <= budget / 3) kind = KIND_BITMAP;
         else kind = KIND_HASH;
@@ -285,15 +288,15 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
         return std::string();
     }
     if (kind == KIND_STRIP) {
-        if (!staging_fits(KIND_STRIP, words(min_r), 0, k, cheb, budget)) return "dense strip does not fit the LDS budget";
-        while (max_r > min_r && !staging_fits(KIND_STRIP, words(max_r), 0, k, cheb, budget)) max_r /= 2;
+        if (!staging_fits(KIND_STRIP, words(min_r), 0, k, cheb, budget, lists(min_r))) return "dense strip does not fit the LDS budget";
+        while (max_r > min_r && !staging_fits(KIND_STRIP, words(max_r), 0, k, cheb, budget, lists(max_r))) max_r /= 2;
         return std::string();
     }
-    if (!staging_fits(kind, words(min_r), 1, k, cheb, budget)) return "LDS budget too small to stage a single entry";
+    if (!staging_fits(kind, words(min_r), 1, k, cheb, budget, lists(min_r))) return "LDS budget too small to stage a single entry";
     uint64_t lo = 1, hi = 65534;
     while (lo < hi) {
         uint64_t mid = (lo + hi + 1) / 2;
-        if (staging_fits(kind, words(min_r), mid, k, cheb, budget)) lo = mid; else hi = mid - 1;
+        if (staging_fits(kind, words(min_r), mid, k, cheb, budget, lists(min_r))) lo = mid; else hi = mid - 1;
     }
     dmax = lo;
     return std::string();
@@ -330,15 +333,15 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
         if (!why.empty()) return why;
     }
     const int64_t budget = opt.lds_budget - kStaticLds;
-    auto fits = [&](int kd, int R, uint64_t sumlen) { return staging_fits(kd, table_words(op, R), sumlen, k, cheb, budget); };
-    // the fused k-NN instances hold more registers per lane: fewer of their wavefronts fit
-    const int want_waves = opt.waves_per_cu > 0 ? opt.waves_per_cu : (knn_k > 0 ? 16 : 32);
+    auto lists = [&](int R) { return knn_k > 0 ? (uint32_t)R : 0u; };
+    auto fits = [&](int kd, int R, uint64_t sumlen) { return staging_fits(kd, table_words(op, R), sumlen, k, cheb, budget, lists(R)); };
+    const int want_waves = opt.waves_per_cu > 0 ? opt.waves_per_cu : 32;
 
     auto finish_class = [&](AClass &c) {
         auto need_at = [&](int hs) {
             uint32_t need = 0;
             for (int g = 0; g < c.n_groups; ++g)
-                need = std::max(need, lds_layout(c.kind, table_words(op, c.R), (uint32_t)c.sumlen[(size_t)g], k, cheb, hs).total);
+                need = std::max(need, lds_layout(c.kind, table_words(op, c.R), (uint32_t)c.sumlen[(size_t)g], k, cheb, hs, lists(c.R)).total);
             return need;
         };
         uint32_t need = need_at(1);
@@ -353,10 +356,6 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
             }
         }
         c.block = std::min(block_for(need, opt.lds_budget, want_waves), scan_max_block(op, c.R, knn_k > 0));
-        if (knn_k > 0) {
-            while (c.block > kWave && (int64_t)knn_merge_bytes(c.block, c.R, knn_k) > budget) c.block /= 2;
-            need = std::max(need, knn_merge_bytes(c.block, c.R, knn_k));
-        }
         c.lds_bytes = (need + 15u) & ~15u;
     };
 
@@ -455,7 +454,7 @@ std::string plan_a(const int64_t *indptr, int64_t n_rows, int64_t n_cols, int me
     auto emit_group = [&](int R, const ARow *rows, size_t n, uint64_t sum) {
         int ci = 0;
         while ((32 >> ci) != R) ++ci;
-        uint32_t need = lds_layout(kind, table_words(op, R), (uint32_t)sum, k, cheb, 1).total;
+        uint32_t need = lds_layout(kind, table_words(op, R), (uint32_t)sum, k, cheb, 1, lists(R)).total;
         AClass &c = *by_key[ci][occupancy_bucket(need, opt.lds_budget)];
         for (int q = 0; q < R; ++q)
             c.rows.push_back((size_t)q < n ? rows[q] : ARow{0, 0, -1, kRowFirst | kRowLast, 0});
@@ -588,7 +587,6 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
         if (c.block != 256 && c.block != 512 && c.block != 1024 && c.block != 128 && c.block != 64) return "class block";
         if ((int64_t)c.lds_bytes + kStaticLds > opt.lds_budget) return "class LDS over budget";
         if ((size_t)c.n_groups * c.R != c.rows.size() || (size_t)c.n_groups != c.sumlen.size()) return "class sizes";
-        if (knn_k > 0 && knn_merge_bytes(c.block, c.R, knn_k) > c.lds_bytes) return "k-NN merge area";
         if (c.block > scan_max_block(op, c.R, knn_k > 0)) return "class block over the kernel's bound";
         for (int g = 0; g < c.n_groups; ++g) {
             int64_t sum = 0;
@@ -614,7 +612,9 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
             }
             if (sum != c.sumlen[(size_t)g]) return "group sumlen";
             if (c.hscale < 1 || c.hscale > 3) return "class hash scale";
-            LdsLayout L = lds_layout(c.kind, table_words(op, c.R), (uint32_t)sum, (uint32_t)n_cols, cheb, c.hscale);
+            LdsLayout L = lds_layout(c.kind, table_words(op, c.R), (uint32_t)sum, (uint32_t)n_cols, cheb, c.hscale,
+                                     knn_k > 0 ? (uint32_t)c.R : 0u);
+            if (knn_k > 0 && (L.off_knn & 7u)) return "k-NN lists not 8-byte aligned";
             if (c.kind == KIND_HASH && (L.cap < 2u * (uint32_t)sum || L.cap < 16u)) return "hash table too full";
             if (L.total > c.lds_bytes) return "group LDS over the launch size";
             if (c.kind != KIND_STRIP && L.nslots > 65535u) return "slot ids over 16 bits";

@@ -49,7 +49,7 @@ struct PlanOptions {
     int window = 2048;
     int chunks = 0;
     int n_cus = 256;
-    int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32, or 16 for k-NN)
+    int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32)
     int bloom_long_rows = 0;                // 1: a row too long for the LDS gets a Bloom filter instead of slices
     int sort_slack = 1;                     // 1: B's rows are sorted by length in whole blocks of steps, 0: by exact length
     int partial_groups = 1;                 // 1: a group of R rows may leave a quarter of its places empty rather than fall to R/2
@@ -115,8 +115,12 @@ SPD_HD constexpr int scan_min_waves(int op, int R, int kind, bool knn) {
 struct LdsLayout {
     uint32_t nslots;     // rows of the value table (R floats each)
     uint32_t cap;        // hash capacity in entries (power of two, two entries per bucket), 0 otherwise
-    uint32_t off_vals, off_map, off_rank, total;
+    uint32_t off_vals, off_map, off_rank, off_knn, total;
 };
+
+// Fused k-NN: per staged row the workgroup keeps one sorted list of the best candidates so far
+// (64 keys of 8 bytes) and a queue of 64 candidates waiting to be merged into it.
+constexpr uint32_t kKnnAreaBytes = 2u * 64u * 8u;
 
 // Bitmap staging: one 8-byte word per 32 columns {the columns' bits, the number of staged columns
 // below the word plus one}; the word of the column one past the last (the idle column) exists too.
@@ -129,7 +133,8 @@ SPD_HD uint32_t pow2_at_least(uint32_t v) {
 }
 
 // `hscale`: the hash table holds at least sumlen << hscale entries (1..3: load <= 1/2, 1/4, 1/8).
-SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool cheb, int hscale) {
+// `knn_rows`: staged rows that keep a k-NN list (0 for a pairwise launch).
+SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool cheb, int hscale, uint32_t knn_rows = 0) {
     LdsLayout L;
     L.cap = 0;
     if (kind == KIND_BLOOM) {
@@ -141,7 +146,8 @@ SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool c
         L.nslots = 0;
         L.off_vals = 0; L.off_map = 0;
         L.off_rank = bits / 8u;
-        L.total = bits / 8u;
+        L.off_knn = bits / 8u;
+        L.total = bits / 8u + knn_rows * kKnnAreaBytes;
         return L;
     }
     L.nslots = (kind == KIND_STRIP) ? k + 1u : sumlen + 1u;
@@ -159,6 +165,8 @@ SPD_HD LdsLayout lds_layout(int kind, int R, uint32_t sumlen, uint32_t k, bool c
     }
     L.off_rank = off;
     if (cheb) off += ((L.nslots * (uint32_t)R) + 15u) & ~15u;
+    L.off_knn = off;
+    off += knn_rows * kKnnAreaBytes;
     L.total = off;
     return L;
 }
@@ -242,10 +250,5 @@ void plan_chunks(const BPlan &b, AClass &c, const PlanOptions &opt);
 // LDS sizes).  Empty string if consistent.
 std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, const int64_t *b_indptr,
                        int64_t n_cols, int metric, int op, int knn_k, const PlanOptions &opt);
-
-// LDS needed to merge the per-wave k-NN lists of a workgroup (overlays the staging area).
-inline uint32_t knn_merge_bytes(int block, int R, int k) {
-    return (uint32_t)(block / kWave) * (uint32_t)R * (uint32_t)k * 8u;
-}
 
 }  // namespace spd

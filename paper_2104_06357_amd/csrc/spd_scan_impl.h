@@ -162,6 +162,65 @@ struct KnnList {
     }
 };
 
+// ------------------------------------------------------------------------------------
+// fused k-NN inside the scan kernel: one list per staged row and workgroup, in LDS
+// ------------------------------------------------------------------------------------
+// The key no candidate reaches: (+infinity, the largest index).
+constexpr uint64_t kKnnUnused = 0xFF8000007FFFFFFFull;
+constexpr int kKnnQueue = 64;             // candidates a row's queue holds (one wavefront's offer always fits an empty queue)
+constexpr int kKnnLockSpins = 1 << 24;    // bound of the wait for a row's lock (never reached: the holder does not wait for anyone)
+
+// A staged row's selection state: `list` holds the best keys so far in ascending order (entry
+// t at position t, kKnnUnused beyond the k-th), `queue` the candidates that passed the bound
+// since the list was last brought up to date.
+struct KnnRowArea { uint64_t list[kWave]; uint64_t queue[kKnnQueue]; };
+static_assert(sizeof(KnnRowArea) == kKnnAreaBytes, "the planner sizes the launch with kKnnAreaBytes per row");
+
+// Merges the first `cnt` queued candidates into the list (the whole wavefront takes part: the
+// queue is sorted descending, its lane-wise minimum with the ascending list is a bitonic
+// sequence of the 64 smallest keys of both) and returns the list's new k-th key.
+__device__ __forceinline__ uint64_t knn_merge_queue(KnnRowArea *area, int cnt, int k, int lane) {
+    uint64_t c = lane < cnt ? area->queue[lane] : kKnnUnused;
+    c = wave_sort_desc(c, lane);
+    const uint64_t mine = area->list[lane];
+    c = wave_merge_asc(c < mine ? c : mine, lane);
+    if (lane >= k) c = kKnnUnused;
+    area->list[lane] = c;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)c, k - 1);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(c >> 32), k - 1);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Every lane may offer one candidate key for the staged row whose state is (area, tau, count,
+// lock).  Candidates below the row's bound are appended to its queue under the row's lock; a
+// queue that cannot take them is merged into the list first, which tightens the bound.  The
+// lock is held for a few dozen instructions by a wavefront that waits for nothing meanwhile.
+__device__ __forceinline__ void knn_offer(KnnRowArea *area, unsigned long long *tau_p, int *count_p, int *lock_p,
+                                          uint64_t key, bool valid, uint64_t tau, int k, int lane) {
+    bool pass = valid && key < tau;
+    uint64_t m = __ballot(pass);
+    if (m == 0) return;
+    if (lane == 0) {
+        int spins = 0;
+        while (atomicCAS(lock_p, 0, 1) != 0 && ++spins < kKnnLockSpins) __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    int cnt = wave_uniform(__atomic_load_n(count_p, __ATOMIC_RELAXED));
+    int n = (int)__popcll(m);
+    if (cnt + n > kKnnQueue) {
+        const uint64_t now = knn_merge_queue(area, cnt, k, lane);
+        if (lane == 0) __atomic_store_n(tau_p, (unsigned long long)now, __ATOMIC_RELAXED);
+        cnt = 0;
+        pass = pass && key < now;               // the merge may have ruled some of them out
+        m = __ballot(pass);
+        n = (int)__popcll(m);
+    }
+    if (pass) area->queue[cnt + (int)lane_rank_in(m)] = key;
+    if (lane == 0) __atomic_store_n(count_p, cnt + n, __ATOMIC_RELAXED);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) __atomic_store_n(lock_p, 0, __ATOMIC_RELAXED);
+}
+
 // c ? b : a on any plain struct, word by word (selects, no branch).
 template <typename T> __device__ __forceinline__ T select_words(bool c, const T &a, const T &b) {
     static_assert(sizeof(T) % 4 == 0, "whole words");
@@ -354,8 +413,9 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     __shared__ int s_ctr;
     __shared__ int s_reach;                      // hash staging: buckets the longest insertion walked
     __shared__ uint32_t s_scan[KIND == KIND_BITMAP ? 16 : 1];   // bitmap staging: the wavefronts' totals of the scan
-    __shared__ uint32_t s_tau[KNN ? R : 1];      // k-NN: an upper bound of the workgroup's k-th distance, per row
-    __shared__ uint32_t s_share[KNN ? R * 16 : 1];   // k-NN: each wavefront's ceil(k / wavefronts)-th distance, per row
+    __shared__ unsigned long long s_knn_tau[KNN ? R : 1];   // k-NN: the k-th key of the row's list (the bar a candidate has to beat)
+    __shared__ int s_knn_count[KNN ? R : 1];                // k-NN: candidates waiting in the row's queue
+    __shared__ int s_knn_lock[KNN ? R : 1];                 // k-NN: 1 while a wavefront works on the row's queue
     __shared__ float s_top[kCheb ? R * kTopRanks : 1];
     __shared__ int s_topn[R];
     __shared__ uint32_t s_clo[kCheb ? R : 1], s_cspan[kCheb ? R : 1];   // column range a slice answers for
@@ -449,9 +509,10 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         s_ctr = slab_begin;
         s_reach = 1;
     }
+    KnnRowArea *knn_rows = reinterpret_cast<KnnRowArea *>(dyn + L.off_knn);
     if constexpr (KNN) {
-        if (tid < R) s_tau[tid] = float_order_key(__builtin_huge_valf());
-        for (int e = tid; e < R * 16; e += nthr) s_share[e] = float_order_key(__builtin_huge_valf());
+        if (tid < R) { s_knn_tau[tid] = kKnnUnused; s_knn_count[tid] = 0; s_knn_lock[tid] = 0; }
+        for (int e = tid; e < R * kWave; e += nthr) knn_rows[e / kWave].list[e % kWave] = kKnnUnused;
     }
     // 2. row norms: one wavefront per row, summed in a fixed order (Section 3.4)
     for (int r = wave; r < R; r += nw) {
@@ -702,11 +763,6 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     }
 
     // ---- scan: every wavefront takes slabs of the chunk until none is left -----------
-    KnnList lists[KNN ? R : 1];
-    if constexpr (KNN) {
-#pragma unroll
-        for (int r = 0; r < R; ++r) lists[r].reset();
-    }
     const int64_t n_b = args.b.n_rows;
     const float *bloom_values = args.a_values + (KIND == KIND_BLOOM ? s_rows[0].start : 0);
 
@@ -723,7 +779,6 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         Acc acc[R];
         uint32_t hit[kCheb ? R : 1];
         uint32_t counts[kCnt ? W : 1];            // set metrics: four byte counters to the word
-        bool lists_changed = false;
 #pragma unroll
         for (int r = 0; r < R; ++r) { O::init(acc[r]); if constexpr (kCheb) hit[r] = 0u; }
         if constexpr (kCnt) {
@@ -863,11 +918,6 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
         double nb0 = 0.0, nb1 = 0.0;
         if (leader) { nb0 = args.b.norms[(size_t)row * 2]; nb1 = args.b.norms[(size_t)row * 2 + 1]; }
 
-        // k-NN: the workgroup's bounds of all R rows are read and decoded once per slab, row r's in
-        // lane r (a wavefront publishes its own list's k-th distance there as soon as it has one,
-        // so the shared bound is never looser than the list's own)
-        float tau_of_lane = 0.0f;
-        if constexpr (KNN) tau_of_lane = float_from_order_key(s_tau[lane < R ? lane : 0]);
 #pragma unroll
         for (int r0 = 0; r0 < R; r0 += RB) {
             double v0[RB], v1[RB], v2[RB];
@@ -939,13 +989,12 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                 for (int i = 0; i < RB; ++i) {
                     const int r = r0 + i;
                     if (row_out[r] < 0) continue;
-                    const float bound = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tau_of_lane), r));
-                    if (__ballot(leader && dist[i] <= bound) == 0) continue;      // the usual case once the lists are warm
-                    if (lists[r].offer(dist[i], row, leader, args.knn_k, bound)) {
-                        lists_changed = true;
-                        if (lists[r].full(args.knn_k) && lane == 0)
-                            atomicMin(&s_tau[r], float_order_key(lists[r].bar_d(args.knn_k)));
-                    }
+                    // (the bound may be out of date: then it is only looser)
+                    const uint64_t tau = (uint64_t)__atomic_load_n(&s_knn_tau[r], __ATOMIC_RELAXED);
+                    const float bound = float_from_order_key((uint32_t)(tau >> 32));
+                    if (__ballot(leader && dist[i] <= bound) == 0) continue;      // the usual case once the list is warm
+                    knn_offer(&knn_rows[r], &s_knn_tau[r], &s_knn_count[r], &s_knn_lock[r], knn_key(dist[i], row), leader, tau,
+                              args.knn_k, lane);
                 }
             }
             if (leader) {
@@ -960,73 +1009,20 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                 }
             }
         }
-        if constexpr (KNN) {
-            // The wavefronts' lists hold different rows of B.  Once every wavefront holds at
-            // least q = ceil(k / wavefronts) entries, the largest of their q-th distances has k
-            // entries at or below it: a bound on the k-th distance that is far tighter than any
-            // single list's own.  (What is read here may be out of date: then it is only looser.)
-            if (lists_changed) {
-                const int q = (args.knn_k + nw - 1) / nw - 1;
-                float mine = 0.0f;
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const float qd = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lists[r].d), q));
-                    if (lane == r) mine = qd;
-                }
-                if (lane < R) s_share[lane * 16 + wave] = float_order_key(mine);
-                for (int base = 0; base < R * nw; base += kWave) {
-                    const int e = base + lane;
-                    const int r = e / nw, w = e % nw;
-                    uint32_t key = r < R ? s_share[r * 16 + w] : 0u;
-                    for (int m = 1; m < nw; m <<= 1) key = max(key, (uint32_t)__shfl_xor((int)key, m));
-                    if (r < R && w == 0 && key < s_tau[r]) atomicMin(&s_tau[r], key);
-                }
-            }
-        }
     }
 
-    // ---- k-NN: merge the wavefronts' lists, one staged row per wavefront -------------
+    // ---- k-NN: what is still queued joins the lists, which go to the chunk's place in memory --
     if constexpr (KNN) {
         const int kk = args.knn_k;
-        __syncthreads();                              // the staging area is dead from here on
-        KnnEntry *area = reinterpret_cast<KnnEntry *>(dyn);
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (lane < kk) area[((size_t)wave * R + r) * kk + lane] = KnnEntry{lists[r].d, lists[r].j};
-        __syncthreads();
+        __syncthreads();                              // every wavefront has left the scan
         for (int r = wave; r < R; r += nw) {
             const int out = s_rows[r].out;
             if (out < 0) continue;
-            KnnList merged;
-            merged.reset();
-            if (kk <= 32) {
-                // the lists are sorted: the running best ascending in the low lanes and the next
-                // list descending in the high lanes form a bitonic sequence, six steps sort it
-                const uint64_t unused = knn_key(__builtin_huge_valf(), 0x7fffffff);
-                uint64_t best = unused;
-                if (lane < kk) { const KnnEntry c = area[(size_t)r * kk + lane]; best = knn_key(c.d, c.j); }
-                for (int w = 1; w < nw; ++w) {
-                    const int t = 63 - lane;
-                    uint64_t x = best;
-                    if (t < kk) { const KnnEntry c = area[((size_t)w * R + r) * kk + t]; x = knn_key(c.d, c.j); }
-                    x = wave_merge_asc(x, lane);
-                    best = lane < kk ? x : unused;
-                }
-                merged.d = float_from_order_key((uint32_t)(best >> 32));
-                merged.j = (int)(uint32_t)best;
-            } else {
-                const int total_e = nw * kk;
-                for (int e0 = 0; e0 < total_e; e0 += 64) {
-                    int e = e0 + lane;
-                    bool valid = e < total_e;
-                    KnnEntry c = KnnEntry{0.f, 0};
-                    if (valid) c = area[((size_t)(e / kk) * R + r) * kk + (e % kk)];
-                    valid = valid && c.j != 0x7fffffff;
-                    merged.offer(c.d, c.j, valid, kk, __builtin_huge_valf());
-                }
-            }
+            knn_merge_queue(&knn_rows[r], s_knn_count[r], kk, lane);
+            const uint64_t key = knn_rows[r].list[lane];
             if (lane < kk)
-                args.knn_part[args.knn_row_off[out] + (size_t)chunk * kk + lane] = KnnEntry{merged.d, merged.j};
+                args.knn_part[args.knn_row_off[out] + (size_t)chunk * kk + lane] =
+                    KnnEntry{float_from_order_key((uint32_t)(key >> 32)), (int)(uint32_t)key};
         }
     }
 }

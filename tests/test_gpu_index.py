@@ -66,7 +66,7 @@ def test_split_rows_sliced_rows_and_every_staging_kind(handle, spd, metric):
     handle.set_option("window", 64)
     ix = handle.index_create(dB, metric, p)            # the index keeps this cut of B's rows
     want = oracle.pairwise(A, B, ORACLE_NAME[metric], p, mode="full")
-    for kind, budget in ((1, 163840), (2, 163840), (3, 163840), (5, 163840), (3, 8192)):
+    for kind, budget in ((1, 163840), (2, 163840), (3, 163840), (5, 163840), (3, 12288)):
         handle.set_option("force_kind", kind)
         handle.set_option("lds_budget", budget)
         assert_distances_close(_np(ix.pairwise(dA)), want, "%s kind %d budget %d" % (metric, kind, budget))

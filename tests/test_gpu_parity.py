@@ -349,9 +349,12 @@ def test_knn_with_sliced_rows_and_split_rows(handle, spd):
     dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
     handle.set_option("split_len", 4)
     handle.set_option("force_kind", 3)
-    handle.set_option("lds_budget", 8192)
+    handle.set_option("lds_budget", 12288)       # (a kilobyte per staged row goes to the k-NN lists)
     for metric in ("l1", "cosine", "inner_product", "jensen_shannon", "minkowski", "chebyshev", "jaccard"):
         print("knn slices", metric, flush=True)
+        plan = spd.host_plan_summary(A["indptr"], B["indptr"], 400, metric, k_neighbors=16, split_len=4, force_kind=3,
+                                     lds_budget=12288)
+        assert plan["spilled_rows"] > 0 and plan["split_rows"] > 0
         idx, dist = handle.knn(dA, dB, metric, 16, _p_of(metric))
         torch.cuda.synchronize()
         rows = oracle.pairwise(A, B, ORACLE_NAME[metric], _p_of(metric))

@@ -128,10 +128,16 @@ def test_random_case(spd, seed):
         torch.cuda.synchronize()
         assert_distances_close(got.cpu().numpy(), want, tag)
         kk = min(knn_k, B["n_rows"])
-        if semiring:
-            idx, dist = h.semiring_knn(dA, dB, *what, kk)
-        else:
-            idx, dist = index.knn(dA, kk) if via_index else h.knn(dA, dB, what, kk, p)
+        try:
+            if semiring:
+                idx, dist = h.semiring_knn(dA, dB, *what, kk)
+            else:
+                idx, dist = index.knn(dA, kk) if via_index else h.knn(dA, dB, what, kk, p)
+        except spd.SpdError as e:
+            # the k-NN lists take a kilobyte of LDS per staged row: a tight budget may not hold them
+            assert e.status_name == "SPD_ERR_UNSUPPORTED" and "lds_budget" in options, (tag, str(e))
+            print("k-NN refused:", e, flush=True)
+            return
         torch.cuda.synchronize()
         assert_knn_matches(idx.cpu().numpy(), dist.cpu().numpy(), want, kk, "semiring" if semiring else what, tag)
     finally:
