@@ -21,8 +21,13 @@ METRICS = (
     "jensen_shannon", "russell_rao", "kl_divergence_strict", "jaccard_literal",
 )
 
-PRODUCTS = ("times", "plus", "min", "max", "abs_diff", "sq_diff")
+PRODUCTS = ("times", "plus", "min", "max", "abs_diff", "sq_diff")          # the commutative menu, any sum(), any domain
+MORE_PRODUCTS = ("abs_diff_pow", "canberra", "not_equal", "x_log_x_over_y", "js_term")   # Table 1's other products
+ALL_PRODUCTS = PRODUCTS + MORE_PRODUCTS
 SUMS = ("plus", "min", "max")
+TRANSFORMS = ("none", "sqrt", "nonzero")
+EPILOGUES = ("none", "root_p", "div_k", "sqrt_half", "cosine", "l2", "correlation", "jaccard", "dice", "hellinger",
+             "russell_rao", "strict")
 
 _lib = None
 
@@ -53,7 +58,8 @@ def _load():
         lib.oracle_pairwise.restype = ctypes.c_int
         lib.oracle_semiring_pairwise.argtypes = [
             ctypes.c_int64, ctypes.c_int64, P, P, P, ctypes.c_int64, P, P, P, ctypes.c_int, ctypes.c_int,
-            ctypes.c_int, P, ctypes.c_int64, P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, P]
+            ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_int, P, ctypes.c_int64, P, ctypes.c_int64,
+            ctypes.c_int, ctypes.c_int, P]
         lib.oracle_semiring_pairwise.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -102,10 +108,13 @@ def pairwise(A, B, metric: str, p: float = 2.0, rows_a=None, rows_b=None, mode: 
 
 
 def semiring_pairwise(A, B, product: str, sum: str, over_union: bool, rows_a=None, rows_b=None,
-                      mode: str = "support", threads: int = 0):
+                      mode: str = "support", threads: int = 0, p: float = 2.0, transform: str = "none",
+                      epilogue: str = "none"):
     """fp64 semiring products between rows (Section 2.2): the `sum` fold of `product` over the
     columns stored in both rows (over_union False) or in either row, the missing side read as 0
-    (over_union True); the identity of `sum` where that set is empty."""
+    (over_union True); the identity of `sum` where that set is empty.  `transform` is applied to
+    every stored value first, `epilogue` (Table 1's expansion functions and closing steps) to the
+    folded value; `p` is the degree of "abs_diff_pow" and "root_p"."""
     lib = _load()
     if A["n_cols"] != B["n_cols"]:
         raise ValueError("column counts differ")
@@ -118,16 +127,19 @@ def semiring_pairwise(A, B, product: str, sum: str, over_union: bool, rows_a=Non
     out = np.empty((na, nb), dtype=np.float64)
     used = lib.oracle_semiring_pairwise(
         A["n_rows"], A["n_cols"], _ptr(aip), _ptr(aix), _ptr(av), B["n_rows"], _ptr(bip), _ptr(bix),
-        _ptr(bv), PRODUCTS.index(product), SUMS.index(sum), int(bool(over_union)), _ptr(ra), na, _ptr(rb), nb,
+        _ptr(bv), ALL_PRODUCTS.index(product), SUMS.index(sum), int(bool(over_union)), float(p),
+        TRANSFORMS.index(transform), EPILOGUES.index(epilogue), _ptr(ra), na, _ptr(rb), nb,
         {"full": 0, "support": 1}[mode], int(threads), _ptr(out))
     if used < 0:
         raise RuntimeError("oracle failed (%d)" % used)
     return out
 
 
-def semiring_knn(Q, Index, product: str, sum: str, over_union: bool, k: int, rows_q=None, threads: int = 0):
+def semiring_knn(Q, Index, product: str, sum: str, over_union: bool, k: int, rows_q=None, threads: int = 0,
+                 p: float = 2.0, transform: str = "none", epilogue: str = "none"):
     """The k index rows with the smallest semiring value for each query row, by (value, index)."""
-    d = semiring_pairwise(Q, Index, product, sum, over_union, rows_a=rows_q, threads=threads)
+    d = semiring_pairwise(Q, Index, product, sum, over_union, rows_a=rows_q, threads=threads, p=p,
+                          transform=transform, epilogue=epilogue)
     n = d.shape[1]
     idx = np.empty((d.shape[0], k), dtype=np.int64)
     for r in range(d.shape[0]):

@@ -231,13 +231,54 @@ static double eval_pair(int metric, double p, const double *x, const double *y,
  *   domain = columns stored in EITHER row, the missing side read as 0, for a
  *            non-annihilating product (the NAMM of Section 2.2, Eq. 2);
  * an empty domain gives the identity of sum(): 0 for +, +infinity for min, -infinity for max.
+ * Every distance of Table 1 is such a fold with a transform of the stored values in front of it
+ * and an epilogue after it (Section 2.2 for the products, Table 1's "Expansion" column and
+ * Section 3.4 for the epilogues of the dot-product family; the C++ interface shown in Section 4.2
+ * passes the product and the sum as functors to one primitive): the transforms and epilogues are
+ * spelled out here, each from its definition, so that the composition can be checked against the
+ * plain formulas of eval_pair above.
  */
-enum { P_TIMES = 0, P_PLUS, P_MIN, P_MAX, P_ABS_DIFF, P_SQ_DIFF, P_COUNT };
+enum {
+    P_TIMES = 0, P_PLUS, P_MIN, P_MAX, P_ABS_DIFF, P_SQ_DIFF,
+    P_ABS_DIFF_POW,      /* |a - b|^p                                  (Table 1, Minkowski)      */
+    P_CANBERRA,          /* |a - b| / (|a| + |b|), 0 at (0, 0)         (Table 1, Canberra)       */
+    P_NOT_EQUAL,         /* 1 where a != b, else 0                     (Table 1, Hamming)        */
+    P_X_LOG_X_OVER_Y,    /* a log(a / b) where both are positive       (Table 1, KL; Section 2.2)*/
+    P_JS_TERM,           /* a log(a/mu) + b log(b/mu), mu = (a + b)/2, 0 log 0 = 0 (Jensen-Shannon) */
+    P_COUNT
+};
 enum { S_PLUS = 0, S_MIN, S_MAX, S_COUNT };
+/* applied to every stored value before anything else (Table 1: Hellinger works on square roots,
+ * the set distances on the supports) */
+enum { T_NONE = 0, T_SQRT, T_NONZERO, T_COUNT };
+/* what turns the folded value v into the distance: Table 1's "Expansion" column for the
+ * dot-product family (norms of the transformed rows x, y over k columns), the closing steps
+ * of the others */
+enum {
+    E_NONE = 0,
+    E_ROOT_P,            /* v^(1/p)                                                  */
+    E_DIV_K,             /* v / k                                                    */
+    E_SQRT_HALF,         /* sqrt(v / 2)                                              */
+    E_COSINE,            /* 1 - v / (|x|_2 |y|_2); 1 if one row is zero, 0 if both   */
+    E_L2,                /* sqrt(|x|_2^2 - 2 v + |y|_2^2)                            */
+    E_CORRELATION,       /* 1 - (k v - sum x sum y) / sqrt((k sum x^2 - (sum x)^2)(k sum y^2 - (sum y)^2)); 1 without variance */
+    E_JACCARD,           /* 1 - v / (|x|_0 + |y|_0 - v); 0 where the denominator is 0 */
+    E_DICE,              /* 1 - 2 v / (|x|_0 + |y|_0); 0 if both rows are empty       */
+    E_HELLINGER,         /* sqrt((|x|_2^2 + |y|_2^2) / 2 - v)                         */
+    E_RUSSELL_RAO,       /* (k - v) / k                                               */
+    E_STRICT,            /* v if y is positive wherever x is, else +infinity          */
+    E_COUNT
+};
 
-typedef struct { int product, sum, over_union; } semiring_t;
+typedef struct { int product, sum, over_union; double p; int transform, epilogue; } semiring_t;
 
-static double semiring_product(int product, double a, double b) {
+static double semiring_transform(int transform, double v) {
+    if (transform == T_SQRT) return sqrt(v);
+    if (transform == T_NONZERO) return v != 0.0 ? 1.0 : 0.0;
+    return v;
+}
+
+static double semiring_product(int product, double p, double a, double b) {
     switch (product) {
     case P_TIMES: return a * b;
     case P_PLUS: return a + b;
@@ -245,24 +286,64 @@ static double semiring_product(int product, double a, double b) {
     case P_MAX: return a > b ? a : b;
     case P_ABS_DIFF: return fabs(a - b);
     case P_SQ_DIFF: return (a - b) * (a - b);
+    case P_ABS_DIFF_POW: return pow(fabs(a - b), p);
+    case P_CANBERRA: { double den = fabs(a) + fabs(b); return den != 0.0 ? fabs(a - b) / den : 0.0; }
+    case P_NOT_EQUAL: return a != b ? 1.0 : 0.0;
+    case P_X_LOG_X_OVER_Y: return (a > 0.0 && b > 0.0) ? a * log(a / b) : 0.0;
+    case P_JS_TERM: {
+        double mu = 0.5 * (a + b), s = 0.0;
+        if (a > 0.0) s += a * log(a / mu);
+        if (b > 0.0) s += b * log(b / mu);
+        return s;
+    }
     default: return NAN;
     }
 }
 
+/* The columns not visited hold (0, 0): no product and no norm below gets anything from them,
+ * and the places where k itself enters use k. */
 static double eval_semiring(const semiring_t *sr, const double *x, const double *y,
-                            const int32_t *cols, int64_t nc) {
+                            const int32_t *cols, int64_t nc, int64_t k) {
     double acc = sr->sum == S_PLUS ? 0.0 : (sr->sum == S_MIN ? INFINITY : -INFINITY);
+    double sx = 0.0, sy = 0.0, sxx = 0.0, syy = 0.0, n0x = 0.0, n0y = 0.0;
+    int covered = 1;
     for (int64_t t = 0; t < nc; ++t) {
         int64_t c = COL(t);
-        int in_x = x[c] != 0.0, in_y = y[c] != 0.0;
+        double u = semiring_transform(sr->transform, x[c]), v = semiring_transform(sr->transform, y[c]);
+        sx += u; sy += v; sxx += u * u; syy += v * v;
+        n0x += (double)(u != 0.0); n0y += (double)(v != 0.0);
+        if (u > 0.0 && !(v > 0.0)) covered = 0;
+        int in_x = u != 0.0, in_y = v != 0.0;
         int in_domain = sr->over_union ? (in_x || in_y) : (in_x && in_y);
         if (!in_domain) continue;
-        double v = semiring_product(sr->product, x[c], y[c]);
-        if (sr->sum == S_PLUS) acc += v;
-        else if (sr->sum == S_MIN) { if (v < acc) acc = v; }
-        else { if (v > acc) acc = v; }
+        double w = semiring_product(sr->product, sr->p, u, v);
+        if (sr->sum == S_PLUS) acc += w;
+        else if (sr->sum == S_MIN) { if (w < acc) acc = w; }
+        else { if (w > acc) acc = w; }
     }
-    return acc;
+    double kk = (double)k;
+    switch (sr->epilogue) {
+    case E_NONE: return acc;
+    case E_ROOT_P: return pow(acc, 1.0 / sr->p);
+    case E_DIV_K: return acc / kk;
+    case E_SQRT_HALF: return sqrt(0.5 * (acc > 0.0 ? acc : 0.0));
+    case E_COSINE:
+        if (sxx == 0.0 && syy == 0.0) return 0.0;
+        if (sxx == 0.0 || syy == 0.0) return 1.0;
+        return 1.0 - acc / (sqrt(sxx) * sqrt(syy));
+    case E_L2: { double r = sxx - 2.0 * acc + syy; return sqrt(r > 0.0 ? r : 0.0); }
+    case E_CORRELATION: {
+        double vx = kk * sxx - sx * sx, vy = kk * syy - sy * sy;
+        if (vx <= 0.0 || vy <= 0.0) return 1.0;
+        return 1.0 - (kk * acc - sx * sy) / (sqrt(vx) * sqrt(vy));
+    }
+    case E_JACCARD: { double den = n0x + n0y - acc; return den == 0.0 ? 0.0 : 1.0 - acc / den; }
+    case E_DICE: return (n0x + n0y == 0.0) ? 0.0 : 1.0 - 2.0 * acc / (n0x + n0y);
+    case E_HELLINGER: { double r = 0.5 * (sxx + syy) - acc; return sqrt(r > 0.0 ? r : 0.0); }
+    case E_RUSSELL_RAO: return (kk - acc) / kk;
+    case E_STRICT: return covered ? acc : INFINITY;
+    default: return NAN;
+    }
 }
 
 typedef struct {
@@ -315,7 +396,7 @@ static int run_pairs(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, co
                     for (int64_t q = b0; q < b1; ++q) y[b_indices[q]] = (double)b_values[q];
                     double d;
                     if (mode == 0) {
-                        d = sr ? eval_semiring(sr, x, y, NULL, n_cols)
+                        d = sr ? eval_semiring(sr, x, y, NULL, n_cols, n_cols)
                                : eval_pair(metric, p, x, y, NULL, n_cols, n_cols);
                     } else {
                         int64_t cap = (a1 - a0) + (b1 - b0), nc = 0;
@@ -328,7 +409,7 @@ static int run_pairs(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, co
                             int32_t c = b_indices[q];
                             if (!seen[c]) { seen[c] = 1; cols[nc++] = c; }
                         }
-                        d = sr ? eval_semiring(sr, x, y, cols, nc) : eval_pair(metric, p, x, y, cols, nc, n_cols);
+                        d = sr ? eval_semiring(sr, x, y, cols, nc, n_cols) : eval_pair(metric, p, x, y, cols, nc, n_cols);
                         for (int64_t t = 0; t < nc; ++t) seen[cols[t]] = 0;
                     }
                     out[ia * n_sel_b + jb] = d;
@@ -352,14 +433,17 @@ int oracle_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, con
                      metric, p, NULL, sel_a, n_sel_a, sel_b, n_sel_b, mode, n_threads, out);
 }
 
-/* The same for a semiring: out[a * n_sel_b + b] = sum()-fold of product() over the domain. */
+/* The same for a semiring: out[a * n_sel_b + b] = epilogue of the sum()-fold of product() over
+ * the domain, on the transformed values. */
 int oracle_semiring_pairwise(int64_t a_rows, int64_t n_cols, const int64_t *a_indptr, const int32_t *a_indices,
                              const float *a_values, int64_t b_rows, const int64_t *b_indptr,
                              const int32_t *b_indices, const float *b_values, int product, int sum,
-                             int over_union, const int64_t *sel_a, int64_t n_sel_a, const int64_t *sel_b,
-                             int64_t n_sel_b, int mode, int n_threads, double *out) {
+                             int over_union, double p, int transform, int epilogue, const int64_t *sel_a,
+                             int64_t n_sel_a, const int64_t *sel_b, int64_t n_sel_b, int mode, int n_threads,
+                             double *out) {
     if (product < 0 || product >= P_COUNT || sum < 0 || sum >= S_COUNT) return -1;
-    semiring_t sr = {product, sum, over_union != 0};
+    if (transform < 0 || transform >= T_COUNT || epilogue < 0 || epilogue >= E_COUNT) return -1;
+    semiring_t sr = {product, sum, over_union != 0, p, transform, epilogue};
     return run_pairs(a_rows, n_cols, a_indptr, a_indices, a_values, b_rows, b_indptr, b_indices, b_values,
                      0, 0.0, &sr, sel_a, n_sel_a, sel_b, n_sel_b, mode, n_threads, out);
 }

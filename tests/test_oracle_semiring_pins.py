@@ -160,3 +160,118 @@ def test_semiring_knn_orders_by_value_then_index():
         order = sorted(range(40), key=lambda j: (full[r, j], j))[:7]
         assert list(idx[r]) == order
         np.testing.assert_array_equal(val[r], full[r, order])
+
+
+# ---------------------------------------------------------------- Table 1 through the semiring evaluator
+MORE_PRODUCT_FN = {
+    "abs_diff_pow": lambda a, b, p: np.abs(a - b) ** p,
+    "canberra": lambda a, b, p: np.where(np.abs(a) + np.abs(b) != 0, np.abs(a - b) / np.where(np.abs(a) + np.abs(b) != 0, np.abs(a) + np.abs(b), 1.0), 0.0),
+    "not_equal": lambda a, b, p: (a != b).astype(np.float64),
+}
+
+
+@pytest.mark.parametrize("union", [False, True])
+@pytest.mark.parametrize("sum_", oracle.SUMS)
+@pytest.mark.parametrize("product", sorted(MORE_PRODUCT_FN))
+def test_more_products_against_masked_dense_tensor(product, sum_, union):
+    X, Y = _dense_pair(23)
+    fold, ident = FOLD[sum_]
+    px, py = X[:, None, :] != 0.0, Y[None, :, :] != 0.0
+    domain = (px | py) if union else (px & py)
+    t = MORE_PRODUCT_FN[product](X[:, None, :], Y[None, :, :], 2.5)
+    want = fold(np.where(domain, t, ident), axis=2)
+    for mode in ("full", "support"):
+        got = oracle.semiring_pairwise(synth.from_dense(X), synth.from_dense(Y), product, sum_, union, mode=mode, p=2.5)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+
+
+def test_log_products_against_scipy_special():
+    from scipy.special import rel_entr
+    X, Y = _dense_pair(29, signed=False)
+    A, B = synth.from_dense(X), synth.from_dense(Y)
+    both = (X[:, None, :] > 0) & (Y[None, :, :] > 0)
+    kl = np.where(both, rel_entr(np.where(both, X[:, None, :], 1.0), np.where(both, Y[None, :, :], 1.0)), 0.0).sum(axis=2)
+    np.testing.assert_allclose(oracle.semiring_pairwise(A, B, "x_log_x_over_y", "plus", False, mode="full"), kl,
+                               rtol=1e-12, atol=1e-13)
+    mu = 0.5 * (X[:, None, :] + Y[None, :, :])
+    js = (rel_entr(X[:, None, :] + 0 * mu, mu) + rel_entr(Y[None, :, :] + 0 * mu, mu)).sum(axis=2)   # rel_entr(0, m) = 0
+    np.testing.assert_allclose(oracle.semiring_pairwise(A, B, "js_term", "plus", True, mode="full"), js,
+                               rtol=1e-12, atol=1e-13)
+    # the same product over the intersection leaves the one-sided columns (a log 2 each) out
+    inter = oracle.semiring_pairwise(A, B, "js_term", "plus", False, mode="full")
+    one_sided = np.log(2.0) * (np.where(Y[None, :, :] == 0, X[:, None, :], 0.0) + np.where(X[:, None, :] == 0, Y[None, :, :], 0.0)).sum(axis=2)
+    np.testing.assert_allclose(inter + one_sided, js, rtol=1e-12, atol=1e-13)
+
+
+def test_transforms_and_epilogues_against_scipy():
+    X, Y = _dense_pair(31, signed=False)
+    keep = np.ones(X.shape[0], bool); keep[X.shape[0] // 2] = False          # scipy has no convention for zero rows
+    keepy = np.ones(Y.shape[0], bool); keepy[Y.shape[0] // 2] = False
+    Xs, Ys = X[keep], Y[keepy]
+    A, B = synth.from_dense(Xs), synth.from_dense(Ys)
+    k = Xs.shape[1]
+
+    def run(**kw):
+        kw.setdefault("over_union", False)
+        product, sum_, union = kw.pop("product"), kw.pop("sum"), kw.pop("over_union")
+        full = oracle.semiring_pairwise(A, B, product, sum_, union, mode="full", **kw)
+        np.testing.assert_allclose(oracle.semiring_pairwise(A, B, product, sum_, union, mode="support", **kw), full,
+                                   rtol=1e-12, atol=1e-13)
+        return full
+
+    close = lambda got, want: np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+    close(run(product="times", sum="plus", epilogue="cosine"), ssd.cdist(Xs, Ys, "cosine"))
+    close(run(product="times", sum="plus", epilogue="l2"), ssd.cdist(Xs, Ys, "euclidean"))
+    close(run(product="times", sum="plus", epilogue="correlation"), ssd.cdist(Xs, Ys, "correlation"))
+    close(run(product="times", sum="plus", transform="nonzero", epilogue="jaccard"), ssd.cdist(Xs != 0, Ys != 0, "jaccard"))
+    close(run(product="times", sum="plus", transform="nonzero", epilogue="dice"), ssd.cdist(Xs != 0, Ys != 0, "dice"))
+    close(run(product="times", sum="plus", transform="nonzero", epilogue="russell_rao"), ssd.cdist(Xs != 0, Ys != 0, "russellrao"))
+    close(run(product="times", sum="plus", transform="sqrt", epilogue="hellinger"),
+          ssd.cdist(np.sqrt(Xs), np.sqrt(Ys), "euclidean") / np.sqrt(2.0))
+    close(run(product="abs_diff_pow", sum="plus", over_union=True, epilogue="root_p", p=3.0), ssd.cdist(Xs, Ys, "minkowski", p=3.0))
+    close(run(product="sq_diff", sum="plus", over_union=True, epilogue="root_p", p=2.0), ssd.cdist(Xs, Ys, "euclidean"))
+    close(run(product="canberra", sum="plus", over_union=True), ssd.cdist(Xs, Ys, "canberra"))
+    close(run(product="not_equal", sum="plus", over_union=True, epilogue="div_k"), ssd.cdist(Xs, Ys, "hamming"))
+    P, Q = Xs / Xs.sum(1, keepdims=True), Ys / Ys.sum(1, keepdims=True)
+    Ap, Bq = synth.from_dense(P), synth.from_dense(Q)
+    js = oracle.semiring_pairwise(Ap, Bq, "js_term", "plus", True, mode="full", epilogue="sqrt_half")
+    # the arrays went through fp32 on their way into the CSR: compare on what the oracle saw
+    P32, Q32 = synth.to_dense(Ap), synth.to_dense(Bq)
+    want = np.array([[ssd.jensenshannon(p / p.sum(), q / q.sum()) for q in Q32] for p in P32])
+    scale = np.sqrt(0.5 * (P32.sum(1)[:, None] + Q32.sum(1)[None, :]))       # rows sum to 1 up to fp32 rounding
+    np.testing.assert_allclose(js, want * scale, rtol=1e-6)
+    # strict: infinite exactly where x holds mass that y does not cover
+    strict = oracle.semiring_pairwise(A, B, "x_log_x_over_y", "plus", False, mode="full", epilogue="strict")
+    uncovered = ((Xs[:, None, :] > 0) & ~(Ys[None, :, :] > 0)).any(axis=2)
+    assert np.array_equal(np.isinf(strict), uncovered) and uncovered.any() and (~uncovered).any()
+    assert k == 23
+
+
+def test_every_distance_of_table_1_is_a_semiring_call():
+    """The composition (transform, product, sum, domain, epilogue) against the plain formula the
+    metric oracle evaluates: Table 1's expansion column equals its formula column."""
+    import sys
+    sys.path.insert(0, os.path.dirname(__file__))
+    from util import NONNEGATIVE_ONLY, ORACLE_NAME, TABLE1_SEMIRINGS
+    assert set(TABLE1_SEMIRINGS) == set(ORACLE_NAME)
+    for signed in (True, False):
+        X, Y = _dense_pair(37 + signed, rows_a=13, rows_b=17, signed=signed)
+        Y[3] = X[3] * 2.0                      # proportional rows, equal supports
+        A, B = synth.from_dense(X), synth.from_dense(Y)
+        for metric, sr in TABLE1_SEMIRINGS.items():
+            if signed and metric in NONNEGATIVE_ONLY:
+                continue
+            sr = dict(sr)
+            p = sr.pop("p", 3.0)
+            for mode in ("full", "support"):
+                got = oracle.semiring_pairwise(A, B, sr["product"], sr["sum"], sr["over_union"],
+                                               mode=mode, p=p, transform=sr.get("transform", "none"),
+                                               epilogue=sr.get("epilogue", "none"))
+                want = oracle.pairwise(A, B, ORACLE_NAME[metric], p, mode=mode)
+                if metric == "chebyshev":      # two empty rows: the identity of max, where the distance says 0
+                    empty = (np.abs(X).sum(1)[:, None] + np.abs(Y).sum(1)[None, :]) == 0
+                    assert np.all(got[empty] == -np.inf) and empty.sum() == 1
+                    got = np.where(empty, 0.0, got)
+                inf = np.isinf(want)
+                assert np.array_equal(np.isinf(got), inf), metric
+                np.testing.assert_allclose(np.where(inf, 0, got), np.where(inf, 0, want), rtol=1e-9, atol=1e-11, err_msg=metric)

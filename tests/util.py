@@ -90,3 +90,27 @@ def quotient_cases():
         a[9], b[11] = 0.125, 0.375            # one-sided columns
         cases.append((a, b))
     return cases
+
+
+# Every distance of Table 1 as a semiring call: product(), sum(), domain, the transform of the
+# stored values and the epilogue (Section 2.2; Table 1's expansion column).  `p` where it matters.
+TABLE1_SEMIRINGS = {
+    "inner_product": dict(product="times", sum="plus", over_union=False),
+    "cosine": dict(product="times", sum="plus", over_union=False, epilogue="cosine"),
+    "l2_expanded": dict(product="times", sum="plus", over_union=False, epilogue="l2"),
+    "correlation": dict(product="times", sum="plus", over_union=False, epilogue="correlation"),
+    "jaccard": dict(product="times", sum="plus", over_union=False, transform="nonzero", epilogue="jaccard"),
+    "dice": dict(product="times", sum="plus", over_union=False, transform="nonzero", epilogue="dice"),
+    "hellinger": dict(product="times", sum="plus", over_union=False, transform="sqrt", epilogue="hellinger"),
+    "l1": dict(product="abs_diff", sum="plus", over_union=True),
+    "chebyshev": dict(product="abs_diff", sum="max", over_union=True),      # (-infinity, not 0, between two empty rows)
+    "minkowski": dict(product="abs_diff_pow", sum="plus", over_union=True, epilogue="root_p"),
+    "canberra": dict(product="canberra", sum="plus", over_union=True),
+    "hamming": dict(product="not_equal", sum="plus", over_union=True, epilogue="div_k"),
+    "kl_divergence": dict(product="x_log_x_over_y", sum="plus", over_union=False),
+    "jensen_shannon": dict(product="js_term", sum="plus", over_union=True, epilogue="sqrt_half"),
+    "russell_rao": dict(product="times", sum="plus", over_union=False, transform="nonzero", epilogue="russell_rao"),
+    "l2_unexpanded": dict(product="sq_diff", sum="plus", over_union=True, epilogue="root_p", p=2.0),
+    "kl_divergence_strict": dict(product="x_log_x_over_y", sum="plus", over_union=False, epilogue="strict"),
+    "jaccard_literal": dict(product="times", sum="plus", over_union=False, epilogue="jaccard"),
+}
