@@ -167,13 +167,22 @@ spd_status spd_index_pairwise(spd_handle *handle, const spd_csr *A, const spd_in
 spd_status spd_index_knn(spd_handle *handle, const spd_csr *Q, const spd_index *index, int k,
                          int64_t *out_idx, float *out_dist);
 
-/* Semirings (Section 2.2).  A value between two rows is the sum() fold of product(x_c, y_c) over
- * the columns c both rows store, when 0 annihilates the product (the dot-product semiring is
- * {TIMES, PLUS}; the tropical semiring of Eq. 1 is {PLUS, MIN}); with `over_union` set, over the
- * columns either row stores, the missing side read as 0: the non-annihilating multiplicative
- * monoid of Section 2.2 ({ABS_DIFF, PLUS} is the Manhattan distance, {ABS_DIFF, MAX} Chebyshev's).
- * A pair with no such column gets the identity of sum(): 0, +infinity (MIN) or -infinity (MAX).
- * Every product offered is commutative, as Section 2.2 asks of the union form. */
+/* Semirings (Section 2.2; the product and the sum that Section 4.2's interface passes to one
+ * primitive).  A value between two rows is the sum() fold of product(x_c, y_c) over the columns c
+ * both rows store, when 0 annihilates the product (the dot-product semiring is {TIMES, PLUS}; the
+ * tropical semiring of Eq. 1 is {PLUS, MIN}); with `over_union` set, over the columns either row
+ * stores, the missing side read as 0: the non-annihilating multiplicative monoid of Section 2.2
+ * ({ABS_DIFF, PLUS} is the Manhattan distance, {ABS_DIFF, MAX} Chebyshev's).  A pair with no such
+ * column gets the identity of sum(): 0, +infinity (MIN) or -infinity (MAX).  `transform` is applied
+ * to every stored value first (a value it sends to 0 counts as absent), `epilogue` to the folded
+ * value: together they spell every distance of Table 1, e.g.
+ *   cosine          {TIMES, PLUS, 0, -, NONE, COSINE}        Hellinger  {TIMES, PLUS, 0, -, SQRT, HELLINGER}
+ *   Jaccard         {TIMES, PLUS, 0, -, NONZERO, JACCARD}    Canberra   {CANBERRA, PLUS, 1, -, NONE, NONE}
+ *   Minkowski       {ABS_DIFF_POW, PLUS, 1, p, NONE, ROOT_P} Hamming    {NOT_EQUAL, PLUS, 1, -, NONE, DIV_K}
+ *   KL divergence   {X_LOG_X_OVER_Y, PLUS, 0, -, NONE, NONE} Jensen-Shannon {JS_TERM, PLUS, 1, -, NONE, SQRT_HALF}
+ * A call that spells one of Table 1's distances runs on that distance's own kernels; any other
+ * combination on kernels that take the product as a run-time choice.  Every product but
+ * X_LOG_X_OVER_Y is commutative, as Section 2.2 asks of the union form. */
 typedef enum {
     SPD_PRODUCT_TIMES = 0,  /* x * y     */
     SPD_PRODUCT_PLUS,       /* x + y     */
@@ -181,19 +190,52 @@ typedef enum {
     SPD_PRODUCT_MAX,        /* max(x, y) */
     SPD_PRODUCT_ABS_DIFF,   /* |x - y|   */
     SPD_PRODUCT_SQ_DIFF,    /* (x - y)^2 */
+    SPD_PRODUCT_ABS_DIFF_POW,   /* |x - y|^p, p > 0 from the semiring                                   */
+    SPD_PRODUCT_CANBERRA,       /* |x - y| / (|x| + |y|), 0 at (0, 0)                                   */
+    SPD_PRODUCT_NOT_EQUAL,      /* 1 where x != y, else 0                                               */
+    SPD_PRODUCT_X_LOG_X_OVER_Y, /* x log(x / y) where both are positive, else 0; over_union must be 0   */
+    SPD_PRODUCT_JS_TERM,        /* x log(x/mu) + y log(y/mu), mu = (x + y)/2, 0 log 0 = 0; x, y >= 0    */
     SPD_PRODUCT_COUNT
 } spd_product;
 
 typedef enum { SPD_SUM_PLUS = 0, SPD_SUM_MIN, SPD_SUM_MAX, SPD_SUM_COUNT } spd_sum;
 
+typedef enum { SPD_TRANSFORM_NONE = 0, SPD_TRANSFORM_SQRT, SPD_TRANSFORM_NONZERO /* 1 where the value is not 0 */,
+               SPD_TRANSFORM_COUNT } spd_transform;
+
+/* v: the folded value; x, y: the two rows after the transform; k: the number of columns. */
+typedef enum {
+    SPD_EPILOGUE_NONE = 0,      /* v                                                                    */
+    SPD_EPILOGUE_ROOT_P,        /* v^(1/p)                                                              */
+    SPD_EPILOGUE_DIV_K,         /* v / k                                                                */
+    SPD_EPILOGUE_SQRT_HALF,     /* sqrt(v / 2)                                                          */
+    /* The expansion functions over row norms (Table 1, Section 3.4) and the strict reading of the KL
+     * divergence: each is accepted in the combination that makes it one of the library's distances
+     * (the comment names product, sum, transform), and refused with SPD_ERR_BAD_METRIC otherwise.  */
+    SPD_EPILOGUE_COSINE,        /* {TIMES, PLUS, NONE}: 1 - v/(|x|_2 |y|_2); 1 if one row is zero, 0 if both */
+    SPD_EPILOGUE_L2,            /* {TIMES, PLUS, NONE}: sqrt(max(0, |x|_2^2 - 2v + |y|_2^2))              */
+    SPD_EPILOGUE_CORRELATION,   /* {TIMES, PLUS, NONE}: 1 - Pearson correlation over k columns; 1 without variance */
+    SPD_EPILOGUE_JACCARD,       /* {TIMES, PLUS, NONZERO or NONE}: 1 - v/(|x|_0 + |y|_0 - v); 0 if that is 0/0 */
+    SPD_EPILOGUE_DICE,          /* {TIMES, PLUS, NONZERO}: 1 - 2v/(|x|_0 + |y|_0); 0 if both rows are empty */
+    SPD_EPILOGUE_HELLINGER,     /* {TIMES, PLUS, SQRT}: sqrt(max(0, (|x|_2^2 + |y|_2^2)/2 - v))           */
+    SPD_EPILOGUE_RUSSELL_RAO,   /* {TIMES, PLUS, NONZERO}: (k - v)/k                                      */
+    SPD_EPILOGUE_STRICT,        /* {X_LOG_X_OVER_Y, PLUS, NONE}: v if y is positive wherever x is, else +infinity */
+    SPD_EPILOGUE_COUNT
+} spd_epilogue;
+
 typedef struct {
     spd_product product;
     spd_sum sum;
     int over_union;         /* 0: columns stored in both rows; 1: in either row */
+    float p;                /* degree of SPD_PRODUCT_ABS_DIFF_POW and SPD_EPILOGUE_ROOT_P (finite, > 0); ignored otherwise */
+    spd_transform transform;
+    spd_epilogue epilogue;
 } spd_semiring;
 
 /* out[i * B.n_rows + j] = the semiring's value between A_i and B_j, fp32, row-major, m x n.
- * An unknown product or sum returns SPD_ERR_BAD_METRIC.  Scratch: the bound spd_workspace_bytes()
+ * An unknown product, sum, transform or epilogue, X_LOG_X_OVER_Y over the union, or an expansion
+ * epilogue outside its combination returns SPD_ERR_BAD_METRIC; a degree that is needed and is
+ * not a finite p > 0 returns SPD_ERR_BAD_P.  Scratch: the bound spd_workspace_bytes()
  * gives for SPD_MINKOWSKI covers every semiring. */
 spd_status spd_semiring_pairwise(spd_handle *handle, const spd_csr *A, const spd_csr *B,
                                  const spd_semiring *semiring, float *out);

@@ -1,6 +1,8 @@
 """spd: sparse all-pairs distances as a semiring product on one MI355X (gfx950).
 
-The package is a thin binding over ``libspd.so`` (built from ``csrc/`` by ``build.py``).
+The package is a thin binding over ``libspd.so`` (built from ``csrc/`` by ``build.py``);
+``paper_2104_06357_amd.testing`` holds the host-only hooks the tests use.
 """
-from .binding import (KNN_MAX_K, METRICS, PRODUCTS, SUMS, DeviceCsr, Handle, SpdError, host_pair_value,  # noqa: F401
-                      host_plan_summary, lib)
+from . import testing  # noqa: F401
+from .binding import (EPILOGUES, KNN_MAX_K, METRICS, PRODUCTS, SUMS, TRANSFORMS, DeviceCsr, Handle, SpdError,  # noqa: F401
+                      lib)

@@ -17,8 +17,12 @@ METRICS = (
     "l2_unexpanded", "kl_divergence_strict", "jaccard_literal",
 )
 METRIC_ID = {name: i for i, name in enumerate(METRICS)}
-PRODUCTS = ("times", "plus", "min", "max", "abs_diff", "sq_diff")       # spd_product
+PRODUCTS = ("times", "plus", "min", "max", "abs_diff", "sq_diff", "abs_diff_pow", "canberra", "not_equal",
+            "x_log_x_over_y", "js_term")                                 # spd_product
 SUMS = ("plus", "min", "max")                                            # spd_sum
+TRANSFORMS = ("none", "sqrt", "nonzero")                                 # spd_transform
+EPILOGUES = ("none", "root_p", "div_k", "sqrt_half", "cosine", "l2", "correlation", "jaccard", "dice", "hellinger",
+             "russell_rao", "strict")                                    # spd_epilogue
 STATUS = ("SPD_OK", "SPD_ERR_NULL", "SPD_ERR_DIM_MISMATCH", "SPD_ERR_BAD_CSR", "SPD_ERR_BAD_METRIC",
           "SPD_ERR_BAD_P", "SPD_ERR_BAD_K", "SPD_ERR_WORKSPACE", "SPD_ERR_HIP", "SPD_ERR_UNSUPPORTED")
 KNN_MAX_K = 64
@@ -38,7 +42,8 @@ class CsrStruct(ctypes.Structure):
 
 
 class SemiringStruct(ctypes.Structure):
-    _fields_ = [("product", ctypes.c_int), ("sum", ctypes.c_int), ("over_union", ctypes.c_int)]
+    _fields_ = [("product", ctypes.c_int), ("sum", ctypes.c_int), ("over_union", ctypes.c_int), ("p", ctypes.c_float),
+                ("transform", ctypes.c_int), ("epilogue", ctypes.c_int)]
 
 
 class KernelTime(ctypes.Structure):
@@ -241,29 +246,33 @@ class Handle:
         return Index_(self, ptr, Index)
 
     @staticmethod
-    def _semiring(product, sum, over_union) -> SemiringStruct:
+    def _semiring(product, sum, over_union, p=2.0, transform="none", epilogue="none") -> SemiringStruct:
         prod = PRODUCTS.index(product) if isinstance(product, str) else int(product)
         sm = SUMS.index(sum) if isinstance(sum, str) else int(sum)
-        return SemiringStruct(prod, sm, int(bool(over_union)))
+        tr = TRANSFORMS.index(transform) if isinstance(transform, str) else int(transform)
+        ep = EPILOGUES.index(epilogue) if isinstance(epilogue, str) else int(epilogue)
+        return SemiringStruct(prod, sm, int(bool(over_union)), float(p), tr, ep)
 
-    def semiring_pairwise(self, A: DeviceCsr, B: DeviceCsr, product, sum, over_union: bool, out=None):
+    def semiring_pairwise(self, A: DeviceCsr, B: DeviceCsr, product, sum, over_union: bool, out=None, p: float = 2.0,
+                          transform="none", epilogue="none"):
         """out[i, j] = the semiring's value between A_i and B_j as an fp32 torch tensor (m, n)."""
         import torch
         if out is None:
             out = torch.empty((A.n_rows, B.n_rows), dtype=torch.float32, device=A.indptr.device)
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
         assert tuple(out.shape) == (A.n_rows, B.n_rows)
-        sa, sb, sr = A.struct(), B.struct(), self._semiring(product, sum, over_union)
+        sa, sb, sr = A.struct(), B.struct(), self._semiring(product, sum, over_union, p, transform, epilogue)
         self._check(self._lib.spd_semiring_pairwise(self._h, ctypes.byref(sa), ctypes.byref(sb), ctypes.byref(sr),
                                                     out.data_ptr() if out.numel() else None))
         return out
 
-    def semiring_knn(self, Q: DeviceCsr, Index: DeviceCsr, product, sum, over_union: bool, k: int):
+    def semiring_knn(self, Q: DeviceCsr, Index: DeviceCsr, product, sum, over_union: bool, k: int, p: float = 2.0,
+                     transform="none", epilogue="none"):
         """(idx int64 [m, k], value fp32 [m, k]) of the k smallest semiring values per query row."""
         import torch
         out_idx = torch.empty((Q.n_rows, k), dtype=torch.int64, device=Q.indptr.device)
         out_dist = torch.empty((Q.n_rows, k), dtype=torch.float32, device=Q.indptr.device)
-        sa, sb, sr = Q.struct(), Index.struct(), self._semiring(product, sum, over_union)
+        sa, sb, sr = Q.struct(), Index.struct(), self._semiring(product, sum, over_union, p, transform, epilogue)
         self._check(self._lib.spd_semiring_knn(self._h, ctypes.byref(sa), ctypes.byref(sb), ctypes.byref(sr), int(k),
                                                out_idx.data_ptr() if out_idx.numel() else None,
                                                out_dist.data_ptr() if out_dist.numel() else None))
@@ -310,34 +319,3 @@ class Index_:
                                       out_idx.data_ptr() if out_idx.numel() else None,
                                       out_dist.data_ptr() if out_dist.numel() else None))
         return out_idx, out_dist
-
-
-# ---- host-only test hooks (include/spd_testing.h) -------------------------------------------
-def host_pair_value(metric, p, n_cols, a_cols, a_vals, b_cols, b_vals) -> float:
-    import numpy as np
-    a_cols = np.ascontiguousarray(a_cols, dtype=np.int32); a_vals = np.ascontiguousarray(a_vals, dtype=np.float32)
-    b_cols = np.ascontiguousarray(b_cols, dtype=np.int32); b_vals = np.ascontiguousarray(b_vals, dtype=np.float32)
-    out = ctypes.c_float()
-    st = lib().spd_host_pair_value(metric_id(metric), float(p), int(n_cols), a_cols.ctypes.data, a_vals.ctypes.data,
-                                   a_cols.size, b_cols.ctypes.data, b_vals.ctypes.data, b_cols.size, ctypes.byref(out))
-    if st != 0:
-        raise SpdError(st, "spd_host_pair_value")
-    return float(out.value)
-
-
-def host_plan_summary(a_indptr, b_indptr, n_cols, metric, k_neighbors=0, **options) -> dict:
-    import json
-
-    import numpy as np
-    a_indptr = np.ascontiguousarray(a_indptr, dtype=np.int64)
-    b_indptr = np.ascontiguousarray(b_indptr, dtype=np.int64)
-    names = (ctypes.c_char_p * max(1, len(options)))(*[k.encode() for k in options])
-    vals = (ctypes.c_int64 * max(1, len(options)))(*[int(v) for v in options.values()])
-    buf = ctypes.create_string_buffer(1 << 16)
-    st = lib().spd_host_plan_summary(a_indptr.ctypes.data, a_indptr.size - 1, b_indptr.ctypes.data, b_indptr.size - 1,
-                                     int(n_cols), metric_id(metric), int(k_neighbors), names, vals, len(options),
-                                     buf, len(buf))
-    text = buf.value.decode()
-    if st != 0:
-        raise SpdError(st, text)
-    return json.loads(text)

@@ -195,6 +195,44 @@ spd_status check_csr_args(spd_handle *h, const spd_csr *M, const char *name) {
     return SPD_OK;
 }
 
+// The distance of Table 1 (or one of the library's variants of them) that a semiring call spells,
+// or -1: such a call runs on the distance's own kernels.  The inner product is left out for k-NN
+// (spd_knn returns its largest values, spd_semiring_knn the smallest), and so is Chebyshev, whose
+// value between two empty rows is 0 where the semiring's is the identity of max.
+int table1_metric(const spd_semiring &s, bool knn) {
+    if (s.sum != SPD_SUM_PLUS) return -1;
+    const int T = (int)s.transform, E = (int)s.epilogue;
+    const bool U = s.over_union != 0;
+    switch (s.product) {
+    case SPD_PRODUCT_TIMES:          // (0 annihilates: the union adds nothing to the intersection)
+        if (T == SPD_TRANSFORM_NONE) {
+            if (E == SPD_EPILOGUE_NONE) return knn ? -1 : (int)SPD_INNER_PRODUCT;
+            if (E == SPD_EPILOGUE_COSINE) return SPD_COSINE;
+            if (E == SPD_EPILOGUE_L2) return SPD_L2_EXPANDED;
+            if (E == SPD_EPILOGUE_CORRELATION) return SPD_CORRELATION;
+            if (E == SPD_EPILOGUE_JACCARD) return SPD_JACCARD_LITERAL;
+        } else if (T == SPD_TRANSFORM_NONZERO) {
+            if (E == SPD_EPILOGUE_JACCARD) return SPD_JACCARD;
+            if (E == SPD_EPILOGUE_DICE) return SPD_DICE;
+            if (E == SPD_EPILOGUE_RUSSELL_RAO) return SPD_RUSSELL_RAO;
+        } else if (T == SPD_TRANSFORM_SQRT) {
+            if (E == SPD_EPILOGUE_HELLINGER) return SPD_HELLINGER;
+        }
+        return -1;
+    case SPD_PRODUCT_ABS_DIFF: return (U && T == SPD_TRANSFORM_NONE && E == SPD_EPILOGUE_NONE) ? (int)SPD_L1 : -1;
+    case SPD_PRODUCT_ABS_DIFF_POW: return (U && T == SPD_TRANSFORM_NONE && E == SPD_EPILOGUE_ROOT_P) ? (int)SPD_MINKOWSKI : -1;
+    case SPD_PRODUCT_SQ_DIFF:
+        return (U && T == SPD_TRANSFORM_NONE && E == SPD_EPILOGUE_ROOT_P && s.p == 2.0f) ? (int)SPD_L2_UNEXPANDED : -1;
+    case SPD_PRODUCT_CANBERRA: return (U && T == SPD_TRANSFORM_NONE && E == SPD_EPILOGUE_NONE) ? (int)SPD_CANBERRA : -1;
+    case SPD_PRODUCT_NOT_EQUAL: return (U && T == SPD_TRANSFORM_NONE && E == SPD_EPILOGUE_DIV_K) ? (int)SPD_HAMMING : -1;
+    case SPD_PRODUCT_X_LOG_X_OVER_Y:
+        if (U || T != SPD_TRANSFORM_NONE) return -1;
+        return E == SPD_EPILOGUE_NONE ? (int)SPD_KL_DIVERGENCE : (E == SPD_EPILOGUE_STRICT ? (int)SPD_KL_STRICT : -1);
+    case SPD_PRODUCT_JS_TERM: return (U && T == SPD_TRANSFORM_NONE && E == SPD_EPILOGUE_SQRT_HALF) ? (int)SPD_JENSEN_SHANNON : -1;
+    default: return -1;
+    }
+}
+
 spd_status check_call_args(spd_handle *h, const spd_csr *A, const spd_csr *B, spd_metric metric, float p, int knn_k,
                            bool is_knn, const void *o1, const void *o2, const spd_semiring *semiring = nullptr,
                            bool is_semiring = false) {
@@ -210,6 +248,18 @@ spd_status check_call_args(spd_handle *h, const spd_csr *A, const spd_csr *B, sp
         if ((int)semiring->product < 0 || (int)semiring->product >= SPD_PRODUCT_COUNT)
             return fail(h, SPD_ERR_BAD_METRIC, "unknown product");
         if ((int)semiring->sum < 0 || (int)semiring->sum >= SPD_SUM_COUNT) return fail(h, SPD_ERR_BAD_METRIC, "unknown sum");
+        if ((int)semiring->transform < 0 || (int)semiring->transform >= SPD_TRANSFORM_COUNT)
+            return fail(h, SPD_ERR_BAD_METRIC, "unknown transform");
+        if ((int)semiring->epilogue < 0 || (int)semiring->epilogue >= SPD_EPILOGUE_COUNT)
+            return fail(h, SPD_ERR_BAD_METRIC, "unknown epilogue");
+        if (semiring->product == SPD_PRODUCT_X_LOG_X_OVER_Y && semiring->over_union)
+            return fail(h, SPD_ERR_BAD_METRIC, "x log(x/y) has no value where y is absent: it is offered over the columns both rows store");
+        if ((semiring->product == SPD_PRODUCT_ABS_DIFF_POW || semiring->epilogue == SPD_EPILOGUE_ROOT_P) &&
+            !(semiring->p > 0.0f && std::isfinite(semiring->p)))
+            return fail(h, SPD_ERR_BAD_P, "the semiring needs a finite degree p > 0");
+        if (semiring->epilogue > SPD_EPILOGUE_SQRT_HALF && table1_metric(*semiring, false) < 0)
+            return fail(h, SPD_ERR_BAD_METRIC, "this epilogue is an expansion over row norms: it is defined for the product, "
+                                               "sum and transform of its own distance only");
     } else {
         if ((int)metric < 0 || (int)metric >= SPD_METRIC_COUNT) return fail(h, SPD_ERR_BAD_METRIC, "unknown metric");
         if (metric == SPD_MINKOWSKI && !(p > 0.0f && std::isfinite(p)))
@@ -404,6 +454,11 @@ OpParams op_params(int metric, float p, int64_t n_cols, const spd_semiring *semi
         q.product = (int)semiring->product;
         q.over_union = semiring->over_union != 0;
         q.sign = semiring->sum == SPD_SUM_MIN ? -1.0f : 1.0f;
+        q.epilogue = (int)semiring->epilogue;          // (only the first four reach the kernels)
+        if (semiring->product == SPD_PRODUCT_ABS_DIFF_POW || semiring->epilogue == SPD_EPILOGUE_ROOT_P) {
+            q.p = semiring->p;
+            q.inv_p = 1.0f / semiring->p;
+        }
     }
     return q;
 }
@@ -422,7 +477,10 @@ int effective_metric(int metric, float p) { return (metric == SPD_MINKOWSKI && p
 // R results are neighbours in its own output row: whole 32-byte sectors.  The roles can be
 // exchanged for every distance that is symmetric in its two rows, and pay where the scan of a pair
 // is short against its store (short rows of B) and A is large enough to be worth sweeping.
-bool operands_may_swap(int metric) { return metric != SPD_KL_DIVERGENCE && metric != SPD_KL_STRICT; }
+bool operands_may_swap(int metric, const spd_semiring *semiring) {
+    if (semiring && semiring->product == SPD_PRODUCT_X_LOG_X_OVER_Y) return false;
+    return metric != SPD_KL_DIVERGENCE && metric != SPD_KL_STRICT;
+}
 bool operands_swap_pays(const spd_csr *A, const spd_csr *B) {
     return A->nnz >= ((int64_t)1 << 18) && A->n_rows >= 1024 && B->nnz <= 96 * B->n_rows;
 }
@@ -430,7 +488,7 @@ bool operands_swap_pays(const spd_csr *A, const spd_csr *B) {
 spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, float p, const spd_semiring *semiring,
                int knn_k, float *out, int64_t *out_idx, float *out_dist, const spd_index *index = nullptr) {
     metric = effective_metric(metric, p);
-    const bool swapped = knn_k == 0 && !index && operands_may_swap(metric) &&
+    const bool swapped = knn_k == 0 && !index && operands_may_swap(metric, semiring) &&
                          (h->swap_operands == 2 || (h->swap_operands == 1 && operands_swap_pays(A, B)));
     if (swapped) std::swap(A, B);           // from here on A is the staged operand, B the streamed one
     const int64_t m = A->n_rows, n = B->n_rows;
@@ -489,6 +547,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     //      busy while the host plans A (an index brings all of that with it) ---------------
     MetricInfo mi = metric_info(metric);
     if (semiring && mi.norm == NORM_SEMI) mi.norm = NORM_SEMI + (int)semiring->product;
+    if (semiring) mi.transform = (int)semiring->transform;
     APlan &ap = h->plan_of_a;
     const BPlan &bp = index ? index->plan : h->plan_of_b;
     // the set metrics count shared columns in byte lanes, or (option) as a dot product of 0/1 values
@@ -878,7 +937,7 @@ spd_status spd_workspace_bytes(const spd_handle *h, const spd_csr *A, const spd_
     if (A->n_rows < 0 || B->n_rows < 0 || A->nnz < 0 || B->nnz < 0 || A->n_cols != B->n_cols) return SPD_ERR_DIM_MISMATCH;
     *bytes = workspace_bound(h, A, B, (int)metric, k_neighbors);
     // (a pairwise call may exchange the roles of its operands)
-    if (k_neighbors == 0 && h->swap_operands != 0 && operands_may_swap((int)metric))
+    if (k_neighbors == 0 && h->swap_operands != 0 && operands_may_swap((int)metric, nullptr))
         *bytes = std::max(*bytes, workspace_bound(h, B, A, (int)metric, 0));
     return SPD_OK;
 }
@@ -990,6 +1049,8 @@ spd_status spd_semiring_pairwise(spd_handle *h, const spd_csr *A, const spd_csr 
                                  float *out) {
     spd_status st = check_call_args(h, A, B, SPD_INNER_PRODUCT, 0.0f, 0, false, out, nullptr, semiring, true);
     if (st != SPD_OK) return st;
+    const int as_metric = table1_metric(*semiring, false);
+    if (as_metric >= 0) return run(h, A, B, as_metric, semiring->p, nullptr, 0, out, nullptr, nullptr);
     return run(h, A, B, semiring->sum == SPD_SUM_PLUS ? MT_SEMI_SUM : MT_SEMI_EXT, 1.0f, semiring, 0, out, nullptr, nullptr);
 }
 
@@ -997,6 +1058,8 @@ spd_status spd_semiring_knn(spd_handle *h, const spd_csr *Q, const spd_csr *Inde
                             int64_t *out_idx, float *out_dist) {
     spd_status st = check_call_args(h, Q, Index, SPD_INNER_PRODUCT, 0.0f, k, true, out_idx, out_dist, semiring, true);
     if (st != SPD_OK) return st;
+    const int as_metric = table1_metric(*semiring, true);
+    if (as_metric >= 0) return run(h, Q, Index, as_metric, semiring->p, nullptr, k, nullptr, out_idx, out_dist);
     return run(h, Q, Index, semiring->sum == SPD_SUM_PLUS ? MT_SEMI_SUM : MT_SEMI_EXT, 1.0f, semiring, k, nullptr, out_idx,
                out_dist);
 }

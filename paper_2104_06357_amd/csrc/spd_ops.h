@@ -41,8 +41,15 @@ enum NormKind {
     NORM_SEMI            // NORM_SEMI + product id: the sum of product(t, 0), and the number of entries
 };
 // products and sums a semiring may be built from; the ids follow spd_product / spd_sum in include/spd.h
-enum SemiProduct { SP_TIMES = 0, SP_PLUS, SP_MIN, SP_MAX, SP_ABS_DIFF, SP_SQ_DIFF, SP_COUNT };
+enum SemiProduct {
+    SP_TIMES = 0, SP_PLUS, SP_MIN, SP_MAX, SP_ABS_DIFF, SP_SQ_DIFF,
+    SP_ABS_DIFF_POW, SP_CANBERRA, SP_NOT_EQUAL, SP_X_LOG_X_OVER_Y, SP_JS_TERM,     // the other products of Table 1
+    SP_COUNT
+};
 enum SemiSum { SS_PLUS = 0, SS_MIN, SS_MAX, SS_COUNT };
+// what a semiring call applies to the folded value; the ids follow spd_epilogue in include/spd.h
+// (the expansions over row norms that follow SE_SQRT_HALF there run as the metrics they spell)
+enum SemiEpilogue { SE_NONE = 0, SE_ROOT_P, SE_DIV_K, SE_SQRT_HALF };
 
 // metric ids follow spd_metric in include/spd.h
 enum MetricId {
@@ -91,6 +98,7 @@ struct OpParams {
     int product = 0;      // SemiProduct
     int over_union = 0;   // 1: product() over the union of the stored columns, the missing side read as 0
     float sign = 1.0f;    // sum() = min is carried as the max of the negated products
+    int epilogue = 0;     // SemiEpilogue
 };
 
 // log2, exp2 and 1/x as the kernels use them: the hardware's transcendental units on the device
@@ -185,13 +193,43 @@ SPD_HD float min_of(float a, float b) { return __builtin_fminf(a, b); }
 SPD_HD double min_of(double a, double b) { return __builtin_fmin(a, b); }
 SPD_HD float max_of(float a, float b) { return __builtin_fmaxf(a, b); }
 SPD_HD double max_of(double a, double b) { return __builtin_fmax(a, b); }
-template <int P, typename T> SPD_HD T semi_product(T a, T b) {
+// The five products beyond the first six are formed in fp32 from the (exact) fp32 values, with
+// the same quotient and logarithm routines as the distances they come from, and widened:
+//   |a - b|^p;  |a - b| / (|a| + |b|) (0 at (0, 0));  [a != b];  a ln(a / b) where both are
+//   positive (else 0);  a ln(a / mu) + b ln(b / mu), mu = (a + b) / 2, 0 ln 0 = 0.
+// Equal entries give exactly 0 in all five.
+template <int P> SPD_HD float semi_product_f32(float a, float b, float p) {
+    const float LN2 = 0.693147180559945309f;
+    if constexpr (P == SP_ABS_DIFF_POW) {
+        return pow_abs(a - b, p);
+    } else if constexpr (P == SP_CANBERRA) {
+        const float den = fabsf(a) + fabsf(b);
+        return den != 0.0f ? divide(fabsf(a - b), divisor_of(den)) : 0.0f;
+    } else if constexpr (P == SP_NOT_EQUAL) {
+        return a != b ? 1.0f : 0.0f;
+    } else if constexpr (P == SP_X_LOG_X_OVER_Y) {
+        const bool both = a > 0.0f && b > 0.0f;
+        return both ? LN2 * (a * fast_log2(divide(a, divisor_of(b)))) : 0.0f;
+    } else {
+        static_assert(P == SP_JS_TERM, "the products formed in fp32");
+        const bool in_a = a > 0.0f, in_b = b > 0.0f;
+        if (in_a && in_b) {
+            const float sum = median3(a + b, 0x1p-100f, 0x1p100f);
+            const float u = median3(divide_in_range(a, sum), 0x1p-126f, 0x1.fffffep-1f);
+            return LN2 * (a * fast_log2(2.0f * u) + b * fast_log2(2.0f * (1.0f - u)));
+        }
+        return in_a ? LN2 * a : (in_b ? LN2 * b : 0.0f);
+    }
+}
+template <int P, typename T> SPD_HD T semi_product(T a, T b, float p) {
+    (void)p;
     if constexpr (P == SP_TIMES) return a * b;
     else if constexpr (P == SP_PLUS) return a + b;
     else if constexpr (P == SP_MIN) return min_of(a, b);
     else if constexpr (P == SP_MAX) return max_of(a, b);
     else if constexpr (P == SP_ABS_DIFF) return abs_of(a - b);
-    else { T d = a - b; return d * d; }
+    else if constexpr (P == SP_SQ_DIFF) { T d = a - b; return d * d; }
+    else return (T)semi_product_f32<P>((float)a, (float)b, p);
 }
 // A product and where it is applied (UNION: over the columns either row stores), as a type.
 template <int P, bool UNION = false> struct ProductTag {
@@ -203,13 +241,14 @@ template <typename F> SPD_HD void for_product(int product, bool over_union, F &&
 #define SPD_CASE(P) case P: if (over_union) f(ProductTag<P, true>{}); else f(ProductTag<P, false>{}); break;
     switch (product) {
         SPD_CASE(SP_TIMES) SPD_CASE(SP_PLUS) SPD_CASE(SP_MIN) SPD_CASE(SP_MAX) SPD_CASE(SP_ABS_DIFF) SPD_CASE(SP_SQ_DIFF)
+        SPD_CASE(SP_ABS_DIFF_POW) SPD_CASE(SP_CANBERRA) SPD_CASE(SP_NOT_EQUAL) SPD_CASE(SP_X_LOG_X_OVER_Y) SPD_CASE(SP_JS_TERM)
     default: break;
     }
 #undef SPD_CASE
 }
-template <typename T> SPD_HD T semi_product_of(int product, T a, T b) {
+template <typename T> SPD_HD T semi_product_of(int product, T a, T b, float p) {
     T out = (T)0;
-    for_product(product, false, [&](auto tag) { out = semi_product<decltype(tag)::value, T>(a, b); });
+    for_product(product, false, [&](auto tag) { out = semi_product<decltype(tag)::value, T>(a, b, p); });
     return out;
 }
 
@@ -252,7 +291,7 @@ SPD_HD void norm_accumulate(int norm, float t, float p, double &s0, double &s1) 
     case NORM_SUM_POW:   s0 += (double)pow_abs(t, p); s1 += (t != 0.0f) ? 1.0 : 0.0; break;
     case NORM_NNZ:       s0 += (t != 0.0f) ? 1.0 : 0.0; break;
     default:
-        if (norm >= NORM_SEMI && t != 0.0f) { s0 += semi_product_of<double>(norm - NORM_SEMI, d, 0.0); s1 += 1.0; }
+        if (norm >= NORM_SEMI && t != 0.0f) { s0 += semi_product_of<double>(norm - NORM_SEMI, d, 0.0, p); s1 += 1.0; }
         break;
     }
 }
@@ -464,13 +503,13 @@ template <> struct Op<OP_SEMI_SUM> {
     struct Bv { float b; };
     SPD_HD static void init(Acc &x) { x.d = 0.0; x.s = 0.0; x.hits = 0; }
     SPD_HD static Bv prep(float b, const OpParams &) { return {b}; }
-    template <int P, bool UNION> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &) {
+    template <int P, bool UNION> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &q) {
         // every product offered gives 0 at (0, 0): a column that one side does not store is
         // silenced by clearing the other side's value, not by selecting among the fp64 results
         const double da = (double)((b.b != 0.0f) ? a : 0.0f), db = (double)((a != 0.0f) ? b.b : 0.0f);
-        x.d += semi_product<P, double>(da, db);
+        x.d += semi_product<P, double>(da, db, q.p);
         if constexpr (UNION) {
-            x.s += semi_product<P, double>(da, 0.0) + semi_product<P, double>(0.0, db);
+            x.s += semi_product<P, double>(da, 0.0, q.p) + semi_product<P, double>(0.0, db, q.p);
             x.hits += ((a != 0.0f) && (b.b != 0.0f)) ? 1 : 0;
         }
     }
@@ -497,7 +536,7 @@ template <> struct Op<OP_SEMI_EXT> {
     template <int P, bool UNION> SPD_HD static void visit_as(Acc &x, float a, const Bv &b, const OpParams &q) {
         const bool in_a = a != 0.0f, in_b = b.b != 0.0f;
         const bool take = UNION ? (in_a || in_b) : (in_a && in_b);
-        const float v = q.sign * semi_product<P, float>(a, b.b);
+        const float v = q.sign * semi_product<P, float>(a, b.b, q.p);
         x.m = fmaxf(x.m, take ? v : -__builtin_huge_valf());
     }
     SPD_HD static void visit(Acc &x, float a, const Bv &b, const OpParams &q) {
@@ -514,7 +553,7 @@ template <> struct Op<OP_SEMI_EXT> {
 // What a staged row's entry a would contribute in a column the other row does not store, as the
 // key the rows' largest such contributions are ranked by (Chebyshev: |a|).
 template <int OP> SPD_HD float one_sided_key(float a, const OpParams &q) {
-    if constexpr (OP == OP_SEMI_EXT) return q.sign * semi_product_of<float>(q.product, a, 0.0f);
+    if constexpr (OP == OP_SEMI_EXT) return q.sign * semi_product_of<float>(q.product, a, 0.0f, q.p);
     else return fabsf(a);
 }
 
@@ -531,6 +570,22 @@ SPD_HD void visit_with(typename Op<OP>::Acc &x, float a, const typename Op<OP>::
 // family).  v, s, w: the accumulated sums; a0,a1 / b0,b1: derived norms of the two rows.
 // The metric is a template argument so that a kernel can pick the formula once per slab
 // instead of once per pair.
+// The closing step of a semiring call on its folded value: nothing, the p-th root, the division
+// by the number of columns, or the square root of the half.
+SPD_HD float semi_epilogue(const OpParams &q, double v) {
+    switch (q.epilogue) {
+    case SE_ROOT_P: {
+        const float tf = (float)v;
+        if (q.p == 1.0f) return tf;
+        if (q.p == 2.0f) return sqrtf(tf);
+        return tf == 0.0f ? 0.0f : fast_exp2(q.inv_p * fast_log2(tf));
+    }
+    case SE_DIV_K: return (float)(v / q.k);
+    case SE_SQRT_HALF: return sqrtf((float)(v > 0.0 ? 0.5 * v : 0.0));
+    default: return (float)v;
+    }
+}
+
 template <int MT>
 SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a0, double a1, double b0, double b1) {
     const double LN2 = 0.693147180559945309417232121458;
@@ -599,10 +654,10 @@ SPD_HD float finish_as(const OpParams &q, double v, double s, double w, double a
     } else if constexpr (MT == MT_SEMI_SUM) {
         // v: products on shared columns, s: what those columns hold of the two rows' sums of
         // product(., 0), w: how many they are; a1 / b1 count the entries of the rows
-        if (!q.over_union) return (float)v;
-        return (float)(v + ((w == a1 && w == b1) ? 0.0 : (a0 + b0) - s));
+        if (!q.over_union) return semi_epilogue(q, v);
+        return semi_epilogue(q, v + ((w == a1 && w == b1) ? 0.0 : (a0 + b0) - s));
     } else if constexpr (MT == MT_SEMI_EXT) {
-        return (float)((double)q.sign * v);
+        return semi_epilogue(q, (double)q.sign * v);
     } else {
         return 0.0f;
     }

@@ -94,9 +94,9 @@ def test_long_rows_get_a_filter_instead_of_slices(handle, spd, metric):
     options = dict(force_kind=3, lds_budget=8192 + 65536, bloom_long_rows=1)
     for name, value in options.items():
         handle.set_option(name, value)
-    plan = spd.host_plan_summary(A["indptr"], B["indptr"], 8000, metric, **options)
+    plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 8000, metric, **options)
     assert plan["spilled_rows"] == 0 and {c["kind"] for c in plan["classes"]} == {3, 4}
-    without = spd.host_plan_summary(A["indptr"], B["indptr"], 8000, metric, force_kind=3, lds_budget=8192 + 65536)
+    without = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 8000, metric, force_kind=3, lds_budget=8192 + 65536)
     assert without["spilled_rows"] == 9
     want = oracle.pairwise(A, B, ORACLE_NAME[metric], p, mode="full")
     assert_distances_close(_np(handle.pairwise(dA, dB, metric, p)), want, metric)
@@ -127,7 +127,7 @@ def test_a_row_longer_than_the_largest_filter_serves(handle, spd):
             want = oracle.pairwise(A, B, ORACLE_NAME[metric])
             assert_distances_close(_np(h.pairwise(dA, dB, metric)), want, "%s %s" % (metric, options))
         if "bloom_long_rows" in options:
-            plan = spd.host_plan_summary(A["indptr"], B["indptr"], k, "cosine", **options)
+            plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], k, "cosine", **options)
             assert plan["spilled_rows"] == 0 and 4 in {c["kind"] for c in plan["classes"]}
         h.close()
 
@@ -149,6 +149,6 @@ def test_semirings_and_what_the_filter_does_not_serve(handle, spd):
     options = dict(force_kind=3, lds_budget=8192 + 65536, bloom_long_rows=1)
     for name, value in options.items():
         handle.set_option(name, value)
-    assert spd.host_plan_summary(A["indptr"], B["indptr"], 8000, "chebyshev", **options)["spilled_rows"] > 0
+    assert spd.testing.host_plan_summary(A["indptr"], B["indptr"], 8000, "chebyshev", **options)["spilled_rows"] > 0
     want = oracle.pairwise(A, B, "chebyshev", mode="full")
     assert_distances_close(_np(handle.pairwise(dA, dB, "chebyshev")), want, "chebyshev keeps its slices")

@@ -72,6 +72,17 @@ def test_config2_bag_of_words_tile(spd, capsys):
     cos = h.pairwise(dQ, dI, "cosine", out=out).index_select(0, torch.as_tensor(ra, device="cuda")).clone()
     ip = h.pairwise(dQ, dI, "inner_product", out=out).index_select(0, torch.as_tensor(ra, device="cuda"))
     assert float((cos + ip - 1.0).abs().max()) < 2e-6
+    # correlation (means over all 102,660 columns) on the same tile
+    _timed(capsys, "config2 correlation", lambda: h.pairwise(dQ, dI, "correlation", out=out))
+    want = oracle.pairwise(tile, I, "correlation", rows_a=ra, rows_b=rb)
+    assert_distances_close(_gather(out, ra, rb), want, "config2 correlation")
+    del out
+    # the fused top-32 of the same tile: full distance rows of a sample of the queries
+    rq = _extremes_and_sample(tile, 12, rng)
+    idx, dist = _timed(capsys, "config2 knn cosine", lambda: h.knn(dQ, dI, "cosine", 32))
+    rows = oracle.pairwise(tile, I, "cosine", rows_a=rq)
+    assert_knn_matches(idx.cpu().numpy()[rq], dist.cpu().numpy()[rq], rows, 32, "cosine", "config2 knn cosine")
+    progress(capsys, "config2 knn cosine checked against the oracle")
     h.close()
 
 
@@ -99,9 +110,18 @@ def test_config3_count_matrix_tile(spd, capsys):
         want = oracle.pairwise(tile, M, ORACLE_NAME[metric], rows_a=ra, rows_b=rb)
         assert_distances_close(_gather(out, ra, rb), want, "config3 " + metric)
         progress(capsys, "config3 %s checked against the oracle" % metric)
+    # the protocol of Section 4.2 on the same tile (its rows are rows of the index): fused top-32
+    rq = _extremes_and_sample(tile, 8, rng, extra=heavy_in_tile[:2])
+    for metric in ("l1", "jensen_shannon"):
+        idx, dist = _timed(capsys, "config3 knn " + metric, lambda: h.knn(dQ, dM, metric, 32))
+        idx, dist = idx.cpu().numpy(), dist.cpu().numpy()
+        rows = oracle.pairwise(tile, M, ORACLE_NAME[metric], rows_a=rq)
+        assert_knn_matches(idx[rq], dist[rq], rows, 32, metric, "config3 knn " + metric)
+        assert np.all(dist[:, 0] <= 1e-5), metric           # every query finds itself (or a copy) first
+        progress(capsys, "config3 knn %s checked against the oracle" % metric)
     # the same rows through hash staging: the >10,240-entry rows are cut into slices
     h.set_option("force_kind", 3)
-    plan = spd.host_plan_summary(tile["indptr"], M["indptr"], M["n_cols"], "l1", force_kind=3)
+    plan = spd.testing.host_plan_summary(tile["indptr"], M["indptr"], M["n_cols"], "l1", force_kind=3)
     assert plan["spilled_rows"] >= 8
     _timed(capsys, "config3 l1 (hash staging)", lambda: h.pairwise(dQ, dM, "l1", out=out))
     want = oracle.pairwise(tile, M, "manhattan", rows_a=ra, rows_b=rb)
@@ -119,22 +139,27 @@ def test_config4_binary_knn(spd, capsys):
     h.set_option("check_plan", 1)
     rng = np.random.default_rng(4)
     rq = _extremes_and_sample(Q, 24, rng)
-    plan = spd.host_plan_summary(Q["indptr"], I["indptr"], Q["n_cols"], "jaccard", k_neighbors=32)
+    plan = spd.testing.host_plan_summary(Q["indptr"], I["indptr"], Q["n_cols"], "jaccard", k_neighbors=32)
     progress(capsys, "config4 plan: spilled rows %d, slabs %d" % (plan["spilled_rows"], plan["slabs"]))
     for metric in ("jaccard", "dice", "hamming"):
         idx, dist = _timed(capsys, "config4 knn " + metric, lambda: h.knn(dQ, dI, metric, 32))
-        rows = oracle.pairwise(Q, I, ORACLE_NAME[metric], rows_a=rq)
-        assert_knn_matches(idx.cpu().numpy()[rq], dist.cpu().numpy()[rq], rows, 32, metric, "config4 " + metric)
+        # (the oracle takes 3 s per query row here: 24 rows for Jaccard, the extremes and 5 more for the others)
+        rows_checked = rq if metric == "jaccard" else rq[:: 3]
+        rows = oracle.pairwise(Q, I, ORACLE_NAME[metric], rows_a=rows_checked)
+        assert_knn_matches(idx.cpu().numpy()[rows_checked], dist.cpu().numpy()[rows_checked], rows, 32, metric,
+                           "config4 " + metric)
         progress(capsys, "config4 %s checked against the oracle" % metric)
     h.close()
 
 
-def _knn_tile_against_oracle(spd, capsys, label, M, tile_rows, metrics, k, n_checked):
+def _knn_tile_against_oracle(spd, capsys, label, M, tile_rows, metrics, k, n_checked, options=()):
     """Self-join protocol: a tile of the matrix's own rows queries the whole matrix."""
     tile = synth.take_rows(M, tile_rows)
     dQ, dM = spd.DeviceCsr.from_host(tile), spd.DeviceCsr.from_host(M)
     h = spd.Handle()
     h.set_option("check_plan", 1)
+    for name, value in options:
+        h.set_option(name, value)
     rng = np.random.default_rng(len(tile_rows))
     rq = _extremes_and_sample(tile, n_checked, rng)
     for metric in metrics:
@@ -173,16 +198,21 @@ def test_shape5_ngram_like(spd, capsys):
 
 def test_shape6_ratings_like(spd, capsys):
     """283,000 x 194,000 with power-law degrees up to 24,000 (46 M entries): 1,024 of its rows,
-    the 24,000-entry one among them (cut into slices), against all of it, fused top-32."""
+    the 24,000-entry one among them, against all of it, fused top-32."""
     M, _ = synth.workload(6)
     progress(capsys, "shape 6 generated: %d entries" % int(M["indptr"][-1]))
     rng = np.random.default_rng(6)
     tile_rows = _extremes_and_sample(M, 1024, rng)
-    plan = spd.host_plan_summary(synth.take_rows(M, tile_rows)["indptr"], M["indptr"], M["n_cols"], "cosine",
-                                 k_neighbors=32)
+    tile_ip = synth.take_rows(M, tile_rows)["indptr"]
+    plan = spd.testing.host_plan_summary(tile_ip, M["indptr"], M["n_cols"], "cosine", k_neighbors=32)
     progress(capsys, "shape6 plan: spilled rows %d, slabs %d" % (plan["spilled_rows"], plan["slabs"]))
-    assert plan["spilled_rows"] >= 1
+    # 194,000 columns: the bitmap of the columns leaves room for the 24,000-entry row as a whole
+    assert all(c["kind"] == 5 for c in plan["classes"]) and plan["spilled_rows"] == 0
     _knn_tile_against_oracle(spd, capsys, "shape6", M, tile_rows, ("cosine", "l1"), 32, 8)
+    # behind a hash table that row is cut into slices
+    hashed = spd.testing.host_plan_summary(tile_ip, M["indptr"], M["n_cols"], "l1", k_neighbors=32, force_kind=3)
+    assert hashed["spilled_rows"] >= 1
+    _knn_tile_against_oracle(spd, capsys, "shape6 (hash staging)", M, tile_rows, ("l1",), 32, 8, options=(("force_kind", 3),))
 
 
 def test_output_of_more_than_2_to_32_distances(spd, capsys):

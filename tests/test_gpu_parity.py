@@ -105,7 +105,7 @@ def test_split_rows_and_sliced_rows(handle, spd, metric):
     A, B = _wide_pair(metric not in NONNEGATIVE_ONLY)
     dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
     print("split+slices", metric, flush=True)
-    plan = spd.host_plan_summary(A["indptr"], B["indptr"], 400, metric, split_len=4, window=64, force_kind=3,
+    plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 400, metric, split_len=4, window=64, force_kind=3,
                                  lds_budget=8192, chunks=3)
     assert plan["spilled_rows"] > 0 and plan["split_rows"] > 0
     handle.set_option("split_len", 4)
@@ -144,7 +144,7 @@ def test_set_metrics_both_routes_and_long_slabs(handle, spd, metric, byte_counte
     print("set metric", metric, "byte_counters", byte_counters, flush=True)
     handle.set_option("byte_counters", byte_counters)
     handle.set_option("split_len", 1 << 20)
-    plan = spd.host_plan_summary(A["indptr"], B["indptr"], 1000, metric, split_len=1 << 20)
+    plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 1000, metric, split_len=1 << 20)
     assert plan["split_rows"] == 0 and plan["max_slab_steps"] >= 900
     want = oracle.pairwise(A, B, ORACLE_NAME[metric], mode="full")
     for kind in (2, 3, 5):
@@ -352,7 +352,7 @@ def test_knn_with_sliced_rows_and_split_rows(handle, spd):
     handle.set_option("lds_budget", 12288)       # (a kilobyte per staged row goes to the k-NN lists)
     for metric in ("l1", "cosine", "inner_product", "jensen_shannon", "minkowski", "chebyshev", "jaccard"):
         print("knn slices", metric, flush=True)
-        plan = spd.host_plan_summary(A["indptr"], B["indptr"], 400, metric, k_neighbors=16, split_len=4, force_kind=3,
+        plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 400, metric, k_neighbors=16, split_len=4, force_kind=3,
                                      lds_budget=12288)
         assert plan["spilled_rows"] > 0 and plan["split_rows"] > 0
         idx, dist = handle.knn(dA, dB, metric, 16, _p_of(metric))
@@ -516,7 +516,7 @@ def test_operands_swapped_split_rows_and_sliced_rows(handle, spd, metric):
     A, B = _wide_pair(metric not in NONNEGATIVE_ONLY)
     dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
     print("swapped split+slices", metric, flush=True)
-    plan = spd.host_plan_summary(B["indptr"], A["indptr"], 400, metric, split_len=4, window=64, force_kind=3,
+    plan = spd.testing.host_plan_summary(B["indptr"], A["indptr"], 400, metric, split_len=4, window=64, force_kind=3,
                                  lds_budget=8192, chunks=3, consecutive_groups=1)
     assert plan["spilled_rows"] > 0 and plan["split_rows"] > 0
     for name, value in (("split_len", 4), ("window", 64), ("force_kind", 3), ("lds_budget", 8192), ("chunks", 3),

@@ -8,7 +8,8 @@ import pytest
 import oracle
 from gen import synth
 from test_gpu_parity import _edge_matrices, _sample_rows, _wide_pair
-from util import assert_distances_close, assert_knn_matches
+from util import (ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, TABLE1_SEMIRINGS, assert_distances_close,
+                  assert_knn_matches)
 
 pytestmark = pytest.mark.gpu
 
@@ -163,24 +164,115 @@ def test_knn_with_sliced_rows_and_split_rows(handle, spd):
         assert_knn_matches(idx.cpu().numpy(), val.cpu().numpy(), rows, 9, "semiring", _name(sr))
 
 
-def test_semirings_reproduce_the_metrics(handle, config0):
-    """The library's own distances through the semiring entry point: the dot product, Manhattan,
-    Chebyshev (where the two rows are not both empty) and the squared Euclidean distance."""
+def _call(handle, dA, dB, sr, p=3.0):
+    """spd_semiring_pairwise for a dict {product, sum, over_union[, transform][, epilogue][, p]}."""
+    import torch
+    out = handle.semiring_pairwise(dA, dB, sr["product"], sr["sum"], sr["over_union"], p=sr.get("p", p),
+                                   transform=sr.get("transform", "none"), epilogue=sr.get("epilogue", "none"))
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _oracle_call(A, B, sr, p=3.0, **kw):
+    return oracle.semiring_pairwise(A, B, sr["product"], sr["sum"], sr["over_union"], p=sr.get("p", p),
+                                    transform=sr.get("transform", "none"), epilogue=sr.get("epilogue", "none"), **kw)
+
+
+@pytest.mark.parametrize("metric", ALL_METRICS)
+def test_semirings_reproduce_the_metrics(handle, spd, config0, metric):
+    """Every distance of Table 1 (and the library's variants of them) through spd_semiring_pairwise
+    and spd_semiring_knn: transform, product, sum, domain and epilogue as Section 2.2 and Table 1
+    give them, against the oracle's semiring evaluator, the oracle's plain formula, and the
+    library's own spd_pairwise."""
+    import torch
+    sr = TABLE1_SEMIRINGS[metric]
+    p = sr.get("p", 3.0)
+    cases = [("config0",) + tuple(config0)]
+    M = _edge_matrices(metric not in NONNEGATIVE_ONLY)
+    dM = spd.DeviceCsr.from_host(M)
+    cases.append(("edge rows", M, M, dM, dM))
+    for tag, A, B, dA, dB in cases:
+        print("table 1 as a semiring", metric, tag, flush=True)
+        got = _call(handle, dA, dB, sr)
+        assert_distances_close(got, _oracle_call(A, B, sr, mode="full"), "%s as a semiring, %s" % (metric, tag))
+        want = oracle.pairwise(A, B, ORACLE_NAME[metric], p, mode="full")
+        lib = handle.pairwise(dA, dB, metric, p)
+        torch.cuda.synchronize()
+        lib = lib.cpu().numpy()
+        if metric == "chebyshev":      # the identity of max between two empty rows, where the distance says 0
+            both_empty = (np.diff(A["indptr"]) == 0)[:, None] & (np.diff(B["indptr"]) == 0)[None, :]
+            assert np.all(got[both_empty] == -np.inf)
+            got = np.where(both_empty, 0.0, got)
+        assert_distances_close(got, want, "%s as a semiring against the formula, %s" % (metric, tag))
+        if metric != "chebyshev":
+            assert np.array_equal(got, lib, equal_nan=True), metric     # the same kernels ran
+    A, B, dA, dB = config0
+    if metric != "inner_product":          # (spd_knn returns the largest inner products)
+        idx, val = handle.semiring_knn(dA, dB, sr["product"], sr["sum"], sr["over_union"], 9, p=p,
+                                       transform=sr.get("transform", "none"), epilogue=sr.get("epilogue", "none"))
+        torch.cuda.synchronize()
+        rows = _oracle_call(A, B, sr)
+        assert_knn_matches(idx.cpu().numpy(), val.cpu().numpy(), rows, 9, "semiring", metric + " knn")
+
+
+# combinations that spell none of Table 1's distances: they run on the kernels that take the
+# product as a run-time choice
+OTHER_SEMIRINGS = [
+    dict(product="abs_diff_pow", sum="max", over_union=True, p=2.5),
+    dict(product="abs_diff_pow", sum="plus", over_union=True, p=3.0),                       # no root
+    dict(product="abs_diff_pow", sum="plus", over_union=False, p=0.5, epilogue="root_p"),
+    dict(product="canberra", sum="plus", over_union=False),
+    dict(product="canberra", sum="max", over_union=True),
+    dict(product="canberra", sum="plus", over_union=True, epilogue="div_k"),
+    dict(product="not_equal", sum="plus", over_union=False),
+    dict(product="not_equal", sum="min", over_union=True),
+    dict(product="x_log_x_over_y", sum="max", over_union=False),
+    dict(product="x_log_x_over_y", sum="min", over_union=False),
+    dict(product="x_log_x_over_y", sum="plus", over_union=False, transform="sqrt"),
+    dict(product="js_term", sum="plus", over_union=False),
+    dict(product="js_term", sum="max", over_union=True),
+    dict(product="js_term", sum="plus", over_union=True),                                    # the divergence, no root
+    dict(product="times", sum="plus", over_union=False, transform="sqrt"),                   # the Bhattacharyya coefficient
+    dict(product="abs_diff", sum="plus", over_union=True, transform="nonzero", epilogue="div_k"),
+    dict(product="sq_diff", sum="plus", over_union=True, epilogue="sqrt_half"),
+    dict(product="min", sum="plus", over_union=False, transform="sqrt", epilogue="root_p", p=2.0),
+    dict(product="max", sum="max", over_union=True, epilogue="div_k"),
+]
+
+
+def _sr_name(sr):
+    return "/".join(str(sr[k]) for k in ("product", "sum", "over_union", "transform", "epilogue", "p") if k in sr)
+
+
+@pytest.mark.parametrize("sr", OTHER_SEMIRINGS, ids=_sr_name)
+def test_other_combinations_of_the_menu(handle, spd, config0, sr):
+    """Pairwise on config 0 through every staging kind, on rows cut into slices with the operands'
+    roles exchanged, on the edge rows, and fused k-NN."""
     import torch
     A, B, dA, dB = config0
-
-    def metric(name):
-        out = handle.pairwise(dA, dB, name)
-        torch.cuda.synchronize()
-        return out.cpu().numpy().astype(np.float64)
-
-    assert_distances_close(_run(handle, dA, dB, ("times", "plus", False)), metric("inner_product"), "dot")
-    assert_distances_close(_run(handle, dA, dB, ("abs_diff", "plus", True)), metric("l1"), "l1")
-    assert_distances_close(_run(handle, dA, dB, ("sq_diff", "plus", True)), metric("l2_unexpanded") ** 2, "l2^2")
-    cheb = _run(handle, dA, dB, ("abs_diff", "max", True))
-    both_empty = (np.diff(A["indptr"]) == 0)[:, None] & (np.diff(B["indptr"]) == 0)[None, :]
-    assert np.all(cheb[both_empty] == -np.inf)
-    assert_distances_close(np.where(both_empty, 0.0, cheb), metric("chebyshev"), "chebyshev")
+    print("semiring", _sr_name(sr), flush=True)
+    want = _oracle_call(A, B, sr, mode="full")
+    for kind, max_rows in ((1, 8), (2, 4), (3, 8), (5, 2)):
+        handle.set_option("force_kind", kind)
+        handle.set_option("max_rows", max_rows)
+        assert_distances_close(_call(handle, dA, dB, sr), want, "%s kind %d" % (_sr_name(sr), kind))
+    idx, val = handle.semiring_knn(dA, dB, sr["product"], sr["sum"], sr["over_union"], 10, p=sr.get("p", 3.0),
+                                   transform=sr.get("transform", "none"), epilogue=sr.get("epilogue", "none"))
+    torch.cuda.synchronize()
+    assert_knn_matches(idx.cpu().numpy(), val.cpu().numpy(), _oracle_call(A, B, sr), 10, "semiring", _sr_name(sr) + " knn")
+    handle.set_option("force_kind", 0)
+    handle.set_option("max_rows", 8)
+    M = _edge_matrices(False)
+    dM = spd.DeviceCsr.from_host(M)
+    assert_distances_close(_call(handle, dM, dM, sr), _oracle_call(M, M, sr, mode="full"), _sr_name(sr) + " edge rows")
+    A, B = _wide_pair(False)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    want = _oracle_call(A, B, sr, mode="full")
+    for swap in (0, 2):
+        for name, value in (("split_len", 4), ("window", 64), ("force_kind", 3), ("lds_budget", 8192), ("chunks", 3),
+                            ("swap_operands", swap)):
+            handle.set_option(name, value)
+        assert_distances_close(_call(handle, dA, dB, sr), want, "%s slices, swap_operands %d" % (_sr_name(sr), swap))
 
 
 @pytest.mark.parametrize("sr", [("plus", "min", False), ("abs_diff", "max", True), ("max", "plus", True)], ids=_name)
@@ -206,6 +298,23 @@ def test_error_statuses(handle, spd, config0):
     with pytest.raises(spd.SpdError) as e:
         handle.semiring_knn(dA, dB, "plus", "min", False, 65)
     assert e.value.status_name == "SPD_ERR_BAD_K"
+    for bad in (dict(product="x_log_x_over_y", sum="plus", over_union=True),             # no value where y is absent
+                dict(product="abs_diff", sum="plus", over_union=True, epilogue="cosine"),   # an expansion outside its distance
+                dict(product="times", sum="max", over_union=False, epilogue="l2"),
+                dict(product="times", sum="plus", over_union=False, transform="sqrt", epilogue="jaccard"),
+                dict(product="times", sum="plus", over_union=False, transform=7),
+                dict(product="times", sum="plus", over_union=False, epilogue=40)):
+        with pytest.raises(spd.SpdError) as e:
+            handle.semiring_pairwise(dA, dB, bad["product"], bad["sum"], bad["over_union"],
+                                     transform=bad.get("transform", "none"), epilogue=bad.get("epilogue", "none"))
+        assert e.value.status_name == "SPD_ERR_BAD_METRIC", bad
+    for p in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(spd.SpdError) as e:
+            handle.semiring_pairwise(dA, dB, "abs_diff_pow", "plus", True, p=p)
+        assert e.value.status_name == "SPD_ERR_BAD_P"
+        with pytest.raises(spd.SpdError) as e:
+            handle.semiring_knn(dA, dB, "abs_diff", "plus", True, 3, p=p, epilogue="root_p")
+        assert e.value.status_name == "SPD_ERR_BAD_P"
 
 
 @pytest.mark.parametrize("sr", SEMIRINGS, ids=_name)

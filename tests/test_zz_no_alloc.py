@@ -65,7 +65,7 @@ def test_sliced_rows_keep_their_partial_sums_in_the_static_array(spd):
         for name, value in (("split_len", 4), ("window", 64), ("force_kind", 3), ("lds_budget", 8192), ("check_plan", 1)):
             h.set_option(name, value)
         A, B = wide(ra, rb)
-        plan = spd.host_plan_summary(A["indptr"], B["indptr"], 400, "minkowski", split_len=4, window=64, force_kind=3,
+        plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 400, "minkowski", split_len=4, window=64, force_kind=3,
                                      lds_budget=8192)
         assert plan["spilled_rows"] > 0
         for metric in ("minkowski", "chebyshev", "hellinger"):
