@@ -283,6 +283,9 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 the handle's stream still orders the whole call (0: everything on the handle's stream);
  *                 they are used when the largest launch is short or the small ones hold a tenth of
  *                 the call's sweeps over B, and not otherwise
+ *   "cuckoo_attempts" hash staging of a half-full table tries up to three pairs of hash functions
+ *                 before it falls back to linear probing (3, the default); fewer, down to 0 (linear
+ *                 probing at once), let a test reach that fall-back, which no input has needed so far
  *   "swap_operands" spd_pairwise may stage B and stream A instead of the other way round (every distance
  *                 but the two KL divergences is symmetric in its rows): B's rows are then staged in
  *                 groups of consecutive rows, so that a lane's results are neighbours in the output

@@ -129,6 +129,7 @@ struct spd_handle {
     bool profile = false;
     bool check_plan = false;
     bool no_byte_counters = false;   // option "byte_counters" 0: set metrics through the dot product
+    int cuckoo_attempts = 3;     // option "cuckoo_attempts"
     int swap_operands = 1;       // option "swap_operands": 0 never, 1 where it pays, 2 wherever the distance allows it
     int side_streams = 3;        // option "side_streams": how many internal streams the small launches may use beside the large one
     static constexpr int kSideStreams = 3;
@@ -796,6 +797,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         sa.q = q;
         sa.kind = c.kind;
         sa.hscale = c.hscale;
+        sa.cuckoo_attempts = h->cuckoo_attempts;
         sa.transform = mi.transform;
         sa.norm = mi.norm;
         sa.k = (uint32_t)A->n_cols;
@@ -1226,6 +1228,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "side_streams") {
         if (value < 0 || value > spd_handle::kSideStreams) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must lie in [0, 3]");
         h->side_streams = (int)value;
+    } else if (s == "cuckoo_attempts") {
+        if (value < 0 || value > 3) return fail(h, SPD_ERR_UNSUPPORTED, "cuckoo_attempts must lie in [0, 3]");
+        h->cuckoo_attempts = (int)value;
     } else if (s == "swap_operands") {
         if (value < 0 || value > 2) return fail(h, SPD_ERR_UNSUPPORTED, "swap_operands must be 0, 1 or 2");
         h->swap_operands = (int)value;

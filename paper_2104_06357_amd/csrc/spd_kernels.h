@@ -41,6 +41,7 @@ struct ScanArgs {
     OpParams q;
     int32_t kind, transform, norm;
     int32_t hscale;               // hash staging: log2 of table entries per staged entry
+    int32_t cuckoo_attempts;      // hash staging, half-full tables: pairs of hash functions tried (0: linear probing at once)
     uint32_t k;                   // columns
     uint32_t padcol;              // column an idle lane looks up (maps to the zero row)
     // results

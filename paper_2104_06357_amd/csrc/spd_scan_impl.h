@@ -599,7 +599,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             bool built = false;
             if (args.hscale == 1) {
                 // dense table: two candidate buckets per column
-                for (int attempt = 0; attempt < kCuckooAttempts && !built; ++attempt) {
+                for (int attempt = 0; attempt < min(kCuckooAttempts, args.cuckoo_attempts) && !built; ++attempt) {
                     cmap.mult1 = kHashMult[attempt][0];
                     cmap.mult2 = kHashMult[attempt][1];
                     if (attempt > 0) {
@@ -633,7 +633,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
             if (!built) {
                 cmap.mult1 = kHashMult[0][0];
                 cmap.two_choice = false;
-                if (args.hscale == 1) {
+                if (args.hscale == 1 && args.cuckoo_attempts > 0) {       // (what the failed attempts left behind)
                     for (uint32_t i = tid; i < L.cap / 2u; i += nthr) table[i] = make_uint4(kEmptyKey, 0u, kEmptyKey, 0u);
                     if (tid == 0) s_reach = 1;
                     __syncthreads();

@@ -127,8 +127,9 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
         char buf[320];
         std::snprintf(buf, sizeof buf,
                       "%s{\"R\": %d, \"kind\": %d, \"block\": %d, \"lds_bytes\": %u, \"groups\": %d, \"max_sumlen\": %lld, "
-                      "\"chunks\": %d, \"cost\": %.1f}",
-                      i ? ", " : "", c.R, c.kind, c.block, c.lds_bytes, c.n_groups, (long long)max_sum, c.n_chunks, c.cost);
+                      "\"chunks\": %d, \"cost\": %.1f, \"hscale\": %d}",
+                      i ? ", " : "", c.R, c.kind, c.block, c.lds_bytes, c.n_groups, (long long)max_sum, c.n_chunks, c.cost,
+                      c.hscale);
         js += buf;
     }
     int64_t split_rows = 0, max_steps = 0, total_steps = 0;

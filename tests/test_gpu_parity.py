@@ -542,3 +542,144 @@ def test_config1_both_orientations(handle, config1):
             got = _run_pairwise(handle, dA, dB, metric)
             assert_distances_close(got[np.ix_(ra, rb)], want, "%s swap_operands=%d" % (metric, mode))
             assert np.all(np.isfinite(got))
+
+
+# ------------------------------------------------------------------ branches that ordinary inputs do not reach
+@pytest.mark.parametrize("attempts", [0, 1, 3])
+def test_hash_staging_falls_back_to_linear_probing(handle, spd, attempts):
+    """A half-full hash table is filled by cuckoo hashing with up to three pairs of hash functions
+    and, should all fail, by linear probing with as many probes as the fullest run needs.  No input
+    has made them fail: the option limits the attempts (0: linear probing at once)."""
+    A, B = _wide_pair(True)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    options = dict(split_len=4, window=64, force_kind=3, lds_budget=8192)
+    plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 400, "l1", **options)
+    assert any(c["hscale"] == 1 for c in plan["classes"])          # tables as full as they get
+    for name, value in options.items():
+        handle.set_option(name, value)
+    handle.set_option("cuckoo_attempts", attempts)
+    for metric in ("l1", "cosine", "chebyshev", "jaccard", "hamming"):
+        print("hash fall-back", attempts, metric, flush=True)
+        got = _run_pairwise(handle, dA, dB, metric)
+        assert_distances_close(got, oracle.pairwise(A, B, ORACLE_NAME[metric], mode="full"), "%s attempts=%d" % (metric, attempts))
+    idx, dist = handle.knn(dA, dB, "l1", 9)
+    import torch
+    torch.cuda.synchronize()
+    assert_knn_matches(idx.cpu().numpy(), dist.cpu().numpy(), oracle.pairwise(A, B, "manhattan"), 9, "l1", "fall-back knn")
+
+
+def _threshold(lo, hi, pred):
+    """Largest v in [lo, hi] with pred(v), pred being true up to some point and false after it."""
+    assert pred(lo) and not pred(hi)
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if pred(mid):
+            lo = mid
+        else:
+            hi = mid
+    return lo
+
+
+def _rows_of_lengths(lengths, k, rng):
+    d = np.zeros((len(lengths), k))
+    for r, n in enumerate(lengths):
+        d[r, rng.choice(k, size=n, replace=False)] = rng.random(n) + 0.05
+    return synth.from_dense(np.asarray(d.astype(np.float32), dtype=np.float64))
+
+
+def test_rows_and_column_counts_at_the_planner_thresholds(handle, spd):
+    """One below, at and one above each point where the planner changes its mind: the column
+    count where the dense strip gives way to the column-slot strip, that to the bitmap and that
+    to the hash table; the row length from which a row is cut into slices; the row length from
+    which a row of B is split over lanes.  The thresholds are read off the planner itself."""
+    rng = np.random.default_rng(314)
+    ip = np.array([0, 3, 5], dtype=np.int64)
+    kind_at = lambda k: spd.testing.host_plan_summary(ip, ip, k, "l1")["classes"][0]["kind"]
+    k_strip = _threshold(16, 1 << 22, lambda k: kind_at(k) == 1)
+    k_slot = _threshold(k_strip + 1, 1 << 22, lambda k: kind_at(k) == 2)
+    k_bitmap = _threshold(k_slot + 1, 1 << 22, lambda k: kind_at(k) == 5)
+    assert kind_at(k_bitmap + 1) == 3
+    for k_edge in (k_strip, k_slot, k_bitmap):
+        for k in (k_edge - 1, k_edge, k_edge + 1):
+            A = _rows_of_lengths([0, 1, 7, 40, 300], k, rng)
+            B = _rows_of_lengths([2, 0, 9, 64, 65, 257], k, rng)
+            # the last column is stored too: the map has to reach it
+            for M in (A, B):
+                M["indices"] = M["indices"].copy()
+                last = int(M["indptr"][-1]) - 1
+                M["indices"][last] = k - 1
+            print("threshold k", k, "kind", kind_at(k), flush=True)
+            dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+            handle.csr_validate(dA)
+            handle.csr_validate(dB)
+            for metric in ("l1", "cosine", "chebyshev", "jaccard"):
+                assert_distances_close(_run_pairwise(handle, dA, dB, metric), oracle.pairwise(A, B, ORACLE_NAME[metric]),
+                                       "%s at k=%d" % (metric, k))
+    # the longest row that is staged whole (hash staging under a 16 KB budget), and one more entry
+    opts = dict(force_kind=3, lds_budget=16384)
+    one = lambda n: np.array([0, n], dtype=np.int64)
+    spilled = lambda n: spd.testing.host_plan_summary(one(n), ip, 4000, "l1", **opts)["spilled_rows"]
+    d_whole = _threshold(1, 3999, lambda n: spilled(n) == 0)
+    # the shortest row of B that is split over lanes
+    split = lambda n: spd.testing.host_plan_summary(ip, one(n), 4000, "l1", **opts)["split_rows"]
+    b_unsplit = _threshold(1, 3999, lambda n: split(n) == 0)
+    A = _rows_of_lengths([d_whole - 1, d_whole, d_whole + 1, 2 * d_whole, 2 * d_whole + 1, 3], 4000, rng)
+    B = _rows_of_lengths([b_unsplit - 1, b_unsplit, b_unsplit + 1, b_unsplit + 2, 1, 0], 4000, rng)
+    plan = spd.testing.host_plan_summary(A["indptr"], B["indptr"], 4000, "l1", **opts)
+    assert plan["spilled_rows"] == 3 and plan["split_rows"] == 2, plan
+    for name, value in opts.items():
+        handle.set_option(name, value)
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    for metric in ("l1", "cosine", "chebyshev", "jaccard", "minkowski", "jensen_shannon"):
+        print("threshold rows", metric, d_whole, b_unsplit, flush=True)
+        assert_distances_close(_run_pairwise(handle, dA, dB, metric, 3.0), oracle.pairwise(A, B, ORACLE_NAME[metric], 3.0),
+                               "%s at the row thresholds" % metric)
+    idx, dist = handle.knn(dA, dB, "l1", 4)
+    import torch
+    torch.cuda.synchronize()
+    assert_knn_matches(idx.cpu().numpy(), dist.cpu().numpy(), oracle.pairwise(A, B, "manhattan"), 4, "l1", "threshold knn")
+
+
+def test_set_metrics_beyond_2_to_23_columns_and_2_to_24_entries(handle, spd):
+    """Jaccard and Dice take an exact fp32 quotient of their integer counts while those are
+    exact in fp32, and an fp64 one beyond: more than 2^22 / 2^23 columns, and two rows whose
+    union holds more than 2^24 entries (9 million each, a million shared; the staged one is cut
+    into some nine hundred slices)."""
+    import torch
+    rng = np.random.default_rng(2718)
+    for k in ((1 << 22) + 1, (1 << 23) + 1):
+        A = _rows_of_lengths([0, 5, 60], 2000, rng)
+        B = _rows_of_lengths([3, 0, 61, 400], 2000, rng)
+        for M in (A, B):                     # spread the columns over all k, the last one included
+            M["n_cols"] = k
+            M["indices"] = (M["indices"].astype(np.int64) * ((k - 1) // 1999)).astype(np.int32)
+        dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+        handle.csr_validate(dA)
+        handle.csr_validate(dB)
+        for metric in ("jaccard", "dice", "russell_rao", "hamming", "cosine", "correlation"):
+            print("wide k", k, metric, flush=True)
+            want = oracle.pairwise(A, B, ORACLE_NAME[metric], threads=2)
+            assert_distances_close(_run_pairwise(handle, dA, dB, metric), want, "%s at k=%d" % (metric, k))
+    k = 17_000_001
+    x = np.arange(0, 9_000_000, dtype=np.int32)
+    y = np.arange(8_000_000, 17_000_000, dtype=np.int32)
+    small = np.array([5, 8_500_000, 16_999_999], dtype=np.int32)
+
+    def csr(rows):
+        ip = np.zeros(len(rows) + 1, dtype=np.int64)
+        np.cumsum([r.size for r in rows], out=ip[1:])
+        cols = np.concatenate(rows)
+        return {"n_rows": len(rows), "n_cols": k, "indptr": ip, "indices": cols, "values": np.ones(cols.size, dtype=np.float32)}
+
+    A, B = csr([x, small]), csr([y, small, x])
+    dA, dB = spd.DeviceCsr.from_host(A), spd.DeviceCsr.from_host(B)
+    for metric in ("jaccard", "dice"):
+        print("2^24 entries", metric, flush=True)
+        got = _run_pairwise(handle, dA, dB, metric)
+        want = oracle.pairwise(A, B, ORACLE_NAME[metric], threads=1)
+        assert_distances_close(got, want, metric + " beyond 2^24 entries")
+        exact = {"jaccard": 1.0 - 1_000_000 / 17_000_000, "dice": 1.0 - 2_000_000 / 18_000_000}[metric]
+        assert abs(got[0, 0] - exact) <= 1e-6 and got[0, 2] == 0.0
+    idx, dist = handle.knn(dA, dB, "jaccard", 2)
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == [[2, 0], [1, 0]]
