@@ -262,7 +262,7 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 cut into slices (default 0: measured slower than slices on every shape tried)
  *   "max_rows"    largest number of A rows staged together (1, 2, 4, 8 or 16; the set metrics,
  *                 whose rows take a byte each in the staged table, stage four times as many,
- *                 up to 32; with fused k-NN 8, or 16 for max_rows = 16)
+ *                 up to 32; with fused k-NN 16, or 32 for max_rows = 16)
  *   "split_len"   B rows at least this long are split over several lanes (0 = automatic: 256,
  *                 or 512 when B has 2^22 stored entries or more)
  *   "window"      B rows per degree-sorting window

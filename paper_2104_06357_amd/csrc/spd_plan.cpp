@@ -266,7 +266,7 @@ std::string plan_staging(int64_t n_cols, int metric, int op, bool knn, const Pla
         // a byte per row: four rows to the word; with the k-NN lists in registers as well, 8 rows
         // run faster than 16 (which max_rows = 16 still selects)
         min_r = 4;
-        max_r = std::min(4 * max_r, knn ? (opt.max_rows > 8 ? 16 : 8) : 32);
+        max_r = std::min(4 * max_r, knn ? (opt.max_rows > 8 ? 32 : 16) : 32);
     }
     auto words = [&](int R) { return table_words(op, R); };
     auto lists = [&](int R) { return knn ? (uint32_t)R : 0u; };
@@ -579,7 +579,7 @@ std::string plan_check(const APlan &a, const BPlan &b, const int64_t *a_indptr, 
     std::vector<uint32_t> slot_flags((size_t)a.n_partial_slots, 0);
     for (const AClass &c : a.classes) {
         if (c.R != 1 && c.R != 2 && c.R != 4 && c.R != 8 && c.R != 16 && c.R != 32) return "class R";
-        if (op == OP_CNT ? (c.R < 4 || (knn_k > 0 && c.R > 16)) : c.R > 16) return "class R outside the product's range";
+        if (op == OP_CNT ? c.R < 4 : c.R > 16) return "class R outside the product's range";
         if (wide_sums(metric) && c.R > 8) return "two-sum product with R > 8";
         if ((op == OP_MINK || op == OP_MINK_ANY) && c.R > 4) return "Minkowski with R > 4";
         if (c.kind < KIND_STRIP || c.kind > KIND_BITMAP) return "class kind";

@@ -1097,9 +1097,7 @@ static hipError_t launch_scan_op(hipStream_t st, int R, int block, uint32_t lds_
         case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
         case 8: return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
         case 16: return launch_scan_r<OP, 16, WHICH>(st, block, lds_bytes, args);
-        case 32:
-            if constexpr (WHICH == 0) return launch_scan_r<OP, 32, WHICH>(st, block, lds_bytes, args);
-            else return hipErrorInvalidValue;
+        case 32: return launch_scan_r<OP, 32, WHICH>(st, block, lds_bytes, args);
         default: return hipErrorInvalidValue;
         }
     } else {
