@@ -99,10 +99,11 @@ SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
 }
 
 // Wavefronts per SIMD the compiler is asked to make room for (it bounds the registers per
-// lane: 8 means at most 64).  The light pairwise instances run two workgroups of 16
-// wavefronts per compute unit that way.
+// lane: 8 means at most 64).  The light pairwise instances of eight rows run two workgroups of
+// 16 wavefronts per compute unit that way, and hide the LDS reads of a step behind each other;
+// every other instance runs fewer wavefronts and looks its columns up a block of steps ahead.
 SPD_HD constexpr int scan_min_waves(int op, int R, int kind, bool knn) {
-    if (!knn && R <= 8 && kind != 3 /* KIND_HASH */ && kind != 5 /* KIND_BITMAP */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM || op == OP_CANB)) return 8;
+    if (!knn && R == 8 && kind != 3 /* KIND_HASH */ && kind != 5 /* KIND_BITMAP */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM || op == OP_CANB)) return 8;
     // 128 registers: two workgroups of 8 wavefronts per compute unit
     if (!knn && R == 8 && (op == OP_SEMI_SUM || op == OP_SEMI_EXT)) return 4;
     // (the k-NN instances of these sit a register or two above 128 otherwise)

@@ -406,6 +406,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     static_assert(kTopRanks == 32, "a pair's visited ranks are the bits of one 32-bit word");
     static_assert(KIND != KIND_BLOOM || (R == 1 && bloom_serves(OP)), "a Bloom-staged row is alone in its workgroup");
     constexpr int U = kScanUnroll;
+    // the instances compiled for 64 registers per lane (eight wavefronts per SIMD) keep the short pipeline
+    constexpr bool kDeepPipeline = KIND != KIND_BLOOM && scan_min_waves(OP, R, KIND, KNN) < 8;
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ ARow s_rows[R];
     __shared__ uint32_t s_prefix[R + 1];
@@ -849,12 +851,8 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
                 unfolded = 0;
             }
         };
-        auto visit_block = [&](const uint2 (&cur)[U]) {
-            if constexpr (kCnt) {
-                if (unfolded > kCntMaxSteps - U) fold_counts();
-                unfolded += U;
-            }
-            uint32_t slot[U];
+        // the slots of a block's columns (the LDS reads of a block are issued together)
+        auto lookup_block = [&](const uint2 (&cur)[U], uint32_t (&slot)[U]) {
             if constexpr (KIND == KIND_HASH) {
                 uint32_t h[U];
                 uint4 e[U];
@@ -872,25 +870,68 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
 #pragma unroll
                 for (int u = 0; u < U; ++u) slot[u] = cmap.lookup(cur[u].x);
             }
+        };
+        auto visit_block = [&](const uint2 (&cur)[U], const uint32_t (&slot)[U]) {
+            if constexpr (kCnt) {
+                if (unfolded > kCntMaxSteps - U) fold_counts();
+                unfolded += U;
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) visit_step(cur[u], slot[u]);
         };
+        // first step of the block that follows the one at t (past the slab's end the last block is
+        // simply read again)
+        auto block_after = [&](int t, int ahead) { return min(t + ahead * U, steps - U); };
         if (steps > 0) {
-            // two register sets take turns: while one block is worked on, the next one is in
-            // flight (past the slab's end the last block is simply read again)
-            uint2 even[U], odd[U];
-            fetch_block(even, 0);
-            for (int t0 = 0;;) {
-                fetch_block(odd, min(t0 + U, steps - U));
-                __builtin_amdgcn_sched_barrier(0);        // keep the loads ahead of the arithmetic
-                visit_block(even);
-                t0 += U;
-                if (t0 >= steps) break;
-                fetch_block(even, min(t0 + U, steps - U));
-                __builtin_amdgcn_sched_barrier(0);
-                visit_block(odd);
-                t0 += U;
-                if (t0 >= steps) break;
+            if constexpr (kDeepPipeline) {
+                // Three register sets take turns: while block t is worked on, the columns of block
+                // t + 1 are being looked up in LDS and block t + 2 is in flight from memory.  (A
+                // launch that the LDS holds to a few wavefronts per SIMD has nobody else to hide the
+                // two dependent LDS reads of a step behind.)
+                uint2 e0[U], e1[U], e2[U];
+                uint32_t s0[U], s1[U], s2[U];
+                fetch_block(e0, 0);
+                fetch_block(e1, block_after(0, 1));
+                lookup_block(e0, s0);
+                for (int t0 = 0;;) {
+                    fetch_block(e2, block_after(t0, 2));
+                    lookup_block(e1, s1);
+                    __builtin_amdgcn_sched_barrier(0);    // keep the loads and lookups ahead of the arithmetic
+                    visit_block(e0, s0);
+                    t0 += U;
+                    if (t0 >= steps) break;
+                    fetch_block(e0, block_after(t0, 2));
+                    lookup_block(e2, s2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    visit_block(e1, s1);
+                    t0 += U;
+                    if (t0 >= steps) break;
+                    fetch_block(e1, block_after(t0, 2));
+                    lookup_block(e0, s0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    visit_block(e2, s2);
+                    t0 += U;
+                    if (t0 >= steps) break;
+                }
+            } else {
+                // two register sets take turns: while one block is worked on, the next one is in flight
+                uint2 even[U], odd[U];
+                uint32_t slot[U];
+                fetch_block(even, 0);
+                for (int t0 = 0;;) {
+                    fetch_block(odd, block_after(t0, 1));
+                    __builtin_amdgcn_sched_barrier(0);        // keep the loads ahead of the arithmetic
+                    lookup_block(even, slot);
+                    visit_block(even, slot);
+                    t0 += U;
+                    if (t0 >= steps) break;
+                    fetch_block(even, block_after(t0, 1));
+                    __builtin_amdgcn_sched_barrier(0);
+                    lookup_block(odd, slot);
+                    visit_block(odd, slot);
+                    t0 += U;
+                    if (t0 >= steps) break;
+                }
             }
         }
 
