@@ -305,8 +305,14 @@ def main():
         }
         key = ROOFLINE_KEYS.get(name, "roofline_" + name)
         if key in stored_traffic:
-            out["traffic"] = stored_traffic[key]["bytes_per_launch"]
-            out["traffic_source"] = ("stored, not measured in this run: " + stored_traffic[key]["source"])
+            st = stored_traffic[key]
+            out["traffic"] = st["bytes_per_launch"]
+            out["traffic_source"] = "stored, not measured in this run: " + st["source"]
+            # what the counters said of the same launch (of the build that was profiled): how busy
+            # the vector ALUs and the LDS units really were, beside the instruction and byte models above
+            out["counters_of_the_profiled_run"] = {k: st[k] for k in ("valu_busy", "lds_busy", "l2_hit_rate",
+                                                                         "valu_instructions_per_wavefront_step",
+                                                                         "fetch_bytes", "write_bytes") if k in st}
         return out
 
     described = [CALLS[name][3] for name in names]

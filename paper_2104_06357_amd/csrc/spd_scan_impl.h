@@ -425,19 +425,11 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     const int tid = (int)threadIdx.x, nthr = (int)blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nw = nthr >> 6;
 
-    // workgroups that run at the same time on one XCD (ids equal mod 8) share a chunk of B
-    int g, chunk;
-    {
-        int w = (int)blockIdx.x;
-        if ((args.n_chunks & 7) == 0) {
-            int t = w >> 3;
-            chunk = (w & 7) + 8 * (t / args.n_groups);
-            g = t % args.n_groups;
-        } else {
-            chunk = w / args.n_groups;
-            g = w % args.n_groups;
-        }
-    }
+    // Consecutive workgroups are consecutive groups of rows on one chunk of B: whatever runs at the
+    // same time, on any XCD, sweeps the same stretch of B, which the memory-side cache then serves
+    // to all of them (giving each XCD a chunk of its own, so that its L2 alone is shared, measured
+    // slower on every configuration: eight stretches of B in flight instead of one or two).
+    const int chunk = (int)blockIdx.x / args.n_groups, g = (int)blockIdx.x % args.n_groups;
     const int slab_begin = args.chunk_begin[chunk], slab_end = args.chunk_begin[chunk + 1];
     if (slab_begin >= slab_end) {
         if constexpr (KNN) {
