@@ -30,8 +30,9 @@ HBM_PEAK_GBS = 8000.0
 # Vector ALU: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (one
 # fp64 FMA or one fp32 instruction per lane and clock; the packed fp32 forms are compiled off).
 ALU_LANE_OPS = 256 * 4 * 16 * 2.4e9
-# LDS: 128 bytes per clock and compute unit.
-LDS_PEAK_BYTES = 256 * 128 * 2.4e9
+# LDS: 256 bytes per clock and compute unit, the rate of the 128-bit reads that fetch a column's staged
+# values (a conflict-free stream of them measures 208 on this chip; 64-bit reads 163, 32-bit reads 83).
+LDS_PEAK_BYTES = 256 * 256 * 2.4e9
 COPY_BYTES = 256 << 20
 
 # What one visit (a staged row of A meeting a stored entry of B) cannot cost less than in vector
@@ -341,7 +342,7 @@ def main():
         import oracle
         # a bounded sample of the same workload: every pair of config 1 for L1 and cosine, and a
         # few query rows of each larger config against a sample of its index rows
-        samples = {1: (None, None), 2: (64, 65536), 3: (64, 16384), 4: (16, 131072)}
+        samples = {1: (None, None), 2: (128, 65536), 3: (128, 16384), 4: (32, 131072)}
         oracle_name = {"l1": "manhattan", "cosine": "cosine", "jensen_shannon": "jensen_shannon", "jaccard": "jaccard"}
         rng = np.random.default_rng(0)
         pairs, used, parts = 0.0, 1, []
