@@ -265,7 +265,10 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 up to 32; with fused k-NN 16, or 32 for max_rows = 16)
  *   "split_len"   B rows at least this long are split over several lanes (0 = automatic: 256,
  *                 or 512 when B has 2^22 stored entries or more)
- *   "window"      B rows per degree-sorting window
+ *   "window"      rows of the streamed operand per degree-sorting window (0 = automatic: 2,048 for a
+ *                 pairwise call that stages A, whose stores want the rows of a slab near each other;
+ *                 and for an index, which serves such calls too; 65,536 for k-NN calls and for pairwise
+ *                 calls with the operands' roles exchanged, where a wide window only means fewer idle lanes)
  *   "chunks"      number of B chunks (0 = automatic)
  *   "sort_slack"  1 (default): inside a window B's rows are sorted by their length in blocks of four
  *                 entries, and by row number among equals (neighbouring rows then share slabs and
@@ -286,6 +289,11 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *   "cuckoo_attempts" hash staging of a half-full table tries up to three pairs of hash functions
  *                 before it falls back to linear probing (3, the default); fewer, down to 0 (linear
  *                 probing at once), let a test reach that fall-back, which no input has needed so far
+ *   "knn_seed"    fused top-k of the distances that grow with a row's mass (L1, Minkowski, Canberra,
+ *                 Hamming, Jensen-Shannon, Chebyshev): 1 (default) lets the wavefronts of a workgroup
+ *                 agree on a first bound of the k-th distance from the shortest rows of their share
+ *                 of B before any candidate is queued (the result does not depend on it); 0 starts
+ *                 every list with no bound
  *   "swap_operands" spd_pairwise may stage B and stream A instead of the other way round (every distance
  *                 but the two KL divergences is symmetric in its rows): B's rows are then staged in
  *                 groups of consecutive rows, so that a lane's results are neighbours in the output

@@ -130,6 +130,7 @@ struct spd_handle {
     bool check_plan = false;
     bool no_byte_counters = false;   // option "byte_counters" 0: set metrics through the dot product
     int cuckoo_attempts = 3;     // option "cuckoo_attempts"
+    int knn_seed = 1;            // option "knn_seed"
     int swap_operands = 1;       // option "swap_operands": 0 never, 1 where it pays, 2 wherever the distance allows it
     int side_streams = 3;        // option "side_streams": how many internal streams the small launches may use beside the large one
     static constexpr int kSideStreams = 3;
@@ -573,7 +574,9 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     struct WaitForHelper { Helper &w; ~WaitForHelper() { w.wait(); } } wait_for_helper{h->helper};
     std::string why;
     if (!index) {
-        why = plan_b(b_ip, n, h->opt, h->plan_of_b);
+        PlanOptions opt_b = h->opt;
+        opt_b.window = window_for(h->opt, knn_k > 0 || swapped ? WINDOW_NO_SCATTERED_STORES : WINDOW_SCATTERED_STORES);
+        why = plan_b(b_ip, n, opt_b, h->plan_of_b);
         if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "B: " + why);
         lap("plan b");
     }
@@ -798,6 +801,7 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
         sa.kind = c.kind;
         sa.hscale = c.hscale;
         sa.cuckoo_attempts = h->cuckoo_attempts;
+        sa.knn_seed = h->knn_seed;
         sa.transform = mi.transform;
         sa.norm = mi.norm;
         sa.k = (uint32_t)A->n_cols;
@@ -952,7 +956,7 @@ size_t workspace_bound(const spd_handle *h, const spd_csr *A, const spd_csr *B, 
     const size_t m = (size_t)A->n_rows, n = (size_t)B->n_rows;
     const int split_len = split_len_for(o, B->nnz);
     const size_t seg_target = (size_t)std::max(1, std::max(2, split_len) / 2);
-    const size_t window = (size_t)std::max(64, o.window);
+    const size_t window = (size_t)std::max(64, window_for(o, WINDOW_SCATTERED_STORES));   // the narrowest: the largest bound
     size_t slabs = n / 64 + n / window + (n + 4 * (size_t)B->nnz / seg_target) / 64 + 4;
     size_t lanes = slabs * 64;
     // at most 15 launches (5 group sizes x 3 occupancies), each cutting B at most 4096 times and
@@ -1102,7 +1106,9 @@ spd_status spd_index_create(spd_handle *h, const spd_csr *Index, spd_metric metr
     if (b_ip[n] != Index->nnz) return fail(h, SPD_ERR_BAD_CSR, "indptr[n_rows] != nnz");
     std::string why;
     try {
-        why = plan_b(b_ip, n, h->opt, ix->plan);
+        PlanOptions opt_b = h->opt;
+        opt_b.window = window_for(h->opt, WINDOW_SCATTERED_STORES);      // an index serves pairwise calls that stage A as well
+        why = plan_b(b_ip, n, opt_b, ix->plan);
     } catch (const std::exception &ex) {
         why = std::string("planning failed: ") + ex.what();
     }
@@ -1204,7 +1210,8 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
             return fail(h, SPD_ERR_UNSUPPORTED, "split_len must be 0 (automatic) or lie in [2, 2^20]");
         o.split_len = (int)value;
     } else if (s == "window") {
-        if (value < 64 || value > (1 << 24)) return fail(h, SPD_ERR_UNSUPPORTED, "window must lie in [64, 2^24]");
+        if (value != 0 && (value < 64 || value > (1 << 24)))
+            return fail(h, SPD_ERR_UNSUPPORTED, "window must be 0 (automatic) or lie in [64, 2^24]");
         o.window = (int)value;
     } else if (s == "chunks") {
         if (value < 0 || value > 4096) return fail(h, SPD_ERR_UNSUPPORTED, "chunks must lie in [0, 4096]");
@@ -1228,6 +1235,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
     } else if (s == "side_streams") {
         if (value < 0 || value > spd_handle::kSideStreams) return fail(h, SPD_ERR_UNSUPPORTED, "side_streams must lie in [0, 3]");
         h->side_streams = (int)value;
+    } else if (s == "knn_seed") {
+        if (value < 0 || value > 1) return fail(h, SPD_ERR_UNSUPPORTED, "knn_seed must be 0 or 1");
+        h->knn_seed = (int)value;
     } else if (s == "cuckoo_attempts") {
         if (value < 0 || value > 3) return fail(h, SPD_ERR_UNSUPPORTED, "cuckoo_attempts must lie in [0, 3]");
         h->cuckoo_attempts = (int)value;

@@ -42,6 +42,7 @@ struct ScanArgs {
     int32_t kind, transform, norm;
     int32_t hscale;               // hash staging: log2 of table entries per staged entry
     int32_t cuckoo_attempts;      // hash staging, half-full tables: pairs of hash functions tried (0: linear probing at once)
+    int32_t knn_seed;             // fused top-k: 1 = the wavefronts' first slabs set a bar before any candidate is queued
     uint32_t k;                   // columns
     uint32_t padcol;              // column an idle lane looks up (maps to the zero row)
     // results

@@ -41,7 +41,7 @@ std::string plan_b(const int64_t *indptr, int64_t n_rows, const PlanOptions &opt
     if (n_rows >= (int64_t)1 << 31) return "more than 2^31-1 rows";
     const int64_t T = std::max<int64_t>(2, split_len_for(opt, n_rows > 0 ? indptr[n_rows] : 0));
     const int64_t seg_target = std::max<int64_t>(1, T / 2);
-    const int64_t Wn = std::max<int64_t>(kWave, (opt.window / kWave) * kWave);
+    const int64_t Wn = std::max<int64_t>(kWave, (window_for(opt, WINDOW_SCATTERED_STORES) / kWave) * kWave);
     out.n_rows = n_rows;
     out.nnz = n_rows ? indptr[n_rows] : 0;
     if (n_rows && indptr[0] != 0) return "indptr[0] != 0";

@@ -46,7 +46,7 @@ struct PlanOptions {
     int force_kind = KIND_AUTO;
     int max_rows = 8;                       // 16 halves the wavefronts a compute unit can hold
     int split_len = 0;                      // 0: by the size of B (see split_len_for)
-    int window = 2048;
+    int window = 0;                         // rows of the streamed operand per degree-sorting window (0: see window_for)
     int chunks = 0;
     int n_cus = 256;
     int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32)
@@ -55,6 +55,20 @@ struct PlanOptions {
     int partial_groups = 1;                 // 1: a group of R rows may leave a quarter of its places empty rather than fall to R/2
     int consecutive_groups = 0;             // 1: a group holds consecutive rows, in row order (see plan_a)
 };
+
+// Rows per degree-sorting window of the streamed operand.  A wide window leaves fewer idle lanes
+// (a slab runs as long as its longest row: 18 % of the steps are padding on 10,000 rows of 5-250
+// entries sorted 2,048 at a time, 7 % when they are sorted as one), a narrow one keeps the 64 rows
+// of a slab near each other, which only matters where a lane's store is a lone 4-byte word of the
+// streamed row's column: a pairwise call that stages A.  The fused top-k writes no distances, and
+// with the operands' roles exchanged a lane writes whole sectors of its own row.
+// (Measured: 10,000 x 10,000 rows, dominant launch of L1 0.62 -> 0.56 ms with the roles exchanged;
+// a pairwise call that stages 1,024 rows against 300,000 goes from 11.2 to 13.6 ms at 8,192.)
+enum WindowUse { WINDOW_SCATTERED_STORES = 0, WINDOW_NO_SCATTERED_STORES = 1 };
+inline int window_for(const PlanOptions &opt, WindowUse use) {
+    if (opt.window > 0) return opt.window;
+    return use == WINDOW_SCATTERED_STORES ? 2048 : 65536;
+}
 
 // Bloom staging: filter bits per stored entry (two hash functions: ~1.4 % false positives), and
 // the bounds of a filter's size.

@@ -343,6 +343,42 @@ def test_knn_ties_go_to_the_lower_index(handle, spd):
         assert_distances_close(dist.cpu().numpy(), want_dist, metric)
 
 
+@pytest.mark.parametrize("k", [6, 32, 64])
+def test_knn_first_bound_from_the_first_slabs(spd, k):
+    """A chunk of eight slabs or more per wavefront: the wavefronts agree on a bound of the k-th key from
+    their first slabs before any candidate is queued (option knn_seed).  Every row of the index 250
+    times over, so that the bound itself is a distance many rows tie at: same lists with and without
+    it, and the oracle's (ties to the lower index)."""
+    import torch
+    rng = np.random.default_rng(31)
+    base = (rng.random((40, 96)) < 0.1) * rng.integers(1, 4, size=(40, 96)).astype(np.float64)
+    base[7] = 0.0                                          # an empty row among them
+    I = synth.from_dense(np.concatenate([base] * 250))     # 10,000 rows: 157 slabs
+    Q = synth.from_dense(base[:24])
+    dI, dQ = spd.DeviceCsr.from_host(I), spd.DeviceCsr.from_host(Q)
+    for metric in ("l1", "hamming", "chebyshev", "l2_unexpanded", "canberra", "jensen_shannon", "cosine", "jaccard"):
+        print("knn first bound", metric, k, flush=True)
+        results = []
+        for seed in (1, 0):
+            h = spd.Handle()
+            h.set_option("check_plan", 1)
+            h.set_option("chunks", 1)
+            h.set_option("knn_seed", seed)
+            idx, dist = h.knn(dQ, dI, metric, k)
+            torch.cuda.synchronize()
+            results.append((idx.cpu().numpy(), dist.cpu().numpy()))
+            h.close()
+        assert np.array_equal(results[0][0], results[1][0]), metric
+        assert np.array_equal(results[0][1], results[1][1], equal_nan=True), metric
+        want_idx, want_dist = oracle.knn(Q, I, ORACLE_NAME[metric], k)
+        if metric in ("jaccard", "l1", "chebyshev", "hamming"):       # (exact in fp32 on these small integers: ties are ties)
+            assert np.array_equal(results[0][0], want_idx), metric
+        else:
+            rows = oracle.pairwise(Q, I, ORACLE_NAME[metric])
+            assert_knn_matches(results[0][0], results[0][1], rows, k, metric, metric)
+        assert_distances_close(results[0][1], want_dist, metric)
+
+
 def test_knn_with_sliced_rows_and_split_rows(handle, spd):
     import torch
     A, B = _wide_pair(False)
