@@ -109,7 +109,7 @@ SPD_HD constexpr bool wide_sums(int metric) {
 SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
     if (op == OP_CNT) return (knn && R >= 16) ? 512 : 1024;
     if (op == OP_MINK || op == OP_MINK_ANY) return 512;
-    return (R == 16 || ((op == OP_JS || op == OP_CHEB || op == OP_SEMI_SUM || op == OP_SEMI_EXT) && R == 8)) ? 512 : 1024;
+    return (R == 16 || ((op == OP_JS || op == OP_CHEB) && R == 8)) ? 512 : 1024;
 }
 
 // Wavefronts per SIMD the compiler is asked to make room for (it bounds the registers per
@@ -118,8 +118,6 @@ SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
 // every other instance runs fewer wavefronts and looks its columns up a block of steps ahead.
 SPD_HD constexpr int scan_min_waves(int op, int R, int kind, bool knn) {
     if (!knn && R == 8 && kind != 3 /* KIND_HASH */ && kind != 5 /* KIND_BITMAP */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM || op == OP_CANB)) return 8;
-    // 128 registers: two workgroups of 8 wavefronts per compute unit
-    if (!knn && R == 8 && (op == OP_SEMI_SUM || op == OP_SEMI_EXT)) return 4;
     // (the k-NN instances of these sit a register or two above 128 otherwise)
     if (knn && R == 8 && ((op == OP_JS && kind != 3 /* KIND_HASH */) || op == OP_CHEB)) return 4;
     return 1;

@@ -435,7 +435,7 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     static_assert(KIND != KIND_BLOOM || (R == 1 && bloom_serves(OP)), "a Bloom-staged row is alone in its workgroup");
     constexpr int U = kScanUnroll;
     // the instances compiled for 64 registers per lane (eight wavefronts per SIMD) keep the short pipeline
-    constexpr bool kDeepPipeline = KIND != KIND_BLOOM && scan_min_waves(OP, R, KIND, KNN) < 8;
+    constexpr bool kDeepPipeline = KIND != KIND_BLOOM && scan_min_waves(OP, R, KIND, KNN) < 8 && !kSemi;
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ ARow s_rows[R];
     __shared__ uint32_t s_prefix[R + 1];
@@ -1216,7 +1216,7 @@ static hipError_t launch_scan_op(hipStream_t st, int R, int block, uint32_t lds_
         case 2: return launch_scan_r<OP, 2, WHICH>(st, block, lds_bytes, args);
         case 4: return launch_scan_r<OP, 4, WHICH>(st, block, lds_bytes, args);
         case 8:
-            if constexpr (OP == OP_MINK || OP == OP_MINK_ANY) return hipErrorInvalidValue;
+            if constexpr (OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) return hipErrorInvalidValue;
             else return launch_scan_r<OP, 8, WHICH>(st, block, lds_bytes, args);
         case 16:
             if constexpr (OP == OP_JS || OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_SEMI_SUM || OP == OP_SEMI_EXT) return hipErrorInvalidValue;
