@@ -10,7 +10,7 @@ from util import ALL_METRICS, NONNEGATIVE_ONLY, ORACLE_NAME, assert_distances_cl
 
 pytestmark = pytest.mark.gpu
 
-N_CASES = 160
+N_CASES = 200
 
 
 @pytest.fixture(scope="module")
@@ -61,12 +61,17 @@ def _case(seed):
         signed = what not in NONNEGATIVE_ONLY and rng.random() < 0.7
     k = int(rng.choice([7, 64, 65, 300, 1000, 3000]))
     m, n = int(rng.integers(1, 120)), int(rng.integers(1, 400))
+    long_index = rng.random() < 0.12
+    if long_index:
+        # an index of many slabs (a chunk then has eight or more per wavefront), few query rows
+        k = int(rng.choice([64, 300]))
+        m, n = int(rng.integers(1, 24)), int(rng.integers(8200, 11000))
     binary = (not semiring) and rng.random() < 0.15
     A = _matrix(rng, m, k, signed, binary)
     B = A if (rng.random() < 0.15) else _matrix(rng, n, k, signed, binary)
     options = {}
     if rng.random() < 0.7:
-        options["force_kind"] = int(rng.choice([1, 2, 3, 4]))
+        options["force_kind"] = int(rng.choice([1, 2, 3, 4, 5]))
     if rng.random() < 0.2:
         options["bloom_long_rows"] = 1
     if rng.random() < 0.6:
@@ -89,6 +94,17 @@ def _case(seed):
         options["sort_slack"] = 0
     if rng.random() < 0.3:
         options["partial_groups"] = int(rng.choice([0, 2]))
+    if rng.random() < 0.4:
+        options["swap_operands"] = int(rng.choice([0, 2]))       # never / wherever the distance allows it
+    if rng.random() < 0.2:
+        options["knn_seed"] = 0
+    if rng.random() < 0.15:
+        options["cuckoo_attempts"] = int(rng.choice([0, 1]))
+    if long_index:
+        options.pop("lds_budget", None)
+        if options.get("force_kind") == 1:
+            options.pop("force_kind")
+        options["chunks"] = int(rng.choice([1, 2]))
     knn_k = int(rng.choice([1, 3, 17, 64]))
     p = float(rng.choice([0.5, 1.0, 2.0, 3.0, 3.5]))
     via_index = (not semiring) and rng.random() < 0.3
