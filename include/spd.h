@@ -290,7 +290,7 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 before it falls back to linear probing (3, the default); fewer, down to 0 (linear
  *                 probing at once), let a test reach that fall-back, which no input has needed so far
  *   "knn_seed"    fused top-k of the distances that grow with a row's mass (L1, Minkowski, Canberra,
- *                 Hamming, Jensen-Shannon, Chebyshev): 1 (default) lets the wavefronts of a workgroup
+ *                 Hamming, Jensen-Shannon, Chebyshev, expanded Euclidean, Hellinger): 1 (default) lets the wavefronts of a workgroup
  *                 agree on a first bound of the k-th distance from the shortest rows of their share
  *                 of B before any candidate is queued (the result does not depend on it); 0 starts
  *                 every list with no bound

@@ -797,15 +797,18 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     // distances of the chunk at or below it, so no key of the final list exceeds it, and it is known
     // before the first candidate is queued (10,000 x 10,000 rows, L1, k = 32: 0.87 -> 0.68 ms).  Not in
     // a chunk of a few slabs per wavefront (the short slabs are what evens out the wavefronts' shares
-    // at the end), and not for the dot product family and the set metrics, whose near rows are the
-    // long ones: the short slabs' distances say nothing there, and the exchange costs 2-3 %.
+    // at the end), and not for cosine, correlation, the inner product and the set metrics, whose near
+    // rows are the long ones: the short slabs' distances say nothing there, and the exchange costs 2-3 %.
+    // (the dot product serves both kinds: the expanded Euclidean and Hellinger distances grow with the
+    // row's mass, cosine, correlation and the inner product do not)
     constexpr bool kSeedPays = OP == OP_L1 || OP == OP_MINK || OP == OP_MINK_ANY || OP == OP_CANB || OP == OP_HAMM ||
-                               OP == OP_JS || OP == OP_CHEB;
+                               OP == OP_JS || OP == OP_CHEB || OP == OP_DOT;
     bool seeding = false;
     int seed_rank = 1;
     if constexpr (KNN && kSeedPays) {
         seed_rank = (args.knn_k + nw - 1) / nw;
-        seeding = args.knn_seed != 0 && slab_end - slab_begin >= 8 * nw && seed_rank <= 8;   // the same in every wavefront
+        seeding = args.knn_seed != 0 && slab_end - slab_begin >= 8 * nw && seed_rank <= 8 &&      // the same in every wavefront
+                  (OP != OP_DOT || args.q.metric == MT_L2 || args.q.metric == MT_HELLINGER);
     }
     const int taken_end = seeding ? slab_end - nw : slab_end;    // slabs [slab_begin, taken_end) go to whoever comes first
     for (;;) {

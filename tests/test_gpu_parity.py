@@ -356,7 +356,8 @@ def test_knn_first_bound_from_the_first_slabs(spd, k):
     I = synth.from_dense(np.concatenate([base] * 250))     # 10,000 rows: 157 slabs
     Q = synth.from_dense(base[:24])
     dI, dQ = spd.DeviceCsr.from_host(I), spd.DeviceCsr.from_host(Q)
-    for metric in ("l1", "hamming", "chebyshev", "l2_unexpanded", "canberra", "jensen_shannon", "cosine", "jaccard"):
+    for metric in ("l1", "hamming", "chebyshev", "l2_unexpanded", "canberra", "jensen_shannon", "l2_expanded", "hellinger",
+                   "cosine", "jaccard"):
         print("knn first bound", metric, k, flush=True)
         results = []
         for seed in (1, 0):
