@@ -118,6 +118,10 @@ SPD_HD constexpr int scan_max_block(int op, int R, bool knn) {
 // every other instance runs fewer wavefronts and looks its columns up a block of steps ahead.
 SPD_HD constexpr int scan_min_waves(int op, int R, int kind, bool knn) {
     if (!knn && R == 8 && kind != 3 /* KIND_HASH */ && kind != 5 /* KIND_BITMAP */ && (op == OP_DOT || op == OP_L1 || op == OP_CNT || op == OP_HAMM || op == OP_CANB)) return 8;
+    // (the fused top-k keeps its lists in LDS: these instances fit the 64 registers as well, spilling a
+    // dozen words in the slab epilogue; 10,000 x 10,000 rows, cosine, k = 32: 0.67 -> 0.55 ms.  Not the set
+    // metrics' sixteen rows: 0.54 -> 0.63 ms)
+    if (knn && R == 8 && kind != 3 /* KIND_HASH */ && kind != 5 /* KIND_BITMAP */ && (op == OP_DOT || op == OP_L1 || op == OP_HAMM || op == OP_CANB)) return 8;
     // (the k-NN instances of these sit a register or two above 128 otherwise)
     if (knn && R == 8 && ((op == OP_JS && kind != 3 /* KIND_HASH */) || op == OP_CHEB)) return 4;
     return 1;
