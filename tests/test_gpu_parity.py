@@ -380,6 +380,40 @@ def test_knn_first_bound_from_the_first_slabs(spd, k):
         assert_distances_close(results[0][1], want_dist, metric)
 
 
+def test_knn_first_bound_with_sliced_rows(spd):
+    """The same exchange while some staged rows are slices of a row that does not fit the table whole (their
+    partial sums go to memory and take no part in it) and rows of the index are split over lanes."""
+    import torch
+    rng = np.random.default_rng(32)
+    base = (rng.random((40, 400)) < 0.05) * rng.integers(1, 4, size=(40, 400)).astype(np.float64)
+    I = synth.from_dense(np.concatenate([base] * 250))
+    queries = base[:12].copy()
+    queries[3] = rng.integers(1, 4, size=400)              # a full row: cut into slices
+    queries[8, ::2] = 2.0                                  # and a half-full one
+    Q = synth.from_dense(queries)
+    dI, dQ = spd.DeviceCsr.from_host(I), spd.DeviceCsr.from_host(Q)
+    options = dict(split_len=4, force_kind=3, lds_budget=12288, chunks=1)
+    for metric in ("l1", "l2_expanded", "hamming"):
+        print("knn first bound, slices", metric, flush=True)
+        plan = spd.testing.host_plan_summary(Q["indptr"], I["indptr"], 400, metric, k_neighbors=32, **options)
+        assert plan["spilled_rows"] >= 1 and plan["split_rows"] > 0 and plan["slabs"] >= 128
+        results = []
+        for seed in (1, 0):
+            h = spd.Handle()
+            h.set_option("check_plan", 1)
+            for name, value in options.items():
+                h.set_option(name, value)
+            h.set_option("knn_seed", seed)
+            idx, dist = h.knn(dQ, dI, metric, 32)
+            torch.cuda.synchronize()
+            results.append((idx.cpu().numpy(), dist.cpu().numpy()))
+            h.close()
+        assert np.array_equal(results[0][0], results[1][0]), metric
+        assert np.array_equal(results[0][1], results[1][1]), metric
+        rows = oracle.pairwise(Q, I, ORACLE_NAME[metric])
+        assert_knn_matches(results[0][0], results[0][1], rows, 32, metric, metric)
+
+
 def test_knn_with_sliced_rows_and_split_rows(handle, spd):
     import torch
     A, B = _wide_pair(False)
