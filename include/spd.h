@@ -270,6 +270,8 @@ spd_status spd_csr_validate(spd_handle *handle, const spd_csr *M, int require_no
  *                 and for an index, which serves such calls too; 65,536 for k-NN calls and for pairwise
  *                 calls with the operands' roles exchanged, where a wide window only means fewer idle lanes)
  *   "chunks"      number of B chunks (0 = automatic)
+ *   "chunk_scale" the automatic number of chunks is the cost model's times this (1 to 8; 0 = automatic:
+ *                 2 for k-NN calls, whose lists do better on shorter chunks, 1 for pairwise calls)
  *   "sort_slack"  1 (default): inside a window B's rows are sorted by their length in blocks of four
  *                 entries, and by row number among equals (neighbouring rows then share slabs and
  *                 their results share cache lines); 0: by their exact length

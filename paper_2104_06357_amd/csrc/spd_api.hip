@@ -634,7 +634,11 @@ spd_status run(spd_handle *h, const spd_csr *A, const spd_csr *B, int metric, fl
     why = why_a;
     if (!why.empty()) return fail(h, why.find("pointers") != std::string::npos ? SPD_ERR_BAD_CSR : SPD_ERR_UNSUPPORTED, "A: " + why);
     lap("wait for plan a");
-    for (AClass &c : ap.classes) plan_chunks(bp, c, h->opt);
+    {
+        PlanOptions opt_c = h->opt;
+        opt_c.chunk_scale = chunk_scale_for(h->opt, knn_k > 0);
+        for (AClass &c : ap.classes) plan_chunks(bp, c, opt_c);
+    }
     lap("chunks");
     if (h->check_plan) {
         std::vector<int64_t> index_rows;
@@ -960,7 +964,7 @@ size_t workspace_bound(const spd_handle *h, const spd_csr *A, const spd_csr *B, 
     size_t slabs = n / 64 + n / window + (n + 4 * (size_t)B->nnz / seg_target) / 64 + 4;
     size_t lanes = slabs * 64;
     // at most 15 launches (5 group sizes x 3 occupancies), each cutting B at most 4096 times and
-    // never into more than 4 workgroups per slot of the chip plus one per group
+    // never into more than 4 workgroups per slot of the chip (times the chunk scale) plus one per group
     const size_t launches = 15;
     const size_t chunk_words = launches * 4097;
     // rows of A that do not fit alone are cut into slices of at least 1/2 of the largest
@@ -986,7 +990,7 @@ size_t workspace_bound(const spd_handle *h, const spd_csr *A, const spd_csr *B, 
     add(partial_slots * planes * n * 8); add(partial_slots * 16);
     if (k_neighbors > 0) {
         size_t lists = o.chunks > 0 ? (m + m / 3 + 16 * launches) * (size_t)o.chunks
-                                    : launches * 16 * (16 * (size_t)o.n_cus + 1) + m + m / 3 + 16 * launches;
+                                    : launches * 16 * (16 * (size_t)o.n_cus * (size_t)chunk_scale_for(o, true) + 1) + m + m / 3 + 16 * launches;
         lists += std::min(sliced_rows_max, m) * (n / (size_t)kFinalizeTile + 1);     // the tiles of spilled rows
         add(lists * (size_t)k_neighbors * sizeof(KnnEntry)); add(m * 8); add(m * 4);
     }
@@ -1213,6 +1217,9 @@ spd_status spd_set_option(spd_handle *h, const char *name, int64_t value) {
         if (value != 0 && (value < 64 || value > (1 << 24)))
             return fail(h, SPD_ERR_UNSUPPORTED, "window must be 0 (automatic) or lie in [64, 2^24]");
         o.window = (int)value;
+    } else if (s == "chunk_scale") {
+        if (value < 0 || value > 8) return fail(h, SPD_ERR_UNSUPPORTED, "chunk_scale must lie in [0, 8]");
+        o.chunk_scale = (int)value;
     } else if (s == "chunks") {
         if (value < 0 || value > 4096) return fail(h, SPD_ERR_UNSUPPORTED, "chunks must lie in [0, 4096]");
         o.chunks = (int)value;

@@ -48,6 +48,7 @@ struct PlanOptions {
     int split_len = 0;                      // 0: by the size of B (see split_len_for)
     int window = 0;                         // rows of the streamed operand per degree-sorting window (0: see window_for)
     int chunks = 0;
+    int chunk_scale = 0;                    // the cost model's number of chunks is multiplied by this (0: see chunk_scale_for)
     int n_cus = 256;
     int waves_per_cu = 0;                   // wavefronts the launches aim to keep on a compute unit (0: 32)
     int bloom_long_rows = 0;                // 1: a row too long for the LDS gets a Bloom filter instead of slices
@@ -64,6 +65,16 @@ struct PlanOptions {
 // with the operands' roles exchanged a lane writes whole sectors of its own row.
 // (Measured: 10,000 x 10,000 rows, dominant launch of L1 0.62 -> 0.56 ms with the roles exchanged;
 // a pairwise call that stages 1,024 rows against 300,000 goes from 11.2 to 13.6 ms at 8,192.)
+// The cost model below counts rounds of workgroups and knows nothing of what the fused top-k does
+// with a chunk: its lists meet the rows of B sorted by length, and in a shorter chunk the rows'
+// lengths, hence their distances, vary less, so fewer candidates pass (and the last round of
+// workgroups is a smaller share of the launch).  Measured with twice the model's chunks, k-NN calls:
+// 65,536 x 26,000 L1 93.8 -> 83.4 ms, 500,000 x 2^20 Jaccard 41.8 -> 36.8, 10,000 x 10,000 cosine
+// 0.61 -> 0.58 (dominant launch), 663,000 rows of two entries +3.5 % (plan_chunks leaves such short
+// chunks alone); three or four times: the same or worse.  Pairwise calls: within 2 % either way, so
+// they keep the model's number.
+inline int chunk_scale_for(const PlanOptions &opt, bool knn) { return opt.chunk_scale > 0 ? opt.chunk_scale : (knn ? 2 : 1); }
+
 enum WindowUse { WINDOW_SCATTERED_STORES = 0, WINDOW_NO_SCATTERED_STORES = 1 };
 inline int window_for(const PlanOptions &opt, WindowUse use) {
     if (opt.window > 0) return opt.window;

@@ -100,6 +100,7 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
         else if (s == "sort_slack") opt.sort_slack = (int)v;
         else if (s == "partial_groups") opt.partial_groups = (int)v;
         else if (s == "consecutive_groups") opt.consecutive_groups = (int)v;
+        else if (s == "chunk_scale") opt.chunk_scale = (int)v;
         else return SPD_ERR_UNSUPPORTED;
     }
     APlan ap;
@@ -110,7 +111,9 @@ spd_status spd_host_plan_summary(const int64_t *a_indptr, int64_t a_rows, const 
     // (the planner hook has no degree: it plans Minkowski for the small integer degrees)
     if (why.empty()) why = plan_a(a_indptr, a_rows, n_cols, (int)metric, op, k_neighbors, opt, ap);
     if (why.empty()) {
-        for (AClass &c : ap.classes) plan_chunks(bp, c, opt);
+        PlanOptions opt_c = opt;
+        opt_c.chunk_scale = chunk_scale_for(opt, k_neighbors > 0);
+        for (AClass &c : ap.classes) plan_chunks(bp, c, opt_c);
         why = plan_check(ap, bp, a_indptr, b_indptr, n_cols, (int)metric, op, k_neighbors, opt);
     }
     std::string js = "{";
