@@ -434,8 +434,11 @@ __global__ void __launch_bounds__(scan_max_block(OP, R, KNN))
     static_assert(kTopRanks == 32, "a pair's visited ranks are the bits of one 32-bit word");
     static_assert(KIND != KIND_BLOOM || (R == 1 && bloom_serves(OP)), "a Bloom-staged row is alone in its workgroup");
     constexpr int U = kScanUnroll;
-    // the instances compiled for 64 registers per lane (eight wavefronts per SIMD) keep the short pipeline
-    constexpr bool kDeepPipeline = KIND != KIND_BLOOM && scan_min_waves(OP, R, KIND, KNN) < 8 && !kSemi;
+    // the instances compiled for 64 registers per lane (eight wavefronts per SIMD) keep the short pipeline, and so
+    // do those behind the 16-bit strip, whose lookup is one LDS read and an address (the compiler carries their
+    // slots through the long pipeline as 16 bits and clears the upper half again at every use: 65,536 x 26,000
+    // rows, four rows per group, L1: 56.2 ms with the long pipeline, 54.1 with the short one)
+    constexpr bool kDeepPipeline = KIND != KIND_BLOOM && KIND != KIND_SLOT && scan_min_waves(OP, R, KIND, KNN) < 8 && !kSemi;
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ ARow s_rows[R];
     __shared__ uint32_t s_prefix[R + 1];
