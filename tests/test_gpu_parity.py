@@ -464,6 +464,30 @@ def test_config1_self_join_knn(handle, config1):
             assert np.array_equal(idx[:, 0], np.arange(A["n_rows"])), metric
 
 
+def test_knn_in_a_caller_workspace_of_the_documented_size(spd, config1):
+    """spd_workspace_bytes bounds what a k-NN call carves (candidate lists of every chunk included), whatever
+    the planner's options make of the chunks: the call runs inside exactly that many bytes and returns what it
+    returns with the handle's own scratch."""
+    import torch
+    A, B, dA, dB = config1
+    for options in ({}, {"chunk_scale": 4}, {"chunks": 7}, {"split_len": 16, "window": 64}, {"max_rows": 2}):
+        for metric, k in (("cosine", 32), ("jaccard", 64), ("l1", 5)):
+            print("knn workspace", options, metric, k, flush=True)
+            own = spd.Handle()
+            lent = spd.Handle()
+            for h in (own, lent):
+                h.set_option("check_plan", 1)
+                for name, value in options.items():
+                    h.set_option(name, value)
+            need = lent.workspace_bytes(dA, dB, metric, k)
+            lent.set_workspace(torch.empty(need, dtype=torch.uint8, device="cuda"))
+            want_idx, want_dist = own.knn(dA, dB, metric, k)
+            idx, dist = lent.knn(dA, dB, metric, k)
+            torch.cuda.synchronize()
+            assert torch.equal(idx, want_idx) and torch.equal(dist, want_dist), (options, metric, k)
+            own.close(); lent.close()
+
+
 # ------------------------------------------------------------------ the boundary's error paths
 def test_error_statuses(handle, spd, config0):
     import torch
@@ -488,6 +512,11 @@ def test_error_statuses(handle, spd, config0):
     with pytest.raises(spd.SpdError) as e:
         handle.set_option("no_such_option", 1)
     assert e.value.status_name == "SPD_ERR_UNSUPPORTED"
+    for name, value in (("window", 63), ("window", 1 << 25), ("chunk_scale", 9), ("chunk_scale", -1), ("knn_seed", 2),
+                        ("swap_operands", 3), ("cuckoo_attempts", 4), ("chunks", 4097), ("force_kind", 6), ("side_streams", 4)):
+        with pytest.raises(spd.SpdError) as e:
+            handle.set_option(name, value)
+        assert e.value.status_name == "SPD_ERR_UNSUPPORTED", (name, value)
     # a caller workspace that is too small is reported, a large enough one is used
     need = handle.workspace_bytes(dA, dB, "l1")
     handle.set_workspace(torch.empty(256, dtype=torch.uint8, device="cuda"))
